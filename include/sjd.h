@@ -1,0 +1,161 @@
+/* sjd.h -- C ABI of the MI355X (gfx950) hot path of Speculative Jacobi Decoding (SJD).
+ *
+ * The problem (paper Sec. 4.1, first paragraph): after the prompt has been pre-filled, decode the
+ * image tokens W at a time.  Each iteration runs ONE causal forward of the auto-regressive
+ * transformer over the W draft tokens (Step 2), accepts a prefix of them with the probabilistic
+ * criterion of Eq. 1, resamples the first rejected position from the calibrated distribution of
+ * Eq. 2, re-draws every later position from this iteration's distributions (Eq. 3), and slides the
+ * window (Step 4).  By Theorem 1 every produced token is distributed exactly as under ordinary
+ * auto-regressive sampling.  W is called L here.
+ *
+ * Conventions
+ *  - Every function returns SJD_OK (0) or a negative SJD_E* code; nothing aborts or throws.
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host" pointers are
+ *    ordinary host memory.  The caller owns every buffer it passes; the library owns only its
+ *    opaque handles.  Buffers must not overlap unless stated.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device work is
+ *    enqueued on it and is asynchronous; outputs are valid once the caller has synchronised.
+ *  - Probabilities and logits are fp32 rows over the SAMPLING vocabulary: column t stands for
+ *    token id samp_lo + t, V_s = samp_hi - samp_lo columns per row.
+ *  - All decisions are deterministic functions of the inputs: identical calls give identical bits.
+ */
+#ifndef SJD_H
+#define SJD_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SJD_OK 0
+#define SJD_EINVAL (-1) /* bad argument (null pointer, size out of range, unsupported shape)   */
+#define SJD_ENOMEM (-2) /* device or host allocation failed                                    */
+#define SJD_ESEQ (-3)   /* the call would run past max_seq                                     */
+#define SJD_EHIP (-4)   /* a HIP runtime call failed; sjd_strerror() reports the last message  */
+
+#define SJD_MAX_WINDOW 32     /* largest L accepted by sjd_step / sjd_generate                 */
+#define SJD_MAX_SAMP_VOCAB 32768 /* largest V_s the verification kernels hold in LDS          */
+
+typedef struct sjd_model sjd_model; /* repacked device weights + tables; immutable after init  */
+typedef struct sjd_kv sjd_kv;       /* KV cache, its length n, ids of the cached tokens, scratch */
+
+/* Llama-style decoder (the paper fixes no architecture; Sec. 3.1 only requires an
+ * auto-regressive transformer with a softmax classifier over the token vocabulary).          */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, d_ffn;
+    int32_t vocab_total, samp_lo, samp_hi; /* sampling ids = [samp_lo, samp_hi)                */
+    int32_t max_seq;                       /* KV rows; needs prompt + N + L                    */
+    int32_t dtype;                         /* 0 = fp32, 1 = bf16 (weights, activations, cache) */
+    float rope_theta, rms_eps;
+} sjd_config;
+
+/* top-K sampling (Sec. 3.1).  temperature == 0 or top_k == 1 selects greedy decoding, which
+ * turns SJD into the deterministic Jacobi iteration of Sec. 3.2.                              */
+typedef struct {
+    int32_t top_k;
+    float temperature;
+} sjd_sampler;
+
+/* Initialisation of new window slots (Sec. 4.2).  mode 0: uniform over the sampling ids;
+ * mode 1: strategy (b), repeat the token one grid row above (uniform in the first grid row).
+ * eol_id >= 0 forces that id at the last position of every grid row.                          */
+typedef struct {
+    int32_t mode;
+    int32_t row_stride; /* image tokens per grid row, a row-end token included                 */
+    int32_t eol_id;
+} sjd_init;
+
+typedef struct {
+    int32_t steps;           /* window forwards (the paper's "decoding steps", Sec. 5.1)        */
+    int32_t accept_hist[65]; /* accept_hist[a] = number of steps that accepted a tokens         */
+    float ms_prefill;        /* host wall-clock of the prefill, milliseconds                    */
+    float ms_decode;         /* host wall-clock of the decoding loop (all steps), milliseconds  */
+} sjd_stats;
+
+/* ---- model and cache ---------------------------------------------------------------------- */
+/* host_weights: flat blob, element type per cfg->dtype (fp32, or bf16 bit patterns), tensors in
+ * the order E[vocab,d]; per layer g1[d] Wq Wk Wv Wo [d,d] g2[d] Wg Wu [F,d] Wd [d,F]; gf[d];
+ * Wlm[vocab,d]; every matrix row-major [out][in].  The blob is copied and repacked; the pointer
+ * is not retained.  nbytes must match the configuration exactly (else SJD_EINVAL).            */
+int sjd_init_model(const sjd_config *cfg, const void *host_weights, size_t nbytes, sjd_model **out);
+void sjd_free_model(sjd_model *m);
+
+int sjd_kv_create(const sjd_model *m, sjd_kv **out);
+void sjd_kv_free(sjd_kv *kv);
+int sjd_kv_reset(sjd_kv *kv);                     /* n = 0                                       */
+int sjd_kv_len(const sjd_kv *kv, int32_t *n);     /* synchronises the device, then reads n       */
+int sjd_kv_set_len(sjd_kv *kv, int32_t n);        /* roll the cache back/forward to n rows (resume) */
+
+/* ---- the path ----------------------------------------------------------------------------- */
+/* Pre-fill the prompt (Sec. 4.1 "after pre-filling the tokens of text prompts"): n_ids token ids
+ * (host) followed by n_embeds raw embedding rows (host fp32 [n_embeds x d_model]); either may be
+ * empty, not both.  Resets the cache, leaves n = n_ids + n_embeds, and writes
+ * q_last (dev [V_s]) = the sampling distribution of the first image token.                     */
+int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                int32_t n_embeds, const sjd_sampler *smp, const sjd_init *init, float *q_last, void *stream);
+
+/* First Jacobi window (Sec. 4.1 "starts with a sequence of initialized candidate tokens"):
+ * slot 0 is sampled from q_first (dev [V_s]) and carries it as its distribution; slots 1..L-1
+ * follow `init`.  Uses step counter 0.  draft dev [L], p_old dev [L x V_s].                   */
+int sjd_first_window(const sjd_model *m, const float *q_first, int32_t L, const sjd_init *init,
+                     uint64_t philox_seed, int32_t *draft, float *p_old, void *stream);
+
+/* One SJD iteration (Sec. 4.1 Steps 1-4) on the window that starts at cache length n:
+ *   draft   dev [L]        token ids of the window (Step 1)
+ *   p_old   dev [L x V_s]  the distribution each draft was drawn from; row 0 must be the exact
+ *                          conditional of draft[0] (it is never re-verified)
+ *   img_pos0               image index of draft[0] (decides row ends and the row above)
+ *   philox_seed, counter   random stream: Philox4x32-10 keyed by the seed, counter = (counter,
+ *                          window index); counter 0 belongs to sjd_first_window
+ * Outputs (dev): n_accepted[1] in [1, L]; new_draft[L] and p_new[L x V_s] already in the layout
+ * of the next window (unaccepted positions first, then newly initialised slots).  new_draft may
+ * alias draft and p_new may alias p_old.  The cache length advances by n_accepted and the ids of
+ * the accepted tokens are recorded in the cache.  SJD_ESEQ if n + L > max_seq.                 */
+int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const float *p_old, int32_t L,
+             const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0, uint64_t philox_seed,
+             uint64_t counter, int32_t *n_accepted, int32_t *new_draft, float *p_new, void *stream);
+
+/* Whole generation: prefill, first window, then iterations until N image tokens are fixed.
+ * out_tokens host [N]; stats may be NULL.  Runs on the default stream and synchronises.        */
+int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                 int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
+                 uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats);
+
+/* ---- pieces of the step, exported for parity tests and profiling --------------------------- */
+/* Step 2 alone: forward `L` tokens (dev ids) at positions n..n+L-1, write their K/V rows, return
+ * logits dev [L x V_s] fp32.  Does not advance n.                                              */
+int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream);
+
+/* Step 3 + Step 4 alone, from logits (row s belongs to window index s+1).  hist: dev ids of the
+ * image tokens fixed so far [img_pos0] (may be NULL when init->mode == 0 or img_pos0 == 0).
+ * V_s <= SJD_MAX_SAMP_VOCAB.                                                                   */
+int sjd_verify(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
+               int32_t samp_lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
+               const int32_t *hist, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
+               int32_t *new_draft, float *p_new, void *stream);
+
+/* Same from precomputed distributions q dev [(L+1) x V_s] (row 0 ignored, row L = the bonus
+ * distribution of the position just past the window).                                          */
+int sjd_verify_probs(const float *q, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
+                     int32_t samp_lo, const sjd_init *init, int32_t img_pos0, const int32_t *hist,
+                     uint64_t philox_seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
+                     float *p_new, void *stream);
+
+/* The sampling distribution of Sec. 3.1 for `rows` logits rows: top-K, temperature, softmax.
+ * forced: dev [rows] column index to make one-hot, or -1; may be NULL.  q dev [rows x V_s].     */
+int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sjd_sampler *smp, const int32_t *forced,
+             float *q, void *stream);
+
+/* C[M x N] (fp32, dev) = A[M x K] * W[N x K]^T with the kernel the model uses for its projections.
+ * dtype as in sjd_config; A and W are dev, row-major, element type per dtype; W is repacked into
+ * the library's streaming layout first (not timed separately).  For kernel-level parity tests.  */
+int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_t N, int32_t K, float *C,
+                  void *stream);
+
+const char *sjd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

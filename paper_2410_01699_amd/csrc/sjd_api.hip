@@ -1,0 +1,577 @@
+// C-ABI entry points and step orchestration of the SJD library (see include/sjd.h).
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sjd_internal.h"
+
+// ---- errors ---------------------------------------------------------------------------------
+static thread_local char g_hip_msg[256] = "no HIP error recorded";
+void sjd_set_hip_error(hipError_t e, const char *what)
+{
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+}
+
+extern "C" const char *sjd_strerror(int code)
+{
+    switch (code) {
+        case SJD_OK: return "ok";
+        case SJD_EINVAL: return "invalid argument";
+        case SJD_ENOMEM: return "out of memory";
+        case SJD_ESEQ: return "sequence would exceed max_seq";
+        case SJD_EHIP: return g_hip_msg;
+        default: return "unknown error code";
+    }
+}
+
+static size_t elt_size(int dtype) { return dtype == 0 ? 4 : 2; }
+
+static int dev_alloc(void **p, size_t bytes)
+{
+    hipError_t e = hipMalloc(p, bytes ? bytes : 16);
+    if (e == hipErrorOutOfMemory) { *p = nullptr; (void)hipGetLastError(); return SJD_ENOMEM; }
+    HIP_TRY(e);
+    HIP_TRY(hipMemset(*p, 0, bytes ? bytes : 16));
+    return SJD_OK;
+}
+
+// ---- model ----------------------------------------------------------------------------------
+static int check_config(const sjd_config *c)
+{
+    if (!c) return SJD_EINVAL;
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ffn < 1 || c->vocab_total < 1) return SJD_EINVAL;
+    if (c->d_model % c->n_heads) return SJD_EINVAL;
+    const int hd = c->d_model / c->n_heads;
+    if (hd != 16 && hd != 32 && hd != 64 && hd != 128) return SJD_EINVAL;
+    if (c->samp_lo < 0 || c->samp_hi > c->vocab_total || c->samp_lo >= c->samp_hi) return SJD_EINVAL;
+    if (c->samp_hi - c->samp_lo > SJD_MAX_SAMP_VOCAB) return SJD_EINVAL;
+    if (c->max_seq < 2) return SJD_EINVAL;
+    if (c->dtype != 0 && c->dtype != 1) return SJD_EINVAL;
+    if (c->dtype == 0 && (c->d_model % 4 || c->d_ffn % 4)) return SJD_EINVAL;
+    if (c->dtype == 1 && (c->d_model % 32 || c->d_ffn % 32 || (c->samp_hi - c->samp_lo) % 16)) return SJD_EINVAL;
+    if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return SJD_EINVAL;
+    return SJD_OK;
+}
+
+static size_t blob_elems(const sjd_config *c)
+{
+    const size_t d = c->d_model, f = c->d_ffn, v = c->vocab_total;
+    return v * d + (size_t)c->n_layers * (2 * d + 4 * d * d + 3 * d * f) + d + v * d;
+}
+
+extern "C" void sjd_free_model(sjd_model *m)
+{
+    if (!m) return;
+    if (m->weights) (void)hipFree(m->weights);
+    if (m->rope_cos) (void)hipFree(m->rope_cos);
+    if (m->rope_sin) (void)hipFree(m->rope_sin);
+    delete[] m->layers;
+    delete m;
+}
+
+extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, size_t nbytes, sjd_model **out)
+{
+    if (!out) return SJD_EINVAL;
+    *out = nullptr;
+    SJD_TRY(check_config(cfg));
+    if (!host_weights) return SJD_EINVAL;
+    const size_t es = elt_size(cfg->dtype);
+    const size_t total = blob_elems(cfg);
+    if (nbytes != total * es) return SJD_EINVAL;
+
+    sjd_model *m = new (std::nothrow) sjd_model();
+    if (!m) return SJD_ENOMEM;
+    m->cfg = *cfg;
+    m->hd = cfg->d_model / cfg->n_heads;
+    m->V_s = cfg->samp_hi - cfg->samp_lo;
+    m->layers = new (std::nothrow) SjdLayer[cfg->n_layers];
+    if (!m->layers) { sjd_free_model(m); return SJD_ENOMEM; }
+
+    int rc = dev_alloc(&m->weights, total * es);
+    if (rc != SJD_OK) { sjd_free_model(m); return rc; }
+    const size_t d = cfg->d_model, f = cfg->d_ffn, v = cfg->vocab_total;
+    const char *hb = (const char *)host_weights;
+    char *db = (char *)m->weights;
+
+    // staging buffer for the largest matrix that needs repacking (bf16 only)
+    void *stage = nullptr;
+    size_t stage_elems = 0;
+    if (cfg->dtype == 1) {
+        stage_elems = std::max<size_t>({3 * d * d, 2 * f * d, d * f, (size_t)m->V_s * d});
+        rc = dev_alloc(&stage, stage_elems * es);
+        if (rc != SJD_OK) { sjd_free_model(m); return rc; }
+    }
+    auto fail = [&](int code) { if (stage) (void)hipFree(stage); sjd_free_model(m); return code; };
+#define UP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { sjd_set_hip_error(e_, #expr); return fail(SJD_EHIP); } } while (0)
+
+    // copy a tensor as is; returns its device pointer
+    auto plain = [&](size_t off, size_t n) -> const void * {
+        if (hipMemcpy(db + off * es, hb + off * es, n * es, hipMemcpyHostToDevice) != hipSuccess) return nullptr;
+        return db + off * es;
+    };
+    // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
+    auto linear = [&](size_t off, int N, int K, SjdLinear *lin) -> int {
+        lin->N = N; lin->K = K; lin->split_k = 1; lin->tn = 1;
+        lin->w = db + off * es;
+        const size_t n = (size_t)N * K;
+        if (cfg->dtype == 0) {
+            HIP_TRY(hipMemcpy(db + off * es, hb + off * es, n * es, hipMemcpyHostToDevice));
+            return SJD_OK;
+        }
+        HIP_TRY(hipMemcpy(stage, hb + off * es, n * es, hipMemcpyHostToDevice));
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)stage, (bf16_t *)(db + off * es), N, K, 0));
+        HIP_TRY(hipDeviceSynchronize());
+        sjd_choose_split(lin);
+        return SJD_OK;
+    };
+
+    size_t off = 0;
+    m->E = plain(off, v * d); if (!m->E) return fail(SJD_EHIP);
+    off += v * d;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        SjdLayer *L = &m->layers[l];
+        L->g1 = plain(off, d); if (!L->g1) return fail(SJD_EHIP);
+        off += d;
+        rc = linear(off, (int)(3 * d), (int)d, &L->qkv); if (rc) return fail(rc);
+        off += 3 * d * d;
+        rc = linear(off, (int)d, (int)d, &L->o); if (rc) return fail(rc);
+        off += d * d;
+        L->g2 = plain(off, d); if (!L->g2) return fail(SJD_EHIP);
+        off += d;
+        rc = linear(off, (int)(2 * f), (int)d, &L->gu); if (rc) return fail(rc);
+        off += 2 * f * d;
+        rc = linear(off, (int)d, (int)f, &L->down); if (rc) return fail(rc);
+        off += d * f;
+    }
+    m->gf = plain(off, d); if (!m->gf) return fail(SJD_EHIP);
+    off += d;
+    rc = linear(off + (size_t)cfg->samp_lo * d, m->V_s, (int)d, &m->lm); if (rc) return fail(rc);
+    if (stage) { (void)hipFree(stage); stage = nullptr; }
+
+    // RoPE tables in fp64 on the host, rounded once to fp32: angle = pos * theta^(-2j/hd)
+    const int half = m->hd / 2;
+    std::vector<float> c((size_t)cfg->max_seq * half), s((size_t)cfg->max_seq * half);
+    for (int p = 0; p < cfg->max_seq; ++p)
+        for (int j = 0; j < half; ++j) {
+            double ang = (double)p * std::pow((double)cfg->rope_theta, -2.0 * j / m->hd);
+            c[(size_t)p * half + j] = (float)std::cos(ang);
+            s[(size_t)p * half + j] = (float)std::sin(ang);
+        }
+    rc = dev_alloc((void **)&m->rope_cos, c.size() * 4); if (rc) return fail(rc);
+    rc = dev_alloc((void **)&m->rope_sin, s.size() * 4); if (rc) return fail(rc);
+    UP_TRY(hipMemcpy(m->rope_cos, c.data(), c.size() * 4, hipMemcpyHostToDevice));
+    UP_TRY(hipMemcpy(m->rope_sin, s.data(), s.size() * 4, hipMemcpyHostToDevice));
+    UP_TRY(hipDeviceSynchronize());
+#undef UP_TRY
+    *out = m;
+    return SJD_OK;
+}
+
+// ---- cache + scratch ------------------------------------------------------------------------
+extern "C" void sjd_kv_free(sjd_kv *kv)
+{
+    if (!kv) return;
+    void *ptrs[] = {kv->k, kv->v, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
+                    kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
+                    kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
+    for (void *p : ptrs) if (p) (void)hipFree(p);
+    delete kv;
+}
+
+extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
+{
+    if (!m || !out) return SJD_EINVAL;
+    *out = nullptr;
+    sjd_kv *kv = new (std::nothrow) sjd_kv();
+    if (!kv) return SJD_ENOMEM;
+    memset(kv, 0, sizeof(*kv));
+    kv->m = m;
+    const sjd_config &c = m->cfg;
+    const size_t es = elt_size(c.dtype), d = c.d_model, F = c.d_ffn, V = m->V_s, R = SJD_ROWS_MAX;
+    size_t part = 0;
+    auto upd = [&](const SjdLinear &l) { part = std::max(part, (size_t)l.split_k * R * l.N); };
+    for (int l = 0; l < c.n_layers; ++l) { upd(m->layers[l].qkv); upd(m->layers[l].o); upd(m->layers[l].gu); upd(m->layers[l].down); }
+    upd(m->lm);
+    kv->part_elems = part;
+    kv->att_splits = sjd_attention_splits(m);
+    int rc = SJD_OK;
+#define A(ptr, bytes) if (rc == SJD_OK) rc = dev_alloc((void **)&(ptr), (bytes))
+    A(kv->k, (size_t)c.n_layers * c.max_seq * d * es);
+    A(kv->v, (size_t)c.n_layers * c.max_seq * d * es);
+    A(kv->tokens, (size_t)c.max_seq * 4);
+    A(kv->state, sizeof(SjdState));
+    A(kv->x, R * d * 4);
+    A(kv->h, R * d * es);
+    A(kv->part, part * 4);
+    A(kv->qact, R * d * es);
+    A(kv->att_part, sjd_attention_part_elems(m) * 4);
+    A(kv->att_out, R * d * es);
+    A(kv->ffn, R * F * es);
+    A(kv->logits, R * V * 4);
+    A(kv->q, (R + 1) * V * 4);
+    A(kv->tok_smp, (R + 1) * 4);
+    A(kv->tok_res, (R + 1) * 4);
+    A(kv->acc_flag, (R + 1) * 4);
+    A(kv->draft_snap, (R + 1) * 4);
+    A(kv->snap, 64);
+    A(kv->forced, (R + 1) * 4);
+    A(kv->ids_stage, R * 4);
+    A(kv->emb_stage, R * d * 4);
+    A(kv->g_draft, R * 4);
+    A(kv->g_p, R * V * 4);
+    A(kv->g_nacc, 16);
+    A(kv->q_first, V * 4);
+#undef A
+    if (rc != SJD_OK) { sjd_kv_free(kv); return rc; }
+    *out = kv;
+    return SJD_OK;
+}
+
+static int state_write(sjd_kv *kv, const SjdState &st, hipStream_t s)
+{
+    // small synchronous-with-respect-to-host copy (source is on the stack)
+    HIP_TRY(hipMemcpyAsync(kv->state, &st, sizeof(SjdState), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return SJD_OK;
+}
+static int state_read(const sjd_kv *kv, SjdState *st)
+{
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(st, kv->state, sizeof(SjdState), hipMemcpyDeviceToHost));
+    return SJD_OK;
+}
+
+extern "C" int sjd_kv_reset(sjd_kv *kv)
+{
+    if (!kv) return SJD_EINVAL;
+    HIP_TRY(hipDeviceSynchronize());
+    SjdState st;
+    memset(&st, 0, sizeof(st));
+    return state_write(kv, st, 0);
+}
+
+extern "C" int sjd_kv_len(const sjd_kv *kv, int32_t *n)
+{
+    if (!kv || !n) return SJD_EINVAL;
+    SjdState st;
+    SJD_TRY(state_read(kv, &st));
+    *n = st.n;
+    return SJD_OK;
+}
+
+extern "C" int sjd_kv_set_len(sjd_kv *kv, int32_t n)
+{
+    if (!kv || n < 0 || n > kv->m->cfg.max_seq) return SJD_EINVAL;
+    SjdState st;
+    SJD_TRY(state_read(kv, &st));
+    st.n = n;
+    st.done = 0;
+    return state_write(kv, st, 0);
+}
+
+// ---- the window forward (Step 2) ------------------------------------------------------------
+// rows = rows computed (<= 32), rows_valid = rows whose K/V are written.  Inputs already in kv->x.
+static int forward_rows(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+{
+    const int dt = m->cfg.dtype;
+    const SjdState *st = kv->state;
+    const SjdLinear *prev = nullptr;   // GEMM whose partial sums still have to be added to x
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+        const SjdLayer &L = m->layers[l];
+        SJD_TRY(sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? prev->split_k : 0,
+                                   prev ? sjd_part_stride(prev, rows) : 0, L.g1, rows, kv->h, st, s));
+        SJD_TRY(sjd_launch_gemm(dt, &L.qkv, kv->h, rows, kv->part, st, s));
+        SJD_TRY(sjd_launch_rope_kv(m, kv, l, kv->part, L.qkv.split_k, sjd_part_stride(&L.qkv, rows), rows, rows_valid, s));
+        SJD_TRY(sjd_launch_attention(m, kv, l, rows, s));
+        SJD_TRY(sjd_launch_gemm(dt, &L.o, kv->att_out, rows, kv->part, st, s));
+        SJD_TRY(sjd_launch_rmsnorm(m, kv->x, kv->part, L.o.split_k, sjd_part_stride(&L.o, rows), L.g2, rows, kv->h, st, s));
+        SJD_TRY(sjd_launch_gemm(dt, &L.gu, kv->h, rows, kv->part, st, s));
+        SJD_TRY(sjd_launch_silu_mul(m, kv->part, L.gu.split_k, sjd_part_stride(&L.gu, rows), rows, kv->ffn, st, s));
+        SJD_TRY(sjd_launch_gemm(dt, &L.down, kv->ffn, rows, kv->part, st, s));
+        prev = &L.down;
+    }
+    SJD_TRY(sjd_launch_rmsnorm(m, kv->x, kv->part, prev->split_k, sjd_part_stride(prev, rows), m->gf, rows, kv->h, st, s));
+    SJD_TRY(sjd_launch_gemm(dt, &m->lm, kv->h, rows, kv->part, st, s));
+    SJD_TRY(sjd_launch_reduce_rows(kv->part, m->lm.split_k, sjd_part_stride(&m->lm, rows), rows, m->V_s, logits, st, s));
+    return SJD_OK;
+}
+
+static int check_room(sjd_kv *kv, int32_t L, int32_t *n_out)
+{
+    SjdState st;
+    SJD_TRY(state_read(kv, &st));
+    if (st.n + L > kv->m->cfg.max_seq) return SJD_ESEQ;
+    if (n_out) *n_out = st.n;
+    return SJD_OK;
+}
+
+__global__ void clear_done_kernel(SjdState *st) { st->done = 0; }
+
+extern "C" int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream)
+{
+    if (!m || !kv || kv->m != m || !tokens || !logits || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
+    SJD_TRY(check_room(kv, L, nullptr));
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(clear_done_kernel, dim3(1), dim3(1), 0, s, kv->state);
+    HIP_TRY(hipGetLastError());
+    SJD_TRY(sjd_launch_embed(m, tokens, nullptr, L, kv->x, kv->state, s));
+    return forward_rows(m, kv, L, L, logits, s);
+}
+
+__global__ void advance_n_kernel(SjdState *st, int32_t *tokens, const int32_t *ids, int rows)
+{
+    const int n = st->n;
+    for (int r = threadIdx.x; r < rows; r += blockDim.x) tokens[n + r] = ids ? ids[r] : -1;
+    __syncthreads();
+    if (threadIdx.x == 0) st->n = n + rows;
+}
+
+__global__ void forced_first_kernel(int32_t *forced, sjd_init init, int lo)
+{
+    forced[0] = (init.eol_id >= 0 && init.row_stride == 1) ? init.eol_id - lo : -1;
+}
+
+extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                           int32_t n_embeds, const sjd_sampler *smp, const sjd_init *init, float *q_last, void *stream)
+{
+    if (!m || !kv || kv->m != m || !smp || !q_last || n_ids < 0 || n_embeds < 0 || n_ids + n_embeds < 1) return SJD_EINVAL;
+    if ((n_ids && !ids) || (n_embeds && !embeds)) return SJD_EINVAL;
+    if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
+    const int P = n_ids + n_embeds;
+    if (P + 1 > m->cfg.max_seq) return SJD_ESEQ;
+    for (int i = 0; i < n_ids; ++i) if (ids[i] < 0 || ids[i] >= m->cfg.vocab_total) return SJD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    SJD_TRY(sjd_kv_reset(kv));
+    const int d = m->cfg.d_model;
+    int rows_last = 0;
+    for (int p0 = 0; p0 < P; p0 += SJD_ROWS_MAX) {
+        const int rows = std::min(SJD_ROWS_MAX, P - p0);
+        const int id_rows = std::max(0, std::min(rows, n_ids - p0));   // leading rows that are ids
+        // a chunk is either all ids or all embedding rows; split mixed chunks
+        int done_rows = 0;
+        while (done_rows < rows) {
+            int cnt; bool is_id = (p0 + done_rows) < n_ids;
+            cnt = is_id ? (id_rows - done_rows) : (rows - done_rows);
+            if (is_id) {
+                HIP_TRY(hipMemcpyAsync(kv->ids_stage, ids + p0 + done_rows, (size_t)cnt * 4, hipMemcpyHostToDevice, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                SJD_TRY(sjd_launch_embed(m, kv->ids_stage, nullptr, cnt, kv->x, kv->state, s));
+            } else {
+                HIP_TRY(hipMemcpyAsync(kv->emb_stage, embeds + (size_t)(p0 + done_rows - n_ids) * d, (size_t)cnt * d * 4,
+                                       hipMemcpyHostToDevice, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                SJD_TRY(sjd_launch_embed(m, nullptr, kv->emb_stage, cnt, kv->x, kv->state, s));
+            }
+            SJD_TRY(forward_rows(m, kv, cnt, cnt, kv->logits, s));
+            hipLaunchKernelGGL(advance_n_kernel, dim3(1), dim3(64), 0, s, kv->state, kv->tokens,
+                               is_id ? kv->ids_stage : (const int32_t *)nullptr, cnt);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipStreamSynchronize(s));   // staging buffers are reused by the next chunk
+            done_rows += cnt;
+            rows_last = cnt;
+        }
+    }
+    // distribution of the first image token from the last prompt row
+    sjd_init ini = init ? *init : sjd_init{0, 0, -1};
+    hipLaunchKernelGGL(forced_first_kernel, dim3(1), dim3(1), 0, s, kv->forced, ini, m->cfg.samp_lo);
+    HIP_TRY(hipGetLastError());
+    return sjd_launch_dist(kv->logits + (size_t)(rows_last - 1) * m->V_s, 1, m->V_s, smp, kv->forced, q_last, s);
+}
+
+extern "C" int sjd_first_window(const sjd_model *m, const float *q_first, int32_t L, const sjd_init *init,
+                                uint64_t philox_seed, int32_t *draft, float *p_old, void *stream)
+{
+    if (!m || !q_first || !init || !draft || !p_old || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    if (init->mode < 0 || init->mode > 1 || (init->mode == 1 && init->row_stride < 1)) return SJD_EINVAL;
+    return sjd_launch_first_window(q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, draft, p_old, (hipStream_t)stream);
+}
+
+static int check_sampling(const sjd_sampler *smp, const sjd_init *init, int lo, int hi)
+{
+    if (!smp || !init) return SJD_EINVAL;
+    if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
+    if (init->mode < 0 || init->mode > 1) return SJD_EINVAL;
+    if (init->mode == 1 && init->row_stride < 1) return SJD_EINVAL;
+    if (init->eol_id >= 0 && (init->eol_id < lo || init->eol_id >= hi || init->row_stride < 1)) return SJD_EINVAL;
+    return SJD_OK;
+}
+
+__global__ void set_step_kernel(SjdState *st, int img_pos0, uint64_t counter, int L)
+{
+    st->img_pos0 = img_pos0; st->counter = counter; st->L_eff = L; st->n_image = 0; st->done = 0;
+}
+
+// forward + verification of one window, everything stream-ordered, state device-resident
+static int enqueue_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const float *p_old, int32_t L,
+                        const sjd_sampler *smp, const sjd_init *init, uint64_t seed, int32_t *n_accepted,
+                        int32_t *new_draft, float *p_new, hipStream_t s)
+{
+    SJD_TRY(sjd_launch_embed(m, draft, nullptr, L, kv->x, kv->state, s));
+    SJD_TRY(forward_rows(m, kv, L, L, kv->logits, s));
+    SjdVerifyArgs v;
+    memset(&v, 0, sizeof(v));
+    v.logits = kv->logits; v.p_old = p_old; v.draft = draft; v.L = L; v.V = m->V_s; v.lo = m->cfg.samp_lo;
+    v.smp = *smp; v.init = *init; v.seed = seed; v.state = kv->state; v.kv_tokens = kv->tokens;
+    v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new;
+    v.q = kv->q; v.tok_smp = kv->tok_smp; v.tok_res = kv->tok_res; v.acc_flag = kv->acc_flag;
+    v.draft_snap = kv->draft_snap; v.snap = kv->snap;
+    return sjd_launch_verify(&v, s);
+}
+
+extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const float *p_old, int32_t L,
+                        const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0, uint64_t philox_seed,
+                        uint64_t counter, int32_t *n_accepted, int32_t *new_draft, float *p_new, void *stream)
+{
+    if (!m || !kv || kv->m != m || !draft || !p_old || !n_accepted || !new_draft || !p_new) return SJD_EINVAL;
+    if (L < 1 || L > SJD_MAX_WINDOW || img_pos0 < 0) return SJD_EINVAL;
+    SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
+    SJD_TRY(check_room(kv, L, nullptr));
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(set_step_kernel, dim3(1), dim3(1), 0, s, kv->state, img_pos0, counter, L);
+    HIP_TRY(hipGetLastError());
+    return enqueue_step(m, kv, draft, p_old, L, smp, init, philox_seed, n_accepted, new_draft, p_new, s);
+}
+
+__global__ void begin_generate_kernel(SjdState *st, int N, int L)
+{
+    st->img_pos0 = 0; st->counter = 1; st->n_image = N; st->L_eff = L < N ? L : N; st->done = (N <= 1);
+    st->steps = 0;
+    for (int i = 0; i < 65; ++i) st->accept_hist[i] = 0;
+}
+
+extern "C" int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                            int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
+                            uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats)
+{
+    if (!m || !kv || kv->m != m || !out_tokens || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
+    const int P = n_ids + n_embeds;
+    if (P + N + L > m->cfg.max_seq) return SJD_ESEQ;
+    hipStream_t s = 0;
+    auto t0 = std::chrono::steady_clock::now();
+    SJD_TRY(sjd_prefill(m, kv, ids, n_ids, embeds, n_embeds, smp, init, kv->q_first, s));
+    SJD_TRY(sjd_launch_first_window(kv->q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, kv->g_draft, kv->g_p, s));
+    hipLaunchKernelGGL(begin_generate_kernel, dim3(1), dim3(1), 0, s, kv->state, N, L);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(s));
+    auto t1 = std::chrono::steady_clock::now();
+
+    // The loop: steps are enqueued in batches; kernels of a step that starts after the generation
+    // has finished return at once (state->done), so over-enqueueing is harmless.
+    const int batch = 8;
+    SjdState st;
+    int enq = 0;
+    for (;;) {
+        for (int b = 0; b < batch; ++b, ++enq)
+            SJD_TRY(enqueue_step(m, kv, kv->g_draft, kv->g_p, L, smp, init, philox_seed, kv->g_nacc, kv->g_draft, kv->g_p, s));
+        SJD_TRY(state_read(kv, &st));
+        if (st.done) break;
+        if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every step fixes at least one token
+    }
+    auto t2 = std::chrono::steady_clock::now();
+    // image tokens = cache ids P .. P+N-1; when N-1 were fixed the pending exact slot 0 is the last
+    std::vector<int32_t> tmp((size_t)N);
+    const int fixed = st.img_pos0 < N ? st.img_pos0 : N;
+    HIP_TRY(hipMemcpy(tmp.data(), kv->tokens + P, (size_t)fixed * 4, hipMemcpyDeviceToHost));
+    if (fixed < N) HIP_TRY(hipMemcpy(tmp.data() + fixed, kv->g_draft, 4, hipMemcpyDeviceToHost));
+    memcpy(out_tokens, tmp.data(), (size_t)N * 4);
+    if (stats) {
+        stats->steps = st.steps;
+        for (int i = 0; i < 65; ++i) stats->accept_hist[i] = st.accept_hist[i];
+        stats->ms_prefill = std::chrono::duration<float, std::milli>(t1 - t0).count();
+        stats->ms_decode = std::chrono::duration<float, std::milli>(t2 - t1).count();
+    }
+    return SJD_OK;
+}
+
+// ---- hooks ----------------------------------------------------------------------------------
+struct Scratch {
+    float *q = nullptr; int32_t *ints = nullptr; void *snap = nullptr;
+    ~Scratch() { if (q) (void)hipFree(q); if (ints) (void)hipFree(ints); if (snap) (void)hipFree(snap); }
+};
+
+static int verify_common(const float *logits, const float *q_in, const float *p_old, const int32_t *draft, int32_t L,
+                         int32_t V, int32_t lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
+                         const int32_t *hist, uint64_t seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
+                         float *p_new, hipStream_t s)
+{
+    if (!p_old || !draft || !n_accepted || !new_draft || !p_new || !init) return SJD_EINVAL;
+    if (L < 1 || L > SJD_MAX_WINDOW || V < 1 || V > SJD_MAX_SAMP_VOCAB || img_pos0 < 0) return SJD_EINVAL;
+    sjd_sampler sm = smp ? *smp : sjd_sampler{1, 1.0f};
+    SJD_TRY(check_sampling(&sm, init, lo, lo + V));
+    if (init->mode == 1 && img_pos0 > 0 && !hist) return SJD_EINVAL;
+    Scratch sc;
+    SJD_TRY(dev_alloc((void **)&sc.q, (size_t)(L + 1) * V * 4));
+    SJD_TRY(dev_alloc((void **)&sc.ints, (size_t)(L + 1) * 4 * 4));
+    SJD_TRY(dev_alloc(&sc.snap, 64));
+    SjdVerifyArgs v;
+    memset(&v, 0, sizeof(v));
+    v.logits = logits; v.q_in = q_in; v.p_old = p_old; v.draft = draft; v.L = L; v.V = V; v.lo = lo;
+    v.smp = sm; v.init = *init; v.hist = hist; v.seed = seed; v.img_pos0 = img_pos0; v.counter = counter;
+    v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new; v.q = sc.q;
+    v.tok_smp = sc.ints; v.tok_res = sc.ints + (L + 1); v.acc_flag = sc.ints + 2 * (L + 1);
+    v.draft_snap = sc.ints + 3 * (L + 1); v.snap = sc.snap;
+    SJD_TRY(sjd_launch_verify(&v, s));
+    HIP_TRY(hipStreamSynchronize(s));   // scratch is freed on return
+    return SJD_OK;
+}
+
+extern "C" int sjd_verify(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
+                          int32_t samp_lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
+                          const int32_t *hist, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
+                          int32_t *new_draft, float *p_new, void *stream)
+{
+    if (!logits || !smp) return SJD_EINVAL;
+    return verify_common(logits, nullptr, p_old, draft, L, V_s, samp_lo, smp, init, img_pos0, hist, philox_seed, counter,
+                         n_accepted, new_draft, p_new, (hipStream_t)stream);
+}
+
+extern "C" int sjd_verify_probs(const float *q, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
+                                int32_t samp_lo, const sjd_init *init, int32_t img_pos0, const int32_t *hist,
+                                uint64_t philox_seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
+                                float *p_new, void *stream)
+{
+    if (!q) return SJD_EINVAL;
+    return verify_common(nullptr, q, p_old, draft, L, V_s, samp_lo, nullptr, init, img_pos0, hist, philox_seed, counter,
+                         n_accepted, new_draft, p_new, (hipStream_t)stream);
+}
+
+extern "C" int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sjd_sampler *smp, const int32_t *forced,
+                        float *q, void *stream)
+{
+    if (!logits || !smp || !q || rows < 1) return SJD_EINVAL;
+    if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
+    return sjd_launch_dist(logits, rows, V_s, smp, forced, q, (hipStream_t)stream);
+}
+
+extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_t N, int32_t K, float *C,
+                             void *stream)
+{
+    if (!A || !W || !C || M < 1 || M > SJD_ROWS_MAX || N < 1 || K < 1) return SJD_EINVAL;
+    if (dtype != 0 && dtype != 1) return SJD_EINVAL;
+    if (dtype == 1 && (N % 16 || K % 32)) return SJD_EINVAL;
+    if (dtype == 0 && K % 4) return SJD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t es = elt_size(dtype);
+    void *Ap = nullptr, *Wp = nullptr; float *part = nullptr;
+    struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &part};
+    SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * es));
+    HIP_TRY(hipMemcpyAsync(Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
+    SjdLinear lin;
+    lin.N = N; lin.K = K; lin.split_k = 1; lin.tn = 1; lin.w = W;
+    if (dtype == 1) {
+        SJD_TRY(dev_alloc(&Wp, (size_t)N * K * es));
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)Wp, N, K, s));
+        lin.w = Wp;
+        sjd_choose_split(&lin);
+    }
+    SJD_TRY(dev_alloc((void **)&part, (size_t)lin.split_k * SJD_ROWS_MAX * N * 4));
+    SJD_TRY(sjd_launch_gemm(dtype, &lin, Ap, M, part, nullptr, s));
+    SJD_TRY(sjd_launch_reduce_rows(part, lin.split_k, dtype == 1 ? sjd_part_stride(&lin, M) : 0, M, N, C, nullptr, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return SJD_OK;
+}

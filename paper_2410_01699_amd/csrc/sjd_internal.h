@@ -1,0 +1,159 @@
+// Internal declarations of the SJD HIP library (gfx950 only).  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sjd.h"
+
+#define SJD_ROWS_MAX 32  // rows (window slots or prefill chunk) one forward pass handles
+
+typedef unsigned short bf16_t;  // raw bf16 bit pattern
+
+// ---- error plumbing ------------------------------------------------------------------------
+void sjd_set_hip_error(hipError_t e, const char *what);
+#define HIP_TRY(expr)                              \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) {                    \
+            sjd_set_hip_error(e_, #expr);          \
+            return SJD_EHIP;                       \
+        }                                          \
+    } while (0)
+#define SJD_TRY(expr)                \
+    do {                             \
+        int rc_ = (expr);            \
+        if (rc_ != SJD_OK) return rc_; \
+    } while (0)
+
+// ---- device helpers shared by kernels ------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);                                         // round to nearest even
+    return (bf16_t)(u >> 16);
+}
+
+// ---- one linear layer's weights ------------------------------------------------------------
+// fp32 models keep W as given ([N][K] row-major).  bf16 models hold W in MFMA streaming order:
+// tiles of 16 output features x 32 input features, tile (nt, kt) at ((nt * K/32) + kt) * 512
+// elements, inside a tile lane l (0..63) owns the 8 consecutive elements
+// W[nt*16 + l%16][kt*32 + (l/16)*8 .. +8].
+struct SjdLinear {
+    const void *w;
+    int32_t N, K;
+    int32_t split_k;  // k-slices whose partial sums the consumer adds up (bf16 path)
+    int32_t tn;       // 16-wide output tiles per wave (bf16 path)
+};
+
+struct SjdLayer {
+    const void *g1, *g2;
+    SjdLinear qkv, o, gu, down;  // qkv: rows [Wq; Wk; Wv]; gu: rows [Wg; Wu]
+};
+
+struct sjd_model {
+    sjd_config cfg;
+    int32_t hd, V_s;
+    void *weights;        // one device allocation holding everything below
+    const void *E;        // embedding table [vocab][d], element type per dtype, row-major
+    const void *gf;
+    SjdLinear lm;         // rows samp_lo..samp_hi of the LM head
+    SjdLayer *layers;     // host array
+    float *rope_cos, *rope_sin;  // [max_seq][hd/2]
+};
+
+// Device-resident decoding state: everything that changes from step to step, so that a step can
+// be enqueued (or replayed from a graph) without the host knowing the outcome of the last one.
+struct SjdState {
+    int32_t n;          // cache length (prompt + accepted tokens)
+    int32_t img_pos0;   // image index of window slot 0
+    int32_t L_eff;      // slots of the window in use this step
+    int32_t n_snap;     // n at the start of the step (stable while the step runs)
+    uint64_t counter;   // Philox step counter
+    int32_t n_image;    // N, image tokens to produce (generate loop; 0 = unbounded single steps)
+    int32_t done;       // generation finished: later steps are no-ops
+    int32_t steps;      // window forwards executed
+    int32_t accept_hist[65];
+};
+
+struct sjd_kv {
+    const sjd_model *m;
+    void *k, *v;          // K: [layer][pos][d]; V: bf16 models [layer][head][hd][max_seq], fp32 [layer][pos][d]
+    int32_t *tokens;      // [max_seq] ids of cached positions (-1 for raw-embedding rows)
+    SjdState *state;      // device
+    // ---- scratch for one forward over <= SJD_ROWS_MAX rows ----
+    float *x;             // [rows][d] residual stream
+    void *h;              // [rows][d] normalised activations (GEMM input)
+    float *part;          // split-K partial outputs of the current GEMM
+    size_t part_elems;
+    void *qact;           // [rows][d] rotated queries
+    float *att_part;      // attention partials per (head, split): [rows][hd] + m,l
+    int32_t att_splits;
+    void *att_out;        // [rows][d]
+    void *ffn;            // [rows][F]
+    float *logits;        // [rows][V_s]
+    // ---- scratch for verification ----
+    float *q;             // [(rows+1)][V_s]
+    int32_t *tok_smp, *tok_res, *acc_flag, *draft_snap;  // [rows+1] each
+    void *snap;
+    int32_t *forced;      // [rows+1]
+    int32_t *ids_stage;   // [rows] device copy of prompt ids chunk
+    float *emb_stage;     // [rows][d]
+    // generate loop buffers
+    int32_t *g_draft;     // [rows]
+    float *g_p;           // [rows][V_s]
+    int32_t *g_nacc;      // [1]
+    float *q_first;       // [V_s]
+    int32_t n_upper;      // host-side upper bound of the device-resident n
+};
+
+// ---- kernel launchers (each returns SJD_OK or an SJD_E* code) --------------------------------
+// `st` (device) lets a kernel skip its work once a generation has finished; NULL = always run.
+int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, float *x,
+                     const SjdState *st, hipStream_t s);
+int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
+                       const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
+int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const float *part, int32_t n_part,
+                       size_t part_stride, int32_t rows, int32_t rows_valid, hipStream_t s);
+int sjd_launch_silu_mul(const sjd_model *m, const float *part, int32_t n_part, size_t part_stride, int32_t rows,
+                        void *ffn, const SjdState *st, hipStream_t s);
+int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride, int32_t rows, int32_t cols,
+                           float *out, const SjdState *st, hipStream_t s);
+int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_t rows, float *part,
+                    const SjdState *st, hipStream_t s);
+size_t sjd_part_stride(const SjdLinear *lin, int32_t rows);
+int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, hipStream_t s);
+void sjd_choose_split(SjdLinear *lin);
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s);
+int32_t sjd_attention_splits(const sjd_model *m);
+size_t sjd_attention_part_elems(const sjd_model *m);
+// sampling / verification
+struct SjdVerifyArgs {
+    const float *logits;     // [L][V] or NULL when q rows are given
+    const float *q_in;       // [(L+1)][V] precomputed distributions or NULL
+    const float *p_old;      // [L][V]
+    const int32_t *draft;    // [L]
+    int32_t L, V, lo;
+    sjd_sampler smp;
+    sjd_init init;
+    const int32_t *hist;     // image tokens fixed so far (index = image position) or NULL
+    uint64_t seed;
+    // state: when `state` != NULL, img_pos0 / counter / L_eff come from it and it is advanced
+    SjdState *state;
+    int32_t *kv_tokens;      // record accepted ids at cache positions (with state) or NULL
+    int32_t img_pos0;
+    uint64_t counter;
+    int32_t *n_accepted;     // [1]
+    int32_t *new_draft;      // [L]
+    float *p_new;            // [L][V]
+    // scratch
+    float *q;                // [(L+1)][V]
+    int32_t *tok_smp, *tok_res, *acc_flag, *draft_snap;
+    void *snap;              // 32 bytes: per-step scalars frozen for the second kernel
+};
+int sjd_launch_verify(const SjdVerifyArgs *a, hipStream_t s);
+int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_sampler *smp, const int32_t *forced,
+                    float *q, hipStream_t s);
+int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t lo, const sjd_init *init,
+                            uint64_t seed, int32_t *draft, float *p_old, hipStream_t s);

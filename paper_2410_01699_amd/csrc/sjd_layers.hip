@@ -1,0 +1,189 @@
+// Element-wise pieces of the window forward (paper Sec. 4.1 Step 2; the decoder itself is the
+// Llama-style stack the workloads name): embedding gather, RMSNorm fused with the residual add
+// and the split-K reduction of the producing GEMM, RoPE + KV-cache write, SiLU(gate)*up.
+// All of them are bandwidth-trivial (rows <= 32); they exist to feed the GEMMs the operand
+// layout they stream.
+#include "sjd_internal.h"
+
+template <typename T> struct Act;
+template <> struct Act<float> {
+    __device__ static float load(const float *p, size_t i) { return p[i]; }
+    __device__ static void store(float *p, size_t i, float v) { p[i] = v; }
+};
+template <> struct Act<bf16_t> {
+    __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+    __device__ static void store(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+};
+
+// x[r][:] = E[ids[r]][:]  (or the given raw embedding row)
+template <typename T>
+__global__ void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, float *x,
+                             const SjdState *st)
+{
+    if (st->done) return;
+    const int r = blockIdx.x;
+    for (int j = threadIdx.x; j < d; j += blockDim.x)
+        x[(size_t)r * d + j] = emb_rows ? emb_rows[(size_t)r * d + j] : Act<T>::load(E, (size_t)ids[r] * d + j);
+}
+
+// x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *part, int n_part, size_t part_stride,
+                                                      const T *gain, int d, float eps, T *h, const SjdState *st)
+{
+    if (st->done) return;
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    float *xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int j = threadIdx.x; j < d; j += 256) {
+        float v = xr[j];
+        for (int p = 0; p < n_part; ++p) v += part[(size_t)p * part_stride + (size_t)r * d + j];
+        if (n_part) xr[j] = v;
+        ss += v * v;
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    const float inv = rsqrtf(ss / (float)d + eps);
+    for (int j = threadIdx.x; j < d; j += 256) Act<T>::store(h, (size_t)r * d + j, xr[j] * inv * Act<T>::load(gain, j));
+}
+
+// qkv[r][0:3d] = sum_p part[p][r][:];  rotate q and k (pairs j, j+hd/2) at position n+r;
+// q -> qact[r][d];  k -> K cache row n+r;  v -> V cache (bf16: transposed [head][hd][pos]).
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kv_kernel(const float *part, int n_part, size_t part_stride, int d, int hd,
+                                                      int max_seq, const float *cosT, const float *sinT, T *qact,
+                                                      T *kc, T *vc, int v_transposed, int rows_valid,
+                                                      const SjdState *st)
+{
+    if (st->done) return;
+    const int r = blockIdx.x;
+    const int pos = st->n + r;
+    const int half = hd / 2;
+    const size_t row = (size_t)r * 3 * d;
+    for (int e = threadIdx.x; e < d / 2; e += 256) {
+        const int head = e / half, j = e % half;
+        const int c0 = head * hd + j, c1 = c0 + half;
+        float q0 = 0, q1 = 0, k0 = 0, k1 = 0, v0 = 0, v1 = 0;
+        for (int p = 0; p < n_part; ++p) {
+            const float *src = part + (size_t)p * part_stride + row;
+            q0 += src[c0]; q1 += src[c1];
+            k0 += src[d + c0]; k1 += src[d + c1];
+            v0 += src[2 * d + c0]; v1 += src[2 * d + c1];
+        }
+        const float c = cosT[(size_t)pos * half + j], s = sinT[(size_t)pos * half + j];
+        Act<T>::store(qact, (size_t)r * d + c0, q0 * c - q1 * s);
+        Act<T>::store(qact, (size_t)r * d + c1, q1 * c + q0 * s);
+        if (r < rows_valid) {
+            Act<T>::store(kc, (size_t)pos * d + c0, k0 * c - k1 * s);
+            Act<T>::store(kc, (size_t)pos * d + c1, k1 * c + k0 * s);
+            if (v_transposed) {
+                Act<T>::store(vc, (size_t)c0 * max_seq + pos, v0);
+                Act<T>::store(vc, (size_t)c1 * max_seq + pos, v1);
+            } else {
+                Act<T>::store(vc, (size_t)pos * d + c0, v0);
+                Act<T>::store(vc, (size_t)pos * d + c1, v1);
+            }
+        }
+    }
+}
+
+// ffn[r][f] = SiLU(g) * u with g = sum_p part[p][r][f], u = sum_p part[p][r][F + f]
+template <typename T>
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float *part, int n_part, size_t part_stride, int F, T *ffn,
+                                                       const SjdState *st)
+{
+    if (st->done) return;
+    const int r = blockIdx.y;
+    const int f = blockIdx.x * 256 + threadIdx.x;
+    if (f >= F) return;
+    float g = 0, u = 0;
+    for (int p = 0; p < n_part; ++p) {
+        const float *src = part + (size_t)p * part_stride + (size_t)r * 2 * F;
+        g += src[f]; u += src[F + f];
+    }
+    Act<T>::store(ffn, (size_t)r * F + f, g / (1.0f + __expf(-g)) * u);
+}
+
+// out[r][c] = sum_p part[p][r][c]
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const float *part, int n_part, size_t part_stride, int cols,
+                                                          float *out, const SjdState *st)
+{
+    if (st && st->done) return;
+    const int r = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols) return;
+    float v = 0;
+    for (int p = 0; p < n_part; ++p) v += part[(size_t)p * part_stride + (size_t)r * cols + c];
+    out[(size_t)r * cols + c] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+#define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
+
+int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, float *x,
+                     const SjdState *st, hipStream_t s)
+{
+    const int d = m->cfg.d_model;
+    if (m->cfg.dtype == 0)
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, x, st);
+    else
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, x, st);
+    LAUNCH_CHECK();
+    return SJD_OK;
+}
+
+int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
+                       const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s)
+{
+    const int d = m->cfg.d_model;
+    if (m->cfg.dtype == 0)
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
+                           (const float *)gain, d, m->cfg.rms_eps, (float *)h, st);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
+                           (const bf16_t *)gain, d, m->cfg.rms_eps, (bf16_t *)h, st);
+    LAUNCH_CHECK();
+    return SJD_OK;
+}
+
+int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const float *part, int32_t n_part,
+                       size_t part_stride, int32_t rows, int32_t rows_valid, hipStream_t s)
+{
+    const int d = m->cfg.d_model, ms = m->cfg.max_seq;
+    const size_t per_layer = (size_t)ms * d;
+    if (m->cfg.dtype == 0)
+        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
+                           m->rope_cos, m->rope_sin, (float *)kv->qact, (float *)kv->k + layer * per_layer,
+                           (float *)kv->v + layer * per_layer, 0, rows_valid, kv->state);
+    else
+        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
+                           m->rope_cos, m->rope_sin, (bf16_t *)kv->qact, (bf16_t *)kv->k + layer * per_layer,
+                           (bf16_t *)kv->v + layer * per_layer, 1, rows_valid, kv->state);
+    LAUNCH_CHECK();
+    return SJD_OK;
+}
+
+int sjd_launch_silu_mul(const sjd_model *m, const float *part, int32_t n_part, size_t part_stride, int32_t rows,
+                        void *ffn, const SjdState *st, hipStream_t s)
+{
+    const int F = m->cfg.d_ffn;
+    dim3 grid((F + 255) / 256, rows);
+    if (m->cfg.dtype == 0)
+        hipLaunchKernelGGL(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, st);
+    else
+        hipLaunchKernelGGL(silu_mul_kernel<bf16_t>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (bf16_t *)ffn, st);
+    LAUNCH_CHECK();
+    return SJD_OK;
+}
+
+int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride, int32_t rows, int32_t cols,
+                           float *out, const SjdState *st, hipStream_t s)
+{
+    dim3 grid((cols + 255) / 256, rows);
+    hipLaunchKernelGGL(reduce_rows_kernel, grid, dim3(256), 0, s, part, n_part, part_stride, cols, out, st);
+    LAUNCH_CHECK();
+    return SJD_OK;
+}

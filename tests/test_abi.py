@@ -1,0 +1,41 @@
+"""The C-ABI library loads and exports every function include/sjd.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "sjd.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(sjd_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_header_declares_the_path():
+    names = _declared()
+    for must in ("sjd_init_model", "sjd_prefill", "sjd_step", "sjd_generate"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2410_01699_amd import binding
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in _declared():
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == _declared()
+
+
+def test_error_strings_and_argument_checks_without_gpu():
+    from paper_2410_01699_amd import binding
+    assert binding.sjd_strerror(0) == "ok"
+    assert "invalid" in binding.sjd_strerror(binding.SJD_EINVAL)
+    # null / malformed arguments are rejected before any HIP call
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    lib.sjd_init_model.restype = ctypes.c_int
+    out = ctypes.c_void_p()
+    assert lib.sjd_init_model(None, None, ctypes.c_size_t(0), ctypes.byref(out)) == binding.SJD_EINVAL
+    cfg = binding.sjd_config(2, 130, 4, 512, 1024, 0, 1024, 64, 0, 10000.0, 1e-5)     # d % heads != 0
+    assert lib.sjd_init_model(ctypes.byref(cfg), None, ctypes.c_size_t(0), ctypes.byref(out)) == binding.SJD_EINVAL
+    assert lib.sjd_kv_create(None, ctypes.byref(out)) == binding.SJD_EINVAL
+    assert lib.sjd_step(None, None, None, None, 4, None, None, 0, 0, 0, None, None, None, None) == binding.SJD_EINVAL

@@ -1,0 +1,292 @@
+"""GPU parity: linear layers, window forward (logits), and whole generations vs the CPU oracle.
+
+Bars: logits max-abs <= 1e-4 (fp32 models) / 2e-2 (bf16 models); in fp32 mode whole token
+sequences are identical; given the GPU's own logits the verification is bit-exact in any mode.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import oracle  # noqa: E402
+from paper_2410_01699_amd import synth  # noqa: E402
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2410_01699_amd import binding
+    return binding
+
+
+def _say(msg):
+    print(msg, flush=True, file=sys.stderr)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+class Gpu:
+    """model + cache handles with clean-up"""
+
+    def __init__(self, B, shape, blob):
+        self.B, self.shape = B, shape
+        self.m = B.sjd_init_model(B.config_from_shape(shape), blob)
+        self.kv = B.sjd_kv_create(self.m)
+
+    def close(self):
+        self.B.sjd_kv_free(self.kv); self.B.sjd_free_model(self.m)
+
+    def logits(self, tokens):
+        L = len(tokens)
+        out = torch.empty((L, self.shape.v_s), dtype=torch.float32, device="cuda")
+        self.B.sjd_forward_logits(self.m, self.kv, _dev(np.asarray(tokens, np.int32)), L, out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+
+# ------------------------------------------------------------------ linear layers
+@pytest.mark.parametrize("dtype,M,N,K", [(0, 8, 384, 128), (0, 16, 100, 512), (0, 32, 37, 260), (0, 3, 1024, 128),
+                                         (1, 16, 4608, 1536), (1, 16, 1536, 4096), (1, 32, 256, 320), (1, 5, 48, 64),
+                                         (1, 16, 12288, 4096), (1, 32, 4096, 11008), (1, 16, 22016, 4096),
+                                         (1, 16, 8192, 4096)])
+def test_gemm_against_fp64(B, dtype, M, N, K):
+    _say(f"gemm dtype={dtype} M={M} N={N} K={K}")
+    rng = np.random.default_rng(N + K)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    if dtype == 1:
+        A16, W16 = synth.f32_to_bf16_bits(A).reshape(M, K), synth.f32_to_bf16_bits(W).reshape(N, K)
+        A, W = synth.bf16_bits_to_f32(A16).reshape(M, K), synth.bf16_bits_to_f32(W16).reshape(N, K)
+        dA, dW = _dev(A16.view(np.int16)), _dev(W16.view(np.int16))
+    else:
+        dA, dW = _dev(A), _dev(W)
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    B.sjd_gemm_test(dtype, dA, dW, M, N, K, C)
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    # sampled outputs, one by one in fp64 (all of them when small)
+    if M * N <= 1 << 16:
+        ref = A.astype(np.float64) @ W.astype(np.float64).T
+        assert np.max(np.abs(got - ref)) < 2e-5 * np.sqrt(K / 128)
+    else:
+        rows = rng.integers(0, M, 400); cols = rng.integers(0, N, 400)
+        cols[:8] = [0, 1, 15, 16, N - 1, N - 16, N - 17, N // 2]
+        for r, c in zip(rows, cols):
+            ref = float(np.dot(A[r].astype(np.float64), W[c].astype(np.float64)))
+            assert abs(got[r, c] - ref) < 2e-5 * np.sqrt(K / 128), (r, c)
+
+
+# ------------------------------------------------------------------ window forward
+def _check_forward(B, shape, blob, prompt, windows, tol, embeds=None):
+    om = oracle.Model(shape, blob)
+    g = Gpu(B, shape, blob)
+    try:
+        smp = B.sjd_sampler(8, 1.0); init = B.sjd_init(0, 0, -1)
+        q_last = torch.empty(shape.v_s, dtype=torch.float32, device="cuda")
+        B.sjd_prefill(g.m, g.kv, prompt, embeds, smp, init, q_last)
+        torch.cuda.synchronize()
+        lp = om.prefill(prompt, embeds)
+        P = len(prompt) + (0 if embeds is None else len(embeds))
+        assert B.sjd_kv_len(g.kv) == P
+        q_ref = oracle.dist(lp, 8, 1.0)
+        # top-8 membership can flip on a near-tie at bf16 precision: compare through the logits instead
+        worst = 0.0
+        n = P
+        for toks, keep in windows:
+            _say(f"  window at n={n} L={len(toks)}")
+            got = g.logits(toks)
+            ref = om.forward_tokens(n, toks)
+            err = float(np.max(np.abs(got - ref)))
+            worst = max(worst, err)
+            assert err < tol, (n, err)
+            n += keep
+            B.sjd_kv_set_len(g.kv, n)
+        if tol <= TOL_F32:
+            assert np.max(np.abs(q_last.cpu().numpy() - q_ref)) < 1e-5
+        return worst
+    finally:
+        g.close(); om.close()
+
+
+def test_forward_tiny_fp32(B):
+    w = synth.WORKLOADS["tiny"]
+    blob = synth.make_weights(w.shape, seed=0)
+    prompt, _ = synth.make_prompt(w)
+    toks = synth.random_tokens(64, 0, 1024, seed=3)
+    windows = [(toks[0:8], 3), (toks[8:16], 8), (toks[16:17], 1), (toks[20:28], 5), (toks[30:38], 8)]
+    worst = _check_forward(B, w.shape, blob, prompt, windows, TOL_F32)
+    _say(f"tiny fp32 worst logit error {worst:.3e}")
+
+
+def test_forward_fp32_other_head_sizes_and_large_activations(B):
+    # O(1) weights so that every term matters; heads of 16 and 64; window of 32; long prompt (3 chunks)
+    for heads, d in ((4, 64), (2, 128)):
+        shape = synth.ModelShape(3, d, heads, 96, 300, 44, 300, 120, synth.DTYPE_F32)
+        blob = synth.make_weights(shape, seed=5, std=0.12)
+        prompt = synth.random_tokens(70, 0, 300, seed=1)
+        toks = synth.random_tokens(40, 44, 300, seed=2)
+        worst = _check_forward(B, shape, blob, prompt, [(toks[:32], 7), (toks[3:20], 17), (toks[5:6], 1)], 2e-4)
+        _say(f"fp32 d={d} heads={heads} worst {worst:.3e}")
+
+
+def test_forward_small_bf16(B):
+    shape = synth.ModelShape(4, 256, 4, 512, 2048, 1024, 2048, 200, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=7)
+    prompt = synth.random_tokens(45, 0, 1024, seed=1)
+    toks = synth.random_tokens(64, 1024, 2048, seed=2)
+    worst = _check_forward(B, shape, blob, prompt, [(toks[:16], 5), (toks[16:48], 32), (toks[50:57], 7)], TOL_BF16)
+    _say(f"small bf16 worst {worst:.3e}")
+
+
+def test_forward_775m_bf16(B):
+    """full size of the class-conditional configuration: prompt = 1 id + 120 embedding rows"""
+    w = synth.WORKLOADS["775m"]
+    blob = synth.make_weights(w.shape, seed=0)
+    ids, emb = synth.make_prompt(w)
+    toks = synth.random_tokens(32, 0, w.shape.v_s, seed=4)
+    worst = _check_forward(B, w.shape, blob, ids, [(toks[:16], 6), (toks[16:32], 16)], TOL_BF16, embeds=emb)
+    _say(f"775m bf16 worst {worst:.3e}")
+
+
+# ------------------------------------------------------------------ one step, and whole generations
+def test_step_matches_oracle_given_gpu_logits(B):
+    """sjd_step = forward + verification: the verification applied to the GPU's own logits must be
+    bit-exact in a bf16 model too, and the cache must advance by the accepted count."""
+    shape = synth.ModelShape(2, 256, 4, 512, 2048, 1024, 2048, 160, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=8)
+    g = Gpu(B, shape, blob)
+    try:
+        V, lo, L, K = shape.v_s, shape.samp_lo, 16, 300
+        smp = B.sjd_sampler(K, 1.0); init = B.sjd_init(1, 16, 2047)
+        osmp = oracle.Sampler(K, 1.0); oinit = oracle.Init(1, 16, 2047)
+        prompt = synth.random_tokens(20, 0, 1024, seed=1)
+        q_last = torch.empty(V, dtype=torch.float32, device="cuda")
+        B.sjd_prefill(g.m, g.kv, prompt, None, smp, init, q_last)
+        draft = torch.zeros(L, dtype=torch.int32, device="cuda")
+        p_old = torch.zeros((L, V), dtype=torch.float32, device="cuda")
+        B.sjd_first_window(g.m, q_last, L, init, 42, draft, p_old)
+        na = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nd = torch.zeros(L, dtype=torch.int32, device="cuda"); pn = torch.zeros_like(p_old)
+        hist = []
+        n = 20
+        for c in range(1, 9):
+            _say(f"  step {c} n={n}")
+            d_h, p_h = draft.cpu().numpy(), p_old.cpu().numpy()
+            logits = g.logits(d_h)                                 # hook: same forward, no advance
+            want = oracle.verify(logits, p_h, d_h, lo, osmp, oinit, len(hist), np.array(hist, np.int32), 42, c)
+            B.sjd_step(g.m, g.kv, draft, p_old, L, smp, init, len(hist), 42, c, na, nd, pn)
+            torch.cuda.synchronize()
+            a = int(na.item())
+            assert a == want[0]
+            assert np.array_equal(nd.cpu().numpy(), want[1])
+            assert np.array_equal(pn.cpu().numpy().view(np.uint32), want[2].view(np.uint32))
+            hist += d_h[:a].tolist()
+            n += a
+            assert B.sjd_kv_len(g.kv) == n
+            draft, nd = nd, draft; p_old, pn = pn, p_old
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("L,mode", [(8, 0), (1, 0), (4, 1), (16, 0)])
+def test_generate_tiny_fp32_token_identity(B, L, mode):
+    w = synth.WORKLOADS["tiny"]
+    blob = synth.make_weights(w.shape, seed=0)
+    prompt, _ = synth.make_prompt(w)
+    om = oracle.Model(w.shape, blob)
+    g = Gpu(B, w.shape, blob)
+    try:
+        for seed in range(3):
+            _say(f"generate tiny L={L} mode={mode} seed={seed}")
+            osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(mode, w.row_stride, -1)
+            lp = om.prefill(prompt)
+            want, wst = om.generate_sjd(len(prompt), lp, w.n_image_tokens, L, osmp, oinit, seed)
+            got, st = B.sjd_generate(g.m, g.kv, prompt, None, w.n_image_tokens, L, B.sjd_sampler(w.top_k, w.temperature),
+                                     B.sjd_init(mode, w.row_stride, -1), seed)
+            assert np.array_equal(got, want), (seed, np.nonzero(got != want)[0][:5])
+            assert st.steps == wst.steps
+            assert list(st.accept_hist) == list(wst.accept_hist)
+            if L == 1:
+                lp = om.prefill(prompt)
+                ar = om.generate_ar(len(prompt), lp, w.n_image_tokens, osmp, oinit, seed)
+                assert np.array_equal(got, ar)                     # window 1 == ordinary AR sampling
+    finally:
+        g.close(); om.close()
+
+
+def test_generate_greedy_equals_greedy_ar(B):
+    """K = 1: SJD is deterministic Jacobi decoding and must reproduce greedy decoding exactly"""
+    w = synth.WORKLOADS["tiny"]
+    blob = synth.make_weights(w.shape, seed=0, std=0.05)
+    prompt, _ = synth.make_prompt(w)
+    om = oracle.Model(w.shape, blob)
+    g = Gpu(B, w.shape, blob)
+    try:
+        seq = list(prompt)
+        for _ in range(32):
+            lg = om.forward_full(om.embed(np.array(seq, np.int32)))[-1]
+            seq.append(int(np.argmax(lg)))
+        want = np.array(seq[len(prompt):], np.int32)
+        for L in (1, 8, 32):
+            _say(f"greedy L={L}")
+            got, st = B.sjd_generate(g.m, g.kv, prompt, None, 32, L, B.sjd_sampler(1, 1.0), B.sjd_init(0, 8, -1), 5)
+            assert np.array_equal(got, want)
+            assert st.steps <= 31
+    finally:
+        g.close(); om.close()
+
+
+def test_generate_bf16_statistics_and_validity(B):
+    """bf16 model: tokens cannot be compared one by one (logits differ in the third digit), so check
+    what is unique: ids in range, row-end forcing, step accounting, determinism."""
+    shape = synth.ModelShape(2, 256, 4, 512, 2048, 1024, 2048, 400, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=8)
+    g = Gpu(B, shape, blob)
+    try:
+        prompt = synth.random_tokens(20, 0, 1024, seed=1)
+        smp = B.sjd_sampler(300, 1.0); init = B.sjd_init(1, 9, 2047)
+        N = 9 * 20
+        a, sa = B.sjd_generate(g.m, g.kv, prompt, None, N, 16, smp, init, 3)
+        b, sb = B.sjd_generate(g.m, g.kv, prompt, None, N, 16, smp, init, 3)
+        assert np.array_equal(a, b) and sa.steps == sb.steps
+        assert a.min() >= 1024 and a.max() < 2048
+        assert np.all(a[8::9] == 2047)
+        hist = np.array(sa.accept_hist[:])
+        assert hist[0] == 0 and hist.sum() == sa.steps and 1 <= sa.steps <= N - 1
+        assert int((hist * np.arange(65)).sum()) in (N - 1, N)
+    finally:
+        g.close()
+
+
+def test_step_errors(B):
+    w = synth.WORKLOADS["tiny"]
+    blob = synth.make_weights(w.shape, seed=0)
+    g = Gpu(B, w.shape, blob)
+    try:
+        V = w.shape.v_s
+        d = torch.zeros(8, dtype=torch.int32, device="cuda"); p = torch.zeros((8, V), device="cuda")
+        na = torch.zeros(1, dtype=torch.int32, device="cuda")
+        smp = B.sjd_sampler(64, 1.0); init = B.sjd_init(0, 8, -1)
+        B.sjd_kv_set_len(g.kv, w.shape.max_seq - 4)
+        with pytest.raises(B.SjdError) as e:
+            B.sjd_step(g.m, g.kv, d, p, 8, smp, init, 0, 1, 1, na, d, p)
+        assert e.value.code == B.SJD_ESEQ
+        with pytest.raises(B.SjdError) as e:
+            B.sjd_step(g.m, g.kv, d, p, 33, smp, init, 0, 1, 1, na, d, p)
+        assert e.value.code == B.SJD_EINVAL
+        with pytest.raises(B.SjdError) as e:
+            B.sjd_generate(g.m, g.kv, np.arange(16, dtype=np.int32), None, 1000, 8, smp, init, 0)
+        assert e.value.code == B.SJD_ESEQ
+        with pytest.raises(B.SjdError):
+            B.sjd_init_model(B.config_from_shape(w.shape), blob[:-1])
+    finally:
+        g.close()
