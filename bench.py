@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Throughput of the SJD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one SJD iteration (window forward + verification + window slide) of a running
+generation, with weights, KV cache, window and loop state resident in HBM.  Prints ONE JSON line:
+image tokens/s over exactly K timed steps, forward passes per image for SJD and for ordinary
+auto-regressive decoding (the same loop with window 1), the roofline position of the dominant
+kernel (the weight-streaming projections) measured with HIP events inside the library, and the CPU
+oracle timed on a bounded sample of the same workload on this host's cores.
+
+Only one GPU is used; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, blob, prompt_ids, prompt_emb, seed, budget_steps):
+    """The oracle as it stands, on a bounded sample: a truncated prompt (so that the CPU prefill
+    stays short; untimed) and `budget_steps` timed SJD iterations."""
+    import numpy as np
+    import oracle
+    om = oracle.Model(w.shape, blob)
+    keep_ids = prompt_ids[:8]
+    keep_emb = None if prompt_emb is None or len(prompt_emb) == 0 else prompt_emb[:8 - len(keep_ids)]
+    P = len(keep_ids) + (0 if keep_emb is None else len(keep_emb))
+    lp = om.prefill(keep_ids, keep_emb)
+    smp = oracle.Sampler(w.top_k, w.temperature)
+    init = oracle.Init(w.init_mode, w.row_stride, w.eol_id)
+    lo, L = w.shape.samp_lo, w.window
+    q0 = oracle.dist(lp, smp.top_k, smp.temperature)
+    draft, p_old = oracle.first_window(q0, L, lo, init, seed)
+    out = []
+    t0 = time.perf_counter()
+    for c in range(1, budget_steps + 1):
+        logits = om.forward_tokens(P + len(out), draft)
+        a, nd, pn = oracle.verify(logits, p_old, draft, lo, smp, init, len(out), np.array(out, np.int32), seed, c)
+        out += draft[:a].tolist()
+        draft, p_old = nd, pn
+    dt = time.perf_counter() - t0
+    om.close()
+    return {"value": len(out) / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"prompt cut to {P} positions (prefill untimed), {budget_steps} SJD iterations of L={L} timed "
+                      f"({len(out)} tokens fixed in {dt:.2f} s)",
+            "s_per_step": dt / budget_steps}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="7b_32x32")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--profile-steps", type=int, default=24)
+    ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle iterations to time (0 = skip)")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--skip-images", action="store_true", help="skip the whole-image SJD / AR runs")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (independent images per GPU is how it would scale); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_01699_amd import binding as B
+    from paper_2410_01699_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    shape = w.shape
+    t0 = time.perf_counter()
+    blob = synth.make_weights(shape, seed=0, threads=16)
+    log(f"weights: {shape.n_params() / 1e9:.2f} G params generated in {time.perf_counter() - t0:.1f} s")
+    ids, emb = synth.make_prompt(w)
+    t0 = time.perf_counter()
+    m = B.sjd_init_model(B.config_from_shape(shape), blob)
+    kv = B.sjd_kv_create(m)
+    log(f"model on device in {time.perf_counter() - t0:.1f} s")
+    if args.no_graph:
+        B.sjd_kv_use_graph(kv, False)
+    smp = B.sjd_sampler(w.top_k, w.temperature)
+    init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id)
+    N, L = w.n_image_tokens, w.window
+    q_first = torch.empty(shape.v_s, dtype=torch.float32, device="cuda")
+
+    image = [args.seed]
+
+    def new_image():
+        B.sjd_prefill(m, kv, ids, emb, smp, init, q_first)
+        B.sjd_decode_begin(m, kv, q_first, N, L, smp, init, image[0])
+        image[0] += 1
+        torch.cuda.synchronize()
+
+    def safe_steps():
+        fixed, _, done = B.sjd_decode_status(kv)
+        return 0 if done else (N - 2 - fixed) // L, fixed
+
+    def run_steps(k, timed):
+        """exactly k iterations of a live generation; returns (seconds, tokens fixed)"""
+        secs, toks = 0.0, 0
+        while k > 0:
+            safe, fixed0 = safe_steps()
+            if safe < 1:
+                new_image()
+                continue
+            seg = min(k, safe)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            B.sjd_decode_steps(m, kv, seg)
+            torch.cuda.synchronize()
+            secs += time.perf_counter() - t
+            fixed1, _, _ = B.sjd_decode_status(kv)
+            toks += fixed1 - fixed0
+            k -= seg
+        return secs, toks
+
+    new_image()
+    run_steps(args.warmup, False)
+    secs, toks = run_steps(args.steps, True)
+    ms_per_step = secs / args.steps * 1e3
+    log(f"{args.steps} steps: {ms_per_step:.3f} ms/step, {toks} tokens fixed, {toks / secs:.1f} tokens/s")
+
+    # ---- roofline of the dominant kernel: HIP events around every launch, same stream ----
+    prof_steps = args.profile_steps
+    safe, _ = safe_steps()
+    if safe < prof_steps:
+        new_image()
+    p = B.sjd_profile_steps(m, kv, prof_steps)
+    classes = {}
+    for i, name in enumerate(B.PROF_KINDS):
+        ms, by, n = p.ms[i], p.bytes[i], p.launches[i]
+        classes[name] = {"ms_per_step": ms / prof_steps, "launches_per_step": n / prof_steps,
+                         "us_per_launch": (ms * 1e3 / n) if n else None,
+                         "algorithmic_GB_per_step": by / prof_steps / 1e9,
+                         "GBps": (by / 1e9) / (ms / 1e3) if ms > 0 else None}
+    g = classes["gemm"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload)
+    roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (all projections + LM head)" if shape.dtype == 1
+                else "gemm_f32_kernel", "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
+                "bytes_per_launch": g["algorithmic_GB_per_step"] * 1e9 / g["launches_per_step"],
+                "us_per_launch": g["us_per_launch"], "launches_per_step": g["launches_per_step"]}
+    weight_bytes = g["algorithmic_GB_per_step"] * 1e9
+    step_floor_ms = weight_bytes / (HBM_PEAK_GBS * 1e9) * 1e3
+    log(f"gemm: {g['GBps']:.0f} GB/s over {g['launches_per_step']:.0f} launches/step; "
+        f"whole step at {weight_bytes / 1e9 / (ms_per_step / 1e3):.0f} GB/s of weight stream")
+
+    # ---- whole images: forward passes per image, SJD vs ordinary AR (window 1) ----
+    extra = {}
+    if not args.skip_images:
+        t = time.perf_counter()
+        _, st = B.sjd_generate(m, kv, ids, emb, N, L, smp, init, args.seed)
+        extra["sjd_forwards_per_image"] = st.steps
+        extra["sjd_image_seconds"] = st.ms_decode / 1e3
+        extra["sjd_image_tokens_per_s"] = N / (st.ms_decode / 1e3)
+        _, sa = B.sjd_generate(m, kv, ids, emb, N, 1, smp, init, args.seed)
+        extra["ar_forwards_per_image"] = sa.steps
+        extra["ar_image_seconds"] = sa.ms_decode / 1e3
+        extra["ar_image_tokens_per_s"] = N / (sa.ms_decode / 1e3)
+        extra["step_compression"] = sa.steps / st.steps
+        extra["latency_speedup_vs_ar"] = sa.ms_decode / st.ms_decode
+        log(f"images: SJD {st.steps} forwards / {st.ms_decode:.0f} ms, AR {sa.steps} forwards / {sa.ms_decode:.0f} ms "
+            f"({time.perf_counter() - t:.1f} s)")
+    B.sjd_kv_free(kv)
+    B.sjd_free_model(m)
+
+    cpu_steps = args.cpu_steps
+    if cpu_steps < 0:
+        cpu_steps = 2 if shape.n_params() > 2e9 else (6 if shape.n_params() > 1e8 else 40)
+    cpu = None
+    if cpu_steps > 0:
+        log("timing the CPU oracle on a bounded sample ...")
+        cpu = cpu_baseline(w, blob, ids, emb, args.seed, cpu_steps)
+
+    out = {
+        "metric": "image_tokens_per_s", "value": toks / secs, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == 1 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "window_L": L, "top_k": w.top_k, "temperature": w.temperature,
+                   "image_tokens_N": N, "prompt_positions": len(ids) + len(emb), "layers": shape.n_layers,
+                   "d_model": shape.d_model, "sampling_vocab": shape.v_s, "hip_graph": not args.no_graph,
+                   "tokens_fixed_per_step": toks / args.steps, "step_hbm_floor_ms": step_floor_ms,
+                   "step_weight_stream_GBps": weight_bytes / 1e9 / (ms_per_step / 1e3), **extra},
+        "roofline": roofline, "kernel_classes": classes, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -122,6 +122,39 @@ int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, co
                  int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
                  uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats);
 
+/* The same loop in pieces, with the loop state (cache length, image position, Philox counter,
+ * window, its distributions) resident on the device so that iterations can be enqueued without
+ * waiting for the outcome of the previous one (Sec. 4.1: the accepted count of Step 3 decides
+ * where the next window starts, which is a data dependence, not a host decision).
+ *   sjd_decode_begin   after sjd_prefill: first window from q_first (dev [V_s]), counters reset.
+ *   sjd_decode_steps   enqueue n_steps iterations on `stream` (one HIP-graph replay each);
+ *                      iterations that start after the N-th token is fixed do nothing.
+ *   sjd_decode_status  synchronise; image tokens fixed so far, iterations run, finished flag.
+ *   sjd_decode_result  after `done`: the N tokens (host) and the step statistics.
+ *   sjd_kv_use_graph   0: launch kernels one by one instead of replaying a captured graph.     */
+int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, int32_t N, int32_t L,
+                     const sjd_sampler *smp, const sjd_init *init, uint64_t philox_seed, void *stream);
+int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void *stream);
+int sjd_decode_status(sjd_kv *kv, int32_t *n_fixed, int32_t *steps, int32_t *done);
+int sjd_decode_result(sjd_kv *kv, int32_t *out_tokens, sjd_stats *stats);
+int sjd_kv_use_graph(sjd_kv *kv, int32_t on);
+
+/* Per-kernel-class timing: runs n_steps iterations of the loop above kernel by kernel with a HIP
+ * event pair around every launch (on `stream`), and adds up milliseconds, launch counts and
+ * algorithmic HBM bytes (weights for the projections, K/V rows for attention, logits + both
+ * probability windows for the verification) per class.  Synchronises.                          */
+#define SJD_PROF_GEMM 0        /* QKV / O / gate-up / down projections and the LM head           */
+#define SJD_PROF_ATTENTION 1   /* window attention incl. the merge of its key chunks             */
+#define SJD_PROF_ELEMENTWISE 2 /* embedding, RMSNorm, RoPE + cache write, SiLU*up, reductions    */
+#define SJD_PROF_VERIFY 3      /* Sec. 4.1 Step 3 + Step 4 kernels                               */
+typedef struct {
+    double ms[4];
+    double bytes[4];
+    int64_t launches[4];
+    int32_t steps;
+} sjd_profile;
+int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream);
+
 /* ---- pieces of the step, exported for parity tests and profiling --------------------------- */
 /* Step 2 alone: forward `L` tokens (dev ids) at positions n..n+L-1, write their K/V rows, return
  * logits dev [L x V_s] fp32.  Does not advance n.                                              */

@@ -63,6 +63,7 @@ def lib():
         vp, i32, u32, u64, i64, f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_int64, C.c_float
         P = C.POINTER
         sig = {
+            "orc_num_threads": (i32, []),
             "orc_philox4x32_10": (None, [vp, vp, vp]),
             "orc_draw": (None, [u64, u64, u32, vp]),
             "orc_u_acc": (f32, [u32]),
@@ -105,6 +106,10 @@ def _f32(a):
 
 def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
 
 
 # ---- thin numpy wrappers -------------------------------------------------------------------

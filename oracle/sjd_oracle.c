@@ -11,6 +11,19 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* threads the fp64 matrix products use (for reporting timings) */
+int32_t orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ===================================================================================== */
 /* Philox4x32-10: the published counter-based generator (Salmon et al., SC'11).          */

@@ -20,6 +20,8 @@
 extern "C" {
 #endif
 
+int32_t orc_num_threads(void);
+
 /* ---- random numbers: Philox4x32-10 (Salmon et al., SC'11) ------------------------- */
 void orc_philox4x32_10(const uint32_t key[2], const uint32_t ctr[4], uint32_t out[4]);
 /* the four words drawn for (seed, step counter c, window index i): acc, res, smp, init */

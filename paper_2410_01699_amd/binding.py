@@ -20,7 +20,10 @@ SJD_MAX_SAMP_VOCAB = 32768
 
 EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "sjd_kv_reset", "sjd_kv_len",
            "sjd_kv_set_len", "sjd_prefill", "sjd_first_window", "sjd_step", "sjd_generate", "sjd_forward_logits",
-           "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror"]
+           "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror", "sjd_decode_begin",
+           "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps"]
+
+PROF_KINDS = ("gemm", "attention", "elementwise", "verify")
 
 
 class sjd_config(C.Structure):
@@ -40,6 +43,10 @@ class sjd_init(C.Structure):
 class sjd_stats(C.Structure):
     _fields_ = [("steps", C.c_int32), ("accept_hist", C.c_int32 * 65), ("ms_prefill", C.c_float),
                 ("ms_decode", C.c_float)]
+
+
+class sjd_profile(C.Structure):
+    _fields_ = [("ms", C.c_double * 4), ("bytes", C.c_double * 4), ("launches", C.c_int64 * 4), ("steps", C.c_int32)]
 
 
 class SjdError(RuntimeError):
@@ -77,6 +84,12 @@ _SIG = {
     "sjd_dist": (C.c_int, [_vp, _i32, _i32, _P(sjd_sampler), _vp, _vp, _vp]),
     "sjd_gemm_test": (C.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp]),
     "sjd_strerror": (C.c_char_p, [C.c_int]),
+    "sjd_decode_begin": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _u64, _vp]),
+    "sjd_decode_steps": (C.c_int, [_vp, _vp, _i32, _vp]),
+    "sjd_decode_status": (C.c_int, [_vp, _P(_i32), _P(_i32), _P(_i32)]),
+    "sjd_decode_result": (C.c_int, [_vp, _vp, _P(sjd_stats)]),
+    "sjd_kv_use_graph": (C.c_int, [_vp, _i32]),
+    "sjd_profile_steps": (C.c_int, [_vp, _vp, _i32, _P(sjd_profile), _vp]),
 }
 for _name, (_res, _args) in _SIG.items():
     _fn = getattr(_lib, _name)
@@ -204,3 +217,35 @@ def sjd_dist(logits, rows, V_s, smp, forced, q, stream=None):
 
 def sjd_gemm_test(dtype, A, W, M, N, K, Cout, stream=None):
     _check(_lib.sjd_gemm_test(dtype, _dev(A), _dev(W), M, N, K, _dev(Cout), _stream(stream)))
+
+
+def sjd_decode_begin(m, kv, q_first, N, L, smp, init, seed, stream=None):
+    _check(_lib.sjd_decode_begin(m, kv, _dev(q_first), N, L, C.byref(smp), C.byref(init), seed, _stream(stream)))
+
+
+def sjd_decode_steps(m, kv, n_steps, stream=None):
+    _check(_lib.sjd_decode_steps(m, kv, n_steps, _stream(stream)))
+
+
+def sjd_decode_status(kv):
+    """-> (image tokens fixed, iterations run, done)"""
+    a, b, c = _i32(0), _i32(0), _i32(0)
+    _check(_lib.sjd_decode_status(kv, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, bool(c.value)
+
+
+def sjd_decode_result(kv, N):
+    out = np.empty(N, np.int32)
+    st = sjd_stats()
+    _check(_lib.sjd_decode_result(kv, _host(out), C.byref(st)))
+    return out, st
+
+
+def sjd_kv_use_graph(kv, on: bool):
+    _check(_lib.sjd_kv_use_graph(kv, int(on)))
+
+
+def sjd_profile_steps(m, kv, n_steps, stream=None) -> sjd_profile:
+    p = sjd_profile()
+    _check(_lib.sjd_profile_steps(m, kv, n_steps, C.byref(p), _stream(stream)))
+    return p

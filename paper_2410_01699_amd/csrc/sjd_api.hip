@@ -179,6 +179,8 @@ extern "C" void sjd_kv_free(sjd_kv *kv)
                     kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
                     kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
     for (void *p : ptrs) if (p) (void)hipFree(p);
+    if (kv->graph_exec) (void)hipGraphExecDestroy(kv->graph_exec);
+    if (kv->graph) (void)hipGraphDestroy(kv->graph);
     delete kv;
 }
 
@@ -190,6 +192,7 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     if (!kv) return SJD_ENOMEM;
     memset(kv, 0, sizeof(*kv));
     kv->m = m;
+    kv->use_graph = 1;
     const sjd_config &c = m->cfg;
     const size_t es = elt_size(c.dtype), d = c.d_model, F = c.d_ffn, V = m->V_s, R = SJD_ROWS_MAX;
     size_t part = 0;
@@ -205,12 +208,12 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     A(kv->tokens, (size_t)c.max_seq * 4);
     A(kv->state, sizeof(SjdState));
     A(kv->x, R * d * 4);
-    A(kv->h, R * d * es);
+    A(kv->h, R * d * es * 2);          // bf16 models: hi + lo planes
     A(kv->part, part * 4);
-    A(kv->qact, R * d * es);
+    A(kv->qact, R * d * 4);
     A(kv->att_part, sjd_attention_part_elems(m) * 4);
-    A(kv->att_out, R * d * es);
-    A(kv->ffn, R * F * es);
+    A(kv->att_out, R * d * es * 2);
+    A(kv->ffn, R * F * es * 2);
     A(kv->logits, R * V * 4);
     A(kv->q, (R + 1) * V * 4);
     A(kv->tok_smp, (R + 1) * 4);
@@ -226,6 +229,7 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     A(kv->g_nacc, 16);
     A(kv->q_first, V * 4);
 #undef A
+    if (rc == SJD_OK) rc = sjd_sample_setup(m->V_s);
     if (rc != SJD_OK) { sjd_kv_free(kv); return rc; }
     *out = kv;
     return SJD_OK;
@@ -251,6 +255,8 @@ extern "C" int sjd_kv_reset(sjd_kv *kv)
     HIP_TRY(hipDeviceSynchronize());
     SjdState st;
     memset(&st, 0, sizeof(st));
+    kv->n_upper = 0;
+    kv->dec_active = 0;
     return state_write(kv, st, 0);
 }
 
@@ -260,6 +266,7 @@ extern "C" int sjd_kv_len(const sjd_kv *kv, int32_t *n)
     SjdState st;
     SJD_TRY(state_read(kv, &st));
     *n = st.n;
+    const_cast<sjd_kv *>(kv)->n_upper = st.n;
     return SJD_OK;
 }
 
@@ -270,42 +277,92 @@ extern "C" int sjd_kv_set_len(sjd_kv *kv, int32_t n)
     SJD_TRY(state_read(kv, &st));
     st.n = n;
     st.done = 0;
+    kv->n_upper = n;
     return state_write(kv, st, 0);
 }
 
+// ---- optional event timing ------------------------------------------------------------------
+struct SjdProfiler {
+    hipStream_t stream = 0;
+    std::vector<hipEvent_t> ev;      // pairs (begin, end)
+    std::vector<int> kind;           // per pair
+    std::vector<double> bytes;       // per pair: algorithmic HBM bytes of the launch
+    size_t used = 0;
+    int begin(int k, double b)
+    {
+        if (used + 2 > ev.size()) {
+            for (int i = 0; i < 2; ++i) { hipEvent_t e; HIP_TRY(hipEventCreate(&e)); ev.push_back(e); }
+            kind.push_back(k); bytes.push_back(b);
+        } else { kind[used / 2] = k; bytes[used / 2] = b; }
+        HIP_TRY(hipEventRecord(ev[used], stream));
+        return SJD_OK;
+    }
+    int end()
+    {
+        HIP_TRY(hipEventRecord(ev[used + 1], stream));
+        used += 2;
+        return SJD_OK;
+    }
+    int drain(sjd_profile *out)
+    {
+        HIP_TRY(hipStreamSynchronize(stream));
+        for (size_t i = 0; i < used; i += 2) {
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+            const int k = kind[i / 2];
+            out->ms[k] += ms; out->launches[k] += 1; out->bytes[k] += bytes[i / 2];
+        }
+        used = 0;
+        return SJD_OK;
+    }
+    void destroy() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); ev.clear(); }
+};
+#define PROF(kv, k, b, call)                                             \
+    do {                                                                 \
+        if ((kv)->prof) SJD_TRY(((SjdProfiler *)(kv)->prof)->begin((k), (b))); \
+        SJD_TRY(call);                                                   \
+        if ((kv)->prof) SJD_TRY(((SjdProfiler *)(kv)->prof)->end());     \
+    } while (0)
+
 // ---- the window forward (Step 2) ------------------------------------------------------------
 // rows = rows computed (<= 32), rows_valid = rows whose K/V are written.  Inputs already in kv->x.
+static double lin_bytes(const sjd_model *m, const SjdLinear &l) { return (double)l.N * l.K * elt_size(m->cfg.dtype); }
+
 static int forward_rows(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
 {
     const int dt = m->cfg.dtype;
     const SjdState *st = kv->state;
     const SjdLinear *prev = nullptr;   // GEMM whose partial sums still have to be added to x
+    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * m->cfg.d_model * elt_size(dt);   // upper bound
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
-        SJD_TRY(sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? prev->split_k : 0,
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? prev->split_k : 0,
                                    prev ? sjd_part_stride(prev, rows) : 0, L.g1, rows, kv->h, st, s));
-        SJD_TRY(sjd_launch_gemm(dt, &L.qkv, kv->h, rows, kv->part, st, s));
-        SJD_TRY(sjd_launch_rope_kv(m, kv, l, kv->part, L.qkv.split_k, sjd_part_stride(&L.qkv, rows), rows, rows_valid, s));
-        SJD_TRY(sjd_launch_attention(m, kv, l, rows, s));
-        SJD_TRY(sjd_launch_gemm(dt, &L.o, kv->att_out, rows, kv->part, st, s));
-        SJD_TRY(sjd_launch_rmsnorm(m, kv->x, kv->part, L.o.split_k, sjd_part_stride(&L.o, rows), L.g2, rows, kv->h, st, s));
-        SJD_TRY(sjd_launch_gemm(dt, &L.gu, kv->h, rows, kv->part, st, s));
-        SJD_TRY(sjd_launch_silu_mul(m, kv->part, L.gu.split_k, sjd_part_stride(&L.gu, rows), rows, kv->ffn, st, s));
-        SJD_TRY(sjd_launch_gemm(dt, &L.down, kv->ffn, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm(dt, &L.qkv, kv->h, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rope_kv(m, kv, l, kv->part, L.qkv.split_k, sjd_part_stride(&L.qkv, rows), rows, rows_valid, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm(dt, &L.o, kv->att_out, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, L.o.split_k, sjd_part_stride(&L.o, rows), L.g2, rows, kv->h, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm(dt, &L.gu, kv->h, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_silu_mul(m, kv->part, L.gu.split_k, sjd_part_stride(&L.gu, rows), rows, kv->ffn, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm(dt, &L.down, kv->ffn, rows, kv->part, st, s));
         prev = &L.down;
     }
-    SJD_TRY(sjd_launch_rmsnorm(m, kv->x, kv->part, prev->split_k, sjd_part_stride(prev, rows), m->gf, rows, kv->h, st, s));
-    SJD_TRY(sjd_launch_gemm(dt, &m->lm, kv->h, rows, kv->part, st, s));
-    SJD_TRY(sjd_launch_reduce_rows(kv->part, m->lm.split_k, sjd_part_stride(&m->lm, rows), rows, m->V_s, logits, st, s));
+    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, prev->split_k, sjd_part_stride(prev, rows), m->gf, rows, kv->h, st, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm(dt, &m->lm, kv->h, rows, kv->part, st, s));
+    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_reduce_rows(kv->part, m->lm.split_k, sjd_part_stride(&m->lm, rows), rows, m->V_s, logits, st, s));
     return SJD_OK;
 }
 
-static int check_room(sjd_kv *kv, int32_t L, int32_t *n_out)
+// n lives on the device; the host keeps an upper bound and only synchronises to refresh it when
+// the bound (not necessarily n itself) would run past max_seq.
+static int check_room(sjd_kv *kv, int32_t L)
 {
+    if (kv->n_upper + L <= kv->m->cfg.max_seq) return SJD_OK;
     SjdState st;
     SJD_TRY(state_read(kv, &st));
+    kv->n_upper = st.n;
     if (st.n + L > kv->m->cfg.max_seq) return SJD_ESEQ;
-    if (n_out) *n_out = st.n;
     return SJD_OK;
 }
 
@@ -314,7 +371,7 @@ __global__ void clear_done_kernel(SjdState *st) { st->done = 0; }
 extern "C" int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream)
 {
     if (!m || !kv || kv->m != m || !tokens || !logits || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
-    SJD_TRY(check_room(kv, L, nullptr));
+    SJD_TRY(check_room(kv, L));
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(clear_done_kernel, dim3(1), dim3(1), 0, s, kv->state);
     HIP_TRY(hipGetLastError());
@@ -371,6 +428,7 @@ extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
                                is_id ? kv->ids_stage : (const int32_t *)nullptr, cnt);
             HIP_TRY(hipGetLastError());
             HIP_TRY(hipStreamSynchronize(s));   // staging buffers are reused by the next chunk
+            kv->n_upper += cnt;
             done_rows += cnt;
             rows_last = cnt;
         }
@@ -410,7 +468,7 @@ static int enqueue_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
                         const sjd_sampler *smp, const sjd_init *init, uint64_t seed, int32_t *n_accepted,
                         int32_t *new_draft, float *p_new, hipStream_t s)
 {
-    SJD_TRY(sjd_launch_embed(m, draft, nullptr, L, kv->x, kv->state, s));
+    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, draft, nullptr, L, kv->x, kv->state, s));
     SJD_TRY(forward_rows(m, kv, L, L, kv->logits, s));
     SjdVerifyArgs v;
     memset(&v, 0, sizeof(v));
@@ -419,7 +477,8 @@ static int enqueue_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
     v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new;
     v.q = kv->q; v.tok_smp = kv->tok_smp; v.tok_res = kv->tok_res; v.acc_flag = kv->acc_flag;
     v.draft_snap = kv->draft_snap; v.snap = kv->snap;
-    return sjd_launch_verify(&v, s);
+    PROF(kv, SJD_PROF_VERIFY, 3.0 * L * m->V_s * 4, sjd_launch_verify(&v, s));
+    return SJD_OK;
 }
 
 extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const float *p_old, int32_t L,
@@ -429,11 +488,14 @@ extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
     if (!m || !kv || kv->m != m || !draft || !p_old || !n_accepted || !new_draft || !p_new) return SJD_EINVAL;
     if (L < 1 || L > SJD_MAX_WINDOW || img_pos0 < 0) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
-    SJD_TRY(check_room(kv, L, nullptr));
+    SJD_TRY(check_room(kv, L));
     hipStream_t s = (hipStream_t)stream;
+    kv->dec_active = 0;
     hipLaunchKernelGGL(set_step_kernel, dim3(1), dim3(1), 0, s, kv->state, img_pos0, counter, L);
     HIP_TRY(hipGetLastError());
-    return enqueue_step(m, kv, draft, p_old, L, smp, init, philox_seed, n_accepted, new_draft, p_new, s);
+    SJD_TRY(enqueue_step(m, kv, draft, p_old, L, smp, init, philox_seed, n_accepted, new_draft, p_new, s));
+    kv->n_upper += L;
+    return SJD_OK;
 }
 
 __global__ void begin_generate_kernel(SjdState *st, int N, int L)
@@ -441,6 +503,109 @@ __global__ void begin_generate_kernel(SjdState *st, int N, int L)
     st->img_pos0 = 0; st->counter = 1; st->n_image = N; st->L_eff = L < N ? L : N; st->done = (N <= 1);
     st->steps = 0;
     for (int i = 0; i < 65; ++i) st->accept_hist[i] = 0;
+}
+
+// ---- device-resident decoding loop -----------------------------------------------------------
+static void drop_graph(sjd_kv *kv)
+{
+    if (kv->graph_exec) { (void)hipGraphExecDestroy(kv->graph_exec); kv->graph_exec = nullptr; }
+    if (kv->graph) { (void)hipGraphDestroy(kv->graph); kv->graph = nullptr; }
+}
+
+extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, int32_t N, int32_t L,
+                                const sjd_sampler *smp, const sjd_init *init, uint64_t philox_seed, void *stream)
+{
+    if (!m || !kv || kv->m != m || !q_first || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
+    if (kv->n_upper + N + L > m->cfg.max_seq) {
+        int32_t n;
+        SJD_TRY(sjd_kv_len(kv, &n));
+        if (n + N + L > m->cfg.max_seq) return SJD_ESEQ;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const bool same = kv->graph_exec && kv->dec_L == L && kv->dec_smp.top_k == smp->top_k &&
+                      kv->dec_smp.temperature == smp->temperature && kv->dec_init.mode == init->mode &&
+                      kv->dec_init.row_stride == init->row_stride && kv->dec_init.eol_id == init->eol_id &&
+                      kv->dec_seed == philox_seed;
+    if (!same) drop_graph(kv);          // the captured step has these baked into its kernel arguments
+    kv->dec_N = N; kv->dec_L = L; kv->dec_smp = *smp; kv->dec_init = *init; kv->dec_seed = philox_seed;
+    kv->dec_active = 1;
+    SJD_TRY(sjd_launch_first_window(q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, kv->g_draft, kv->g_p, s));
+    hipLaunchKernelGGL(begin_generate_kernel, dim3(1), dim3(1), 0, s, kv->state, N, L);
+    HIP_TRY(hipGetLastError());
+    kv->n_upper += N;                    // the loop never fixes more than N tokens
+    return SJD_OK;
+}
+
+static int decode_one(sjd_model *m, sjd_kv *kv, hipStream_t s)
+{
+    return enqueue_step(m, kv, kv->g_draft, kv->g_p, kv->dec_L, &kv->dec_smp, &kv->dec_init, kv->dec_seed, kv->g_nacc,
+                        kv->g_draft, kv->g_p, s);
+}
+
+extern "C" int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void *stream)
+{
+    if (!m || !kv || kv->m != m || n_steps < 0 || !kv->dec_active) return SJD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if (!kv->use_graph) {
+        for (int i = 0; i < n_steps; ++i) SJD_TRY(decode_one(m, kv, s));
+        return SJD_OK;
+    }
+    if (!kv->graph_exec) {
+        // capture one iteration; everything that varies between iterations lives in device memory
+        hipStream_t cs;
+        HIP_TRY(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+        hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
+        int rc = SJD_OK;
+        if (e != hipSuccess) { sjd_set_hip_error(e, "hipStreamBeginCapture"); rc = SJD_EHIP; }
+        if (rc == SJD_OK) rc = decode_one(m, kv, cs);
+        hipGraph_t g = nullptr;
+        e = hipStreamEndCapture(cs, &g);
+        if (rc == SJD_OK && e != hipSuccess) { sjd_set_hip_error(e, "hipStreamEndCapture"); rc = SJD_EHIP; }
+        (void)hipStreamDestroy(cs);
+        if (rc != SJD_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+        kv->graph = g;
+        e = hipGraphInstantiate(&kv->graph_exec, g, nullptr, nullptr, 0);
+        if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_graph(kv); return SJD_EHIP; }
+    }
+    for (int i = 0; i < n_steps; ++i) HIP_TRY(hipGraphLaunch(kv->graph_exec, s));
+    return SJD_OK;
+}
+
+extern "C" int sjd_decode_status(sjd_kv *kv, int32_t *n_fixed, int32_t *steps, int32_t *done)
+{
+    if (!kv) return SJD_EINVAL;
+    SjdState st;
+    SJD_TRY(state_read(kv, &st));
+    if (n_fixed) *n_fixed = st.img_pos0;
+    if (steps) *steps = st.steps;
+    if (done) *done = st.done;
+    return SJD_OK;
+}
+
+extern "C" int sjd_decode_result(sjd_kv *kv, int32_t *out_tokens, sjd_stats *stats)
+{
+    if (!kv || !kv->dec_active || !out_tokens) return SJD_EINVAL;
+    SjdState st;
+    SJD_TRY(state_read(kv, &st));
+    if (!st.done) return SJD_EINVAL;
+    const int N = kv->dec_N, P = st.n - st.img_pos0;
+    // image tokens = cache ids P .. ; when N-1 were fixed the pending exact slot 0 is the last one
+    const int fixed = st.img_pos0 < N ? st.img_pos0 : N;
+    HIP_TRY(hipMemcpy(out_tokens, kv->tokens + P, (size_t)fixed * 4, hipMemcpyDeviceToHost));
+    if (fixed < N) HIP_TRY(hipMemcpy(out_tokens + fixed, kv->g_draft, 4, hipMemcpyDeviceToHost));
+    if (stats) {
+        stats->steps = st.steps;
+        for (int i = 0; i < 65; ++i) stats->accept_hist[i] = st.accept_hist[i];
+    }
+    return SJD_OK;
+}
+
+extern "C" int sjd_kv_use_graph(sjd_kv *kv, int32_t on)
+{
+    if (!kv) return SJD_EINVAL;
+    kv->use_graph = on ? 1 : 0;
+    return SJD_OK;
 }
 
 extern "C" int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
@@ -454,38 +619,45 @@ extern "C" int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_
     hipStream_t s = 0;
     auto t0 = std::chrono::steady_clock::now();
     SJD_TRY(sjd_prefill(m, kv, ids, n_ids, embeds, n_embeds, smp, init, kv->q_first, s));
-    SJD_TRY(sjd_launch_first_window(kv->q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, kv->g_draft, kv->g_p, s));
-    hipLaunchKernelGGL(begin_generate_kernel, dim3(1), dim3(1), 0, s, kv->state, N, L);
-    HIP_TRY(hipGetLastError());
+    SJD_TRY(sjd_decode_begin(m, kv, kv->q_first, N, L, smp, init, philox_seed, s));
     HIP_TRY(hipStreamSynchronize(s));
     auto t1 = std::chrono::steady_clock::now();
-
-    // The loop: steps are enqueued in batches; kernels of a step that starts after the generation
-    // has finished return at once (state->done), so over-enqueueing is harmless.
-    const int batch = 8;
-    SjdState st;
-    int enq = 0;
-    for (;;) {
-        for (int b = 0; b < batch; ++b, ++enq)
-            SJD_TRY(enqueue_step(m, kv, kv->g_draft, kv->g_p, L, smp, init, philox_seed, kv->g_nacc, kv->g_draft, kv->g_p, s));
-        SJD_TRY(state_read(kv, &st));
-        if (st.done) break;
-        if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every step fixes at least one token
+    // Iterations are enqueued in batches; the kernels of an iteration that starts after the
+    // generation has finished return at once (state->done), so over-enqueueing is harmless.
+    int enq = 0, done = 0;
+    while (!done) {
+        SJD_TRY(sjd_decode_steps(m, kv, 8, s));
+        enq += 8;
+        SJD_TRY(sjd_decode_status(kv, nullptr, nullptr, &done));
+        if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every iteration fixes at least one token
     }
     auto t2 = std::chrono::steady_clock::now();
-    // image tokens = cache ids P .. P+N-1; when N-1 were fixed the pending exact slot 0 is the last
-    std::vector<int32_t> tmp((size_t)N);
-    const int fixed = st.img_pos0 < N ? st.img_pos0 : N;
-    HIP_TRY(hipMemcpy(tmp.data(), kv->tokens + P, (size_t)fixed * 4, hipMemcpyDeviceToHost));
-    if (fixed < N) HIP_TRY(hipMemcpy(tmp.data() + fixed, kv->g_draft, 4, hipMemcpyDeviceToHost));
-    memcpy(out_tokens, tmp.data(), (size_t)N * 4);
+    SJD_TRY(sjd_decode_result(kv, out_tokens, stats));
     if (stats) {
-        stats->steps = st.steps;
-        for (int i = 0; i < 65; ++i) stats->accept_hist[i] = st.accept_hist[i];
         stats->ms_prefill = std::chrono::duration<float, std::milli>(t1 - t0).count();
         stats->ms_decode = std::chrono::duration<float, std::milli>(t2 - t1).count();
     }
     return SJD_OK;
+}
+
+// ---- per-kernel-class timing of eager iterations (HIP events on the launch stream) ------------
+extern "C" int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream)
+{
+    if (!m || !kv || kv->m != m || n_steps < 1 || !out || !kv->dec_active) return SJD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    memset(out, 0, sizeof(*out));
+    SjdProfiler prof;
+    prof.stream = s;
+    kv->prof = &prof;
+    int rc = SJD_OK;
+    for (int i = 0; i < n_steps && rc == SJD_OK; ++i) {
+        rc = decode_one(m, kv, s);
+        if (rc == SJD_OK) rc = prof.drain(out);
+    }
+    kv->prof = nullptr;
+    prof.destroy();
+    out->steps = n_steps;
+    return rc;
 }
 
 // ---- hooks ----------------------------------------------------------------------------------
@@ -559,7 +731,7 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     const size_t es = elt_size(dtype);
     void *Ap = nullptr, *Wp = nullptr; float *part = nullptr;
     struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &part};
-    SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * es));
+    SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * es * 2));   // lo plane stays zero
     HIP_TRY(hipMemcpyAsync(Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
     SjdLinear lin;
     lin.N = N; lin.K = K; lin.split_k = 1; lin.tn = 1; lin.w = W;

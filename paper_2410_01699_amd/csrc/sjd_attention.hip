@@ -14,13 +14,19 @@
 template <typename T> __device__ __forceinline__ float ld(const T *p, size_t i);
 template <> __device__ __forceinline__ float ld<float>(const float *p, size_t i) { return p[i]; }
 template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
-template <typename T> __device__ __forceinline__ void st_act(T *p, size_t i, float v);
-template <> __device__ __forceinline__ void st_act<float>(float *p, size_t i, float v) { p[i] = v; }
-template <> __device__ __forceinline__ void st_act<bf16_t>(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+// attention output feeds the O projection: bf16 models store it as hi/lo bf16 planes
+template <typename T> __device__ __forceinline__ void st_act(T *p, size_t plane, size_t i, float v);
+template <> __device__ __forceinline__ void st_act<float>(float *p, size_t, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void st_act<bf16_t>(bf16_t *p, size_t plane, size_t i, float v)
+{
+    const bf16_t hi = f32_to_bf16(v);
+    p[i] = hi;
+    p[plane + i] = f32_to_bf16(v - bf16_to_f32(hi));
+}
 
 // part layout per (head, split): [rows][hd] unnormalised output, then m[rows], then l[rows]
 template <typename T, int HD>
-__global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(const T *__restrict__ qact, const T *__restrict__ kc,
+__global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(const float *__restrict__ qact, const T *__restrict__ kc,
                                                                    const T *__restrict__ vc, int d, int max_seq,
                                                                    int rows, int v_transposed, int splits,
                                                                    float *__restrict__ part, const SjdState *st)
@@ -44,7 +50,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(const T *__re
 
     for (int e = tid; e < ROWS * HD; e += ATT_THREADS) {
         int r = e / HD, j = e % HD;
-        qs[r][j] = r < rows ? ld<T>(qact, (size_t)r * d + head * HD + j) * inv_sqrt : 0.f;
+        qs[r][j] = r < rows ? qact[(size_t)r * d + head * HD + j] * inv_sqrt : 0.f;
     }
     if (tid < ROWS) { m_run[tid] = -INFINITY; l_run[tid] = 0.f; }
     float acc[RPT];
@@ -139,7 +145,7 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, int splits, 
             num += w * p[r * HD + j];
             den += w * p[ROWS * HD + ROWS + r];
         }
-        st_act<T>(out, (size_t)r * d + head * HD + j, num / den);
+        st_act<T>(out, (size_t)ROWS * d, (size_t)r * d + head * HD + j, num / den);
     }
 }
 
@@ -163,7 +169,7 @@ static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows,
     const size_t per_layer = (size_t)ms * d;
     const int vt = m->cfg.dtype == 1;
     hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(H, kv->att_splits), dim3(ATT_THREADS), 0, s,
-                       (const T *)kv->qact, (const T *)kv->k + layer * per_layer, (const T *)kv->v + layer * per_layer,
+                       kv->qact, (const T *)kv->k + layer * per_layer, (const T *)kv->v + layer * per_layer,
                        d, ms, rows, vt, kv->att_splits, kv->att_part, kv->state);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(H), dim3(256), 0, s, kv->att_part, kv->att_splits, d, rows,
@@ -176,10 +182,12 @@ int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
 {
     const int hd = m->hd;
     if (m->cfg.dtype == 0) {
+        if (hd == 16) return launch_t<float, 16>(m, kv, layer, rows, s);
         if (hd == 32) return launch_t<float, 32>(m, kv, layer, rows, s);
         if (hd == 64) return launch_t<float, 64>(m, kv, layer, rows, s);
         if (hd == 128) return launch_t<float, 128>(m, kv, layer, rows, s);
     } else {
+        if (hd == 16) return launch_t<bf16_t, 16>(m, kv, layer, rows, s);
         if (hd == 32) return launch_t<bf16_t, 32>(m, kv, layer, rows, s);
         if (hd == 64) return launch_t<bf16_t, 64>(m, kv, layer, rows, s);
         if (hd == 128) return launch_t<bf16_t, 128>(m, kv, layer, rows, s);

@@ -6,7 +6,7 @@
 // bf16: W is pre-packed into 16x32 MFMA tiles (see SjdLinear) so that one wave-wide 16-byte-per-lane
 // load fetches 1 KiB of contiguous HBM and lands directly in the A-operand registers of
 // v_mfma_f32_16x16x32_bf16; the activations are the B operand (tokens along the 16 columns), read
-// from L2.  Each wave owns `TN` output tiles and one k-slice; slices write separate fp32 partial
+// from L2 as two bf16 planes (hi + lo, see the element-wise kernels) and multiplied separately.  Each wave owns `TN` output tiles and one k-slice; slices write separate fp32 partial
 // sums that the consuming element-wise kernel adds in a fixed order (deterministic, no atomics).
 // fp32: plain FMA dot products, one output feature per wave (used by the small fp32 models only).
 #include "sjd_internal.h"
@@ -42,13 +42,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     for (int tn = 0; tn < TN; ++tn)
         wbase[tn] = reinterpret_cast<const bf16x8 *>(Wp) + ((size_t)(group * TN + tn) * KT) * 64 + lane;
     const bf16_t *abase = A + (size_t)(lane & 15) * K + (lane >> 4) * 8;
+    const size_t plane = (size_t)SJD_ROWS_MAX * K;    // activations: hi plane, then lo plane
 
 #pragma unroll 4
     for (int kt = kt0; kt < kt1; ++kt) {
-        bf16x8 b[MT];
+        bf16x8 b[MT], bl[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
             b[mt] = *reinterpret_cast<const bf16x8 *>(abase + (size_t)mt * 16 * K + (size_t)kt * 32);
+            bl[mt] = *reinterpret_cast<const bf16x8 *>(abase + plane + (size_t)mt * 16 * K + (size_t)kt * 32);
+        }
         bf16x8 a[TN];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) a[tn] = __builtin_nontemporal_load(wbase[tn] + (size_t)kt * 64);
@@ -56,7 +59,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
+            {
                 acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tn], b[mt], acc[mt][tn], 0, 0, 0);
+                acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tn], bl[mt], acc[mt][tn], 0, 0, 0);
+            }
     }
 
     // D[i][j]: lane holds i = (l/16)*4 + 0..3 (output feature within the tile), j = l%16 (token)

@@ -84,10 +84,10 @@ struct sjd_kv {
     SjdState *state;      // device
     // ---- scratch for one forward over <= SJD_ROWS_MAX rows ----
     float *x;             // [rows][d] residual stream
-    void *h;              // [rows][d] normalised activations (GEMM input)
+    void *h;              // [rows][d] normalised activations (GEMM input; bf16: hi and lo planes)
     float *part;          // split-K partial outputs of the current GEMM
     size_t part_elems;
-    void *qact;           // [rows][d] rotated queries
+    float *qact;          // [rows][d] rotated queries (fp32)
     float *att_part;      // attention partials per (head, split): [rows][hd] + m,l
     int32_t att_splits;
     void *att_out;        // [rows][d]
@@ -106,6 +106,15 @@ struct sjd_kv {
     int32_t *g_nacc;      // [1]
     float *q_first;       // [V_s]
     int32_t n_upper;      // host-side upper bound of the device-resident n
+    // device-resident decoding loop (sjd_decode_*)
+    int32_t dec_active, dec_N, dec_L;
+    sjd_sampler dec_smp;
+    sjd_init dec_init;
+    uint64_t dec_seed;
+    int32_t use_graph;
+    hipGraph_t graph;
+    hipGraphExec_t graph_exec;
+    void *prof;           // SjdProfiler* while sjd_profile_steps runs, else NULL
 };
 
 // ---- kernel launchers (each returns SJD_OK or an SJD_E* code) --------------------------------
@@ -153,6 +162,7 @@ struct SjdVerifyArgs {
     void *snap;              // 32 bytes: per-step scalars frozen for the second kernel
 };
 int sjd_launch_verify(const SjdVerifyArgs *a, hipStream_t s);
+int sjd_sample_setup(int32_t V);   // raise the dynamic-LDS limit of the sampling kernels for vocabulary V
 int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_sampler *smp, const int32_t *forced,
                     float *q, hipStream_t s);
 int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t lo, const sjd_init *init,

@@ -5,14 +5,24 @@
 // layout they stream.
 #include "sjd_internal.h"
 
+// Element access per model dtype.  GEMM inputs of bf16 models are kept as TWO bf16 planes,
+// hi = bf16(v) and lo = bf16(v - hi) (`plane` elements apart): the GEMM multiplies the weight
+// tile with both, which keeps ~16 significant bits of the activations at no extra HBM traffic.
 template <typename T> struct Act;
 template <> struct Act<float> {
     __device__ static float load(const float *p, size_t i) { return p[i]; }
     __device__ static void store(float *p, size_t i, float v) { p[i] = v; }
+    __device__ static void store_split(float *p, size_t, size_t i, float v) { p[i] = v; }
 };
 template <> struct Act<bf16_t> {
     __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
     __device__ static void store(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+    __device__ static void store_split(bf16_t *p, size_t plane, size_t i, float v)
+    {
+        const bf16_t hi = f32_to_bf16(v);
+        p[i] = hi;
+        p[plane + i] = f32_to_bf16(v - bf16_to_f32(hi));
+    }
 };
 
 // x[r][:] = E[ids[r]][:]  (or the given raw embedding row)
@@ -29,7 +39,8 @@ __global__ void embed_kernel(const T *E, const int32_t *ids, const float *emb_ro
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *part, int n_part, size_t part_stride,
-                                                      const T *gain, int d, float eps, T *h, const SjdState *st)
+                                                      const T *gain, int d, float eps, T *h, size_t plane,
+                                                      const SjdState *st)
 {
     if (st->done) return;
     __shared__ float red[4];
@@ -47,14 +58,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *par
     __syncthreads();
     ss = red[0] + red[1] + red[2] + red[3];
     const float inv = rsqrtf(ss / (float)d + eps);
-    for (int j = threadIdx.x; j < d; j += 256) Act<T>::store(h, (size_t)r * d + j, xr[j] * inv * Act<T>::load(gain, j));
+    for (int j = threadIdx.x; j < d; j += 256) Act<T>::store_split(h, plane, (size_t)r * d + j, xr[j] * inv * Act<T>::load(gain, j));
 }
 
 // qkv[r][0:3d] = sum_p part[p][r][:];  rotate q and k (pairs j, j+hd/2) at position n+r;
 // q -> qact[r][d];  k -> K cache row n+r;  v -> V cache (bf16: transposed [head][hd][pos]).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kv_kernel(const float *part, int n_part, size_t part_stride, int d, int hd,
-                                                      int max_seq, const float *cosT, const float *sinT, T *qact,
+                                                      int max_seq, const float *cosT, const float *sinT, float *qact,
                                                       T *kc, T *vc, int v_transposed, int rows_valid,
                                                       const SjdState *st)
 {
@@ -74,8 +85,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *part, int n_p
             v0 += src[2 * d + c0]; v1 += src[2 * d + c1];
         }
         const float c = cosT[(size_t)pos * half + j], s = sinT[(size_t)pos * half + j];
-        Act<T>::store(qact, (size_t)r * d + c0, q0 * c - q1 * s);
-        Act<T>::store(qact, (size_t)r * d + c1, q1 * c + q0 * s);
+        qact[(size_t)r * d + c0] = q0 * c - q1 * s;
+        qact[(size_t)r * d + c1] = q1 * c + q0 * s;
         if (r < rows_valid) {
             Act<T>::store(kc, (size_t)pos * d + c0, k0 * c - k1 * s);
             Act<T>::store(kc, (size_t)pos * d + c1, k1 * c + k0 * s);
@@ -93,7 +104,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *part, int n_p
 // ffn[r][f] = SiLU(g) * u with g = sum_p part[p][r][f], u = sum_p part[p][r][F + f]
 template <typename T>
 __global__ __launch_bounds__(256) void silu_mul_kernel(const float *part, int n_part, size_t part_stride, int F, T *ffn,
-                                                       const SjdState *st)
+                                                       size_t plane, const SjdState *st)
 {
     if (st->done) return;
     const int r = blockIdx.y;
@@ -104,7 +115,7 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const float *part, int n_
         const float *src = part + (size_t)p * part_stride + (size_t)r * 2 * F;
         g += src[f]; u += src[F + f];
     }
-    Act<T>::store(ffn, (size_t)r * F + f, g / (1.0f + __expf(-g)) * u);
+    Act<T>::store_split(ffn, plane, (size_t)r * F + f, g / (1.0f + expf(-g)) * u);
 }
 
 // out[r][c] = sum_p part[p][r][c]
@@ -141,10 +152,10 @@ int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t 
     const int d = m->cfg.d_model;
     if (m->cfg.dtype == 0)
         hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
-                           (const float *)gain, d, m->cfg.rms_eps, (float *)h, st);
+                           (const float *)gain, d, m->cfg.rms_eps, (float *)h, (size_t)0, st);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
-                           (const bf16_t *)gain, d, m->cfg.rms_eps, (bf16_t *)h, st);
+                           (const bf16_t *)gain, d, m->cfg.rms_eps, (bf16_t *)h, (size_t)SJD_ROWS_MAX * d, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
@@ -156,11 +167,11 @@ int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const floa
     const size_t per_layer = (size_t)ms * d;
     if (m->cfg.dtype == 0)
         hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
-                           m->rope_cos, m->rope_sin, (float *)kv->qact, (float *)kv->k + layer * per_layer,
+                           m->rope_cos, m->rope_sin, kv->qact, (float *)kv->k + layer * per_layer,
                            (float *)kv->v + layer * per_layer, 0, rows_valid, kv->state);
     else
         hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
-                           m->rope_cos, m->rope_sin, (bf16_t *)kv->qact, (bf16_t *)kv->k + layer * per_layer,
+                           m->rope_cos, m->rope_sin, kv->qact, (bf16_t *)kv->k + layer * per_layer,
                            (bf16_t *)kv->v + layer * per_layer, 1, rows_valid, kv->state);
     LAUNCH_CHECK();
     return SJD_OK;
@@ -172,9 +183,10 @@ int sjd_launch_silu_mul(const sjd_model *m, const float *part, int32_t n_part, s
     const int F = m->cfg.d_ffn;
     dim3 grid((F + 255) / 256, rows);
     if (m->cfg.dtype == 0)
-        hipLaunchKernelGGL(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, st);
+        hipLaunchKernelGGL(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, (size_t)0, st);
     else
-        hipLaunchKernelGGL(silu_mul_kernel<bf16_t>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (bf16_t *)ffn, st);
+        hipLaunchKernelGGL(silu_mul_kernel<bf16_t>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (bf16_t *)ffn,
+                           (size_t)SJD_ROWS_MAX * F, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }

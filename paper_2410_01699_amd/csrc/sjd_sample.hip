@@ -550,9 +550,24 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const fl
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-static int ensure_lds(const void *fn, size_t bytes)
+// Dynamic LDS above the default limit has to be enabled per kernel.  The limit is only ever
+// raised, and sjd_sample_setup() raises it when a cache is created, so that launches recorded
+// during graph capture never need to touch function attributes.
+static size_t g_lds_set[3] = {0, 0, 0};
+static int ensure_lds(int which, const void *fn, size_t bytes)
 {
-    if (bytes > 48 * 1024) HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    if (bytes <= 48 * 1024 || bytes <= g_lds_set[which]) return SJD_OK;
+    HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    g_lds_set[which] = bytes;
+    return SJD_OK;
+}
+
+int sjd_sample_setup(int32_t V)
+{
+    const size_t lds = (size_t)V * 4;
+    SJD_TRY(ensure_lds(0, (const void *)sjd_rows_kernel, lds));
+    SJD_TRY(ensure_lds(1, (const void *)sjd_dist_kernel, lds));
+    SJD_TRY(ensure_lds(2, (const void *)sjd_first_window_kernel, lds));
     return SJD_OK;
 }
 
@@ -560,7 +575,7 @@ int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
 {
     if (v->V < 1 || v->V > SJD_MAX_SAMP_VOCAB || v->L < 1 || v->L > SJD_ROWS_MAX) return SJD_EINVAL;
     size_t lds = (size_t)v->V * 4;
-    SJD_TRY(ensure_lds((const void *)sjd_rows_kernel, lds));
+    SJD_TRY(ensure_lds(0, (const void *)sjd_rows_kernel, lds));
     RowsArgs r;
     r.logits = v->logits; r.q_in = v->q_in; r.p_old = v->p_old; r.draft = v->draft;
     r.L = v->L; r.V = v->V; r.lo = v->lo; r.smp = v->smp; r.init = v->init; r.seed = v->seed;
@@ -584,7 +599,7 @@ int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_samp
 {
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || rows < 1) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
-    SJD_TRY(ensure_lds((const void *)sjd_dist_kernel, lds));
+    SJD_TRY(ensure_lds(1, (const void *)sjd_dist_kernel, lds));
     hipLaunchKernelGGL(sjd_dist_kernel, dim3(rows), dim3(DIST_THREADS), lds, s, logits, V, *smp, forced, q);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
@@ -595,7 +610,7 @@ int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t 
 {
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
-    SJD_TRY(ensure_lds((const void *)sjd_first_window_kernel, lds));
+    SJD_TRY(ensure_lds(2, (const void *)sjd_first_window_kernel, lds));
     hipLaunchKernelGGL(sjd_first_window_kernel, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo, *init, seed,
                        draft, p_old);
     HIP_TRY(hipGetLastError());

@@ -106,7 +106,7 @@ _SHAPE_7B_LONG = _shape(32, 4096, 32, 11008, 65536, 57344, 65536, 64 + 2352 + 32
 
 WORKLOADS = {
     # Tiny: 2 layers, d=128, vocab 1024 all image codes, 8x8 grid.
-    "tiny": Workload("tiny", _shape(2, 128, 4, 512, 1024, 0, 1024, 16 + 64 + 8, DTYPE_F32),
+    "tiny": Workload("tiny", _shape(2, 128, 4, 512, 1024, 0, 1024, 16 + 64 + 32, DTYPE_F32),
                      16, 0, 64, 8, 64, 1.0, INIT_UNIFORM, 8, -1),
     # ~775M class-conditional style: 1 condition id + 120 embedding rows.
     "775m": Workload("775m", _shape(24, 1536, 24, 4096, 16384, 0, 16384, 121 + 1024 + 16, DTYPE_BF16),
