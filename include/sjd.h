@@ -186,6 +186,13 @@ int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sjd_sampler *
 int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_t N, int32_t K, float *C,
                   void *stream);
 
+/* Tuning aid: average microseconds per launch of the bf16 projection kernel (plain-store epilogue) at
+ * shape M x N x K with `tn` output tiles per workgroup, `wk` waves splitting K and `u` k-steps per
+ * prefetch stage, over `iters` back-to-back launches on zero-filled operands.  SJD_EINVAL for a
+ * combination that is not compiled in.                                                          */
+int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32_t wk, int32_t u, int32_t iters,
+                   float *us_per_launch);
+
 const char *sjd_strerror(int code);
 
 #ifdef __cplusplus

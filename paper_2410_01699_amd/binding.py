@@ -21,7 +21,7 @@ SJD_MAX_SAMP_VOCAB = 32768
 EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "sjd_kv_reset", "sjd_kv_len",
            "sjd_kv_set_len", "sjd_prefill", "sjd_first_window", "sjd_step", "sjd_generate", "sjd_forward_logits",
            "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror", "sjd_decode_begin",
-           "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps"]
+           "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps", "sjd_gemm_bench"]
 
 PROF_KINDS = ("gemm", "attention", "elementwise", "verify")
 
@@ -90,6 +90,7 @@ _SIG = {
     "sjd_decode_result": (C.c_int, [_vp, _vp, _P(sjd_stats)]),
     "sjd_kv_use_graph": (C.c_int, [_vp, _i32]),
     "sjd_profile_steps": (C.c_int, [_vp, _vp, _i32, _P(sjd_profile), _vp]),
+    "sjd_gemm_bench": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _P(C.c_float)]),
 }
 for _name, (_res, _args) in _SIG.items():
     _fn = getattr(_lib, _name)
@@ -249,3 +250,10 @@ def sjd_profile_steps(m, kv, n_steps, stream=None) -> sjd_profile:
     p = sjd_profile()
     _check(_lib.sjd_profile_steps(m, kv, n_steps, C.byref(p), _stream(stream)))
     return p
+
+
+def sjd_gemm_bench(M, N, K, tn, wk, u, iters=50) -> float:
+    """microseconds per launch of the bf16 projection kernel at this shape and tiling"""
+    us = C.c_float(0)
+    _check(_lib.sjd_gemm_bench(M, N, K, tn, wk, u, iters, C.byref(us)))
+    return us.value

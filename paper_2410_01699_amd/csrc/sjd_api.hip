@@ -52,7 +52,8 @@ static int check_config(const sjd_config *c)
     if (c->max_seq < 2) return SJD_EINVAL;
     if (c->dtype != 0 && c->dtype != 1) return SJD_EINVAL;
     if (c->dtype == 0 && (c->d_model % 4 || c->d_ffn % 4)) return SJD_EINVAL;
-    if (c->dtype == 1 && (c->d_model % 32 || c->d_ffn % 32 || (c->samp_hi - c->samp_lo) % 16)) return SJD_EINVAL;
+    if (c->dtype == 1 && (c->d_model % 32 || c->d_ffn % 32 || (c->samp_hi - c->samp_lo) % 16 || c->d_model > 8192))
+        return SJD_EINVAL;
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return SJD_EINVAL;
     return SJD_OK;
 }
@@ -114,8 +115,8 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
         return db + off * es;
     };
     // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
-    auto linear = [&](size_t off, int N, int K, SjdLinear *lin) -> int {
-        lin->N = N; lin->K = K; lin->split_k = 1; lin->tn = 1;
+    auto linear = [&](size_t off, int N, int K, int perm, SjdLinear *lin) -> int {
+        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 8; lin->u = 4;
         lin->w = db + off * es;
         const size_t n = (size_t)N * K;
         if (cfg->dtype == 0) {
@@ -123,9 +124,9 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
             return SJD_OK;
         }
         HIP_TRY(hipMemcpy(stage, hb + off * es, n * es, hipMemcpyHostToDevice));
-        SJD_TRY(sjd_repack_bf16((const bf16_t *)stage, (bf16_t *)(db + off * es), N, K, 0));
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)stage, (bf16_t *)(db + off * es), N, K, perm, (int)d, m->hd, 0));
         HIP_TRY(hipDeviceSynchronize());
-        sjd_choose_split(lin);
+        sjd_choose_tiles(lin);
         return SJD_OK;
     };
 
@@ -136,20 +137,20 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
         SjdLayer *L = &m->layers[l];
         L->g1 = plain(off, d); if (!L->g1) return fail(SJD_EHIP);
         off += d;
-        rc = linear(off, (int)(3 * d), (int)d, &L->qkv); if (rc) return fail(rc);
+        rc = linear(off, (int)(3 * d), (int)d, 1, &L->qkv); if (rc) return fail(rc);
         off += 3 * d * d;
-        rc = linear(off, (int)d, (int)d, &L->o); if (rc) return fail(rc);
+        rc = linear(off, (int)d, (int)d, 0, &L->o); if (rc) return fail(rc);
         off += d * d;
         L->g2 = plain(off, d); if (!L->g2) return fail(SJD_EHIP);
         off += d;
-        rc = linear(off, (int)(2 * f), (int)d, &L->gu); if (rc) return fail(rc);
+        rc = linear(off, (int)(2 * f), (int)d, 2, &L->gu); if (rc) return fail(rc);
         off += 2 * f * d;
-        rc = linear(off, (int)d, (int)f, &L->down); if (rc) return fail(rc);
+        rc = linear(off, (int)d, (int)f, 0, &L->down); if (rc) return fail(rc);
         off += d * f;
     }
     m->gf = plain(off, d); if (!m->gf) return fail(SJD_EHIP);
     off += d;
-    rc = linear(off + (size_t)cfg->samp_lo * d, m->V_s, (int)d, &m->lm); if (rc) return fail(rc);
+    rc = linear(off + (size_t)cfg->samp_lo * d, m->V_s, (int)d, 0, &m->lm); if (rc) return fail(rc);
     if (stage) { (void)hipFree(stage); stage = nullptr; }
 
     // RoPE tables in fp64 on the host, rounded once to fp32: angle = pos * theta^(-2j/hd)
@@ -196,7 +197,7 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     const sjd_config &c = m->cfg;
     const size_t es = elt_size(c.dtype), d = c.d_model, F = c.d_ffn, V = m->V_s, R = SJD_ROWS_MAX;
     size_t part = 0;
-    auto upd = [&](const SjdLinear &l) { part = std::max(part, (size_t)l.split_k * R * l.N); };
+    auto upd = [&](const SjdLinear &l) { part = std::max(part, (size_t)R * l.N); };
     for (int l = 0; l < c.n_layers; ++l) { upd(m->layers[l].qkv); upd(m->layers[l].o); upd(m->layers[l].gu); upd(m->layers[l].down); }
     upd(m->lm);
     kv->part_elems = part;
@@ -328,30 +329,66 @@ struct SjdProfiler {
 // rows = rows computed (<= 32), rows_valid = rows whose K/V are written.  Inputs already in kv->x.
 static double lin_bytes(const sjd_model *m, const SjdLinear &l) { return (double)l.N * l.K * elt_size(m->cfg.dtype); }
 
-static int forward_rows(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
 {
-    const int dt = m->cfg.dtype;
     const SjdState *st = kv->state;
-    const SjdLinear *prev = nullptr;   // GEMM whose partial sums still have to be added to x
-    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * m->cfg.d_model * elt_size(dt);   // upper bound
+    const SjdLinear *prev = nullptr;   // GEMM whose output still has to be added to x
+    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * m->cfg.d_model * 4;   // upper bound
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? prev->split_k : 0,
-                                   prev ? sjd_part_stride(prev, rows) : 0, L.g1, rows, kv->h, st, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm(dt, &L.qkv, kv->h, rows, kv->part, st, s));
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rope_kv(m, kv, l, kv->part, L.qkv.split_k, sjd_part_stride(&L.qkv, rows), rows, rows_valid, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? 1 : 0, 0, L.g1, rows, kv->h, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm(0, &L.qkv, kv->h, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rope_kv(m, kv, l, kv->part, 1, 0, rows, rows_valid, s));
         PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm(dt, &L.o, kv->att_out, rows, kv->part, st, s));
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, L.o.split_k, sjd_part_stride(&L.o, rows), L.g2, rows, kv->h, st, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm(dt, &L.gu, kv->h, rows, kv->part, st, s));
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_silu_mul(m, kv->part, L.gu.split_k, sjd_part_stride(&L.gu, rows), rows, kv->ffn, st, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm(dt, &L.down, kv->ffn, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm(0, &L.o, kv->att_out, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, 1, 0, L.g2, rows, kv->h, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm(0, &L.gu, kv->h, rows, kv->part, st, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_silu_mul(m, kv->part, 1, 0, rows, kv->ffn, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm(0, &L.down, kv->ffn, rows, kv->part, st, s));
         prev = &L.down;
     }
-    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, prev->split_k, sjd_part_stride(prev, rows), m->gf, rows, kv->h, st, s));
-    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm(dt, &m->lm, kv->h, rows, kv->part, st, s));
-    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_reduce_rows(kv->part, m->lm.split_k, sjd_part_stride(&m->lm, rows), rows, m->V_s, logits, st, s));
+    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, 1, 0, m->gf, rows, kv->h, st, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm(0, &m->lm, kv->h, rows, logits, st, s));
     return SJD_OK;
+}
+
+// bf16: residual adds, SiLU*up, RoPE and the cache write happen inside the GEMM epilogues
+static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+{
+    const SjdState *st = kv->state;
+    const int d = m->cfg.d_model, F = m->cfg.d_ffn, ms = m->cfg.max_seq;
+    const size_t per_layer = (size_t)ms * d;
+    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * d * 2;   // upper bound
+    SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
+    memset(&e_qkv, 0, sizeof(e_qkv));
+    e_qkv.st = st;
+    e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
+    e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
+    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.max_seq = ms; e_qkv.rows_valid = rows_valid;
+    e_res.kind = SJD_EPI_RESID; e_res.out = kv->x;
+    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (bf16_t *)kv->ffn; e_silu.ffn_plane = (size_t)SJD_ROWS_MAX * F; e_silu.F = F;
+    e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+        const SjdLayer &L = m->layers[l];
+        e_qkv.kc = (bf16_t *)kv->k + l * per_layer;
+        e_qkv.vc = (bf16_t *)kv->v + l * per_layer;
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, L.g1, rows, kv->h, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, (const bf16_t *)kv->h, rows, e_qkv, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, (const bf16_t *)kv->att_out, rows, e_res, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, L.g2, rows, kv->h, st, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, (const bf16_t *)kv->h, rows, e_silu, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, (const bf16_t *)kv->ffn, rows, e_res, s));
+    }
+    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, m->gf, rows, kv->h, st, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, (const bf16_t *)kv->h, rows, e_lm, s));
+    return SJD_OK;
+}
+
+static int forward_rows(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+{
+    return m->cfg.dtype == 0 ? forward_rows_f32(m, kv, rows, rows_valid, logits, s)
+                             : forward_rows_bf16(m, kv, rows, rows_valid, logits, s);
 }
 
 // n lives on the device; the host keeps an upper bound and only synchronises to refresh it when
@@ -729,21 +766,59 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     if (dtype == 0 && K % 4) return SJD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     const size_t es = elt_size(dtype);
-    void *Ap = nullptr, *Wp = nullptr; float *part = nullptr;
-    struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &part};
+    void *Ap = nullptr, *Wp = nullptr; float *out = nullptr;
+    struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &out};
     SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * es * 2));   // lo plane stays zero
     HIP_TRY(hipMemcpyAsync(Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
+    SJD_TRY(dev_alloc((void **)&out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.split_k = 1; lin.tn = 1; lin.w = W;
+    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 8; lin.u = 4; lin.w = W;
     if (dtype == 1) {
         SJD_TRY(dev_alloc(&Wp, (size_t)N * K * es));
-        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)Wp, N, K, s));
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)Wp, N, K, 0, 0, 0, s));
         lin.w = Wp;
-        sjd_choose_split(&lin);
+        sjd_choose_tiles(&lin);
+        SjdGemmEpi ep;
+        memset(&ep, 0, sizeof(ep));
+        ep.kind = SJD_EPI_STORE; ep.out = out;
+        SJD_TRY(sjd_launch_gemm_bf16(&lin, (const bf16_t *)Ap, M, ep, s));
+    } else {
+        SJD_TRY(sjd_launch_gemm(0, &lin, Ap, M, out, nullptr, s));
     }
-    SJD_TRY(dev_alloc((void **)&part, (size_t)lin.split_k * SJD_ROWS_MAX * N * 4));
-    SJD_TRY(sjd_launch_gemm(dtype, &lin, Ap, M, part, nullptr, s));
-    SJD_TRY(sjd_launch_reduce_rows(part, lin.split_k, dtype == 1 ? sjd_part_stride(&lin, M) : 0, M, N, C, nullptr, s));
+    HIP_TRY(hipMemcpyAsync(C, out, (size_t)M * N * 4, hipMemcpyDeviceToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     return SJD_OK;
+}
+
+extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32_t wk, int32_t u, int32_t iters,
+                              float *us_per_launch)
+{
+    if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters == 0 || !us_per_launch) return SJD_EINVAL;
+    if (tn < 1 || N % (16 * tn)) return SJD_EINVAL;
+    void *Ap = nullptr, *Wp = nullptr; float *out = nullptr;
+    struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &out};
+    SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * 2 * 2));
+    SJD_TRY(dev_alloc(&Wp, (size_t)N * K * 2));
+    SJD_TRY(dev_alloc((void **)&out, (size_t)SJD_ROWS_MAX * N * 4));
+    SjdLinear lin;
+    lin.N = N; lin.K = K; lin.tn = tn; lin.wk = wk; lin.u = u; lin.w = Wp;
+    SjdGemmEpi ep;
+    memset(&ep, 0, sizeof(ep));
+    ep.kind = SJD_EPI_STORE; ep.out = out;
+    if (iters < 0) { ep.F = 1; iters = -iters; }   // negative count: time the single-plane variant
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
+    int rc = SJD_OK;
+    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_gemm_bench_launch(&lin, (const bf16_t *)Ap, M, ep, wk, u, 0);
+    if (rc == SJD_OK) {
+        (void)hipEventRecord(e0, 0);
+        for (int i = 0; i < iters && rc == SJD_OK; ++i) rc = sjd_gemm_bench_launch(&lin, (const bf16_t *)Ap, M, ep, wk, u, 0);
+        (void)hipEventRecord(e1, 0);
+        (void)hipEventSynchronize(e1);
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        *us_per_launch = ms * 1e3f / iters;
+    }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    return rc;
 }

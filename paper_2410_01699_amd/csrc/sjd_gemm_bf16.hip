@@ -1,0 +1,274 @@
+// bf16 skinny-M projections of the window forward (paper Sec. 4.1 Step 2) with fused epilogues.
+//
+// C[M x N] = A[M x K] * W^T, M = window size (16 or 32 rows), is a pure weight stream: every weight
+// is read from HBM once and used for M multiply-adds (about M flop per byte, far left of the MFMA
+// ridge), so the design goal is HBM bandwidth, not matrix-core throughput.
+//
+//  - W is pre-packed (sjd_repack_bf16) into 16x32 tiles in the exact A-operand register order of
+//    v_mfma_f32_16x16x32_bf16: one 16-byte load per lane fetches 1 KiB of contiguous HBM per wave.
+//  - One workgroup owns TN output tiles (16*TN features) for the WHOLE reduction; its WK waves
+//    split K between them and add their fp32 accumulators through LDS in a fixed order.  No
+//    global partial sums, no atomics: results are deterministic and the epilogue sees final values.
+//  - Each wave keeps U k-steps of loads in flight ahead of the MFMAs (register double buffering).
+//  - The activations are the B operand (tokens on the 16 columns), read from L2 as two bf16 planes
+//    hi + lo (see sjd_layers.hip) and multiplied separately: ~16 significant bits of activation at
+//    no extra HBM traffic.
+//  - Epilogues: plain store (LM head logits), residual add into the fp32 stream (O and down
+//    projections), SiLU(gate)*up (gate and up rows are interleaved inside each tile when packed, so a
+//    lane holds both), RoPE + KV-cache write (Q/K rows of a head are packed as (j, j+hd/2) pairs, so
+//    the rotation is lane-local).
+#include "sjd_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int MT, int TN, int WK, int U, int EPI, int PLANES = 2>
+__global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__restrict__ Wp,
+                                                            const bf16_t *__restrict__ A, int N, int K,
+                                                            SjdGemmEpi ep)
+{
+    if (ep.st && ep.st->done) return;
+    __shared__ f32x4 red[WK][MT * TN][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tile0 = blockIdx.x * TN;
+    const int KT = K / 32;
+    const int kps = (KT + WK - 1) / WK;
+    const int kt0 = wave * kps;
+    const int kt1 = min(KT, kt0 + kps);
+
+    f32x4 acc[MT][TN];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) acc[mt][tn] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)tile0 * KT * 64 + lane;
+    const size_t tile_stride = (size_t)KT * 64;                 // in 16-byte units
+    const bf16_t *ab = A + (size_t)(lane & 15) * K + (lane >> 4) * 8;
+    const size_t plane = (size_t)SJD_ROWS_MAX * K;
+
+    bf16x8 a0[U][TN], a1[U][TN], b0[U][MT][2], b1[U][MT][2];
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+
+#define LOAD_STAGE(kbase, a, b)                                                                   \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                               \
+        const int kq_ = (kbase) + u;                                                              \
+        if (kq_ < kt1) {                                                                           \
+            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                     \
+                a[u][tn] = __builtin_nontemporal_load(wp + (size_t)tn * tile_stride + (size_t)kq_ * 64); \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
+                const bf16_t *p = ab + (size_t)mt * 16 * K + (size_t)kq_ * 32;                    \
+                b[u][mt][0] = *reinterpret_cast<const bf16x8 *>(p);                               \
+                if (PLANES == 2) b[u][mt][1] = *reinterpret_cast<const bf16x8 *>(p + plane);      \
+            }                                                                                     \
+        } else {                                                                                  \
+            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) a[u][tn] = zero;                    \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) { b[u][mt][0] = zero; b[u][mt][1] = zero; } \
+        }                                                                                         \
+    }
+#define MMA_STAGE(a, b)                                                                           \
+    _Pragma("unroll") for (int u = 0; u < U; ++u)                                                 \
+        _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                         \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
+                acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][mt][0], acc[mt][tn], 0, 0, 0); \
+                if (PLANES == 2) acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][mt][1], acc[mt][tn], 0, 0, 0); \
+            }
+
+    LOAD_STAGE(kt0, a0, b0)
+    for (int kt = kt0; kt < kt1; kt += 2 * U) {
+        LOAD_STAGE(kt + U, a1, b1)
+        MMA_STAGE(a0, b0)
+        LOAD_STAGE(kt + 2 * U, a0, b0)
+        MMA_STAGE(a1, b1)
+    }
+#undef LOAD_STAGE
+#undef MMA_STAGE
+
+    // add the WK accumulators in wave order (fixed order -> deterministic)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) red[wave][mt * TN + tn][lane] = acc[mt][tn];
+    __syncthreads();
+    for (int unit = threadIdx.x; unit < MT * TN * 64; unit += 64 * WK) {
+        const int mtn = unit >> 6, l = unit & 63;
+        f32x4 v = red[0][mtn][l];
+#pragma unroll
+        for (int w = 1; w < WK; ++w) v += red[w][mtn][l];
+        // D layout: lane l holds features (l/16)*4 + 0..3 of the tile for token l%16
+        const int mt = mtn / TN, tn = mtn % TN;
+        const int m = mt * 16 + (l & 15);
+        const int n0 = (tile0 + tn) * 16 + (l >> 4) * 4;        // packed feature index of v[0]
+        if (EPI == SJD_EPI_STORE) {
+            *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
+        } else if (EPI == SJD_EPI_RESID) {
+            f32x4 *x = reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0);
+            *x = *x + v;
+        } else if (EPI == SJD_EPI_SILU) {
+            // packed rows: (gate f, up f, gate f+1, up f+1)
+            const int f = n0 >> 1;
+            const float y0 = v[0] / (1.0f + __expf(-v[0])) * v[1];
+            const float y1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
+            const size_t o = (size_t)m * ep.F + f;
+            const bf16_t h0 = f32_to_bf16(y0), h1 = f32_to_bf16(y1);
+            *reinterpret_cast<uint32_t *>(ep.ffn + o) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            *reinterpret_cast<uint32_t *>(ep.ffn + ep.ffn_plane + o) =
+                (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
+        } else {   // SJD_EPI_QKV
+            const int d = ep.d, hd = ep.hd, half = hd >> 1;
+            const int pos = ep.st->n + m;
+            if (n0 < 2 * d) {
+                // Q or K: packed order inside a head is (j, j+half, j+1, j+1+half, ...)
+                const int is_k = n0 >= d;
+                const int c = n0 - (is_k ? d : 0);
+                const int head = c / hd, j = (c % hd) >> 1;
+                const float c0 = ep.cosT[(size_t)pos * half + j], s0 = ep.sinT[(size_t)pos * half + j];
+                const float c1 = ep.cosT[(size_t)pos * half + j + 1], s1 = ep.sinT[(size_t)pos * half + j + 1];
+                const float r0 = v[0] * c0 - v[1] * s0, r0p = v[1] * c0 + v[0] * s0;   // dims j, j+half
+                const float r1 = v[2] * c1 - v[3] * s1, r1p = v[3] * c1 + v[2] * s1;   // dims j+1, j+1+half
+                const int col = head * hd + j;
+                if (!is_k) {
+                    float *q = ep.qact + (size_t)m * d + col;
+                    q[0] = r0; q[1] = r1; q[half] = r0p; q[half + 1] = r1p;
+                } else if (m < ep.rows_valid) {
+                    bf16_t *k = ep.kc + (size_t)pos * d + col;
+                    *reinterpret_cast<uint32_t *>(k) = (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16);
+                    *reinterpret_cast<uint32_t *>(k + half) = (uint32_t)f32_to_bf16(r0p) | ((uint32_t)f32_to_bf16(r1p) << 16);
+                }
+            } else if (m < ep.rows_valid) {
+                // V: natural order, cache is transposed [feature][position]
+                const int col = n0 - 2 * d;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ep.vc[(size_t)(col + r) * ep.max_seq + pos] = f32_to_bf16(v[r]);
+            }
+        }
+    }
+}
+
+// row-major [N][K] bf16 -> MFMA streaming order, packed row n' taken from source row perm(n')
+//   perm 0: identity
+//   perm 1: rows [0, 2d) (Q then K) reordered inside each head to (j, j+hd/2) pairs; rest identity
+//   perm 2: N = 2F, packed (gate f, up f) interleaved: n' even -> row n'/2, odd -> row F + n'/2
+__global__ void repack_bf16_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int K, int perm,
+                                   int d, int hd)
+{
+    const int KT = K / 32;
+    const size_t total = (size_t)N * K / 8;   // 16-byte groups
+    for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (size_t)gridDim.x * blockDim.x) {
+        const int l = (int)(g & 63);
+        const size_t tile = g >> 6;
+        const int kt = (int)(tile % KT);
+        const size_t nt = tile / KT;
+        size_t np = nt * 16 + (l & 15), row = np;
+        if (perm == 1 && np < (size_t)2 * d) {
+            const size_t region = np / d * d, c = np % d;
+            const size_t head = c / hd, p = c % hd;
+            row = region + head * hd + (p >> 1) + ((p & 1) ? hd / 2 : 0);
+        } else if (perm == 2) {
+            row = (np >> 1) + ((np & 1) ? (size_t)N / 2 : 0);
+        }
+        const bf16_t *s = src + row * (size_t)K + (size_t)kt * 32 + (l >> 4) * 8;
+        reinterpret_cast<uint4 *>(dst)[g] = *reinterpret_cast<const uint4 *>(s);
+    }
+}
+
+int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t perm, int32_t d,
+                    int32_t hd, hipStream_t s)
+{
+    if (N % 16 || K % 32) return SJD_EINVAL;
+    if (perm == 1 && (hd % 8 || d % hd || N < 2 * d)) return SJD_EINVAL;
+    if (perm == 2 && N % 32) return SJD_EINVAL;
+    hipLaunchKernelGGL(repack_bf16_kernel, dim3(2048), dim3(256), 0, s, src_dev, dst_dev, N, K, perm, d, hd);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+// Tiles per workgroup: fill the 256 CUs evenly.  Prefer the largest TN (fewest re-reads of the
+// activations) among those whose workgroup count wastes the least of the last round.
+void sjd_choose_tiles(SjdLinear *lin)
+{
+    const int tiles = lin->N / 16;
+    int best_tn = 1;
+    double best_eff = -1.0;
+    for (int tn = 1; tn <= 4; ++tn) {
+        if (tiles % tn) continue;
+        const int blocks = tiles / tn;
+        if (blocks < 256 && tn > 1) continue;
+        const double eff = (double)blocks / (256.0 * ((blocks + 255) / 256));
+        if (eff > best_eff + 0.02 || (eff > best_eff - 0.02 && tn > best_tn)) {
+            if (eff > best_eff) best_eff = eff;
+            best_tn = tn;
+        }
+    }
+    lin->tn = best_tn;
+    lin->wk = 8;
+    lin->u = 4;
+}
+
+template <int MT, int TN, int WK, int U>
+static int launch_epi(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, hipStream_t s)
+{
+    dim3 grid(lin->N / (16 * TN)), block(64 * WK);
+    const bf16_t *W = (const bf16_t *)lin->w;
+    switch (ep.kind) {
+        case SJD_EPI_STORE: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+        case SJD_EPI_RESID: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_RESID>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+        case SJD_EPI_SILU: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_SILU>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+        case SJD_EPI_QKV: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_QKV>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+        default: return SJD_EINVAL;
+    }
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s)
+{
+    if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
+    const int mt = rows <= 16 ? 1 : 2;
+#define CASE(MT, TN) if (mt == MT && lin->tn == TN) return launch_epi<MT, TN, 8, 4>(lin, act, ep, s)
+    CASE(1, 1); CASE(1, 2); CASE(1, 3); CASE(1, 4);
+    CASE(2, 1); CASE(2, 2); CASE(2, 3); CASE(2, 4);
+#undef CASE
+    return SJD_EINVAL;
+}
+
+// ---- tuning hook: time the plain-store kernel at a given shape and tiling ----------------------
+template <int MT, int TN, int WK, int U>
+static int launch_store(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, hipStream_t s)
+{
+    if constexpr (WK * MT * TN * 1024 <= 65536) {
+        dim3 grid(lin->N / (16 * TN)), block(64 * WK);
+        if (ep.F == 1)   // tuning only: hi plane alone
+            hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE, 1>), grid, block, 0, s, (const bf16_t *)lin->w,
+                               act, lin->N, lin->K, ep);
+        else
+        hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE>), grid, block, 0, s, (const bf16_t *)lin->w, act,
+                           lin->N, lin->K, ep);
+        HIP_TRY(hipGetLastError());
+        return SJD_OK;
+    } else {
+        return SJD_EINVAL;
+    }
+}
+
+template <int MT, int TN>
+static int bench_variant(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, int wk, int u, hipStream_t s)
+{
+#define V(WK, UU) if (wk == WK && u == UU) return launch_store<MT, TN, WK, UU>(lin, act, ep, s)
+    V(4, 4); V(4, 8); V(8, 2); V(8, 4); V(8, 8); V(16, 2); V(16, 4);
+#undef V
+    return SJD_EINVAL;
+}
+
+int sjd_gemm_bench_launch(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, int wk, int u,
+                          hipStream_t s)
+{
+    const int mt = rows <= 16 ? 1 : 2;
+    if (lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
+#define CASE(MT, TN) if (mt == MT && lin->tn == TN) return bench_variant<MT, TN>(lin, act, ep, wk, u, s)
+    CASE(1, 1); CASE(1, 2); CASE(1, 3); CASE(1, 4);
+    CASE(2, 1); CASE(2, 2); CASE(2, 4);
+#undef CASE
+    return SJD_EINVAL;
+}

@@ -35,6 +35,20 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return (bf16_t)(u >> 16);
 }
 
+// Device-resident decoding state: everything that changes from step to step, so that a step can
+// be enqueued (or replayed from a graph) without the host knowing the outcome of the last one.
+struct SjdState {
+    int32_t n;          // cache length (prompt + accepted tokens)
+    int32_t img_pos0;   // image index of window slot 0
+    int32_t L_eff;      // slots of the window in use this step
+    int32_t n_snap;     // n at the start of the step (stable while the step runs)
+    uint64_t counter;   // Philox step counter
+    int32_t n_image;    // N, image tokens to produce (generate loop; 0 = unbounded single steps)
+    int32_t done;       // generation finished: later steps are no-ops
+    int32_t steps;      // window forwards executed
+    int32_t accept_hist[65];
+};
+
 // ---- one linear layer's weights ------------------------------------------------------------
 // fp32 models keep W as given ([N][K] row-major).  bf16 models hold W in MFMA streaming order:
 // tiles of 16 output features x 32 input features, tile (nt, kt) at ((nt * K/32) + kt) * 512
@@ -43,8 +57,23 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 struct SjdLinear {
     const void *w;
     int32_t N, K;
-    int32_t split_k;  // k-slices whose partial sums the consumer adds up (bf16 path)
-    int32_t tn;       // 16-wide output tiles per wave (bf16 path)
+    int32_t tn;       // bf16: 16-wide output tiles per workgroup
+    int32_t wk;       // bf16: waves per workgroup splitting K
+    int32_t u;        // bf16: k-steps per prefetch stage
+};
+
+// what the bf16 GEMM does with its final fp32 values
+#define SJD_EPI_STORE 0   // out[m][n] = v
+#define SJD_EPI_RESID 1   // out[m][n] += v                       (residual stream)
+#define SJD_EPI_SILU 2    // ffn[m][f] = SiLU(gate) * up          (rows packed gate/up interleaved)
+#define SJD_EPI_QKV 3     // RoPE on q,k at position n+m; q -> qact, k,v -> cache
+struct SjdGemmEpi {
+    int32_t kind;
+    const SjdState *st;          // device state (n, done); may be NULL for STORE
+    float *out;                  // STORE / RESID: [rows][N]
+    bf16_t *ffn; size_t ffn_plane; int32_t F;                     // SILU
+    float *qact; bf16_t *kc, *vc; const float *cosT, *sinT;       // QKV
+    int32_t d, hd, max_seq, rows_valid;
 };
 
 struct SjdLayer {
@@ -61,20 +90,6 @@ struct sjd_model {
     SjdLinear lm;         // rows samp_lo..samp_hi of the LM head
     SjdLayer *layers;     // host array
     float *rope_cos, *rope_sin;  // [max_seq][hd/2]
-};
-
-// Device-resident decoding state: everything that changes from step to step, so that a step can
-// be enqueued (or replayed from a graph) without the host knowing the outcome of the last one.
-struct SjdState {
-    int32_t n;          // cache length (prompt + accepted tokens)
-    int32_t img_pos0;   // image index of window slot 0
-    int32_t L_eff;      // slots of the window in use this step
-    int32_t n_snap;     // n at the start of the step (stable while the step runs)
-    uint64_t counter;   // Philox step counter
-    int32_t n_image;    // N, image tokens to produce (generate loop; 0 = unbounded single steps)
-    int32_t done;       // generation finished: later steps are no-ops
-    int32_t steps;      // window forwards executed
-    int32_t accept_hist[65];
 };
 
 struct sjd_kv {
@@ -131,9 +146,14 @@ int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride
                            float *out, const SjdState *st, hipStream_t s);
 int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_t rows, float *part,
                     const SjdState *st, hipStream_t s);
-size_t sjd_part_stride(const SjdLinear *lin, int32_t rows);
-int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, hipStream_t s);
-void sjd_choose_split(SjdLinear *lin);
+int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t perm, int32_t d,
+                    int32_t hd, hipStream_t s);
+void sjd_choose_tiles(SjdLinear *lin);
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s);
+int sjd_gemm_bench_launch(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, int wk, int u,
+                          hipStream_t s);
+int sjd_launch_norm_bf16(const sjd_model *m, const float *x, const void *gain, int32_t rows, void *h,
+                         const SjdState *st, hipStream_t s);
 int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s);
 int32_t sjd_attention_splits(const sjd_model *m);
 size_t sjd_attention_part_elems(const sjd_model *m);

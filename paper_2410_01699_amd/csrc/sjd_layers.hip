@@ -61,6 +61,49 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *par
     for (int j = threadIdx.x; j < d; j += 256) Act<T>::store_split(h, plane, (size_t)r * d + j, xr[j] * inv * Act<T>::load(gain, j));
 }
 
+// bf16 models: h[r] = RMSNorm(x[r]) as hi/lo bf16 planes, one 1024-thread workgroup per row with the
+// row held in registers (d <= 8192); the residual adds already happened in the GEMM epilogues.
+__global__ __launch_bounds__(1024) void norm_bf16_kernel(const float *__restrict__ x, const bf16_t *__restrict__ gain,
+                                                          int d, float eps, bf16_t *__restrict__ h, size_t plane,
+                                                          const SjdState *st)
+{
+    if (st->done) return;
+    __shared__ float red[16];
+    const int r = blockIdx.x, t = threadIdx.x;
+    const float4 *xr = reinterpret_cast<const float4 *>(x + (size_t)r * d);
+    float4 v[2];
+    float ss = 0.f;
+    const int n4 = d / 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = t + i * 1024;
+        v[i] = c < n4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((t & 63) == 0) red[t >> 6] = ss;
+    __syncthreads();
+    ss = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) ss += red[w];
+    const float inv = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = t + i * 1024;
+        if (c >= n4) continue;
+        const uint2 g = reinterpret_cast<const uint2 *>(gain)[c];
+        const float y0 = v[i].x * inv * __uint_as_float(g.x << 16), y1 = v[i].y * inv * __uint_as_float(g.x & 0xFFFF0000u);
+        const float y2 = v[i].z * inv * __uint_as_float(g.y << 16), y3 = v[i].w * inv * __uint_as_float(g.y & 0xFFFF0000u);
+        const bf16_t h0 = f32_to_bf16(y0), h1 = f32_to_bf16(y1), h2 = f32_to_bf16(y2), h3 = f32_to_bf16(y3);
+        uint2 hi, lo;
+        hi.x = (uint32_t)h0 | ((uint32_t)h1 << 16); hi.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
+        lo.x = (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
+        lo.y = (uint32_t)f32_to_bf16(y2 - bf16_to_f32(h2)) | ((uint32_t)f32_to_bf16(y3 - bf16_to_f32(h3)) << 16);
+        reinterpret_cast<uint2 *>(h + (size_t)r * d)[c] = hi;
+        reinterpret_cast<uint2 *>(h + plane + (size_t)r * d)[c] = lo;
+    }
+}
+
 // qkv[r][0:3d] = sum_p part[p][r][:];  rotate q and k (pairs j, j+hd/2) at position n+r;
 // q -> qact[r][d];  k -> K cache row n+r;  v -> V cache (bf16: transposed [head][hd][pos]).
 template <typename T>
@@ -196,6 +239,17 @@ int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride
 {
     dim3 grid((cols + 255) / 256, rows);
     hipLaunchKernelGGL(reduce_rows_kernel, grid, dim3(256), 0, s, part, n_part, part_stride, cols, out, st);
+    LAUNCH_CHECK();
+    return SJD_OK;
+}
+
+int sjd_launch_norm_bf16(const sjd_model *m, const float *x, const void *gain, int32_t rows, void *h,
+                         const SjdState *st, hipStream_t s)
+{
+    const int d = m->cfg.d_model;
+    if (d % 4 || d > 8192) return SJD_EINVAL;
+    hipLaunchKernelGGL(norm_bf16_kernel, dim3(rows), dim3(1024), 0, s, x, (const bf16_t *)gain, d, m->cfg.rms_eps,
+                       (bf16_t *)h, (size_t)SJD_ROWS_MAX * d, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
