@@ -52,7 +52,7 @@ static int check_config(const sjd_config *c)
     if (c->max_seq < 2) return SJD_EINVAL;
     if (c->dtype != 0 && c->dtype != 1) return SJD_EINVAL;
     if (c->dtype == 0 && (c->d_model % 4 || c->d_ffn % 4)) return SJD_EINVAL;
-    if (c->dtype == 1 && (c->d_model % 32 || c->d_ffn % 32 || (c->samp_hi - c->samp_lo) % 16 || c->d_model > 8192))
+    if (c->dtype == 1 && (c->d_model % 32 || c->d_ffn % 32 || (c->samp_hi - c->samp_lo) % 16 || c->d_model > 8192 || hd < 32))
         return SJD_EINVAL;
     if (!(c->rope_theta > 0.f) || !(c->rms_eps >= 0.f)) return SJD_EINVAL;
     return SJD_OK;
@@ -116,7 +116,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
     };
     // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
     auto linear = [&](size_t off, int N, int K, int perm, SjdLinear *lin) -> int {
-        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 8; lin->u = 4;
+        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 8; lin->u = 2;
         lin->w = db + off * es;
         const size_t n = (size_t)N * K;
         if (cfg->dtype == 0) {
@@ -204,13 +204,18 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     kv->att_splits = sjd_attention_splits(m);
     int rc = SJD_OK;
 #define A(ptr, bytes) if (rc == SJD_OK) rc = dev_alloc((void **)&(ptr), (bytes))
-    A(kv->k, (size_t)c.n_layers * c.max_seq * d * es);
-    A(kv->v, (size_t)c.n_layers * c.max_seq * d * es);
+    // bf16: the attention kernel reads whole 32-key blocks, so both caches are padded past max_seq
+    kv->k_rows = c.dtype == 1 ? (c.max_seq + 31) / 32 * 32 + 32 : c.max_seq;
+    kv->v_stride = kv->k_rows;
+    kv->k_layer_stride = (size_t)kv->k_rows * d;
+    kv->v_layer_stride = (size_t)kv->v_stride * d;
+    A(kv->k, (size_t)c.n_layers * kv->k_layer_stride * es);
+    A(kv->v, (size_t)c.n_layers * kv->v_layer_stride * es);
     A(kv->tokens, (size_t)c.max_seq * 4);
     A(kv->state, sizeof(SjdState));
     A(kv->x, R * d * 4);
     A(kv->h, R * d * es * 2);          // bf16 models: hi + lo planes
-    A(kv->part, part * 4);
+    A(kv->part, (c.dtype == 0 ? part : 4) * 4);
     A(kv->qact, R * d * 4);
     A(kv->att_part, sjd_attention_part_elems(m) * 4);
     A(kv->att_out, R * d * es * 2);
@@ -357,21 +362,20 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t row
 {
     const SjdState *st = kv->state;
     const int d = m->cfg.d_model, F = m->cfg.d_ffn, ms = m->cfg.max_seq;
-    const size_t per_layer = (size_t)ms * d;
     const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * d * 2;   // upper bound
     SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
     memset(&e_qkv, 0, sizeof(e_qkv));
     e_qkv.st = st;
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
-    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.max_seq = ms; e_qkv.rows_valid = rows_valid;
+    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.max_seq = kv->v_stride; e_qkv.rows_valid = rows_valid;
     e_res.kind = SJD_EPI_RESID; e_res.out = kv->x;
     e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (bf16_t *)kv->ffn; e_silu.ffn_plane = (size_t)SJD_ROWS_MAX * F; e_silu.F = F;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
-        e_qkv.kc = (bf16_t *)kv->k + l * per_layer;
-        e_qkv.vc = (bf16_t *)kv->v + l * per_layer;
+        e_qkv.kc = (bf16_t *)kv->k + l * kv->k_layer_stride;
+        e_qkv.vc = (bf16_t *)kv->v + l * kv->v_layer_stride;
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, L.g1, rows, kv->h, st, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, (const bf16_t *)kv->h, rows, e_qkv, s));
         PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
@@ -757,6 +761,11 @@ extern "C" int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sj
     return sjd_launch_dist(logits, rows, V_s, smp, forced, q, (hipStream_t)stream);
 }
 
+struct GemmScratch {
+    void *Ap = nullptr, *Wp = nullptr; float *out = nullptr;
+    ~GemmScratch() { for (void *p : {Ap, Wp, (void *)out}) if (p) (void)hipFree(p); }
+};
+
 extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_t N, int32_t K, float *C,
                              void *stream)
 {
@@ -766,26 +775,26 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     if (dtype == 0 && K % 4) return SJD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     const size_t es = elt_size(dtype);
-    void *Ap = nullptr, *Wp = nullptr; float *out = nullptr;
-    struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &out};
-    SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * es * 2));   // lo plane stays zero
-    HIP_TRY(hipMemcpyAsync(Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
-    SJD_TRY(dev_alloc((void **)&out, (size_t)SJD_ROWS_MAX * N * 4));
+    GemmScratch g;
+    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * es * 2));   // lo plane stays zero
+    SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 8; lin.u = 4; lin.w = W;
+    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 8; lin.u = 2; lin.w = W;
     if (dtype == 1) {
-        SJD_TRY(dev_alloc(&Wp, (size_t)N * K * es));
-        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)Wp, N, K, 0, 0, 0, s));
-        lin.w = Wp;
+        SJD_TRY(sjd_pack_act((const bf16_t *)A, M, K, (bf16_t *)g.Ap, s));
+        SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * es));
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)g.Wp, N, K, 0, 0, 0, s));
+        lin.w = g.Wp;
         sjd_choose_tiles(&lin);
         SjdGemmEpi ep;
         memset(&ep, 0, sizeof(ep));
-        ep.kind = SJD_EPI_STORE; ep.out = out;
-        SJD_TRY(sjd_launch_gemm_bf16(&lin, (const bf16_t *)Ap, M, ep, s));
+        ep.kind = SJD_EPI_STORE; ep.out = g.out;
+        SJD_TRY(sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, s));
     } else {
-        SJD_TRY(sjd_launch_gemm(0, &lin, Ap, M, out, nullptr, s));
+        HIP_TRY(hipMemcpyAsync(g.Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
+        SJD_TRY(sjd_launch_gemm(0, &lin, g.Ap, M, g.out, nullptr, s));
     }
-    HIP_TRY(hipMemcpyAsync(C, out, (size_t)M * N * 4, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(hipMemcpyAsync(C, g.out, (size_t)M * N * 4, hipMemcpyDeviceToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     return SJD_OK;
 }
@@ -793,26 +802,24 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
 extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32_t wk, int32_t u, int32_t iters,
                               float *us_per_launch)
 {
-    if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters == 0 || !us_per_launch) return SJD_EINVAL;
+    if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
     if (tn < 1 || N % (16 * tn)) return SJD_EINVAL;
-    void *Ap = nullptr, *Wp = nullptr; float *out = nullptr;
-    struct Guard { void **a, **b; float **c; ~Guard() { if (*a) (void)hipFree(*a); if (*b) (void)hipFree(*b); if (*c) (void)hipFree(*c); } } g{&Ap, &Wp, &out};
-    SJD_TRY(dev_alloc(&Ap, (size_t)SJD_ROWS_MAX * K * 2 * 2));
-    SJD_TRY(dev_alloc(&Wp, (size_t)N * K * 2));
-    SJD_TRY(dev_alloc((void **)&out, (size_t)SJD_ROWS_MAX * N * 4));
+    GemmScratch g;
+    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 2 * 2));
+    SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * 2));
+    SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.tn = tn; lin.wk = wk; lin.u = u; lin.w = Wp;
+    lin.N = N; lin.K = K; lin.tn = tn; lin.wk = wk; lin.u = u; lin.w = g.Wp;
     SjdGemmEpi ep;
     memset(&ep, 0, sizeof(ep));
-    ep.kind = SJD_EPI_STORE; ep.out = out;
-    if (iters < 0) { ep.F = 1; iters = -iters; }   // negative count: time the single-plane variant
+    ep.kind = SJD_EPI_STORE; ep.out = g.out;
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
     int rc = SJD_OK;
-    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_gemm_bench_launch(&lin, (const bf16_t *)Ap, M, ep, wk, u, 0);
+    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
     if (rc == SJD_OK) {
         (void)hipEventRecord(e0, 0);
-        for (int i = 0; i < iters && rc == SJD_OK; ++i) rc = sjd_gemm_bench_launch(&lin, (const bf16_t *)Ap, M, ep, wk, u, 0);
+        for (int i = 0; i < iters && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
         (void)hipEventRecord(e1, 0);
         (void)hipEventSynchronize(e1);
         float ms = 0.f;

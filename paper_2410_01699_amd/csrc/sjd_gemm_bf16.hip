@@ -6,22 +6,78 @@
 //
 //  - W is pre-packed (sjd_repack_bf16) into 16x32 tiles in the exact A-operand register order of
 //    v_mfma_f32_16x16x32_bf16: one 16-byte load per lane fetches 1 KiB of contiguous HBM per wave.
+//  - The activations are the B operand (tokens on the 16 columns), stored by their producers in
+//    B-operand order too (act_off) as two bf16 planes hi + lo that are multiplied separately:
+//    ~16 significant bits of activation at no extra HBM traffic.  They come from L2; a wave reuses
+//    each activation tile for its TN weight tiles, so TN sets the L2-to-HBM traffic ratio.
 //  - One workgroup owns TN output tiles (16*TN features) for the WHOLE reduction; its WK waves
-//    split K between them and add their fp32 accumulators through LDS in a fixed order.  No
-//    global partial sums, no atomics: results are deterministic and the epilogue sees final values.
+//    split K between them and add their fp32 accumulators through LDS in wave order.  No global
+//    partial sums, no atomics: results are deterministic and the epilogue sees final values.
+//    (A stream-K variant that balanced work across waves through global partial tiles and a ticket
+//    counter was measured 2-4x slower here: the device-scope fences it needs write back L2.)
 //  - Each wave keeps U k-steps of loads in flight ahead of the MFMAs (register double buffering).
-//  - The activations are the B operand (tokens on the 16 columns), read from L2 as two bf16 planes
-//    hi + lo (see sjd_layers.hip) and multiplied separately: ~16 significant bits of activation at
-//    no extra HBM traffic.
-//  - Epilogues: plain store (LM head logits), residual add into the fp32 stream (O and down
-//    projections), SiLU(gate)*up (gate and up rows are interleaved inside each tile when packed, so a
-//    lane holds both), RoPE + KV-cache write (Q/K rows of a head are packed as (j, j+hd/2) pairs, so
-//    the rotation is lane-local).
+//  - Epilogues see final fp32 values: plain store (LM head logits), residual add into the fp32
+//    stream (O and down projections), SiLU(gate)*up (gate and up rows are interleaved inside each
+//    tile when packed, so a lane holds both), RoPE + KV-cache write (Q/K rows of a head are packed
+//    as (j, j+hd/2) pairs, so the rotation is lane-local).
 #include "sjd_internal.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// One accumulator fragment: lane l of the MFMA result holds features n0..n0+3 (packed order) of
+// token m.  v = final sums.
+template <int EPI>
+__device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int m, int n0, f32x4 v)
+{
+    if (EPI == SJD_EPI_STORE) {
+        *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
+    } else if (EPI == SJD_EPI_RESID) {
+        f32x4 *x = reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0);
+        *x = *x + v;
+    } else if (EPI == SJD_EPI_SILU) {
+        // packed rows: (gate f, up f, gate f+1, up f+1)
+        const int f = n0 >> 1;
+        const float y0 = v[0] / (1.0f + __expf(-v[0])) * v[1];
+        const float y1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
+        const size_t o = act_off(m, f, ep.F / 32);
+        const bf16_t h0 = f32_to_bf16(y0), h1 = f32_to_bf16(y1);
+        *reinterpret_cast<uint32_t *>(ep.ffn + o) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        *reinterpret_cast<uint32_t *>(ep.ffn + ep.ffn_plane + o) =
+            (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
+    } else {   // SJD_EPI_QKV
+        const int d = ep.d, hd = ep.hd, half = hd >> 1;
+        const int pos = ep.st->n + m;
+        if (n0 < 2 * d) {
+            // Q or K: packed order inside a head is (j, j+half, j+1, j+1+half, ...)
+            const int is_k = n0 >= d;
+            const int c = n0 - (is_k ? d : 0);
+            const int head = c / hd, j = (c % hd) >> 1;
+            const float c0 = ep.cosT[(size_t)pos * half + j], s0 = ep.sinT[(size_t)pos * half + j];
+            const float c1 = ep.cosT[(size_t)pos * half + j + 1], s1 = ep.sinT[(size_t)pos * half + j + 1];
+            const float r0 = v[0] * c0 - v[1] * s0, r0p = v[1] * c0 + v[0] * s0;   // dims j, j+half
+            const float r1 = v[2] * c1 - v[3] * s1, r1p = v[3] * c1 + v[2] * s1;   // dims j+1, j+1+half
+            const int col = head * hd + j;
+            if (!is_k) {
+                float *q = ep.qact + (size_t)m * d + col;
+                q[0] = r0; q[1] = r1; q[half] = r0p; q[half + 1] = r1p;
+            } else if (m < ep.rows_valid) {
+                bf16_t *k = ep.kc + (size_t)pos * d + col;
+                *reinterpret_cast<uint32_t *>(k) = (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16);
+                *reinterpret_cast<uint32_t *>(k + half) = (uint32_t)f32_to_bf16(r0p) | ((uint32_t)f32_to_bf16(r1p) << 16);
+            }
+        } else if (m < ep.rows_valid) {
+            // V: natural order, cache is transposed [feature][position]
+            const int col = n0 - 2 * d;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ep.vc[(size_t)(col + r) * ep.max_seq + pos] = f32_to_bf16(v[r]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// in-workgroup split-K
+// ---------------------------------------------------------------------------------------------
 template <int MT, int TN, int WK, int U, int EPI, int PLANES = 2>
 __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__restrict__ Wp,
                                                             const bf16_t *__restrict__ A, int N, int K,
@@ -44,8 +100,8 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)tile0 * KT * 64 + lane;
     const size_t tile_stride = (size_t)KT * 64;                 // in 16-byte units
-    const bf16_t *ab = A + (size_t)(lane & 15) * K + (lane >> 4) * 8;
-    const size_t plane = (size_t)SJD_ROWS_MAX * K;
+    const bf16x8 *ap = reinterpret_cast<const bf16x8 *>(A) + lane;
+    const size_t plane = (size_t)SJD_ROWS_MAX * K / 8;          // lo plane, in 16-byte units
 
     bf16x8 a0[U][TN], a1[U][TN], b0[U][MT][2], b1[U][MT][2];
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -53,13 +109,13 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 #define LOAD_STAGE(kbase, a, b)                                                                   \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                               \
         const int kq_ = (kbase) + u;                                                              \
-        if (kq_ < kt1) {                                                                           \
+        if (kq_ < kt1) {                                                                          \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                     \
                 a[u][tn] = __builtin_nontemporal_load(wp + (size_t)tn * tile_stride + (size_t)kq_ * 64); \
             _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
-                const bf16_t *p = ab + (size_t)mt * 16 * K + (size_t)kq_ * 32;                    \
-                b[u][mt][0] = *reinterpret_cast<const bf16x8 *>(p);                               \
-                if (PLANES == 2) b[u][mt][1] = *reinterpret_cast<const bf16x8 *>(p + plane);      \
+                const bf16x8 *p = ap + ((size_t)mt * KT + kq_) * 64;                              \
+                b[u][mt][0] = *p;                                                                 \
+                if (PLANES == 2) b[u][mt][1] = *(p + plane);                                      \
             }                                                                                     \
         } else {                                                                                  \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) a[u][tn] = zero;                    \
@@ -97,54 +153,13 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         for (int w = 1; w < WK; ++w) v += red[w][mtn][l];
         // D layout: lane l holds features (l/16)*4 + 0..3 of the tile for token l%16
         const int mt = mtn / TN, tn = mtn % TN;
-        const int m = mt * 16 + (l & 15);
-        const int n0 = (tile0 + tn) * 16 + (l >> 4) * 4;        // packed feature index of v[0]
-        if (EPI == SJD_EPI_STORE) {
-            *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
-        } else if (EPI == SJD_EPI_RESID) {
-            f32x4 *x = reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0);
-            *x = *x + v;
-        } else if (EPI == SJD_EPI_SILU) {
-            // packed rows: (gate f, up f, gate f+1, up f+1)
-            const int f = n0 >> 1;
-            const float y0 = v[0] / (1.0f + __expf(-v[0])) * v[1];
-            const float y1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
-            const size_t o = (size_t)m * ep.F + f;
-            const bf16_t h0 = f32_to_bf16(y0), h1 = f32_to_bf16(y1);
-            *reinterpret_cast<uint32_t *>(ep.ffn + o) = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            *reinterpret_cast<uint32_t *>(ep.ffn + ep.ffn_plane + o) =
-                (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
-        } else {   // SJD_EPI_QKV
-            const int d = ep.d, hd = ep.hd, half = hd >> 1;
-            const int pos = ep.st->n + m;
-            if (n0 < 2 * d) {
-                // Q or K: packed order inside a head is (j, j+half, j+1, j+1+half, ...)
-                const int is_k = n0 >= d;
-                const int c = n0 - (is_k ? d : 0);
-                const int head = c / hd, j = (c % hd) >> 1;
-                const float c0 = ep.cosT[(size_t)pos * half + j], s0 = ep.sinT[(size_t)pos * half + j];
-                const float c1 = ep.cosT[(size_t)pos * half + j + 1], s1 = ep.sinT[(size_t)pos * half + j + 1];
-                const float r0 = v[0] * c0 - v[1] * s0, r0p = v[1] * c0 + v[0] * s0;   // dims j, j+half
-                const float r1 = v[2] * c1 - v[3] * s1, r1p = v[3] * c1 + v[2] * s1;   // dims j+1, j+1+half
-                const int col = head * hd + j;
-                if (!is_k) {
-                    float *q = ep.qact + (size_t)m * d + col;
-                    q[0] = r0; q[1] = r1; q[half] = r0p; q[half + 1] = r1p;
-                } else if (m < ep.rows_valid) {
-                    bf16_t *k = ep.kc + (size_t)pos * d + col;
-                    *reinterpret_cast<uint32_t *>(k) = (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16);
-                    *reinterpret_cast<uint32_t *>(k + half) = (uint32_t)f32_to_bf16(r0p) | ((uint32_t)f32_to_bf16(r1p) << 16);
-                }
-            } else if (m < ep.rows_valid) {
-                // V: natural order, cache is transposed [feature][position]
-                const int col = n0 - 2 * d;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ep.vc[(size_t)(col + r) * ep.max_seq + pos] = f32_to_bf16(v[r]);
-            }
-        }
+        apply_epilogue<EPI>(ep, N, mt * 16 + (l & 15), (tile0 + tn) * 16 + (l >> 4) * 4, v);
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// weight and activation packing
+// ---------------------------------------------------------------------------------------------
 // row-major [N][K] bf16 -> MFMA streaming order, packed row n' taken from source row perm(n')
 //   perm 0: identity
 //   perm 1: rows [0, 2d) (Q then K) reordered inside each head to (j, j+hd/2) pairs; rest identity
@@ -183,68 +198,60 @@ int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K
     return SJD_OK;
 }
 
-// Tiles per workgroup: fill the 256 CUs evenly.  Prefer the largest TN (fewest re-reads of the
-// activations) among those whose workgroup count wastes the least of the last round.
+// row-major bf16 [rows][K] -> packed hi plane (the lo plane is left as it is)
+__global__ void pack_act_kernel(const bf16_t *__restrict__ src, int rows, int K, bf16_t *__restrict__ dst)
+{
+    const int KT = K / 32;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < (size_t)rows * K; e += (size_t)gridDim.x * blockDim.x) {
+        const int m = (int)(e / K), k = (int)(e % K);
+        dst[act_off(m, k, KT)] = src[e];
+    }
+}
+
+int sjd_pack_act(const bf16_t *src_rowmajor, int32_t rows, int32_t K, bf16_t *dst_packed, hipStream_t s)
+{
+    if (rows < 1 || rows > SJD_ROWS_MAX || K % 32) return SJD_EINVAL;
+    hipLaunchKernelGGL(pack_act_kernel, dim3(256), dim3(256), 0, s, src_rowmajor, rows, K, dst_packed);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// configuration and launch
+// ---------------------------------------------------------------------------------------------
+// Tiles per workgroup: fill the 256 CUs evenly.  Among tilings that waste about the same share of
+// the last round of workgroups, prefer the largest TN (fewest re-reads of the activations).
 void sjd_choose_tiles(SjdLinear *lin)
 {
     const int tiles = lin->N / 16;
     int best_tn = 1;
     double best_eff = -1.0;
-    for (int tn = 1; tn <= 4; ++tn) {
-        if (tiles % tn) continue;
-        const int blocks = tiles / tn;
-        if (blocks < 256 && tn > 1) continue;
+    for (int t = 1; t <= 4; ++t) {
+        if (tiles % t) continue;
+        const int blocks = tiles / t;
+        if (blocks < 128 && t > 1) continue;
         const double eff = (double)blocks / (256.0 * ((blocks + 255) / 256));
-        if (eff > best_eff + 0.02 || (eff > best_eff - 0.02 && tn > best_tn)) {
+        if (eff > best_eff + 0.02 || (eff > best_eff - 0.02 && t > best_tn)) {
             if (eff > best_eff) best_eff = eff;
-            best_tn = tn;
+            best_tn = t;
         }
     }
-    lin->tn = best_tn;
-    lin->wk = 8;
-    lin->u = 4;
+    lin->tn = best_tn; lin->wk = 8; lin->u = 2;
 }
 
 template <int MT, int TN, int WK, int U>
 static int launch_epi(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, hipStream_t s)
 {
-    dim3 grid(lin->N / (16 * TN)), block(64 * WK);
-    const bf16_t *W = (const bf16_t *)lin->w;
-    switch (ep.kind) {
-        case SJD_EPI_STORE: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-        case SJD_EPI_RESID: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_RESID>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-        case SJD_EPI_SILU: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_SILU>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-        case SJD_EPI_QKV: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_QKV>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-        default: return SJD_EINVAL;
-    }
-    HIP_TRY(hipGetLastError());
-    return SJD_OK;
-}
-
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s)
-{
-    if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
-    if (lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
-    const int mt = rows <= 16 ? 1 : 2;
-#define CASE(MT, TN) if (mt == MT && lin->tn == TN) return launch_epi<MT, TN, 8, 4>(lin, act, ep, s)
-    CASE(1, 1); CASE(1, 2); CASE(1, 3); CASE(1, 4);
-    CASE(2, 1); CASE(2, 2); CASE(2, 3); CASE(2, 4);
-#undef CASE
-    return SJD_EINVAL;
-}
-
-// ---- tuning hook: time the plain-store kernel at a given shape and tiling ----------------------
-template <int MT, int TN, int WK, int U>
-static int launch_store(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, hipStream_t s)
-{
     if constexpr (WK * MT * TN * 1024 <= 65536) {
         dim3 grid(lin->N / (16 * TN)), block(64 * WK);
-        if (ep.F == 1)   // tuning only: hi plane alone
-            hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE, 1>), grid, block, 0, s, (const bf16_t *)lin->w,
-                               act, lin->N, lin->K, ep);
-        else
-        hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE>), grid, block, 0, s, (const bf16_t *)lin->w, act,
-                           lin->N, lin->K, ep);
+        const bf16_t *W = (const bf16_t *)lin->w;
+        switch (ep.kind) {
+            case SJD_EPI_STORE: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+            case SJD_EPI_RESID: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_RESID>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+            case SJD_EPI_SILU: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_SILU>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+            case SJD_EPI_QKV: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_QKV>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+            default: return SJD_EINVAL;
+        }
         HIP_TRY(hipGetLastError());
         return SJD_OK;
     } else {
@@ -252,23 +259,15 @@ static int launch_store(const SjdLinear *lin, const bf16_t *act, const SjdGemmEp
     }
 }
 
-template <int MT, int TN>
-static int bench_variant(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, int wk, int u, hipStream_t s)
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s)
 {
-#define V(WK, UU) if (wk == WK && u == UU) return launch_store<MT, TN, WK, UU>(lin, act, ep, s)
-    V(4, 4); V(4, 8); V(8, 2); V(8, 4); V(8, 8); V(16, 2); V(16, 4);
-#undef V
-    return SJD_EINVAL;
-}
-
-int sjd_gemm_bench_launch(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, int wk, int u,
-                          hipStream_t s)
-{
+    if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
-    if (lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
-#define CASE(MT, TN) if (mt == MT && lin->tn == TN) return bench_variant<MT, TN>(lin, act, ep, wk, u, s)
+    if (lin->wk != 8) return SJD_EINVAL;
+#define CASE(MT, TN) if (mt == MT && lin->tn == TN) return lin->u == 4 ? launch_epi<MT, TN, 8, 4>(lin, act, ep, s) : launch_epi<MT, TN, 8, 2>(lin, act, ep, s)
     CASE(1, 1); CASE(1, 2); CASE(1, 3); CASE(1, 4);
-    CASE(2, 1); CASE(2, 2); CASE(2, 4);
+    CASE(2, 1); CASE(2, 2); CASE(2, 3); CASE(2, 4);
 #undef CASE
     return SJD_EINVAL;
 }

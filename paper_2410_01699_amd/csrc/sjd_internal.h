@@ -49,6 +49,15 @@ struct SjdState {
     int32_t accept_hist[65];
 };
 
+// GEMM inputs of bf16 models are stored in the B-operand order of v_mfma_f32_16x16x32_bf16, so a
+// wave fetches one 16x32 activation tile with a single contiguous 1 KiB load: element (row m, column
+// k) of a [32 x K] matrix lives at act_off(m, k, K/32); the lo plane follows the hi plane at
+// 32*K elements.
+__host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
+{
+    return ((size_t)(m >> 4) * KT + (k >> 5)) * 512 + ((((k & 31) >> 3) * 16 + (m & 15)) << 3) + (k & 7);
+}
+
 // ---- one linear layer's weights ------------------------------------------------------------
 // fp32 models keep W as given ([N][K] row-major).  bf16 models hold W in MFMA streaming order:
 // tiles of 16 output features x 32 input features, tile (nt, kt) at ((nt * K/32) + kt) * 512
@@ -94,13 +103,16 @@ struct sjd_model {
 
 struct sjd_kv {
     const sjd_model *m;
-    void *k, *v;          // K: [layer][pos][d]; V: bf16 models [layer][head][hd][max_seq], fp32 [layer][pos][d]
+    void *k, *v;          // K: [layer][pos][d]; V: fp32 models [layer][pos][d], bf16 models transposed
+                          // [layer][d][v_stride] (positions contiguous, v_stride >= max_seq + 32)
+    size_t k_layer_stride, v_layer_stride;   // elements
+    int32_t k_rows, v_stride;
     int32_t *tokens;      // [max_seq] ids of cached positions (-1 for raw-embedding rows)
     SjdState *state;      // device
     // ---- scratch for one forward over <= SJD_ROWS_MAX rows ----
     float *x;             // [rows][d] residual stream
     void *h;              // [rows][d] normalised activations (GEMM input; bf16: hi and lo planes)
-    float *part;          // split-K partial outputs of the current GEMM
+    float *part;          // fp32 models: GEMM output
     size_t part_elems;
     float *qact;          // [rows][d] rotated queries (fp32)
     float *att_part;      // attention partials per (head, split): [rows][hd] + m,l
@@ -150,8 +162,8 @@ int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K
                     int32_t hd, hipStream_t s);
 void sjd_choose_tiles(SjdLinear *lin);
 int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s);
-int sjd_gemm_bench_launch(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, int wk, int u,
-                          hipStream_t s);
+int sjd_pack_act(const bf16_t *src_rowmajor, int32_t rows, int32_t K, bf16_t *dst_packed, hipStream_t s);
+
 int sjd_launch_norm_bf16(const sjd_model *m, const float *x, const void *gain, int32_t rows, void *h,
                          const SjdState *st, hipStream_t s);
 int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s);

@@ -99,8 +99,9 @@ __global__ __launch_bounds__(1024) void norm_bf16_kernel(const float *__restrict
         hi.x = (uint32_t)h0 | ((uint32_t)h1 << 16); hi.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
         lo.x = (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
         lo.y = (uint32_t)f32_to_bf16(y2 - bf16_to_f32(h2)) | ((uint32_t)f32_to_bf16(y3 - bf16_to_f32(h3)) << 16);
-        reinterpret_cast<uint2 *>(h + (size_t)r * d)[c] = hi;
-        reinterpret_cast<uint2 *>(h + plane + (size_t)r * d)[c] = lo;
+        const size_t o = act_off(r, 4 * c, d / 32);
+        *reinterpret_cast<uint2 *>(h + o) = hi;
+        *reinterpret_cast<uint2 *>(h + plane + o) = lo;
     }
 }
 
@@ -207,15 +208,10 @@ int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const floa
                        size_t part_stride, int32_t rows, int32_t rows_valid, hipStream_t s)
 {
     const int d = m->cfg.d_model, ms = m->cfg.max_seq;
-    const size_t per_layer = (size_t)ms * d;
-    if (m->cfg.dtype == 0)
-        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
-                           m->rope_cos, m->rope_sin, kv->qact, (float *)kv->k + layer * per_layer,
-                           (float *)kv->v + layer * per_layer, 0, rows_valid, kv->state);
-    else
-        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
-                           m->rope_cos, m->rope_sin, kv->qact, (bf16_t *)kv->k + layer * per_layer,
-                           (bf16_t *)kv->v + layer * per_layer, 1, rows_valid, kv->state);
+    if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models do this in the QKV GEMM epilogue
+    hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
+                       m->rope_cos, m->rope_sin, kv->qact, (float *)kv->k + (size_t)layer * kv->k_layer_stride,
+                       (float *)kv->v + (size_t)layer * kv->v_layer_stride, 0, rows_valid, kv->state);
     LAUNCH_CHECK();
     return SJD_OK;
 }
