@@ -173,24 +173,29 @@ __device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &
     hi = h.v; lo = l.v;
 }
 
+// One workgroup of AW waves per head.  Wave w takes the 32-key blocks w, w+AW, ... of the range
+// [0, n+rows), prefetching the next block's K/V tiles while it works on the current one, and keeps
+// an online-softmax state (running max, denominator, unnormalised O^T) per query.  The waves then
+// agree on the per-query maximum through LDS, rescale, and their outputs are added AW/4... four
+// waves at a time in wave order (fixed order -> deterministic); the result is written as hi/lo bf16
+// planes in the layout the O projection streams.
+#define AW 8
 template <int HD, int MT>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const float *__restrict__ qact, const bf16_t *__restrict__ kc,
-                                                        const bf16_t *__restrict__ vc, int d, int vstride, int rows,
-                                                        int splits, float *__restrict__ part, const SjdState *st)
+__global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restrict__ qact,
+                                                           const bf16_t *__restrict__ kc,
+                                                           const bf16_t *__restrict__ vc, int d, int vstride,
+                                                           int rows, bf16_t *__restrict__ out, const SjdState *st)
 {
     if (st->done) return;
     constexpr int ROWS = SJD_ROWS_MAX;
     constexpr int KS = HD / 32;      // k-steps of the score product
     constexpr int DT = HD / 16;      // output dim tiles
-    const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+    __shared__ float m_all[AW][MT * 16], l_all[AW][MT * 16];
+    __shared__ f32x4 o_slot[4][DT][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     const int head = blockIdx.x;
-    const int split = blockIdx.y * 4 + (threadIdx.x >> 6);
-    if (split >= splits) return;
     const int n = st->n;
     const int total = n + rows;
-    int chunk = (total + splits - 1) / splits;
-    chunk = (chunk + 31) / 32 * 32;
-    const int k_beg = split * chunk, k_end = min(total, k_beg + chunk);
     const float scale = rsqrtf((float)HD);
 
     // Q as B operand: lane holds Q[query c (+16 mt)][32 ks + 8 g .. +8], scaled, hi/lo
@@ -200,9 +205,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *__restrict_
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             float x[8];
-            const float *src = qact + (size_t)(mt * 16 + c) * d + head * HD + ks * 32 + g * 8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = src[e] * scale;
+            const float4 *src = reinterpret_cast<const float4 *>(qact + (size_t)(mt * 16 + c) * d + head * HD + ks * 32 + g * 8);
+            const float4 x0 = src[0], x1 = src[1];
+            x[0] = x0.x * scale; x[1] = x0.y * scale; x[2] = x0.z * scale; x[3] = x0.w * scale;
+            x[4] = x1.x * scale; x[5] = x1.y * scale; x[6] = x1.z * scale; x[7] = x1.w * scale;
             split8(x, qh[mt][ks], ql[mt][ks]);
         }
 
@@ -215,141 +221,165 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *__restrict_
         for (int t = 0; t < DT; ++t) o[mt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int k0 = k_beg; k0 < k_end; k0 += 32) {
-        // K tiles: keys k0 + c and k0 + 16 + c
-        bf16x8 ka[2][KS];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                ka[h][ks] = *reinterpret_cast<const bf16x8 *>(kc + (size_t)(k0 + h * 16 + c) * d + head * HD + ks * 32 + g * 8);
-        // V^T tiles: dims 16 t + c, keys (k0 + 4g .. +4) and (k0 + 16 + 4g .. +4)
-        bf16x8 va[DT];
-#pragma unroll
-        for (int t = 0; t < DT; ++t) {
-            const bf16_t *vp = vc + (size_t)(head * HD + t * 16 + c) * vstride + k0 + g * 4;
-            union { bf16x8 v; uint2 u[2]; } w;
-            w.u[0] = *reinterpret_cast<const uint2 *>(vp);
-            w.u[1] = *reinterpret_cast<const uint2 *>(vp + 16);
-            va[t] = w.v;
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            f32x4 s[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                s[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], qh[mt][ks], s[h], 0, 0, 0);
-                    s[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], ql[mt][ks], s[h], 0, 0, 0);
-                }
-            }
-            // mask: key position <= n + query row; keys past the chunk end are masked too
-            const int qrow = mt * 16 + c;
-            float p[8];
-            float mx = m_run[mt];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int key = k0 + (e >> 2) * 16 + g * 4 + (e & 3);
-                const bool ok = key < k_end && key <= n + qrow && qrow < rows;
-                p[e] = ok ? s[e >> 2][e & 3] : -INFINITY;
-                mx = fmaxf(mx, p[e]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float so = (mx == -INFINITY) ? 1.f : __expf(m_run[mt] - mx);
-            float sum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                p[e] = (p[e] == -INFINITY) ? 0.f : __expf(p[e] - mx);
-                sum += p[e];
-            }
-            sum += __shfl_xor(sum, 16);
-            sum += __shfl_xor(sum, 32);
-            l_run[mt] = l_run[mt] * so + sum;
-            m_run[mt] = mx;
-            bf16x8 ph, pl;
-            split8(p, ph, pl);
-#pragma unroll
-            for (int t = 0; t < DT; ++t) {
-                o[mt][t] *= so;
-                o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t], ph, o[mt][t], 0, 0, 0);
-                o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t], pl, o[mt][t], 0, 0, 0);
-            }
-        }
+    bf16x8 ka0[2][KS], ka1[2][KS], va[DT];
+    // K tiles: keys k0 + c and k0 + 16 + c (prefetched one block ahead); V^T tiles: dims 16 t + c,
+    // keys (k0 + 4g .. +4), (k0 + 16 + 4g .. +4) (loaded when the block starts: their latency hides
+    // behind the score product and the softmax)
+#define LOAD_K(k0, ka)                                                                               \
+    if ((k0) < total) {                                                                              \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                \
+            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                        \
+                ka[h][ks] = *reinterpret_cast<const bf16x8 *>(kc + (size_t)((k0) + h * 16 + c) * d + head * HD + ks * 32 + g * 8); \
     }
-    // partial: [rows][HD] unnormalised output, m[rows], l[rows]; lane holds dims 16t + 4g .. +4 of query c
-    float *dst = part + (size_t)(head * splits + split) * (ROWS * HD + 2 * ROWS);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-            *reinterpret_cast<f32x4 *>(dst + (size_t)(mt * 16 + c) * HD + t * 16 + g * 4) = o[mt][t];
-        if (g == 0) { dst[ROWS * HD + mt * 16 + c] = m_run[mt]; dst[ROWS * HD + ROWS + mt * 16 + c] = l_run[mt]; }
+#define LOAD_V(k0)                                                                                   \
+    _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
+        const bf16_t *vp = vc + (size_t)(head * HD + t * 16 + c) * vstride + (k0) + g * 4;           \
+        union { bf16x8 v; uint2 u[2]; } w_;                                                          \
+        w_.u[0] = *reinterpret_cast<const uint2 *>(vp);                                              \
+        w_.u[1] = *reinterpret_cast<const uint2 *>(vp + 16);                                         \
+        va[t] = w_.v;                                                                                \
     }
-}
+#define COMPUTE_KV(k0, ka)                                                                           \
+    LOAD_V(k0)                                                                                       \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                              \
+        f32x4 s_[2];                                                                                 \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                              \
+            s_[h] = (f32x4){0.f, 0.f, 0.f, 0.f};                                                     \
+            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                      \
+                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], qh[mt][ks], s_[h], 0, 0, 0); \
+                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], ql[mt][ks], s_[h], 0, 0, 0); \
+            }                                                                                        \
+        }                                                                                            \
+        const int qrow = mt * 16 + c;                                                                \
+        float p_[8];                                                                                 \
+        float mx = m_run[mt];                                                                        \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
+            const int key = (k0) + (e >> 2) * 16 + g * 4 + (e & 3);                                  \
+            const bool ok = key <= n + qrow && qrow < rows;     /* causal inside the window */       \
+            p_[e] = ok ? s_[e >> 2][e & 3] : -INFINITY;                                              \
+            mx = fmaxf(mx, p_[e]);                                                                   \
+        }                                                                                            \
+        mx = fmaxf(mx, __shfl_xor(mx, 16));                                                          \
+        mx = fmaxf(mx, __shfl_xor(mx, 32));                                                          \
+        const float so = (mx == -INFINITY) ? 1.f : __expf(m_run[mt] - mx);                           \
+        float sum = 0.f;                                                                             \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
+            p_[e] = (p_[e] == -INFINITY) ? 0.f : __expf(p_[e] - mx);                                 \
+            sum += p_[e];                                                                            \
+        }                                                                                            \
+        sum += __shfl_xor(sum, 16);                                                                  \
+        sum += __shfl_xor(sum, 32);                                                                  \
+        l_run[mt] = l_run[mt] * so + sum;                                                            \
+        m_run[mt] = mx;                                                                              \
+        bf16x8 ph, pl;                                                                               \
+        split8(p_, ph, pl);                                                                          \
+        _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                             \
+            o[mt][t] *= so;                                                                          \
+            o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t], ph, o[mt][t], 0, 0, 0);        \
+            o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t], pl, o[mt][t], 0, 0, 0);        \
+        }                                                                                            \
+    }
 
-// merge of the key chunks, bf16 models: one workgroup per head; weights exp(m_s - M) per (row, chunk)
-// are computed once into LDS, empty chunks are skipped, output goes out as hi/lo bf16 planes
-template <int HD>
-__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
-                                                         bf16_t *__restrict__ out, const SjdState *st)
-{
-    if (st->done) return;
-    constexpr int ROWS = SJD_ROWS_MAX;
-    constexpr int MAXS = 64;
-    __shared__ float w[ROWS][MAXS];
-    __shared__ float inv_den[ROWS];
-    const int head = blockIdx.x;
-    const size_t stride = ROWS * HD + 2 * ROWS;
-    const float *base = part + (size_t)head * splits * stride;
-    if (threadIdx.x < rows) {
-        const int r = threadIdx.x;
-        float mx = -INFINITY;
-        for (int s = 0; s < splits; ++s) mx = fmaxf(mx, base[s * stride + ROWS * HD + r]);
-        float den = 0.f;
-        for (int s = 0; s < splits; ++s) {
-            const float ms = base[s * stride + ROWS * HD + r];
-            const float ww = (ms == -INFINITY) ? 0.f : __expf(ms - mx);
-            w[r][s] = ww;
-            den += ww * base[s * stride + ROWS * HD + ROWS + r];
+    constexpr bool PREFETCH = (MT * HD <= 128);   // the big variant has no registers to spare
+    int k0 = wave * 32;
+    if constexpr (PREFETCH) {
+        LOAD_K(k0, ka0)
+        while (k0 < total) {
+            LOAD_K(k0 + AW * 32, ka1)
+            COMPUTE_KV(k0, ka0)
+            k0 += AW * 32;
+            if (k0 >= total) break;
+            LOAD_K(k0 + AW * 32, ka0)
+            COMPUTE_KV(k0, ka1)
+            k0 += AW * 32;
         }
-        inv_den[r] = 1.0f / den;
+    } else {
+        for (; k0 < total; k0 += AW * 32) {
+            LOAD_K(k0, ka0)
+            COMPUTE_KV(k0, ka0)
+        }
+        (void)ka1;
+    }
+#undef LOAD_K
+#undef LOAD_V
+#undef COMPUTE_KV
+
+    // ---- merge the AW waves -------------------------------------------------------------------
+    if (g == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) { m_all[wave][mt * 16 + c] = m_run[mt]; l_all[wave][mt * 16 + c] = l_run[mt]; }
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < rows * (HD / 4); e += 256) {
-        const int r = e / (HD / 4), j = (e % (HD / 4)) * 4;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < splits; ++s) {
-            const float ww = w[r][s];
-            if (ww != 0.f) acc += ww * *reinterpret_cast<const f32x4 *>(base + s * stride + (size_t)r * HD + j);
-        }
-        acc *= inv_den[r];
-        const size_t o = act_off(r, head * HD + j, d / 32);
-        bf16_t hi[4], lo[4];
+    float inv_den[MT];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { hi[q] = f32_to_bf16(acc[q]); lo[q] = f32_to_bf16(acc[q] - bf16_to_f32(hi[q])); }
-        uint2 ph, pl;
-        ph.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); ph.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
-        pl.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); pl.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
-        *reinterpret_cast<uint2 *>(out + o) = ph;
-        *reinterpret_cast<uint2 *>(out + (size_t)ROWS * d + o) = pl;
+    for (int mt = 0; mt < MT; ++mt) {
+        float M = -INFINITY;
+        for (int w = 0; w < AW; ++w) M = fmaxf(M, m_all[w][mt * 16 + c]);
+        float den = 0.f;
+        for (int w = 0; w < AW; ++w) {
+            const float mw = m_all[w][mt * 16 + c];
+            den += (mw == -INFINITY) ? 0.f : __expf(mw - M) * l_all[w][mt * 16 + c];
+        }
+        inv_den[mt] = 1.0f / den;
+        const float mine = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - M);
+#pragma unroll
+        for (int t = 0; t < DT; ++t) o[mt][t] *= mine;
     }
+    // add the rescaled outputs four waves at a time; waves 0..3 keep the running sums
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        for (int r = 1; r < AW / 4; ++r) {
+            __syncthreads();
+            if ((wave >> 2) == r) {
+#pragma unroll
+                for (int t = 0; t < DT; ++t) o_slot[wave & 3][t][lane] = o[mt][t];
+            }
+            __syncthreads();
+            if (wave < 4) {
+#pragma unroll
+                for (int t = 0; t < DT; ++t) o[mt][t] += o_slot[wave][t][lane];
+            }
+        }
+        // waves 0..3 -> slots, then wave 0 adds slots 1..3 in order and writes the head's output
+        __syncthreads();
+        if (wave < 4) {
+#pragma unroll
+            for (int t = 0; t < DT; ++t) o_slot[wave][t][lane] = o[mt][t];
+        }
+        __syncthreads();
+        // 256 result fragments (DT x 64) per query tile: spread them over the workgroup
+        for (int u = threadIdx.x; u < DT * 64; u += 64 * AW) {
+            const int t = u >> 6, l = u & 63;
+            f32x4 v = o_slot[0][t][l];
+            v += o_slot[1][t][l]; v += o_slot[2][t][l]; v += o_slot[3][t][l];
+            const int q = mt * 16 + (l & 15);
+            if (q >= rows) continue;
+            // per-query denominator lives with lane c == q of any wave: recompute from LDS
+            float M = -INFINITY;
+            for (int w = 0; w < AW; ++w) M = fmaxf(M, m_all[w][q]);
+            float den = 0.f;
+            for (int w = 0; w < AW; ++w) {
+                const float mw = m_all[w][q];
+                den += (mw == -INFINITY) ? 0.f : __expf(mw - M) * l_all[w][q];
+            }
+            v *= 1.0f / den;
+            const size_t off = act_off(q, head * HD + t * 16 + (l >> 4) * 4, d / 32);
+            bf16_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { hi[e] = f32_to_bf16(v[e]); lo[e] = f32_to_bf16(v[e] - bf16_to_f32(hi[e])); }
+            uint2 ph, pl;
+            ph.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); ph.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+            pl.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); pl.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
+            *reinterpret_cast<uint2 *>(out + off) = ph;
+            *reinterpret_cast<uint2 *>(out + (size_t)ROWS * d + off) = pl;
+        }
+    }
+    (void)inv_den;
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
 {
-    if (m->cfg.dtype == 1) {
-        // MFMA kernel: one wave per chunk, about 512 waves in all, chunks of at least 32 keys
-        int s = (512 + m->cfg.n_heads - 1) / m->cfg.n_heads;
-        s = (s + 3) / 4 * 4;
-        if (s > 64) s = 64;
-        int max_s = (m->cfg.max_seq + 31) / 32;
-        max_s = (max_s + 3) / 4 * 4;
-        if (s > max_s) s = max_s;
-        return s < 4 ? 4 : s;
-    }
+    if (m->cfg.dtype == 1) return 1;   // the MFMA kernel merges its key chunks inside the workgroup
     int s = (512 + m->cfg.n_heads - 1) / m->cfg.n_heads;   // about two workgroups per CU
     int max_s = (m->cfg.max_seq + ATT_TILE - 1) / ATT_TILE;
     if (s > max_s) s = max_s;
@@ -379,19 +409,15 @@ static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows,
 template <int HD>
 static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
 {
-    const int d = m->cfg.d_model, H = m->cfg.n_heads, splits = kv->att_splits;
+    const int d = m->cfg.d_model, H = m->cfg.n_heads;
     const bf16_t *kc = (const bf16_t *)kv->k + (size_t)layer * kv->k_layer_stride;
     const bf16_t *vc = (const bf16_t *)kv->v + (size_t)layer * kv->v_layer_stride;
-    dim3 grid(H, splits / 4), block(256);
     if (rows <= 16)
-        hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, block, 0, s, kv->qact, kc, vc, d, kv->v_stride, rows, splits,
-                           kv->att_part, kv->state);
+        hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), dim3(H), dim3(64 * AW), 0, s, kv->qact, kc, vc, d, kv->v_stride, rows,
+                           (bf16_t *)kv->att_out, kv->state);
     else
-        hipLaunchKernelGGL((attn_mfma_kernel<HD, 2>), grid, block, 0, s, kv->qact, kc, vc, d, kv->v_stride, rows, splits,
-                           kv->att_part, kv->state);
-    HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(H), dim3(256), 0, s, kv->att_part, splits, d, rows,
-                       (bf16_t *)kv->att_out, kv->state);
+        hipLaunchKernelGGL((attn_mfma_kernel<HD, 2>), dim3(H), dim3(64 * AW), 0, s, kv->qact, kc, vc, d, kv->v_stride, rows,
+                           (bf16_t *)kv->att_out, kv->state);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
