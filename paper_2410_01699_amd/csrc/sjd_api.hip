@@ -802,11 +802,16 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
 extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32_t wk, int32_t u, int32_t iters,
                               float *us_per_launch)
 {
+    // iters < 0: rotate through enough weight copies that none is still in the last-level cache
+    const bool cold = iters < 0;
+    if (cold) iters = -iters;
     if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
     if (tn < 1 || N % (16 * tn)) return SJD_EINVAL;
+    const size_t wbytes = (size_t)N * K * 2;
+    const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
     GemmScratch g;
     SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 2 * 2));
-    SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * 2));
+    SJD_TRY(dev_alloc(&g.Wp, wbytes * copies));
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
     lin.N = N; lin.K = K; lin.tn = tn; lin.wk = wk; lin.u = u; lin.w = g.Wp;
@@ -819,7 +824,10 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
     if (rc == SJD_OK) {
         (void)hipEventRecord(e0, 0);
-        for (int i = 0; i < iters && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
+        for (int i = 0; i < iters && rc == SJD_OK; ++i) {
+            lin.w = (const char *)g.Wp + (size_t)(i % copies) * wbytes;
+            rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
+        }
         (void)hipEventRecord(e1, 0);
         (void)hipEventSynchronize(e1);
         float ms = 0.f;

@@ -198,20 +198,7 @@ __global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restr
     const int total = n + rows;
     const float scale = rsqrtf((float)HD);
 
-    // Q as B operand: lane holds Q[query c (+16 mt)][32 ks + 8 g .. +8], scaled, hi/lo
-    bf16x8 qh[MT][KS], ql[MT][KS];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            float x[8];
-            const float4 *src = reinterpret_cast<const float4 *>(qact + (size_t)(mt * 16 + c) * d + head * HD + ks * 32 + g * 8);
-            const float4 x0 = src[0], x1 = src[1];
-            x[0] = x0.x * scale; x[1] = x0.y * scale; x[2] = x0.z * scale; x[3] = x0.w * scale;
-            x[4] = x1.x * scale; x[5] = x1.y * scale; x[6] = x1.z * scale; x[7] = x1.w * scale;
-            split8(x, qh[mt][ks], ql[mt][ks]);
-        }
-
+    __shared__ bf16x8 q_lds[MT][KS][2][64];
     f32x4 o[MT][DT];
     float m_run[MT], l_run[MT];
 #pragma unroll
@@ -221,7 +208,7 @@ __global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restr
         for (int t = 0; t < DT; ++t) o[mt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
-    bf16x8 ka0[2][KS], ka1[2][KS], va[DT];
+    bf16x8 ka0[2][KS], ka1[2][KS], va0[DT], va1[DT];
     // K tiles: keys k0 + c and k0 + 16 + c (prefetched one block ahead); V^T tiles: dims 16 t + c,
     // keys (k0 + 4g .. +4), (k0 + 16 + 4g .. +4) (loaded when the block starts: their latency hides
     // behind the score product and the softmax)
@@ -231,23 +218,22 @@ __global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restr
             _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                        \
                 ka[h][ks] = *reinterpret_cast<const bf16x8 *>(kc + (size_t)((k0) + h * 16 + c) * d + head * HD + ks * 32 + g * 8); \
     }
-#define LOAD_V(k0)                                                                                   \
-    _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
+#define LOAD_V(k0, va)                                                                               \
+    if ((k0) < total) _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
         const bf16_t *vp = vc + (size_t)(head * HD + t * 16 + c) * vstride + (k0) + g * 4;           \
         union { bf16x8 v; uint2 u[2]; } w_;                                                          \
         w_.u[0] = *reinterpret_cast<const uint2 *>(vp);                                              \
         w_.u[1] = *reinterpret_cast<const uint2 *>(vp + 16);                                         \
         va[t] = w_.v;                                                                                \
     }
-#define COMPUTE_KV(k0, ka)                                                                           \
-    LOAD_V(k0)                                                                                       \
+#define COMPUTE_KV(k0, ka, va)                                                                       \
     _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                              \
         f32x4 s_[2];                                                                                 \
         _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                              \
             s_[h] = (f32x4){0.f, 0.f, 0.f, 0.f};                                                     \
             _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                      \
-                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], qh[mt][ks], s_[h], 0, 0, 0); \
-                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], ql[mt][ks], s_[h], 0, 0, 0); \
+                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], q_lds[mt][ks][0][lane], s_[h], 0, 0, 0); \
+                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], q_lds[mt][ks][1][lane], s_[h], 0, 0, 0); \
             }                                                                                        \
         }                                                                                            \
         const int qrow = mt * 16 + c;                                                                \
@@ -280,25 +266,41 @@ __global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restr
         }                                                                                            \
     }
 
-    constexpr bool PREFETCH = (MT * HD <= 128);   // the big variant has no registers to spare
+    constexpr bool PREFETCH = (MT * HD <= 128);   // the biggest variant has no registers to spare
     int k0 = wave * 32;
+    LOAD_K(k0, ka0) LOAD_V(k0, va0)               // in flight while Q is staged
+    // Q as B operand, kept in LDS (all waves use the same tiles): entry [mt][ks][plane][lane] holds
+    // Q[query c (+16 mt)][32 ks + 8 g .. +8], scaled by 1/sqrt(HD), as hi and lo bf16 planes
+    for (int u = threadIdx.x; u < MT * KS * 64; u += 64 * AW) {
+        const int l = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
+        float x[8];
+        const float4 *src = reinterpret_cast<const float4 *>(qact + (size_t)(mt * 16 + (l & 15)) * d + head * HD + ks * 32 + (l >> 4) * 8);
+        const float4 x0 = src[0], x1 = src[1];
+        x[0] = x0.x * scale; x[1] = x0.y * scale; x[2] = x0.z * scale; x[3] = x0.w * scale;
+        x[4] = x1.x * scale; x[5] = x1.y * scale; x[6] = x1.z * scale; x[7] = x1.w * scale;
+        bf16x8 hi, lo;
+        split8(x, hi, lo);
+        q_lds[mt][ks][0][l] = hi; q_lds[mt][ks][1][l] = lo;
+    }
+
+    __syncthreads();                              // q_lds ready
     if constexpr (PREFETCH) {
-        LOAD_K(k0, ka0)
         while (k0 < total) {
-            LOAD_K(k0 + AW * 32, ka1)
-            COMPUTE_KV(k0, ka0)
+            LOAD_K(k0 + AW * 32, ka1) LOAD_V(k0 + AW * 32, va1)
+            COMPUTE_KV(k0, ka0, va0)
             k0 += AW * 32;
             if (k0 >= total) break;
-            LOAD_K(k0 + AW * 32, ka0)
-            COMPUTE_KV(k0, ka1)
+            LOAD_K(k0 + AW * 32, ka0) LOAD_V(k0 + AW * 32, va0)
+            COMPUTE_KV(k0, ka1, va1)
             k0 += AW * 32;
         }
     } else {
-        for (; k0 < total; k0 += AW * 32) {
-            LOAD_K(k0, ka0)
-            COMPUTE_KV(k0, ka0)
+        while (k0 < total) {
+            COMPUTE_KV(k0, ka0, va0)
+            k0 += AW * 32;
+            LOAD_K(k0, ka0) LOAD_V(k0, va0)
         }
-        (void)ka1;
+        (void)ka1; (void)va1;
     }
 #undef LOAD_K
 #undef LOAD_V

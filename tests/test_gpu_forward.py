@@ -290,3 +290,82 @@ def test_step_errors(B):
             B.sjd_init_model(B.config_from_shape(w.shape), blob[:-1])
     finally:
         g.close()
+
+
+# ------------------------------------------------------------------ full size, launch configuration of the benchmark
+def test_forward_and_step_7b_full_size(B):
+    """The 7B workload at its real shape (32 layers, d=4096, window 16, 8192 sampled codes of 65536):
+    every logit of one window against the fp64 oracle, then one whole sjd_step whose verification must
+    be bit-exact given the GPU's logits."""
+    w = synth.WORKLOADS["7b_32x32"]
+    _say("7b: generating weights")
+    blob = synth.make_weights(w.shape, seed=0, threads=16)
+    ids, _ = synth.make_prompt(w)
+    om = oracle.Model(w.shape, blob)
+    g = Gpu(B, w.shape, blob)
+    try:
+        V, lo, L = w.shape.v_s, w.shape.samp_lo, w.window
+        smp = B.sjd_sampler(w.top_k, w.temperature); init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id)
+        q_last = torch.empty(V, dtype=torch.float32, device="cuda")
+        _say("7b: gpu prefill")
+        B.sjd_prefill(g.m, g.kv, ids, None, smp, init, q_last)
+        draft = torch.zeros(L, dtype=torch.int32, device="cuda")
+        p_old = torch.zeros((L, V), dtype=torch.float32, device="cuda")
+        B.sjd_first_window(g.m, q_last, L, init, 7, draft, p_old)
+        torch.cuda.synchronize()
+        d_h, p_h = draft.cpu().numpy(), p_old.cpu().numpy()
+        got = g.logits(d_h)
+        _say("7b: oracle prefill + window (fp64 on the host, about half a minute)")
+        om.prefill(ids)
+        ref = om.forward_tokens(len(ids), d_h)
+        err = float(np.max(np.abs(got - ref)))
+        _say(f"7b: worst logit error {err:.3e} (logit std {ref.std():.3f})")
+        assert err < TOL_BF16
+        want = oracle.verify(got, p_h, d_h, lo, oracle.Sampler(w.top_k, w.temperature),
+                             oracle.Init(w.init_mode, w.row_stride, w.eol_id), 0, None, 7, 1)
+        na = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nd = torch.zeros(L, dtype=torch.int32, device="cuda"); pn = torch.zeros_like(p_old)
+        B.sjd_step(g.m, g.kv, draft, p_old, L, smp, init, 0, 7, 1, na, nd, pn)
+        torch.cuda.synchronize()
+        assert int(na.item()) == want[0]
+        assert np.array_equal(nd.cpu().numpy(), want[1])
+        assert np.array_equal(pn.cpu().numpy().view(np.uint32), want[2].view(np.uint32))
+        assert B.sjd_kv_len(g.kv) == len(ids) + want[0]
+    finally:
+        g.close(); om.close()
+
+
+def test_graph_replay_equals_eager_and_is_deterministic(B):
+    """The decode loop replays one captured iteration; every replay must give what the kernel-by-kernel
+    path gives, run after run (the loop state lives on the device, nothing is baked into the graph)."""
+    shape = synth.ModelShape(3, 512, 8, 1024, 4096, 2048, 4096, 400, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=9)
+    g = Gpu(B, shape, blob)
+    try:
+        prompt = synth.random_tokens(40, 0, 2048, seed=1)
+        smp = B.sjd_sampler(500, 1.0); init = B.sjd_init(0, 16, -1)
+        outs = []
+        for use_graph in (True, False, True):
+            B.sjd_kv_use_graph(g.kv, use_graph)
+            for seed in (1, 2):
+                _say(f"graph={use_graph} seed={seed}")
+                toks, st = B.sjd_generate(g.m, g.kv, prompt, None, 200, 16, smp, init, seed)
+                outs.append((use_graph, seed, toks, st.steps))
+        ref = {s: (t, n) for ug, s, t, n in outs if not ug}
+        for ug, s, t, n in outs:
+            assert np.array_equal(t, ref[s][0]) and n == ref[s][1], (ug, s)
+        # stepping in pieces (status polled in between) gives the same stream as one go
+        q_first = torch.empty(shape.v_s, dtype=torch.float32, device="cuda")
+        B.sjd_kv_use_graph(g.kv, True)
+        B.sjd_prefill(g.m, g.kv, prompt, None, smp, init, q_first)
+        B.sjd_decode_begin(g.m, g.kv, q_first, 200, 16, smp, init, 1)
+        done, guard = False, 0
+        while not done:
+            B.sjd_decode_steps(g.m, g.kv, 3)
+            fixed, steps, done = B.sjd_decode_status(g.kv)
+            guard += 1
+            assert guard < 200
+        toks, st = B.sjd_decode_result(g.kv, 200)
+        assert np.array_equal(toks, ref[1][0]) and st.steps == ref[1][1]
+    finally:
+        g.close()
