@@ -195,7 +195,7 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     kv->m = m;
     kv->use_graph = 1;
     const sjd_config &c = m->cfg;
-    const size_t es = elt_size(c.dtype), d = c.d_model, F = c.d_ffn, V = m->V_s, R = SJD_ROWS_MAX;
+    const size_t d = c.d_model, F = c.d_ffn, V = m->V_s, R = SJD_ROWS_MAX;
     size_t part = 0;
     auto upd = [&](const SjdLinear &l) { part = std::max(part, (size_t)R * l.N); };
     for (int l = 0; l < c.n_layers; ++l) { upd(m->layers[l].qkv); upd(m->layers[l].o); upd(m->layers[l].gu); upd(m->layers[l].down); }
@@ -204,22 +204,25 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     kv->att_splits = sjd_attention_splits(m);
     int rc = SJD_OK;
 #define A(ptr, bytes) if (rc == SJD_OK) rc = dev_alloc((void **)&(ptr), (bytes))
-    // bf16: the attention kernel reads whole 32-key blocks, so both caches are padded past max_seq
-    kv->k_rows = c.dtype == 1 ? (c.max_seq + 31) / 32 * 32 + 32 : c.max_seq;
-    kv->v_stride = kv->k_rows;
-    kv->k_layer_stride = (size_t)kv->k_rows * d;
-    kv->v_layer_stride = (size_t)kv->v_stride * d;
-    A(kv->k, (size_t)c.n_layers * kv->k_layer_stride * es);
-    A(kv->v, (size_t)c.n_layers * kv->v_layer_stride * es);
+    if (c.dtype == 1) {
+        // blocked hi/lo cache: [layer][head][block of 32 positions][128 * hd] bf16, K and V together
+        kv->nblk = (c.max_seq + 31) / 32;
+        kv->k_layer_stride = (size_t)kv->nblk * 128 * d;
+        A(kv->k, (size_t)c.n_layers * kv->k_layer_stride * 2);
+    } else {
+        kv->k_layer_stride = kv->v_layer_stride = (size_t)c.max_seq * d;
+        A(kv->k, (size_t)c.n_layers * kv->k_layer_stride * 4);
+        A(kv->v, (size_t)c.n_layers * kv->v_layer_stride * 4);
+    }
     A(kv->tokens, (size_t)c.max_seq * 4);
     A(kv->state, sizeof(SjdState));
     A(kv->x, R * d * 4);
-    A(kv->h, R * d * es * 2);          // bf16 models: hi + lo planes
+    A(kv->h, c.dtype == 0 ? R * d * 4 : 16);
     A(kv->part, (c.dtype == 0 ? part : 4) * 4);
     A(kv->qact, R * d * 4);
     A(kv->att_part, sjd_attention_part_elems(m) * 4);
-    A(kv->att_out, R * d * es * 2);
-    A(kv->ffn, R * F * es * 2);
+    A(kv->att_out, R * d * 4);
+    A(kv->ffn, R * F * 4);
     A(kv->logits, R * V * 4);
     A(kv->q, (R + 1) * V * 4);
     A(kv->tok_smp, (R + 1) * 4);
@@ -357,35 +360,34 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
     return SJD_OK;
 }
 
-// bf16: residual adds, SiLU*up, RoPE and the cache write happen inside the GEMM epilogues
+// bf16: RMSNorm, residual adds, SiLU*up, RoPE and the cache write happen inside the projection kernel
 static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
 {
     const SjdState *st = kv->state;
-    const int d = m->cfg.d_model, F = m->cfg.d_ffn, ms = m->cfg.max_seq;
-    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * d * 2;   // upper bound
+    const int d = m->cfg.d_model, F = m->cfg.d_ffn;
+    const float eps = m->cfg.rms_eps;
+    // upper bound of the K/V bytes one layer's attention reads (hi + lo planes)
+    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * d * 4;
     SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
     memset(&e_qkv, 0, sizeof(e_qkv));
     e_qkv.st = st;
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
-    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.max_seq = kv->v_stride; e_qkv.rows_valid = rows_valid;
+    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid;
     e_res.kind = SJD_EPI_RESID; e_res.out = kv->x;
-    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (bf16_t *)kv->ffn; e_silu.ffn_plane = (size_t)SJD_ROWS_MAX * F; e_silu.F = F;
+    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (float *)kv->ffn; e_silu.F = F;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
+    const float *x = kv->x, *att = (const float *)kv->att_out, *ffn = (const float *)kv->ffn;
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
-        e_qkv.kc = (bf16_t *)kv->k + l * kv->k_layer_stride;
-        e_qkv.vc = (bf16_t *)kv->v + l * kv->v_layer_stride;
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, L.g1, rows, kv->h, st, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, (const bf16_t *)kv->h, rows, e_qkv, s));
+        e_qkv.kvc = (bf16_t *)kv->k + l * kv->k_layer_stride;
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, (const bf16_t *)L.g1, eps, rows, e_qkv, s));
         PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, (const bf16_t *)kv->att_out, rows, e_res, s));
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, L.g2, rows, kv->h, st, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, (const bf16_t *)kv->h, rows, e_silu, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, (const bf16_t *)kv->ffn, rows, e_res, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, nullptr, 0.f, rows, e_res, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, (const bf16_t *)L.g2, eps, rows, e_silu, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, nullptr, 0.f, rows, e_res, s));
     }
-    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_norm_bf16(m, kv->x, m->gf, rows, kv->h, st, s));
-    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, (const bf16_t *)kv->h, rows, e_lm, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, (const bf16_t *)m->gf, eps, rows, e_lm, s));
     return SJD_OK;
 }
 
@@ -776,12 +778,12 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     hipStream_t s = (hipStream_t)stream;
     const size_t es = elt_size(dtype);
     GemmScratch g;
-    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * es * 2));   // lo plane stays zero
+    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4));     // rows past M stay zero
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
     lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 8; lin.u = 2; lin.w = W;
     if (dtype == 1) {
-        SJD_TRY(sjd_pack_act((const bf16_t *)A, M, K, (bf16_t *)g.Ap, s));
+        SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
         SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * es));
         SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)g.Wp, N, K, 0, 0, 0, s));
         lin.w = g.Wp;
@@ -789,7 +791,7 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
         SjdGemmEpi ep;
         memset(&ep, 0, sizeof(ep));
         ep.kind = SJD_EPI_STORE; ep.out = g.out;
-        SJD_TRY(sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, s));
+        SJD_TRY(sjd_launch_gemm_bf16(&lin, (const float *)g.Ap, nullptr, 0.f, M, ep, s));
     } else {
         HIP_TRY(hipMemcpyAsync(g.Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
         SJD_TRY(sjd_launch_gemm(0, &lin, g.Ap, M, g.out, nullptr, s));
@@ -810,7 +812,7 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     const size_t wbytes = (size_t)N * K * 2;
     const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
     GemmScratch g;
-    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 2 * 2));
+    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4));
     SJD_TRY(dev_alloc(&g.Wp, wbytes * copies));
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
@@ -821,12 +823,12 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
     int rc = SJD_OK;
-    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
+    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const float *)g.Ap, nullptr, 0.f, M, ep, 0);
     if (rc == SJD_OK) {
         (void)hipEventRecord(e0, 0);
         for (int i = 0; i < iters && rc == SJD_OK; ++i) {
             lin.w = (const char *)g.Wp + (size_t)(i % copies) * wbytes;
-            rc = sjd_launch_gemm_bf16(&lin, (const bf16_t *)g.Ap, M, ep, 0);
+            rc = sjd_launch_gemm_bf16(&lin, (const float *)g.Ap, nullptr, 0.f, M, ep, 0);
         }
         (void)hipEventRecord(e1, 0);
         (void)hipEventSynchronize(e1);

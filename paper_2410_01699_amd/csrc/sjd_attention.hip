@@ -4,8 +4,8 @@
 // an online-softmax state (running max, denominator, unnormalised output) for its chunk and a small
 // second kernel merges the chunks in a fixed order.
 //
-// Two kernels: a generic one for the fp32 models (key/value tiles of 64 positions staged in LDS as
-// fp32, plain FMA arithmetic) and an MFMA one for bf16 caches.
+// Two implementations: a generic one for the fp32 models (key/value tiles of 64 positions staged in
+// LDS as fp32, plain FMA arithmetic) and an MFMA one for the blocked hi/lo cache of bf16 models.
 #include "sjd_internal.h"
 
 #define ATT_TILE 64
@@ -13,17 +13,8 @@
 
 template <typename T> __device__ __forceinline__ float ld(const T *p, size_t i);
 template <> __device__ __forceinline__ float ld<float>(const float *p, size_t i) { return p[i]; }
-template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
-// attention output feeds the O projection: bf16 models store it as hi/lo bf16 planes
 template <typename T> __device__ __forceinline__ void st_act(T *p, int r, int c, int d, float v);
 template <> __device__ __forceinline__ void st_act<float>(float *p, int r, int c, int d, float v) { p[(size_t)r * d + c] = v; }
-template <> __device__ __forceinline__ void st_act<bf16_t>(bf16_t *p, int r, int c, int d, float v)
-{
-    const bf16_t hi = f32_to_bf16(v);
-    const size_t o = act_off(r, c, d / 32);
-    p[o] = hi;
-    p[(size_t)SJD_ROWS_MAX * d + o] = f32_to_bf16(v - bf16_to_f32(hi));
-}
 
 // part layout per (head, split): [rows][hd] unnormalised output, then m[rows], then l[rows]
 template <typename T, int HD>
@@ -151,125 +142,59 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, int splits, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 caches: MFMA kernel.  One wave per (head, key chunk); per block of 32 keys
-//   S^T[key][query] = K[key][:] . Q[query][:]      A = K tile (16 keys x 32 dims, straight from the
-//                                                   row-major K cache), B = Q (hi + lo bf16 planes)
-//   O^T[dim][query] += V^T[dim][key] * P[key][query] A = V^T tile from the transposed V cache, B = P
-// The two 16-key score tiles of a block leave lane l (query l%16, group g = l/16) with the keys
-// {4g..4g+3} and {16+4g..16+4g+3}; using the same key order for the V^T operand makes the
-// probabilities the B operand of the second product without any cross-lane movement.
+// bf16 models: MFMA kernels over the blocked hi/lo cache.  Per block of 32 positions
+//   S^T[key][query] = K[key][:] . Q[query][:]       A = K tile (16 keys x 32 dims), B = Q
+//   O^T[dim][query] += V^T[dim][key] * P[key][query] A = V^T tile (16 dims x 32 keys), B = P
+// Both cache operands are stored exactly as the lanes consume them, so a wave fetches a block's K and
+// V tiles as contiguous 1 KiB loads.  Every operand is a hi + lo bf16 pair; a product keeps the
+// three leading terms hi*hi + hi*lo + lo*hi (about 16 significant bits).  The two 16-key score tiles
+// of a block leave lane l (query l%16, group g = l/16) with the keys {4g..4g+3} and {16+4g..16+4g+3};
+// the V^T tiles use the same key order, which makes the probabilities the B operand of the second
+// product without any cross-lane movement.
+//
+// attn_split_kernel: workgroup (head, split) of AW waves takes a contiguous range of blocks; wave w
+// handles every AW-th block of it with an online softmax (running max, denominator, unnormalised
+// O^T per query); the waves are merged through LDS in wave order and the workgroup writes one
+// partial result.  attn_merge_kernel combines the splits of a head in split order.
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &lo)
 {
-    union { bf16x8 v; bf16_t s[8]; } h, l;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        h.s[e] = f32_to_bf16(x[e]);
-        l.s[e] = f32_to_bf16(x[e] - bf16_to_f32(h.s[e]));
+        const __bf16 h = (__bf16)x[e];
+        hi[e] = h;
+        lo[e] = (__bf16)(x[e] - (float)h);
     }
-    hi = h.v; lo = l.v;
 }
 
-// One workgroup of AW waves per head.  Wave w takes the 32-key blocks w, w+AW, ... of the range
-// [0, n+rows), prefetching the next block's K/V tiles while it works on the current one, and keeps
-// an online-softmax state (running max, denominator, unnormalised O^T) per query.  The waves then
-// agree on the per-query maximum through LDS, rescale, and their outputs are added AW/4... four
-// waves at a time in wave order (fixed order -> deterministic); the result is written as hi/lo bf16
-// planes in the layout the O projection streams.
-#define AW 8
+#define AW 4
+// partial record of (head, split): O[MT*16][HD] unnormalised, then m[MT*16], then l[MT*16]
 template <int HD, int MT>
-__global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restrict__ qact,
-                                                           const bf16_t *__restrict__ kc,
-                                                           const bf16_t *__restrict__ vc, int d, int vstride,
-                                                           int rows, bf16_t *__restrict__ out, const SjdState *st)
+__global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__restrict__ qact,
+                                                            const bf16_t *__restrict__ kvc, int d, int nblk_cache,
+                                                            int rows, int splits, float *__restrict__ part,
+                                                            const SjdState *st)
 {
     if (st->done) return;
-    constexpr int ROWS = SJD_ROWS_MAX;
     constexpr int KS = HD / 32;      // k-steps of the score product
     constexpr int DT = HD / 16;      // output dim tiles
+    constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     __shared__ float m_all[AW][MT * 16], l_all[AW][MT * 16];
-    __shared__ f32x4 o_slot[4][DT][64];
+    __shared__ f32x4 o_slot[AW][DT][64];
+    __shared__ bf16x8 q_lds[MT][KS][2][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
-    const int head = blockIdx.x;
+    const int head = blockIdx.x, split = blockIdx.y;
     const int n = st->n;
     const int total = n + rows;
+    const int nblk = (total + 31) >> 5;
+    const int bps = (nblk + splits - 1) / splits;
+    const int b_beg = split * bps, b_end = min(nblk, b_beg + bps);
     const float scale = rsqrtf((float)HD);
 
-    __shared__ bf16x8 q_lds[MT][KS][2][64];
-    f32x4 o[MT][DT];
-    float m_run[MT], l_run[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        m_run[mt] = -INFINITY; l_run[mt] = 0.f;
-#pragma unroll
-        for (int t = 0; t < DT; ++t) o[mt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    }
-
-    bf16x8 ka0[2][KS], ka1[2][KS], va0[DT], va1[DT];
-    // K tiles: keys k0 + c and k0 + 16 + c (prefetched one block ahead); V^T tiles: dims 16 t + c,
-    // keys (k0 + 4g .. +4), (k0 + 16 + 4g .. +4) (loaded when the block starts: their latency hides
-    // behind the score product and the softmax)
-#define LOAD_K(k0, ka)                                                                               \
-    if ((k0) < total) {                                                                              \
-        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                \
-            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                        \
-                ka[h][ks] = *reinterpret_cast<const bf16x8 *>(kc + (size_t)((k0) + h * 16 + c) * d + head * HD + ks * 32 + g * 8); \
-    }
-#define LOAD_V(k0, va)                                                                               \
-    if ((k0) < total) _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                                 \
-        const bf16_t *vp = vc + (size_t)(head * HD + t * 16 + c) * vstride + (k0) + g * 4;           \
-        union { bf16x8 v; uint2 u[2]; } w_;                                                          \
-        w_.u[0] = *reinterpret_cast<const uint2 *>(vp);                                              \
-        w_.u[1] = *reinterpret_cast<const uint2 *>(vp + 16);                                         \
-        va[t] = w_.v;                                                                                \
-    }
-#define COMPUTE_KV(k0, ka, va)                                                                       \
-    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                              \
-        f32x4 s_[2];                                                                                 \
-        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                              \
-            s_[h] = (f32x4){0.f, 0.f, 0.f, 0.f};                                                     \
-            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                      \
-                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], q_lds[mt][ks][0][lane], s_[h], 0, 0, 0); \
-                s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks], q_lds[mt][ks][1][lane], s_[h], 0, 0, 0); \
-            }                                                                                        \
-        }                                                                                            \
-        const int qrow = mt * 16 + c;                                                                \
-        float p_[8];                                                                                 \
-        float mx = m_run[mt];                                                                        \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
-            const int key = (k0) + (e >> 2) * 16 + g * 4 + (e & 3);                                  \
-            const bool ok = key <= n + qrow && qrow < rows;     /* causal inside the window */       \
-            p_[e] = ok ? s_[e >> 2][e & 3] : -INFINITY;                                              \
-            mx = fmaxf(mx, p_[e]);                                                                   \
-        }                                                                                            \
-        mx = fmaxf(mx, __shfl_xor(mx, 16));                                                          \
-        mx = fmaxf(mx, __shfl_xor(mx, 32));                                                          \
-        const float so = (mx == -INFINITY) ? 1.f : __expf(m_run[mt] - mx);                           \
-        float sum = 0.f;                                                                             \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
-            p_[e] = (p_[e] == -INFINITY) ? 0.f : __expf(p_[e] - mx);                                 \
-            sum += p_[e];                                                                            \
-        }                                                                                            \
-        sum += __shfl_xor(sum, 16);                                                                  \
-        sum += __shfl_xor(sum, 32);                                                                  \
-        l_run[mt] = l_run[mt] * so + sum;                                                            \
-        m_run[mt] = mx;                                                                              \
-        bf16x8 ph, pl;                                                                               \
-        split8(p_, ph, pl);                                                                          \
-        _Pragma("unroll") for (int t = 0; t < DT; ++t) {                                             \
-            o[mt][t] *= so;                                                                          \
-            o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t], ph, o[mt][t], 0, 0, 0);        \
-            o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t], pl, o[mt][t], 0, 0, 0);        \
-        }                                                                                            \
-    }
-
-    constexpr bool PREFETCH = (MT * HD <= 128);   // the biggest variant has no registers to spare
-    int k0 = wave * 32;
-    LOAD_K(k0, ka0) LOAD_V(k0, va0)               // in flight while Q is staged
-    // Q as B operand, kept in LDS (all waves use the same tiles): entry [mt][ks][plane][lane] holds
+    // Q as B operand, shared by the waves: entry [mt][ks][plane][lane] holds
     // Q[query c (+16 mt)][32 ks + 8 g .. +8], scaled by 1/sqrt(HD), as hi and lo bf16 planes
     for (int u = threadIdx.x; u < MT * KS * 64; u += 64 * AW) {
         const int l = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
@@ -283,106 +208,156 @@ __global__ __launch_bounds__(64 * AW) void attn_mfma_kernel(const float *__restr
         q_lds[mt][ks][0][l] = hi; q_lds[mt][ks][1][l] = lo;
     }
 
-    __syncthreads();                              // q_lds ready
-    if constexpr (PREFETCH) {
-        while (k0 < total) {
-            LOAD_K(k0 + AW * 32, ka1) LOAD_V(k0 + AW * 32, va1)
-            COMPUTE_KV(k0, ka0, va0)
-            k0 += AW * 32;
-            if (k0 >= total) break;
-            LOAD_K(k0 + AW * 32, ka0) LOAD_V(k0 + AW * 32, va0)
-            COMPUTE_KV(k0, ka1, va1)
-            k0 += AW * 32;
-        }
-    } else {
-        while (k0 < total) {
-            COMPUTE_KV(k0, ka0, va0)
-            k0 += AW * 32;
-            LOAD_K(k0, ka0) LOAD_V(k0, va0)
-        }
-        (void)ka1; (void)va1;
+    f32x4 o[MT][DT];
+    float m_run[MT], l_run[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        m_run[mt] = -INFINITY; l_run[mt] = 0.f;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) o[mt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
-#undef LOAD_K
-#undef LOAD_V
-#undef COMPUTE_KV
+    __syncthreads();                              // q_lds ready
 
-    // ---- merge the AW waves -------------------------------------------------------------------
+    for (int blk = b_beg + wave; blk < b_end; blk += AW) {
+        const bf16x8 *rec = reinterpret_cast<const bf16x8 *>(kvc + kv_block_off(head, blk, nblk_cache, HD)) + lane;
+        bf16x8 ka[2][KS][2], va[DT][2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl) ka[h][ks][pl] = rec[((h * KS + ks) * 2 + pl) * 64];
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl) va[t][pl] = rec[(2 * KS * 2 + t * 2 + pl) * 64];
+        const int k0 = blk * 32;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            f32x4 s_[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                s_[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 qh = q_lds[mt][ks][0][lane], ql = q_lds[mt][ks][1][lane];
+                    s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks][1], qh, s_[h], 0, 0, 0);
+                    s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks][0], ql, s_[h], 0, 0, 0);
+                    s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks][0], qh, s_[h], 0, 0, 0);
+                }
+            }
+            const int qrow = mt * 16 + c;
+            float p_[8];
+            float mx = m_run[mt];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = k0 + (e >> 2) * 16 + g * 4 + (e & 3);
+                const bool ok = key <= n + qrow && qrow < rows;     // causal inside the window
+                p_[e] = ok ? s_[e >> 2][e & 3] : -INFINITY;
+                mx = fmaxf(mx, p_[e]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float so = (mx == -INFINITY) ? 1.f : __expf(m_run[mt] - mx);
+            float sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                p_[e] = (p_[e] == -INFINITY) ? 0.f : __expf(p_[e] - mx);
+                sum += p_[e];
+            }
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            l_run[mt] = l_run[mt] * so + sum;
+            m_run[mt] = mx;
+            bf16x8 ph, pl;
+            split8(p_, ph, pl);
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                o[mt][t] *= so;
+                o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t][1], ph, o[mt][t], 0, 0, 0);
+                o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t][0], pl, o[mt][t], 0, 0, 0);
+                o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t][0], ph, o[mt][t], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- merge the AW waves (wave order) and write the partial record -----------------------------
     if (g == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) { m_all[wave][mt * 16 + c] = m_run[mt]; l_all[wave][mt * 16 + c] = l_run[mt]; }
     }
     __syncthreads();
-    float inv_den[MT];
+    float *dst = part + (size_t)(head * splits + split) * REC;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         float M = -INFINITY;
+#pragma unroll
         for (int w = 0; w < AW; ++w) M = fmaxf(M, m_all[w][mt * 16 + c]);
-        float den = 0.f;
-        for (int w = 0; w < AW; ++w) {
-            const float mw = m_all[w][mt * 16 + c];
-            den += (mw == -INFINITY) ? 0.f : __expf(mw - M) * l_all[w][mt * 16 + c];
-        }
-        inv_den[mt] = 1.0f / den;
         const float mine = (m_run[mt] == -INFINITY) ? 0.f : __expf(m_run[mt] - M);
+        if (mt) __syncthreads();                  // o_slot is reused
 #pragma unroll
-        for (int t = 0; t < DT; ++t) o[mt][t] *= mine;
-    }
-    // add the rescaled outputs four waves at a time; waves 0..3 keep the running sums
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        for (int r = 1; r < AW / 4; ++r) {
-            __syncthreads();
-            if ((wave >> 2) == r) {
-#pragma unroll
-                for (int t = 0; t < DT; ++t) o_slot[wave & 3][t][lane] = o[mt][t];
-            }
-            __syncthreads();
-            if (wave < 4) {
-#pragma unroll
-                for (int t = 0; t < DT; ++t) o[mt][t] += o_slot[wave][t][lane];
-            }
-        }
-        // waves 0..3 -> slots, then wave 0 adds slots 1..3 in order and writes the head's output
+        for (int t = 0; t < DT; ++t) o_slot[wave][t][lane] = o[mt][t] * mine;
         __syncthreads();
-        if (wave < 4) {
-#pragma unroll
-            for (int t = 0; t < DT; ++t) o_slot[wave][t][lane] = o[mt][t];
-        }
-        __syncthreads();
-        // 256 result fragments (DT x 64) per query tile: spread them over the workgroup
         for (int u = threadIdx.x; u < DT * 64; u += 64 * AW) {
             const int t = u >> 6, l = u & 63;
             f32x4 v = o_slot[0][t][l];
-            v += o_slot[1][t][l]; v += o_slot[2][t][l]; v += o_slot[3][t][l];
-            const int q = mt * 16 + (l & 15);
-            if (q >= rows) continue;
-            // per-query denominator lives with lane c == q of any wave: recompute from LDS
-            float M = -INFINITY;
-            for (int w = 0; w < AW; ++w) M = fmaxf(M, m_all[w][q]);
-            float den = 0.f;
-            for (int w = 0; w < AW; ++w) {
-                const float mw = m_all[w][q];
-                den += (mw == -INFINITY) ? 0.f : __expf(mw - M) * l_all[w][q];
-            }
-            v *= 1.0f / den;
-            const size_t off = act_off(q, head * HD + t * 16 + (l >> 4) * 4, d / 32);
-            bf16_t hi[4], lo[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { hi[e] = f32_to_bf16(v[e]); lo[e] = f32_to_bf16(v[e] - bf16_to_f32(hi[e])); }
-            uint2 ph, pl;
-            ph.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); ph.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
-            pl.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); pl.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
-            *reinterpret_cast<uint2 *>(out + off) = ph;
-            *reinterpret_cast<uint2 *>(out + (size_t)ROWS * d + off) = pl;
+            for (int w = 1; w < AW; ++w) v += o_slot[w][t][l];
+            // lane l holds dims 16 t + 4 (l/16) .. +4 of query l%16
+            *reinterpret_cast<f32x4 *>(dst + (size_t)(mt * 16 + (l & 15)) * HD + t * 16 + (l >> 4) * 4) = v;
+        }
+        if (wave == 0 && g == 0) {
+            float den = 0.f;
+#pragma unroll
+            for (int w = 0; w < AW; ++w) {
+                const float mw = m_all[w][mt * 16 + c];
+                den += (mw == -INFINITY) ? 0.f : __expf(mw - M) * l_all[w][mt * 16 + c];
+            }
+            dst[MT * 16 * HD + mt * 16 + c] = M;
+            dst[MT * 16 * HD + MT * 16 + mt * 16 + c] = den;
         }
     }
-    (void)inv_den;
+}
+
+// out[q][head*HD + :] = sum_s w_s O_s[q][:] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s)
+template <int HD, int MT>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
+                                                        float *__restrict__ out, const SjdState *st)
+{
+    if (st->done) return;
+    constexpr int REC = MT * 16 * HD + 2 * MT * 16;
+    constexpr int Q4 = HD / 4;
+    const int head = blockIdx.x;
+    const float *base = part + (size_t)head * splits * REC;
+    for (int u = threadIdx.x; u < rows * Q4; u += 256) {
+        const int q = u / Q4, j4 = u % Q4;
+        float M = -INFINITY;
+        for (int s = 0; s < splits; ++s) M = fmaxf(M, base[(size_t)s * REC + MT * 16 * HD + q]);
+        f32x4 num = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+        for (int s = 0; s < splits; ++s) {
+            const float *p = base + (size_t)s * REC;
+            const float ms = p[MT * 16 * HD + q];
+            if (ms == -INFINITY) continue;
+            const float w = __expf(ms - M);
+            num += w * *reinterpret_cast<const f32x4 *>(p + (size_t)q * HD + j4 * 4);
+            den += w * p[MT * 16 * HD + MT * 16 + q];
+        }
+        *reinterpret_cast<f32x4 *>(out + (size_t)q * d + head * HD + j4 * 4) = num * (1.0f / den);
+    }
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
 {
-    if (m->cfg.dtype == 1) return 1;   // the MFMA kernel merges its key chunks inside the workgroup
-    int s = (512 + m->cfg.n_heads - 1) / m->cfg.n_heads;   // about two workgroups per CU
+    const int H = m->cfg.n_heads;
+    if (m->cfg.dtype == 1) {
+        // about two workgroups per CU, but at least four 32-position blocks per split at full length
+        int s = (512 + H - 1) / H;
+        int max_s = ((m->cfg.max_seq + 31) / 32 + 3) / 4;
+        if (s > max_s) s = max_s;
+        return s < 1 ? 1 : s;
+    }
+    int s = (512 + H - 1) / H;   // about two workgroups per CU
     int max_s = (m->cfg.max_seq + ATT_TILE - 1) / ATT_TILE;
     if (s > max_s) s = max_s;
     return s < 1 ? 1 : s;
@@ -408,20 +383,24 @@ static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows,
     return SJD_OK;
 }
 
+template <int HD, int MT>
+static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
+{
+    const int d = m->cfg.d_model, H = m->cfg.n_heads;
+    const bf16_t *kvc = (const bf16_t *)kv->k + (size_t)layer * kv->k_layer_stride;
+    hipLaunchKernelGGL((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits), dim3(64 * AW), 0, s, kv->qact, kvc, d,
+                       kv->nblk, rows, kv->att_splits, kv->att_part, kv->state);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL((attn_merge_kernel<HD, MT>), dim3(H), dim3(256), 0, s, kv->att_part, kv->att_splits, d, rows,
+                       (float *)kv->att_out, kv->state);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
 template <int HD>
 static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
 {
-    const int d = m->cfg.d_model, H = m->cfg.n_heads;
-    const bf16_t *kc = (const bf16_t *)kv->k + (size_t)layer * kv->k_layer_stride;
-    const bf16_t *vc = (const bf16_t *)kv->v + (size_t)layer * kv->v_layer_stride;
-    if (rows <= 16)
-        hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), dim3(H), dim3(64 * AW), 0, s, kv->qact, kc, vc, d, kv->v_stride, rows,
-                           (bf16_t *)kv->att_out, kv->state);
-    else
-        hipLaunchKernelGGL((attn_mfma_kernel<HD, 2>), dim3(H), dim3(64 * AW), 0, s, kv->qact, kc, vc, d, kv->v_stride, rows,
-                           (bf16_t *)kv->att_out, kv->state);
-    HIP_TRY(hipGetLastError());
-    return SJD_OK;
+    return rows <= 16 ? launch_mfma_t<HD, 1>(m, kv, layer, rows, s) : launch_mfma_t<HD, 2>(m, kv, layer, rows, s);
 }
 
 int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)

@@ -1,4 +1,5 @@
-// bf16 skinny-M projections of the window forward (paper Sec. 4.1 Step 2) with fused epilogues.
+// bf16 skinny-M projections of the window forward (paper Sec. 4.1 Step 2) with fused prologue and
+// epilogues.
 //
 // C[M x N] = A[M x K] * W^T, M = window size (16 or 32 rows), is a pure weight stream: every weight
 // is read from HBM once and used for M multiply-adds (about M flop per byte, far left of the MFMA
@@ -6,10 +7,15 @@
 //
 //  - W is pre-packed (sjd_repack_bf16) into 16x32 tiles in the exact A-operand register order of
 //    v_mfma_f32_16x16x32_bf16: one 16-byte load per lane fetches 1 KiB of contiguous HBM per wave.
-//  - The activations are the B operand (tokens on the 16 columns), stored by their producers in
-//    B-operand order too (act_off) as two bf16 planes hi + lo that are multiplied separately:
-//    ~16 significant bits of activation at no extra HBM traffic.  They come from L2; a wave reuses
-//    each activation tile for its TN weight tiles, so TN sets the L2-to-HBM traffic ratio.
+//  - The activations are the B operand (tokens on the 16 columns).  They are fp32 rows in L2; each
+//    lane loads the 8 consecutive values of its token and k-group and splits them into hi = bf16(x)
+//    and lo = bf16(x - hi), which are multiplied separately: ~16 significant bits of activation for
+//    the same L2 bytes as two packed bf16 planes.  A wave reuses each activation tile for its TN
+//    weight tiles, so TN sets the L2-to-HBM traffic ratio.
+//  - RMSNorm in front of a projection is folded in: the values are multiplied by the gain before the
+//    split, every workgroup accumulates the sum of squares of the rows it streams anyway, and the
+//    factor rsqrt(mean(x^2) + eps) of each token is applied to the final sums (it is constant along
+//    the reduction).  All workgroups add the squares in the same order, so they agree bit for bit.
 //  - One workgroup owns TN output tiles (16*TN features) for the WHOLE reduction; its WK waves
 //    split K between them and add their fp32 accumulators through LDS in wave order.  No global
 //    partial sums, no atomics: results are deterministic and the epilogue sees final values.
@@ -25,6 +31,24 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// hi = bf16(x) (round to nearest even), lo = bf16(x - hi)
+__device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &lo)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const __bf16 h = (__bf16)x[e];
+        hi[e] = h;
+        lo[e] = (__bf16)(x[e] - (float)h);
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_hi2(float a, float b, float &ra, float &rb)
+{
+    const bf16_t ha = f32_to_bf16(a), hb = f32_to_bf16(b);
+    ra = a - bf16_to_f32(ha); rb = b - bf16_to_f32(hb);
+    return (uint32_t)ha | ((uint32_t)hb << 16);
+}
+
 // One accumulator fragment: lane l of the MFMA result holds features n0..n0+3 (packed order) of
 // token m.  v = final sums.
 template <int EPI>
@@ -38,13 +62,10 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
     } else if (EPI == SJD_EPI_SILU) {
         // packed rows: (gate f, up f, gate f+1, up f+1)
         const int f = n0 >> 1;
-        const float y0 = v[0] / (1.0f + __expf(-v[0])) * v[1];
-        const float y1 = v[2] / (1.0f + __expf(-v[2])) * v[3];
-        const size_t o = act_off(m, f, ep.F / 32);
-        const bf16_t h0 = f32_to_bf16(y0), h1 = f32_to_bf16(y1);
-        *reinterpret_cast<uint32_t *>(ep.ffn + o) = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        *reinterpret_cast<uint32_t *>(ep.ffn + ep.ffn_plane + o) =
-            (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
+        float2 y;
+        y.x = v[0] / (1.0f + __expf(-v[0])) * v[1];
+        y.y = v[2] / (1.0f + __expf(-v[2])) * v[3];
+        *reinterpret_cast<float2 *>(ep.ffn + (size_t)m * ep.F + f) = y;
     } else {   // SJD_EPI_QKV
         const int d = ep.d, hd = ep.hd, half = hd >> 1;
         const int pos = ep.st->n + m;
@@ -57,20 +78,32 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
             const float c1 = ep.cosT[(size_t)pos * half + j + 1], s1 = ep.sinT[(size_t)pos * half + j + 1];
             const float r0 = v[0] * c0 - v[1] * s0, r0p = v[1] * c0 + v[0] * s0;   // dims j, j+half
             const float r1 = v[2] * c1 - v[3] * s1, r1p = v[3] * c1 + v[2] * s1;   // dims j+1, j+1+half
-            const int col = head * hd + j;
             if (!is_k) {
-                float *q = ep.qact + (size_t)m * d + col;
+                float *q = ep.qact + (size_t)m * d + head * hd + j;
                 q[0] = r0; q[1] = r1; q[half] = r0p; q[half + 1] = r1p;
             } else if (m < ep.rows_valid) {
-                bf16_t *k = ep.kc + (size_t)pos * d + col;
-                *reinterpret_cast<uint32_t *>(k) = (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16);
-                *reinterpret_cast<uint32_t *>(k + half) = (uint32_t)f32_to_bf16(r0p) | ((uint32_t)f32_to_bf16(r1p) << 16);
+                bf16_t *rec = ep.kvc + kv_block_off(head, pos >> 5, ep.nblk, hd);
+                const int kk = pos & 31;
+                float la, lb, dummy0, dummy1;
+                uint32_t hi = pack_hi2(r0, r1, la, lb);
+                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j, hd, 0)) = hi;
+                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j, hd, 1)) = pack_hi2(la, lb, dummy0, dummy1);
+                hi = pack_hi2(r0p, r1p, la, lb);
+                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 0)) = hi;
+                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 1)) = pack_hi2(la, lb, dummy0, dummy1);
             }
         } else if (m < ep.rows_valid) {
-            // V: natural order, cache is transposed [feature][position]
+            // V: natural feature order
             const int col = n0 - 2 * d;
+            const int head = col / hd, dim = col % hd;
+            bf16_t *rec = ep.kvc + kv_block_off(head, pos >> 5, ep.nblk, hd);
+            const int kk = pos & 31;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) ep.vc[(size_t)(col + r) * ep.max_seq + pos] = f32_to_bf16(v[r]);
+            for (int r = 0; r < 4; ++r) {
+                const bf16_t h = f32_to_bf16(v[r]);
+                rec[kv_v_off(kk, dim + r, hd, 0)] = h;
+                rec[kv_v_off(kk, dim + r, hd, 1)] = f32_to_bf16(v[r] - bf16_to_f32(h));
+            }
         }
     }
 }
@@ -78,14 +111,18 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
 // ---------------------------------------------------------------------------------------------
 // in-workgroup split-K
 // ---------------------------------------------------------------------------------------------
-template <int MT, int TN, int WK, int U, int EPI, int PLANES = 2>
+#define SJD_PRO_PLAIN 0
+#define SJD_PRO_NORM 1
+template <int MT, int TN, int WK, int U, int EPI, int PRO>
 __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__restrict__ Wp,
-                                                            const bf16_t *__restrict__ A, int N, int K,
+                                                            const float *__restrict__ X,
+                                                            const bf16_t *__restrict__ gain, float eps, int N, int K,
                                                             SjdGemmEpi ep)
 {
     if (ep.st && ep.st->done) return;
     __shared__ f32x4 red[WK][MT * TN][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ float ssq[WK][MT * 16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     const int tile0 = blockIdx.x * TN;
     const int KT = K / 32;
     const int kps = (KT + WK - 1) / WK;
@@ -93,49 +130,68 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     const int kt1 = min(KT, kt0 + kps);
 
     f32x4 acc[MT][TN];
+    float ss[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+        ss[mt] = 0.f;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) acc[mt][tn] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
 
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)tile0 * KT * 64 + lane;
     const size_t tile_stride = (size_t)KT * 64;                 // in 16-byte units
-    const bf16x8 *ap = reinterpret_cast<const bf16x8 *>(A) + lane;
-    const size_t plane = (size_t)SJD_ROWS_MAX * K / 8;          // lo plane, in 16-byte units
+    // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8
+    const float *xp = X + (size_t)c * K + g * 8;
+    const bf16_t *gp = gain + g * 8;
 
-    bf16x8 a0[U][TN], a1[U][TN], b0[U][MT][2], b1[U][MT][2];
+    bf16x8 a0[U][TN], a1[U][TN], g0[U], g1[U];
+    f32x4 b0[U][MT][2], b1[U][MT][2];
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-#define LOAD_STAGE(kbase, a, b)                                                                   \
+#define LOAD_STAGE(kbase, a, b, gn)                                                               \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                               \
         const int kq_ = (kbase) + u;                                                              \
         if (kq_ < kt1) {                                                                          \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                     \
                 a[u][tn] = __builtin_nontemporal_load(wp + (size_t)tn * tile_stride + (size_t)kq_ * 64); \
             _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
-                const bf16x8 *p = ap + ((size_t)mt * KT + kq_) * 64;                              \
-                b[u][mt][0] = *p;                                                                 \
-                if (PLANES == 2) b[u][mt][1] = *(p + plane);                                      \
+                const f32x4 *p = reinterpret_cast<const f32x4 *>(xp + (size_t)mt * 16 * K + (size_t)kq_ * 32); \
+                b[u][mt][0] = p[0];                                                               \
+                b[u][mt][1] = p[1];                                                               \
             }                                                                                     \
+            if (PRO == SJD_PRO_NORM) gn[u] = *reinterpret_cast<const bf16x8 *>(gp + (size_t)kq_ * 32); \
         } else {                                                                                  \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) a[u][tn] = zero;                    \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) { b[u][mt][0] = zero; b[u][mt][1] = zero; } \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) { b[u][mt][0] = zero4; b[u][mt][1] = zero4; } \
+            gn[u] = zero;                                                                         \
         }                                                                                         \
     }
-#define MMA_STAGE(a, b)                                                                           \
+#define MMA_STAGE(a, b, gn)                                                                       \
     _Pragma("unroll") for (int u = 0; u < U; ++u)                                                 \
-        _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                         \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
-                acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][mt][0], acc[mt][tn], 0, 0, 0); \
-                if (PLANES == 2) acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], b[u][mt][1], acc[mt][tn], 0, 0, 0); \
-            }
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                       \
+            float x_[8];                                                                          \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) x_[e] = b[u][mt][e >> 2][e & 3];        \
+            if (PRO == SJD_PRO_NORM) {                                                            \
+                _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                   \
+                    ss[mt] = fmaf(x_[e], x_[e], ss[mt]);                                          \
+                    x_[e] *= (float)gn[u][e];                                                     \
+                }                                                                                 \
+            }                                                                                     \
+            bf16x8 bh_, bl_;                                                                      \
+            split8(x_, bh_, bl_);                                                                 \
+            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                   \
+                acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], bh_, acc[mt][tn], 0, 0, 0); \
+                acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], bl_, acc[mt][tn], 0, 0, 0); \
+            }                                                                                     \
+        }
 
-    LOAD_STAGE(kt0, a0, b0)
+    LOAD_STAGE(kt0, a0, b0, g0)
     for (int kt = kt0; kt < kt1; kt += 2 * U) {
-        LOAD_STAGE(kt + U, a1, b1)
-        MMA_STAGE(a0, b0)
-        LOAD_STAGE(kt + 2 * U, a0, b0)
-        MMA_STAGE(a1, b1)
+        LOAD_STAGE(kt + U, a1, b1, g1)
+        MMA_STAGE(a0, b0, g0)
+        LOAD_STAGE(kt + 2 * U, a0, b0, g0)
+        MMA_STAGE(a1, b1, g1)
     }
 #undef LOAD_STAGE
 #undef MMA_STAGE
@@ -145,6 +201,15 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) red[wave][mt * TN + tn][lane] = acc[mt][tn];
+    if (PRO == SJD_PRO_NORM) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float t = ss[mt];
+            t += __shfl_xor(t, 16);
+            t += __shfl_xor(t, 32);
+            if (g == 0) ssq[wave][mt * 16 + c] = t;
+        }
+    }
     __syncthreads();
     for (int unit = threadIdx.x; unit < MT * TN * 64; unit += 64 * WK) {
         const int mtn = unit >> 6, l = unit & 63;
@@ -153,7 +218,14 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         for (int w = 1; w < WK; ++w) v += red[w][mtn][l];
         // D layout: lane l holds features (l/16)*4 + 0..3 of the tile for token l%16
         const int mt = mtn / TN, tn = mtn % TN;
-        apply_epilogue<EPI>(ep, N, mt * 16 + (l & 15), (tile0 + tn) * 16 + (l >> 4) * 4, v);
+        const int m = mt * 16 + (l & 15);
+        if (PRO == SJD_PRO_NORM) {
+            float sq = ssq[0][m];
+#pragma unroll
+            for (int w = 1; w < WK; ++w) sq += ssq[w][m];
+            v *= rsqrtf(sq / (float)K + eps);
+        }
+        apply_epilogue<EPI>(ep, N, m, (tile0 + tn) * 16 + (l >> 4) * 4, v);
     }
 }
 
@@ -198,20 +270,17 @@ int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K
     return SJD_OK;
 }
 
-// row-major bf16 [rows][K] -> packed hi plane (the lo plane is left as it is)
-__global__ void pack_act_kernel(const bf16_t *__restrict__ src, int rows, int K, bf16_t *__restrict__ dst)
+// row-major bf16 [rows][K] -> fp32 rows (test hook: the projections consume fp32 activations)
+__global__ void bf16_rows_to_f32_kernel(const bf16_t *__restrict__ src, size_t n, float *__restrict__ dst)
 {
-    const int KT = K / 32;
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < (size_t)rows * K; e += (size_t)gridDim.x * blockDim.x) {
-        const int m = (int)(e / K), k = (int)(e % K);
-        dst[act_off(m, k, KT)] = src[e];
-    }
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x)
+        dst[e] = bf16_to_f32(src[e]);
 }
 
-int sjd_pack_act(const bf16_t *src_rowmajor, int32_t rows, int32_t K, bf16_t *dst_packed, hipStream_t s)
+int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s)
 {
-    if (rows < 1 || rows > SJD_ROWS_MAX || K % 32) return SJD_EINVAL;
-    hipLaunchKernelGGL(pack_act_kernel, dim3(256), dim3(256), 0, s, src_rowmajor, rows, K, dst_packed);
+    if (rows < 1 || rows > SJD_ROWS_MAX || K < 1) return SJD_EINVAL;
+    hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, dst);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -239,19 +308,22 @@ void sjd_choose_tiles(SjdLinear *lin)
     lin->tn = best_tn; lin->wk = 8; lin->u = 2;
 }
 
-template <int MT, int TN, int WK, int U>
-static int launch_epi(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi &ep, hipStream_t s)
+template <int MT, int TN, int WK, int U, int PRO>
+static int launch_epi(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, const SjdGemmEpi &ep,
+                      hipStream_t s)
 {
-    if constexpr (WK * MT * TN * 1024 <= 65536) {
+    if constexpr (WK * MT * TN * 1024 + WK * MT * 64 <= 65536) {
         dim3 grid(lin->N / (16 * TN)), block(64 * WK);
         const bf16_t *W = (const bf16_t *)lin->w;
+#define GO(EPI) hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, gain, eps, lin->N, lin->K, ep)
         switch (ep.kind) {
-            case SJD_EPI_STORE: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_STORE>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-            case SJD_EPI_RESID: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_RESID>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-            case SJD_EPI_SILU: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_SILU>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
-            case SJD_EPI_QKV: hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, SJD_EPI_QKV>), grid, block, 0, s, W, act, lin->N, lin->K, ep); break;
+            case SJD_EPI_STORE: GO(SJD_EPI_STORE); break;
+            case SJD_EPI_RESID: GO(SJD_EPI_RESID); break;
+            case SJD_EPI_SILU: GO(SJD_EPI_SILU); break;
+            case SJD_EPI_QKV: GO(SJD_EPI_QKV); break;
             default: return SJD_EINVAL;
         }
+#undef GO
         HIP_TRY(hipGetLastError());
         return SJD_OK;
     } else {
@@ -259,15 +331,24 @@ static int launch_epi(const SjdLinear *lin, const bf16_t *act, const SjdGemmEpi 
     }
 }
 
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s)
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
+                         const SjdGemmEpi &ep, hipStream_t s)
 {
     if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
+    int tn = lin->tn;
+    if (mt == 2 && tn == 4) tn = 2;      // the reduction buffer of 2 x 4 tiles would not fit in LDS
     if (lin->wk != 8) return SJD_EINVAL;
-#define CASE(MT, TN) if (mt == MT && lin->tn == TN) return lin->u == 4 ? launch_epi<MT, TN, 8, 4>(lin, act, ep, s) : launch_epi<MT, TN, 8, 2>(lin, act, ep, s)
-    CASE(1, 1); CASE(1, 2); CASE(1, 3); CASE(1, 4);
-    CASE(2, 1); CASE(2, 2); CASE(2, 3); CASE(2, 4);
+#define CASE(MT, TN)                                                                                      \
+    if (mt == MT && tn == TN) {                                                                           \
+        /* with the norm prologue only the 2-deep prefetch fits the register file */                      \
+        if (gain) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);              \
+        return lin->u == 4 ? launch_epi<MT, TN, 8, 4, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s)          \
+                           : launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);         \
+    }
+    CASE(1, 1) CASE(1, 2) CASE(1, 3) CASE(1, 4)
+    CASE(2, 1) CASE(2, 2) CASE(2, 3)
 #undef CASE
     return SJD_EINVAL;
 }

@@ -49,13 +49,30 @@ struct SjdState {
     int32_t accept_hist[65];
 };
 
-// GEMM inputs of bf16 models are stored in the B-operand order of v_mfma_f32_16x16x32_bf16, so a
-// wave fetches one 16x32 activation tile with a single contiguous 1 KiB load: element (row m, column
-// k) of a [32 x K] matrix lives at act_off(m, k, K/32); the lo plane follows the hi plane at
-// 32*K elements.
-__host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
+// bf16 models keep every activation the projections consume (residual stream, attention output, FFN
+// hidden) as fp32 rows [SJD_ROWS_MAX][K]; the projection kernel splits them into hi + lo bf16
+// operands on the fly.
+//
+// KV cache of bf16 models: per layer, per head, per block of 32 positions one contiguous record of
+// 128*hd bf16 values, laid out as the MFMA operands the attention kernel consumes, each value kept
+// as hi = bf16(v) and lo = bf16(v - hi) (two "planes"):
+//   K tiles  [h = 0,1][ks = 0..hd/32)[plane]  512 values: lane l = 16 g + c, element e holds
+//            K[position 32 blk + 16 h + c][dim 32 ks + 8 g + e]             (A operand of S^T = K Q^T)
+//   V tiles  [t = 0..hd/16)[plane]            512 values: lane l = 16 g + c, element e holds
+//            V[position 32 blk + 16 (e/4) + 4 g + e%4][dim 16 t + c]        (A operand of O^T = V^T P)
+__host__ __device__ __forceinline__ size_t kv_block_off(int head, int blk, int nblk, int hd)
 {
-    return ((size_t)(m >> 4) * KT + (k >> 5)) * 512 + ((((k & 31) >> 3) * 16 + (m & 15)) << 3) + (k & 7);
+    return ((size_t)head * nblk + blk) * (size_t)(128 * hd);
+}
+__host__ __device__ __forceinline__ int kv_k_off(int kk, int dim, int hd, int plane)   // kk = position % 32
+{
+    const int h = kk >> 4, c = kk & 15, ks = dim >> 5, g = (dim & 31) >> 3, e = dim & 7;
+    return (((h * (hd >> 5) + ks) * 2 + plane) << 9) + ((g * 16 + c) << 3) + e;
+}
+__host__ __device__ __forceinline__ int kv_v_off(int kk, int dim, int hd, int plane)
+{
+    const int t = dim >> 4, c = dim & 15, g = (kk & 15) >> 2, e = ((kk >> 4) << 2) + (kk & 3);
+    return 64 * hd + (((t * 2 + plane)) << 9) + ((g * 16 + c) << 3) + e;
 }
 
 // ---- one linear layer's weights ------------------------------------------------------------
@@ -80,9 +97,9 @@ struct SjdGemmEpi {
     int32_t kind;
     const SjdState *st;          // device state (n, done); may be NULL for STORE
     float *out;                  // STORE / RESID: [rows][N]
-    bf16_t *ffn; size_t ffn_plane; int32_t F;                     // SILU
-    float *qact; bf16_t *kc, *vc; const float *cosT, *sinT;       // QKV
-    int32_t d, hd, max_seq, rows_valid;
+    float *ffn; int32_t F;                                        // SILU: [rows][F]
+    float *qact; bf16_t *kvc; const float *cosT, *sinT;           // QKV: kvc = this layer's cache
+    int32_t d, hd, nblk, rows_valid;
 };
 
 struct SjdLayer {
@@ -103,22 +120,22 @@ struct sjd_model {
 
 struct sjd_kv {
     const sjd_model *m;
-    void *k, *v;          // K: [layer][pos][d]; V: fp32 models [layer][pos][d], bf16 models transposed
-                          // [layer][d][v_stride] (positions contiguous, v_stride >= max_seq + 32)
+    void *k, *v;          // fp32 models: K and V as [layer][pos][d]; bf16 models: k holds the blocked
+                          // hi/lo cache described above ([layer][head][block][128*hd]), v is unused
     size_t k_layer_stride, v_layer_stride;   // elements
-    int32_t k_rows, v_stride;
+    int32_t nblk;         // bf16 models: 32-position blocks per head
     int32_t *tokens;      // [max_seq] ids of cached positions (-1 for raw-embedding rows)
     SjdState *state;      // device
     // ---- scratch for one forward over <= SJD_ROWS_MAX rows ----
     float *x;             // [rows][d] residual stream
-    void *h;              // [rows][d] normalised activations (GEMM input; bf16: hi and lo planes)
+    void *h;              // fp32 models: [rows][d] normalised activations
     float *part;          // fp32 models: GEMM output
     size_t part_elems;
     float *qact;          // [rows][d] rotated queries (fp32)
     float *att_part;      // attention partials per (head, split): [rows][hd] + m,l
     int32_t att_splits;
-    void *att_out;        // [rows][d]
-    void *ffn;            // [rows][F]
+    void *att_out;        // [rows][d] fp32
+    void *ffn;            // [rows][F] fp32
     float *logits;        // [rows][V_s]
     // ---- scratch for verification ----
     float *q;             // [(rows+1)][V_s]
@@ -161,11 +178,10 @@ int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_
 int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t perm, int32_t d,
                     int32_t hd, hipStream_t s);
 void sjd_choose_tiles(SjdLinear *lin);
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const bf16_t *act, int32_t rows, const SjdGemmEpi &ep, hipStream_t s);
-int sjd_pack_act(const bf16_t *src_rowmajor, int32_t rows, int32_t K, bf16_t *dst_packed, hipStream_t s);
-
-int sjd_launch_norm_bf16(const sjd_model *m, const float *x, const void *gain, int32_t rows, void *h,
-                         const SjdState *st, hipStream_t s);
+// bf16 projection: act = fp32 rows [SJD_ROWS_MAX][K]; gain != NULL fuses RMSNorm(act; gain, eps) in front
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
+                         const SjdGemmEpi &ep, hipStream_t s);
+int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
 int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s);
 int32_t sjd_attention_splits(const sjd_model *m);
 size_t sjd_attention_part_elems(const sjd_model *m);

@@ -1,28 +1,16 @@
 // Element-wise pieces of the window forward (paper Sec. 4.1 Step 2; the decoder itself is the
-// Llama-style stack the workloads name): embedding gather, RMSNorm fused with the residual add
-// and the split-K reduction of the producing GEMM, RoPE + KV-cache write, SiLU(gate)*up.
-// All of them are bandwidth-trivial (rows <= 32); they exist to feed the GEMMs the operand
-// layout they stream.
+// Llama-style stack the workloads name): embedding gather for every model, and for the fp32 models
+// RMSNorm fused with the residual add, RoPE + KV-cache write and SiLU(gate)*up (bf16 models do all of
+// these inside their projection kernel).  All of them are bandwidth-trivial (rows <= 32).
 #include "sjd_internal.h"
 
-// Element access per model dtype.  GEMM inputs of bf16 models are kept as TWO bf16 planes,
-// hi = bf16(v) and lo = bf16(v - hi) (`plane` elements apart): the GEMM multiplies the weight
-// tile with both, which keeps ~16 significant bits of the activations at no extra HBM traffic.
 template <typename T> struct Act;
 template <> struct Act<float> {
     __device__ static float load(const float *p, size_t i) { return p[i]; }
     __device__ static void store(float *p, size_t i, float v) { p[i] = v; }
-    __device__ static void store_split(float *p, size_t, size_t i, float v) { p[i] = v; }
 };
 template <> struct Act<bf16_t> {
     __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
-    __device__ static void store(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
-    __device__ static void store_split(bf16_t *p, size_t plane, size_t i, float v)
-    {
-        const bf16_t hi = f32_to_bf16(v);
-        p[i] = hi;
-        p[plane + i] = f32_to_bf16(v - bf16_to_f32(hi));
-    }
 };
 
 // x[r][:] = E[ids[r]][:]  (or the given raw embedding row)
@@ -39,7 +27,7 @@ __global__ void embed_kernel(const T *E, const int32_t *ids, const float *emb_ro
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *part, int n_part, size_t part_stride,
-                                                      const T *gain, int d, float eps, T *h, size_t plane,
+                                                      const T *gain, int d, float eps, T *h,
                                                       const SjdState *st)
 {
     if (st->done) return;
@@ -58,51 +46,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *par
     __syncthreads();
     ss = red[0] + red[1] + red[2] + red[3];
     const float inv = rsqrtf(ss / (float)d + eps);
-    for (int j = threadIdx.x; j < d; j += 256) Act<T>::store_split(h, plane, (size_t)r * d + j, xr[j] * inv * Act<T>::load(gain, j));
-}
-
-// bf16 models: h[r] = RMSNorm(x[r]) as hi/lo bf16 planes, one 1024-thread workgroup per row with the
-// row held in registers (d <= 8192); the residual adds already happened in the GEMM epilogues.
-__global__ __launch_bounds__(1024) void norm_bf16_kernel(const float *__restrict__ x, const bf16_t *__restrict__ gain,
-                                                          int d, float eps, bf16_t *__restrict__ h, size_t plane,
-                                                          const SjdState *st)
-{
-    if (st->done) return;
-    __shared__ float red[16];
-    const int r = blockIdx.x, t = threadIdx.x;
-    const float4 *xr = reinterpret_cast<const float4 *>(x + (size_t)r * d);
-    float4 v[2];
-    float ss = 0.f;
-    const int n4 = d / 4;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int c = t + i * 1024;
-        v[i] = c < n4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-        ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
-    }
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    if ((t & 63) == 0) red[t >> 6] = ss;
-    __syncthreads();
-    ss = 0.f;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) ss += red[w];
-    const float inv = rsqrtf(ss / (float)d + eps);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int c = t + i * 1024;
-        if (c >= n4) continue;
-        const uint2 g = reinterpret_cast<const uint2 *>(gain)[c];
-        const float y0 = v[i].x * inv * __uint_as_float(g.x << 16), y1 = v[i].y * inv * __uint_as_float(g.x & 0xFFFF0000u);
-        const float y2 = v[i].z * inv * __uint_as_float(g.y << 16), y3 = v[i].w * inv * __uint_as_float(g.y & 0xFFFF0000u);
-        const bf16_t h0 = f32_to_bf16(y0), h1 = f32_to_bf16(y1), h2 = f32_to_bf16(y2), h3 = f32_to_bf16(y3);
-        uint2 hi, lo;
-        hi.x = (uint32_t)h0 | ((uint32_t)h1 << 16); hi.y = (uint32_t)h2 | ((uint32_t)h3 << 16);
-        lo.x = (uint32_t)f32_to_bf16(y0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(y1 - bf16_to_f32(h1)) << 16);
-        lo.y = (uint32_t)f32_to_bf16(y2 - bf16_to_f32(h2)) | ((uint32_t)f32_to_bf16(y3 - bf16_to_f32(h3)) << 16);
-        const size_t o = act_off(r, 4 * c, d / 32);
-        *reinterpret_cast<uint2 *>(h + o) = hi;
-        *reinterpret_cast<uint2 *>(h + plane + o) = lo;
-    }
+    for (int j = threadIdx.x; j < d; j += 256) Act<T>::store(h, (size_t)r * d + j, xr[j] * inv * Act<T>::load(gain, j));
 }
 
 // qkv[r][0:3d] = sum_p part[p][r][:];  rotate q and k (pairs j, j+hd/2) at position n+r;
@@ -148,7 +92,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(const float *part, int n_p
 // ffn[r][f] = SiLU(g) * u with g = sum_p part[p][r][f], u = sum_p part[p][r][F + f]
 template <typename T>
 __global__ __launch_bounds__(256) void silu_mul_kernel(const float *part, int n_part, size_t part_stride, int F, T *ffn,
-                                                       size_t plane, const SjdState *st)
+                                                       const SjdState *st)
 {
     if (st->done) return;
     const int r = blockIdx.y;
@@ -159,7 +103,7 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const float *part, int n_
         const float *src = part + (size_t)p * part_stride + (size_t)r * 2 * F;
         g += src[f]; u += src[F + f];
     }
-    Act<T>::store_split(ffn, plane, (size_t)r * F + f, g / (1.0f + expf(-g)) * u);
+    Act<T>::store(ffn, (size_t)r * F + f, g / (1.0f + expf(-g)) * u);
 }
 
 // out[r][c] = sum_p part[p][r][c]
@@ -194,12 +138,9 @@ int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t 
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s)
 {
     const int d = m->cfg.d_model;
-    if (m->cfg.dtype == 0)
-        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
-                           (const float *)gain, d, m->cfg.rms_eps, (float *)h, (size_t)0, st);
-    else
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
-                           (const bf16_t *)gain, d, m->cfg.rms_eps, (bf16_t *)h, (size_t)SJD_ROWS_MAX * d, st);
+    if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models normalise inside the projection kernel
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
+                       (const float *)gain, d, m->cfg.rms_eps, (float *)h, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
@@ -220,12 +161,9 @@ int sjd_launch_silu_mul(const sjd_model *m, const float *part, int32_t n_part, s
                         void *ffn, const SjdState *st, hipStream_t s)
 {
     const int F = m->cfg.d_ffn;
+    if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models do this in the gate/up epilogue
     dim3 grid((F + 255) / 256, rows);
-    if (m->cfg.dtype == 0)
-        hipLaunchKernelGGL(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, (size_t)0, st);
-    else
-        hipLaunchKernelGGL(silu_mul_kernel<bf16_t>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (bf16_t *)ffn,
-                           (size_t)SJD_ROWS_MAX * F, st);
+    hipLaunchKernelGGL(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
@@ -235,17 +173,6 @@ int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride
 {
     dim3 grid((cols + 255) / 256, rows);
     hipLaunchKernelGGL(reduce_rows_kernel, grid, dim3(256), 0, s, part, n_part, part_stride, cols, out, st);
-    LAUNCH_CHECK();
-    return SJD_OK;
-}
-
-int sjd_launch_norm_bf16(const sjd_model *m, const float *x, const void *gain, int32_t rows, void *h,
-                         const SjdState *st, hipStream_t s)
-{
-    const int d = m->cfg.d_model;
-    if (d % 4 || d > 8192) return SJD_EINVAL;
-    hipLaunchKernelGGL(norm_bf16_kernel, dim3(rows), dim3(1024), 0, s, x, (const bf16_t *)gain, d, m->cfg.rms_eps,
-                       (bf16_t *)h, (size_t)SJD_ROWS_MAX * d, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
