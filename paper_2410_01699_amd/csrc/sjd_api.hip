@@ -124,9 +124,9 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
             return SJD_OK;
         }
         HIP_TRY(hipMemcpy(stage, hb + off * es, n * es, hipMemcpyHostToDevice));
-        SJD_TRY(sjd_repack_bf16((const bf16_t *)stage, (bf16_t *)(db + off * es), N, K, perm, (int)d, m->hd, 0));
+        sjd_choose_tiles(lin);           // the packed order depends on the tiles per workgroup
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)stage, (bf16_t *)(db + off * es), N, K, lin->tn, perm, (int)d, m->hd, 0));
         HIP_TRY(hipDeviceSynchronize());
-        sjd_choose_tiles(lin);
         return SJD_OK;
     };
 
@@ -785,9 +785,9 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     if (dtype == 1) {
         SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
         SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * es));
-        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)g.Wp, N, K, 0, 0, 0, s));
-        lin.w = g.Wp;
         sjd_choose_tiles(&lin);
+        SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)g.Wp, N, K, lin.tn, 0, 0, 0, s));
+        lin.w = g.Wp;
         SjdGemmEpi ep;
         memset(&ep, 0, sizeof(ep));
         ep.kind = SJD_EPI_STORE; ep.out = g.out;

@@ -194,6 +194,25 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     const int b_beg = split * bps, b_end = min(nblk, b_beg + bps);
     const float scale = rsqrtf((float)HD);
 
+    // the first block's K and V tiles are requested before anything else, so that their latency
+    // overlaps the staging of Q
+    bf16x8 ka[2][KS][2], va[DT][2];
+    auto load_block = [&](int blk) {
+        const bf16x8 *rec = reinterpret_cast<const bf16x8 *>(kvc + kv_block_off(head, blk, nblk_cache, HD)) + lane;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl) ka[h][ks][pl] = rec[((h * KS + ks) * 2 + pl) * 64];
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl) va[t][pl] = rec[(2 * KS * 2 + t * 2 + pl) * 64];
+    };
+    int blk = b_beg + wave;
+    if (blk < b_end) load_block(blk);
+
     // Q as B operand, shared by the waves: entry [mt][ks][plane][lane] holds
     // Q[query c (+16 mt)][32 ks + 8 g .. +8], scaled by 1/sqrt(HD), as hi and lo bf16 planes
     for (int u = threadIdx.x; u < MT * KS * 64; u += 64 * AW) {
@@ -218,19 +237,7 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     }
     __syncthreads();                              // q_lds ready
 
-    for (int blk = b_beg + wave; blk < b_end; blk += AW) {
-        const bf16x8 *rec = reinterpret_cast<const bf16x8 *>(kvc + kv_block_off(head, blk, nblk_cache, HD)) + lane;
-        bf16x8 ka[2][KS][2], va[DT][2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl) ka[h][ks][pl] = rec[((h * KS + ks) * 2 + pl) * 64];
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int pl = 0; pl < 2; ++pl) va[t][pl] = rec[(2 * KS * 2 + t * 2 + pl) * 64];
+    while (blk < b_end) {
         const int k0 = blk * 32;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -279,6 +286,8 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
                 o[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[t][0], ph, o[mt][t], 0, 0, 0);
             }
         }
+        blk += AW;
+        if (blk < b_end) load_block(blk);
     }
 
     // ---- merge the AW waves (wave order) and write the partial record -----------------------------
@@ -319,32 +328,44 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     }
 }
 
-// out[q][head*HD + :] = sum_s w_s O_s[q][:] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s)
+// out[q][head*HD + :] = sum_s w_s O_s[q][:] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s), written in
+// the operand order the O projection streams.  All loads of a thread are issued before anything
+// depends on them (splits <= ATT_MAX_SPLITS).
+#define ATT_MAX_SPLITS 16
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
                                                         float *__restrict__ out, const SjdState *st)
 {
-    if (st->done) return;
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
     const int head = blockIdx.x;
     const float *base = part + (size_t)head * splits * REC;
-    for (int u = threadIdx.x; u < rows * Q4; u += 256) {
-        const int q = u / Q4, j4 = u % Q4;
-        float M = -INFINITY;
-        for (int s = 0; s < splits; ++s) M = fmaxf(M, base[(size_t)s * REC + MT * 16 * HD + q]);
-        f32x4 num = {0.f, 0.f, 0.f, 0.f};
-        float den = 0.f;
-        for (int s = 0; s < splits; ++s) {
-            const float *p = base + (size_t)s * REC;
-            const float ms = p[MT * 16 * HD + q];
-            if (ms == -INFINITY) continue;
-            const float w = __expf(ms - M);
-            num += w * *reinterpret_cast<const f32x4 *>(p + (size_t)q * HD + j4 * 4);
-            den += w * p[MT * 16 * HD + MT * 16 + q];
-        }
-        *reinterpret_cast<f32x4 *>(out + (size_t)q * d + head * HD + j4 * 4) = num * (1.0f / den);
+    const int u = blockIdx.y * 256 + threadIdx.x;
+    if (u >= rows * Q4) return;
+    const int q = u / Q4, j4 = u % Q4;
+    float ms[ATT_MAX_SPLITS], ls[ATT_MAX_SPLITS];
+    f32x4 os[ATT_MAX_SPLITS];
+    const int done = st->done;
+#pragma unroll
+    for (int s = 0; s < ATT_MAX_SPLITS; ++s) {
+        const float *p = base + (size_t)(s < splits ? s : 0) * REC;
+        ms[s] = p[MT * 16 * HD + q];
+        ls[s] = p[MT * 16 * HD + MT * 16 + q];
+        os[s] = *reinterpret_cast<const f32x4 *>(p + (size_t)q * HD + j4 * 4);
     }
+    if (done) return;
+    float M = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < ATT_MAX_SPLITS; ++s) if (s < splits) M = fmaxf(M, ms[s]);
+    f32x4 num = {0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+#pragma unroll
+    for (int s = 0; s < ATT_MAX_SPLITS; ++s) {
+        const float w = (s < splits && ms[s] != -INFINITY) ? __expf(ms[s] - M) : 0.f;   // an empty split holds zeros
+        num += w * os[s];
+        den += w * ls[s];
+    }
+    *reinterpret_cast<f32x4 *>(out + act_off(q, head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -355,6 +376,7 @@ int32_t sjd_attention_splits(const sjd_model *m)
         int s = (512 + H - 1) / H;
         int max_s = ((m->cfg.max_seq + 31) / 32 + 3) / 4;
         if (s > max_s) s = max_s;
+        if (s > 16) s = 16;              // ATT_MAX_SPLITS of the merge kernel
         return s < 1 ? 1 : s;
     }
     int s = (512 + H - 1) / H;   // about two workgroups per CU
@@ -391,8 +413,8 @@ static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
     hipLaunchKernelGGL((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits), dim3(64 * AW), 0, s, kv->qact, kvc, d,
                        kv->nblk, rows, kv->att_splits, kv->att_part, kv->state);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL((attn_merge_kernel<HD, MT>), dim3(H), dim3(256), 0, s, kv->att_part, kv->att_splits, d, rows,
-                       (float *)kv->att_out, kv->state);
+    hipLaunchKernelGGL((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256), dim3(256), 0, s, kv->att_part,
+                       kv->att_splits, d, rows, (float *)kv->att_out, kv->state);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }

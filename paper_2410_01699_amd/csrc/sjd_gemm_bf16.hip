@@ -7,10 +7,10 @@
 //
 //  - W is pre-packed (sjd_repack_bf16) into 16x32 tiles in the exact A-operand register order of
 //    v_mfma_f32_16x16x32_bf16: one 16-byte load per lane fetches 1 KiB of contiguous HBM per wave.
-//  - The activations are the B operand (tokens on the 16 columns).  They are fp32 rows in L2; each
-//    lane loads the 8 consecutive values of its token and k-group and splits them into hi = bf16(x)
-//    and lo = bf16(x - hi), which are multiplied separately: ~16 significant bits of activation for
-//    the same L2 bytes as two packed bf16 planes.  A wave reuses each activation tile for its TN
+//  - The activations are the B operand (tokens on the 16 columns).  They are fp32 in L2, stored by
+//    their producers in B-operand order (act_off); each lane loads the 8 values of its token and
+//    k-group and splits them into hi = bf16(x) and lo = bf16(x - hi), which are multiplied
+//    separately: ~16 significant bits of activation.  A wave reuses each activation tile for its TN
 //    weight tiles, so TN sets the L2-to-HBM traffic ratio.
 //  - RMSNorm in front of a projection is folded in: the values are multiplied by the gain before the
 //    split, every workgroup accumulates the sum of squares of the rows it streams anyway, and the
@@ -57,7 +57,7 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
     if (EPI == SJD_EPI_STORE) {
         *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
     } else if (EPI == SJD_EPI_RESID) {
-        f32x4 *x = reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0);
+        f32x4 *x = reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32));
         *x = *x + v;
     } else if (EPI == SJD_EPI_SILU) {
         // packed rows: (gate f, up f, gate f+1, up f+1)
@@ -65,7 +65,7 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
         float2 y;
         y.x = v[0] / (1.0f + __expf(-v[0])) * v[1];
         y.y = v[2] / (1.0f + __expf(-v[2])) * v[3];
-        *reinterpret_cast<float2 *>(ep.ffn + (size_t)m * ep.F + f) = y;
+        *reinterpret_cast<float2 *>(ep.ffn + act_off(m, f, ep.F / 32)) = y;
     } else {   // SJD_EPI_QKV
         const int d = ep.d, hd = ep.hd, half = hd >> 1;
         const int pos = ep.st->n + m;
@@ -138,10 +138,10 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         for (int tn = 0; tn < TN; ++tn) acc[mt][tn] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
-    const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)tile0 * KT * 64 + lane;
-    const size_t tile_stride = (size_t)KT * 64;                 // in 16-byte units
-    // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8
-    const float *xp = X + (size_t)c * K + g * 8;
+    // weights: the TN tiles of a k-step are adjacent (in 16-byte units)
+    const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)blockIdx.x * KT * TN * 64 + lane;
+    // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8, as two float4
+    const f32x4 *xp = reinterpret_cast<const f32x4 *>(X) + lane;
     const bf16_t *gp = gain + g * 8;
 
     bf16x8 a0[U][TN], a1[U][TN], g0[U], g1[U];
@@ -154,11 +154,11 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         const int kq_ = (kbase) + u;                                                              \
         if (kq_ < kt1) {                                                                          \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                     \
-                a[u][tn] = __builtin_nontemporal_load(wp + (size_t)tn * tile_stride + (size_t)kq_ * 64); \
+                a[u][tn] = __builtin_nontemporal_load(wp + ((size_t)kq_ * TN + tn) * 64);         \
             _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
-                const f32x4 *p = reinterpret_cast<const f32x4 *>(xp + (size_t)mt * 16 * K + (size_t)kq_ * 32); \
+                const f32x4 *p = xp + ((size_t)mt * KT + kq_) * 128;                              \
                 b[u][mt][0] = p[0];                                                               \
-                b[u][mt][1] = p[1];                                                               \
+                b[u][mt][1] = p[64];                                                              \
             }                                                                                     \
             if (PRO == SJD_PRO_NORM) gn[u] = *reinterpret_cast<const bf16x8 *>(gp + (size_t)kq_ * 32); \
         } else {                                                                                  \
@@ -232,20 +232,22 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 // ---------------------------------------------------------------------------------------------
 // weight and activation packing
 // ---------------------------------------------------------------------------------------------
-// row-major [N][K] bf16 -> MFMA streaming order, packed row n' taken from source row perm(n')
+// row-major [N][K] bf16 -> MFMA streaming order (tn tiles interleaved along k), packed row n' taken
+// from source row perm(n')
 //   perm 0: identity
 //   perm 1: rows [0, 2d) (Q then K) reordered inside each head to (j, j+hd/2) pairs; rest identity
 //   perm 2: N = 2F, packed (gate f, up f) interleaved: n' even -> row n'/2, odd -> row F + n'/2
-__global__ void repack_bf16_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int K, int perm,
-                                   int d, int hd)
+__global__ void repack_bf16_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int K, int tn,
+                                   int perm, int d, int hd)
 {
     const int KT = K / 32;
     const size_t total = (size_t)N * K / 8;   // 16-byte groups
     for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < total; g += (size_t)gridDim.x * blockDim.x) {
         const int l = (int)(g & 63);
         const size_t tile = g >> 6;
-        const int kt = (int)(tile % KT);
-        const size_t nt = tile / KT;
+        const int t = (int)(tile % tn);
+        const int kt = (int)((tile / tn) % KT);
+        const size_t nt = tile / ((size_t)tn * KT) * tn + t;
         size_t np = nt * 16 + (l & 15), row = np;
         if (perm == 1 && np < (size_t)2 * d) {
             const size_t region = np / d * d, c = np % d;
@@ -259,28 +261,28 @@ __global__ void repack_bf16_kernel(const bf16_t *__restrict__ src, bf16_t *__res
     }
 }
 
-int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t perm, int32_t d,
+int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t tn, int32_t perm, int32_t d,
                     int32_t hd, hipStream_t s)
 {
-    if (N % 16 || K % 32) return SJD_EINVAL;
+    if (N % 16 || K % 32 || tn < 1 || (N / 16) % tn) return SJD_EINVAL;
     if (perm == 1 && (hd % 8 || d % hd || N < 2 * d)) return SJD_EINVAL;
     if (perm == 2 && N % 32) return SJD_EINVAL;
-    hipLaunchKernelGGL(repack_bf16_kernel, dim3(2048), dim3(256), 0, s, src_dev, dst_dev, N, K, perm, d, hd);
+    hipLaunchKernelGGL(repack_bf16_kernel, dim3(2048), dim3(256), 0, s, src_dev, dst_dev, N, K, tn, perm, d, hd);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 
-// row-major bf16 [rows][K] -> fp32 rows (test hook: the projections consume fp32 activations)
-__global__ void bf16_rows_to_f32_kernel(const bf16_t *__restrict__ src, size_t n, float *__restrict__ dst)
+// row-major bf16 [rows][K] -> fp32 in act_off order (test hook)
+__global__ void bf16_rows_to_f32_kernel(const bf16_t *__restrict__ src, size_t n, int K, float *__restrict__ dst)
 {
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x)
-        dst[e] = bf16_to_f32(src[e]);
+        dst[act_off((int)(e / K), (int)(e % K), K / 32)] = bf16_to_f32(src[e]);
 }
 
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s)
 {
-    if (rows < 1 || rows > SJD_ROWS_MAX || K < 1) return SJD_EINVAL;
-    hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, dst);
+    if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
+    hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -295,7 +297,7 @@ void sjd_choose_tiles(SjdLinear *lin)
     const int tiles = lin->N / 16;
     int best_tn = 1;
     double best_eff = -1.0;
-    for (int t = 1; t <= 4; ++t) {
+    for (int t = 1; t <= 3; ++t) {
         if (tiles % t) continue;
         const int blocks = tiles / t;
         if (blocks < 128 && t > 1) continue;
@@ -337,8 +339,7 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *g
     if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
-    int tn = lin->tn;
-    if (mt == 2 && tn == 4) tn = 2;      // the reduction buffer of 2 x 4 tiles would not fit in LDS
+    const int tn = lin->tn;               // fixed when the weights were packed
     if (lin->wk != 8) return SJD_EINVAL;
 #define CASE(MT, TN)                                                                                      \
     if (mt == MT && tn == TN) {                                                                           \
@@ -347,7 +348,7 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *g
         return lin->u == 4 ? launch_epi<MT, TN, 8, 4, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s)          \
                            : launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);         \
     }
-    CASE(1, 1) CASE(1, 2) CASE(1, 3) CASE(1, 4)
+    CASE(1, 1) CASE(1, 2) CASE(1, 3)
     CASE(2, 1) CASE(2, 2) CASE(2, 3)
 #undef CASE
     return SJD_EINVAL;

@@ -50,8 +50,15 @@ struct SjdState {
 };
 
 // bf16 models keep every activation the projections consume (residual stream, attention output, FFN
-// hidden) as fp32 rows [SJD_ROWS_MAX][K]; the projection kernel splits them into hi + lo bf16
-// operands on the fly.
+// hidden) as fp32 in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a wave fetches the
+// 16 x 32 tile of a k-step with two contiguous 1 KiB loads; the projection kernel splits the values
+// into hi + lo bf16 operands on the fly.  Element (row m, column k) of a [32 x K] matrix lives at
+// act_off(m, k, K/32) floats: tile (m/16, k/32) of 512 floats, inside it two halves (k%8 < 4, >= 4) of
+// 64 lanes x 4 floats, lane = 16 * ((k%32)/8) + m%16.
+__host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
+{
+    return (((size_t)(m >> 4) * KT + (k >> 5)) * 2 + ((k >> 2) & 1)) * 256 + ((((k & 31) >> 3) * 16 + (m & 15)) << 2) + (k & 3);
+}
 //
 // KV cache of bf16 models: per layer, per head, per block of 32 positions one contiguous record of
 // 128*hd bf16 values, laid out as the MFMA operands the attention kernel consumes, each value kept
@@ -77,8 +84,9 @@ __host__ __device__ __forceinline__ int kv_v_off(int kk, int dim, int hd, int pl
 
 // ---- one linear layer's weights ------------------------------------------------------------
 // fp32 models keep W as given ([N][K] row-major).  bf16 models hold W in MFMA streaming order:
-// tiles of 16 output features x 32 input features, tile (nt, kt) at ((nt * K/32) + kt) * 512
-// elements, inside a tile lane l (0..63) owns the 8 consecutive elements
+// tiles of 16 output features x 32 input features; the tn tiles a workgroup owns are interleaved
+// along k, tile (nt, kt) at (((nt/tn) * K/32 + kt) * tn + nt%tn) * 512 elements, so that each wave
+// reads one contiguous stream; inside a tile lane l (0..63) owns the 8 consecutive elements
 // W[nt*16 + l%16][kt*32 + (l/16)*8 .. +8].
 struct SjdLinear {
     const void *w;
@@ -175,10 +183,10 @@ int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride
                            float *out, const SjdState *st, hipStream_t s);
 int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_t rows, float *part,
                     const SjdState *st, hipStream_t s);
-int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t perm, int32_t d,
+int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t tn, int32_t perm, int32_t d,
                     int32_t hd, hipStream_t s);
 void sjd_choose_tiles(SjdLinear *lin);
-// bf16 projection: act = fp32 rows [SJD_ROWS_MAX][K]; gain != NULL fuses RMSNorm(act; gain, eps) in front
+// bf16 projection: act = fp32 [SJD_ROWS_MAX x K] in act_off order; gain != NULL fuses RMSNorm(act; gain, eps) in front
 int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s);
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);

@@ -13,15 +13,18 @@ template <> struct Act<bf16_t> {
     __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 };
 
-// x[r][:] = E[ids[r]][:]  (or the given raw embedding row)
+// x[r][:] = E[ids[r]][:]  (or the given raw embedding row); bf16 models keep x in act_off order
 template <typename T>
 __global__ void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, float *x,
                              const SjdState *st)
 {
     if (st->done) return;
     const int r = blockIdx.x;
-    for (int j = threadIdx.x; j < d; j += blockDim.x)
-        x[(size_t)r * d + j] = emb_rows ? emb_rows[(size_t)r * d + j] : Act<T>::load(E, (size_t)ids[r] * d + j);
+    for (int j = threadIdx.x; j < d; j += blockDim.x) {
+        const float v = emb_rows ? emb_rows[(size_t)r * d + j] : Act<T>::load(E, (size_t)ids[r] * d + j);
+        if (sizeof(T) == 2) x[act_off(r, j, d / 32)] = v;
+        else x[(size_t)r * d + j] = v;
+    }
 }
 
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
