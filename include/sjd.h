@@ -139,10 +139,14 @@ int sjd_decode_status(sjd_kv *kv, int32_t *n_fixed, int32_t *steps, int32_t *don
 int sjd_decode_result(sjd_kv *kv, int32_t *out_tokens, sjd_stats *stats);
 int sjd_kv_use_graph(sjd_kv *kv, int32_t on);
 
-/* Per-kernel-class timing: runs n_steps iterations of the loop above kernel by kernel with a HIP
- * event pair around every launch (on `stream`), and adds up milliseconds, launch counts and
- * algorithmic HBM bytes (weights for the projections, K/V rows for attention, logits + both
- * probability windows for the verification) per class.  Synchronises.                          */
+/* Per-kernel-class timing: runs n_steps iterations of the loop above kernel by kernel, every launch
+ * carrying a start/stop HIP event pair that the runtime stamps with the kernel's own begin and end
+ * (on `stream`), and adds up milliseconds, launch counts and algorithmic HBM bytes (weights for the
+ * projections, K/V records for attention, logits + both probability windows for the verification)
+ * per class.  The per-launch intervals include a few microseconds of dispatch latency each, so the
+ * projections (the dominant class) are timed a second time: the projection launches of n_steps
+ * iterations alone, back to back in one event interval (ms_gemm_back_to_back; the same number of
+ * launches and bytes as in the per-launch pass).  Synchronises.                                */
 #define SJD_PROF_GEMM 0        /* QKV / O / gate-up / down projections and the LM head           */
 #define SJD_PROF_ATTENTION 1   /* window attention incl. the merge of its key chunks             */
 #define SJD_PROF_ELEMENTWISE 2 /* embedding, RMSNorm, RoPE + cache write, SiLU*up, reductions    */
@@ -152,6 +156,7 @@ typedef struct {
     double bytes[4];
     int64_t launches[4];
     int32_t steps;
+    double ms_gemm_back_to_back;
 } sjd_profile;
 int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream);
 

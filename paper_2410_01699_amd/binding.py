@@ -46,7 +46,8 @@ class sjd_stats(C.Structure):
 
 
 class sjd_profile(C.Structure):
-    _fields_ = [("ms", C.c_double * 4), ("bytes", C.c_double * 4), ("launches", C.c_int64 * 4), ("steps", C.c_int32)]
+    _fields_ = [("ms", C.c_double * 4), ("bytes", C.c_double * 4), ("launches", C.c_int64 * 4), ("steps", C.c_int32),
+                ("ms_gemm_back_to_back", C.c_double)]
 
 
 class SjdError(RuntimeError):

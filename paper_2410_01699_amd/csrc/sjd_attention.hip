@@ -394,12 +394,12 @@ template <typename T, int HD>
 static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
 {
     const int d = m->cfg.d_model, ms = m->cfg.max_seq, H = m->cfg.n_heads;
-    hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(H, kv->att_splits), dim3(ATT_THREADS), 0, s,
+    SJD_LAUNCH((attn_partial_kernel<T, HD>), dim3(H, kv->att_splits), dim3(ATT_THREADS), 0, s,
                        kv->qact, (const T *)kv->k + (size_t)layer * kv->k_layer_stride,
                        (const T *)kv->v + (size_t)layer * kv->v_layer_stride, d, ms, rows, 0, kv->att_splits,
                        kv->att_part, kv->state);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(H), dim3(256), 0, s, kv->att_part, kv->att_splits, d, rows,
+    SJD_LAUNCH((attn_combine_kernel<T, HD>), dim3(H), dim3(256), 0, s, kv->att_part, kv->att_splits, d, rows,
                        (T *)kv->att_out, kv->state);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
@@ -410,10 +410,10 @@ static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
 {
     const int d = m->cfg.d_model, H = m->cfg.n_heads;
     const bf16_t *kvc = (const bf16_t *)kv->k + (size_t)layer * kv->k_layer_stride;
-    hipLaunchKernelGGL((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits), dim3(64 * AW), 0, s, kv->qact, kvc, d,
+    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits), dim3(64 * AW), 0, s, kv->qact, kvc, d,
                        kv->nblk, rows, kv->att_splits, kv->att_part, kv->state);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256), dim3(256), 0, s, kv->att_part,
+    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256), dim3(256), 0, s, kv->att_part,
                        kv->att_splits, d, rows, (float *)kv->att_out, kv->state);
     HIP_TRY(hipGetLastError());
     return SJD_OK;

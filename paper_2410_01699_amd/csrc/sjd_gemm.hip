@@ -41,9 +41,9 @@ int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_
         if (K % 4) return SJD_EINVAL;
         dim3 grid((N + 3) / 4), block(256);
         const float *W = (const float *)lin->w, *A = (const float *)act;
-        if (rows <= 8) hipLaunchKernelGGL(gemm_f32_kernel<8>, grid, block, 0, s, W, A, N, K, part, st);
-        else if (rows <= 16) hipLaunchKernelGGL(gemm_f32_kernel<16>, grid, block, 0, s, W, A, N, K, part, st);
-        else hipLaunchKernelGGL(gemm_f32_kernel<32>, grid, block, 0, s, W, A, N, K, part, st);
+        if (rows <= 8) SJD_LAUNCH(gemm_f32_kernel<8>, grid, block, 0, s, W, A, N, K, part, st);
+        else if (rows <= 16) SJD_LAUNCH(gemm_f32_kernel<16>, grid, block, 0, s, W, A, N, K, part, st);
+        else SJD_LAUNCH(gemm_f32_kernel<32>, grid, block, 0, s, W, A, N, K, part, st);
         HIP_TRY(hipGetLastError());
         return SJD_OK;
     }

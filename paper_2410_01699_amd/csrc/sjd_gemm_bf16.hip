@@ -119,7 +119,8 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
                                                             const bf16_t *__restrict__ gain, float eps, int N, int K,
                                                             SjdGemmEpi ep)
 {
-    if (ep.st && ep.st->done) return;
+    // the finished flag is only needed before anything is written: its load overlaps the first stage
+    const int finished = ep.st ? ep.st->done : 0;
     __shared__ f32x4 red[WK][MT * TN][64];
     __shared__ float ssq[WK][MT * 16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
@@ -187,6 +188,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         }
 
     LOAD_STAGE(kt0, a0, b0, g0)
+    if (finished) return;
     for (int kt = kt0; kt < kt1; kt += 2 * U) {
         LOAD_STAGE(kt + U, a1, b1, g1)
         MMA_STAGE(a0, b0, g0)
@@ -267,7 +269,7 @@ int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K
     if (N % 16 || K % 32 || tn < 1 || (N / 16) % tn) return SJD_EINVAL;
     if (perm == 1 && (hd % 8 || d % hd || N < 2 * d)) return SJD_EINVAL;
     if (perm == 2 && N % 32) return SJD_EINVAL;
-    hipLaunchKernelGGL(repack_bf16_kernel, dim3(2048), dim3(256), 0, s, src_dev, dst_dev, N, K, tn, perm, d, hd);
+    SJD_LAUNCH(repack_bf16_kernel, dim3(2048), dim3(256), 0, s, src_dev, dst_dev, N, K, tn, perm, d, hd);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -282,7 +284,7 @@ __global__ void bf16_rows_to_f32_kernel(const bf16_t *__restrict__ src, size_t n
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s)
 {
     if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
-    hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst);
+    SJD_LAUNCH(bf16_rows_to_f32_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -317,7 +319,7 @@ static int launch_epi(const SjdLinear *lin, const float *act, const bf16_t *gain
     if constexpr (WK * MT * TN * 1024 + WK * MT * 64 <= 65536) {
         dim3 grid(lin->N / (16 * TN)), block(64 * WK);
         const bf16_t *W = (const bf16_t *)lin->w;
-#define GO(EPI) hipLaunchKernelGGL((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, gain, eps, lin->N, lin->K, ep)
+#define GO(EPI) SJD_LAUNCH((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, gain, eps, lin->N, lin->K, ep)
         switch (ep.kind) {
             case SJD_EPI_STORE: GO(SJD_EPI_STORE); break;
             case SJD_EPI_RESID: GO(SJD_EPI_RESID); break;

@@ -1,6 +1,7 @@
 // Internal declarations of the SJD HIP library (gfx950 only).  Not part of the C ABI.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "sjd.h"
@@ -23,6 +24,29 @@ void sjd_set_hip_error(hipError_t e, const char *what);
     do {                             \
         int rc_ = (expr);            \
         if (rc_ != SJD_OK) return rc_; \
+    } while (0)
+
+// ---- kernel launches -------------------------------------------------------------------------
+// Every kernel of the path is launched through SJD_LAUNCH.  While sjd_profile_steps() runs, a hook
+// hands each launch a start/stop event pair, or lets only the launches of one kernel class through
+// (the others are skipped, so that one class can be timed back to back); otherwise it is a plain
+// launch.
+struct SjdLaunchHook {
+    int (*next)(void *self, hipEvent_t *start, hipEvent_t *stop);   // NULL: no per-launch events
+    void *self;
+    int cur_kind;       // class of the launches being issued (set by the orchestration)
+    int only_kind;      // >= 0: skip every launch of another class
+};
+extern thread_local SjdLaunchHook *sjd_launch_hook;
+#define SJD_LAUNCH(kernel, grid, block, lds, stream, ...)                                            \
+    do {                                                                                             \
+        hipEvent_t ps_ = nullptr, pe_ = nullptr;                                                     \
+        if (sjd_launch_hook) {                                                                       \
+            if (sjd_launch_hook->only_kind >= 0 && sjd_launch_hook->only_kind != sjd_launch_hook->cur_kind) break; \
+            if (sjd_launch_hook->next) (void)sjd_launch_hook->next(sjd_launch_hook->self, &ps_, &pe_); \
+        }                                                                                            \
+        if (ps_) hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ps_, pe_, 0, __VA_ARGS__);  \
+        else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                      \
     } while (0)
 
 // ---- device helpers shared by kernels ------------------------------------------------------

@@ -130,9 +130,9 @@ int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_ro
 {
     const int d = m->cfg.d_model;
     if (m->cfg.dtype == 0)
-        hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, x, st);
+        SJD_LAUNCH(embed_kernel<float>, dim3(rows), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, x, st);
     else
-        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, x, st);
+        SJD_LAUNCH(embed_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, x, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
@@ -142,7 +142,7 @@ int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t 
 {
     const int d = m->cfg.d_model;
     if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models normalise inside the projection kernel
-    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
+    SJD_LAUNCH(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, x, part, n_part, part_stride,
                        (const float *)gain, d, m->cfg.rms_eps, (float *)h, st);
     LAUNCH_CHECK();
     return SJD_OK;
@@ -153,7 +153,7 @@ int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const floa
 {
     const int d = m->cfg.d_model, ms = m->cfg.max_seq;
     if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models do this in the QKV GEMM epilogue
-    hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
+    SJD_LAUNCH(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
                        m->rope_cos, m->rope_sin, kv->qact, (float *)kv->k + (size_t)layer * kv->k_layer_stride,
                        (float *)kv->v + (size_t)layer * kv->v_layer_stride, 0, rows_valid, kv->state);
     LAUNCH_CHECK();
@@ -166,7 +166,7 @@ int sjd_launch_silu_mul(const sjd_model *m, const float *part, int32_t n_part, s
     const int F = m->cfg.d_ffn;
     if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models do this in the gate/up epilogue
     dim3 grid((F + 255) / 256, rows);
-    hipLaunchKernelGGL(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, st);
+    SJD_LAUNCH(silu_mul_kernel<float>, grid, dim3(256), 0, s, part, n_part, part_stride, F, (float *)ffn, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
@@ -175,7 +175,7 @@ int sjd_launch_reduce_rows(const float *part, int32_t n_part, size_t part_stride
                            float *out, const SjdState *st, hipStream_t s)
 {
     dim3 grid((cols + 255) / 256, rows);
-    hipLaunchKernelGGL(reduce_rows_kernel, grid, dim3(256), 0, s, part, n_part, part_stride, cols, out, st);
+    SJD_LAUNCH(reduce_rows_kernel, grid, dim3(256), 0, s, part, n_part, part_stride, cols, out, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }

@@ -582,14 +582,14 @@ int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
     r.state = v->state; r.img_pos0 = v->img_pos0; r.counter = v->counter;
     r.q = v->q; r.tok_smp = v->tok_smp; r.tok_res = v->tok_res; r.acc_flag = v->acc_flag;
     r.draft_snap = v->draft_snap; r.snap = reinterpret_cast<StepSnap *>(v->snap);
-    hipLaunchKernelGGL(sjd_rows_kernel, dim3(v->L), dim3(DIST_THREADS), lds, s, r);
+    SJD_LAUNCH(sjd_rows_kernel, dim3(v->L), dim3(DIST_THREADS), lds, s, r);
     HIP_TRY(hipGetLastError());
     FinalArgs f;
     f.L = v->L; f.V = v->V; f.lo = v->lo; f.init = v->init; f.seed = v->seed; f.hist = v->hist;
     f.state = v->state; f.kv_tokens = v->kv_tokens; f.q = v->q; f.tok_smp = v->tok_smp; f.tok_res = v->tok_res;
     f.acc_flag = v->acc_flag; f.draft_snap = v->draft_snap; f.snap = reinterpret_cast<const StepSnap *>(v->snap);
     f.n_accepted = v->n_accepted; f.new_draft = v->new_draft; f.p_new = v->p_new;
-    hipLaunchKernelGGL(sjd_finalize_kernel, dim3(v->L), dim3(256), 0, s, f);
+    SJD_LAUNCH(sjd_finalize_kernel, dim3(v->L), dim3(256), 0, s, f);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -600,7 +600,7 @@ int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_samp
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || rows < 1) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
     SJD_TRY(ensure_lds(1, (const void *)sjd_dist_kernel, lds));
-    hipLaunchKernelGGL(sjd_dist_kernel, dim3(rows), dim3(DIST_THREADS), lds, s, logits, V, *smp, forced, q);
+    SJD_LAUNCH(sjd_dist_kernel, dim3(rows), dim3(DIST_THREADS), lds, s, logits, V, *smp, forced, q);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -611,7 +611,7 @@ int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t 
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
     SJD_TRY(ensure_lds(2, (const void *)sjd_first_window_kernel, lds));
-    hipLaunchKernelGGL(sjd_first_window_kernel, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo, *init, seed,
+    SJD_LAUNCH(sjd_first_window_kernel, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo, *init, seed,
                        draft, p_old);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
