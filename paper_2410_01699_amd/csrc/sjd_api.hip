@@ -380,7 +380,7 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t row
     e_qkv.st = st;
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
-    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid;
+    e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid; e_qkv.max_seq = m->cfg.max_seq;
     e_res.kind = SJD_EPI_RESID; e_res.out = kv->x;
     e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (float *)kv->ffn; e_silu.F = F;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;

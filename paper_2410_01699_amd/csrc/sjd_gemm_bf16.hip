@@ -49,16 +49,39 @@ __device__ __forceinline__ uint32_t pack_hi2(float a, float b, float &ra, float 
     return (uint32_t)ha | ((uint32_t)hb << 16);
 }
 
+// What an epilogue needs from memory besides the sums; fetched while the weights stream.
+struct EpiPre {
+    f32x4 x;                  // RESID: current residual values
+    float c0, s0, c1, s1;     // QKV: RoPE factors of this thread's two pairs
+    int pos;                  // QKV: absolute position n + m
+};
+
+template <int EPI>
+__device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, int n_now, int m, int n0, EpiPre &pre)
+{
+    if (EPI == SJD_EPI_RESID) {
+        pre.x = *reinterpret_cast<const f32x4 *>(ep.out + act_off(m, n0, N / 32));
+    } else if (EPI == SJD_EPI_QKV) {
+        const int half = ep.hd >> 1;
+        pre.pos = min(n_now + m, ep.max_seq - 1);   // rows past the window are computed but never stored
+        if (n0 < 2 * ep.d) {
+            const int j = ((n0 % ep.d) % ep.hd) >> 1;
+            const float2 cc = *reinterpret_cast<const float2 *>(ep.cosT + (size_t)pre.pos * half + j);
+            const float2 ss = *reinterpret_cast<const float2 *>(ep.sinT + (size_t)pre.pos * half + j);
+            pre.c0 = cc.x; pre.c1 = cc.y; pre.s0 = ss.x; pre.s1 = ss.y;
+        }
+    }
+}
+
 // One accumulator fragment: lane l of the MFMA result holds features n0..n0+3 (packed order) of
 // token m.  v = final sums.
 template <int EPI>
-__device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int m, int n0, f32x4 v)
+__device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int m, int n0, f32x4 v, const EpiPre &pre)
 {
     if (EPI == SJD_EPI_STORE) {
         *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
     } else if (EPI == SJD_EPI_RESID) {
-        f32x4 *x = reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32));
-        *x = *x + v;
+        *reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32)) = pre.x + v;
     } else if (EPI == SJD_EPI_SILU) {
         // packed rows: (gate f, up f, gate f+1, up f+1)
         const int f = n0 >> 1;
@@ -68,19 +91,19 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
         *reinterpret_cast<float2 *>(ep.ffn + act_off(m, f, ep.F / 32)) = y;
     } else {   // SJD_EPI_QKV
         const int d = ep.d, hd = ep.hd, half = hd >> 1;
-        const int pos = ep.st->n + m;
+        const int pos = pre.pos;
         if (n0 < 2 * d) {
             // Q or K: packed order inside a head is (j, j+half, j+1, j+1+half, ...)
             const int is_k = n0 >= d;
             const int c = n0 - (is_k ? d : 0);
             const int head = c / hd, j = (c % hd) >> 1;
-            const float c0 = ep.cosT[(size_t)pos * half + j], s0 = ep.sinT[(size_t)pos * half + j];
-            const float c1 = ep.cosT[(size_t)pos * half + j + 1], s1 = ep.sinT[(size_t)pos * half + j + 1];
+            const float c0 = pre.c0, s0 = pre.s0, c1 = pre.c1, s1 = pre.s1;
             const float r0 = v[0] * c0 - v[1] * s0, r0p = v[1] * c0 + v[0] * s0;   // dims j, j+half
             const float r1 = v[2] * c1 - v[3] * s1, r1p = v[3] * c1 + v[2] * s1;   // dims j+1, j+1+half
             if (!is_k) {
                 float *q = ep.qact + (size_t)m * d + head * hd + j;
-                q[0] = r0; q[1] = r1; q[half] = r0p; q[half + 1] = r1p;
+                *reinterpret_cast<float2 *>(q) = make_float2(r0, r1);
+                *reinterpret_cast<float2 *>(q + half) = make_float2(r0p, r1p);
             } else if (m < ep.rows_valid) {
                 bf16_t *rec = ep.kvc + kv_block_off(head, pos >> 5, ep.nblk, hd);
                 const int kk = pos & 31;
@@ -121,6 +144,8 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 {
     // the finished flag is only needed before anything is written: its load overlaps the first stage
     const int finished = ep.st ? ep.st->done : 0;
+    const int n_now = (EPI == SJD_EPI_QKV) ? ep.st->n : 0;
+    static_assert(MT * TN * 64 <= 64 * WK, "one epilogue fragment per thread");
     __shared__ f32x4 red[WK][MT * TN][64];
     __shared__ float ssq[WK][MT * 16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
@@ -189,6 +214,13 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 
     LOAD_STAGE(kt0, a0, b0, g0)
     if (finished) return;
+    // epilogue fragment of this thread (threads past MT*TN*64 have none): D layout of tile mtn puts
+    // features 4*(l/16) .. +4 of token l%16 in lane l
+    const bool has_frag = threadIdx.x < MT * TN * 64;
+    const int f_mtn = threadIdx.x >> 6;
+    const int f_m = (f_mtn / TN) * 16 + c, f_n0 = (tile0 + f_mtn % TN) * 16 + g * 4;
+    EpiPre pre;
+    if (has_frag) preload_epilogue<EPI>(ep, N, n_now, f_m, f_n0, pre);
     for (int kt = kt0; kt < kt1; kt += 2 * U) {
         LOAD_STAGE(kt + U, a1, b1, g1)
         MMA_STAGE(a0, b0, g0)
@@ -213,21 +245,17 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         }
     }
     __syncthreads();
-    for (int unit = threadIdx.x; unit < MT * TN * 64; unit += 64 * WK) {
-        const int mtn = unit >> 6, l = unit & 63;
-        f32x4 v = red[0][mtn][l];
+    if (has_frag) {
+        f32x4 v = red[0][f_mtn][lane];
 #pragma unroll
-        for (int w = 1; w < WK; ++w) v += red[w][mtn][l];
-        // D layout: lane l holds features (l/16)*4 + 0..3 of the tile for token l%16
-        const int mt = mtn / TN, tn = mtn % TN;
-        const int m = mt * 16 + (l & 15);
+        for (int w = 1; w < WK; ++w) v += red[w][f_mtn][lane];
         if (PRO == SJD_PRO_NORM) {
-            float sq = ssq[0][m];
+            float sq = ssq[0][f_m];
 #pragma unroll
-            for (int w = 1; w < WK; ++w) sq += ssq[w][m];
+            for (int w = 1; w < WK; ++w) sq += ssq[w][f_m];
             v *= rsqrtf(sq / (float)K + eps);
         }
-        apply_epilogue<EPI>(ep, N, m, (tile0 + tn) * 16 + (l >> 4) * 4, v);
+        apply_epilogue<EPI>(ep, N, f_m, f_n0, v, pre);
     }
 }
 

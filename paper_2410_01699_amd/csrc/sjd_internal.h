@@ -131,7 +131,7 @@ struct SjdGemmEpi {
     float *out;                  // STORE / RESID: [rows][N]
     float *ffn; int32_t F;                                        // SILU: [rows][F]
     float *qact; bf16_t *kvc; const float *cosT, *sinT;           // QKV: kvc = this layer's cache
-    int32_t d, hd, nblk, rows_valid;
+    int32_t d, hd, nblk, rows_valid, max_seq;
 };
 
 struct SjdLayer {

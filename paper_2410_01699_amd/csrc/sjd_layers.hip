@@ -13,18 +13,29 @@ template <> struct Act<bf16_t> {
     __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 };
 
-// x[r][:] = E[ids[r]][:]  (or the given raw embedding row); bf16 models keep x in act_off order
+// x[r][:] = E[ids[r]][:]  (or the given raw embedding row); bf16 models keep x in act_off order.
+// One thread per 4 consecutive features; grid (rows, d / 1024).
 template <typename T>
-__global__ void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, float *x,
-                             const SjdState *st)
+__global__ __launch_bounds__(256) void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, float *x,
+                                                    const SjdState *st)
 {
-    if (st->done) return;
+    const int done = st->done;
     const int r = blockIdx.x;
-    for (int j = threadIdx.x; j < d; j += blockDim.x) {
-        const float v = emb_rows ? emb_rows[(size_t)r * d + j] : Act<T>::load(E, (size_t)ids[r] * d + j);
-        if (sizeof(T) == 2) x[act_off(r, j, d / 32)] = v;
-        else x[(size_t)r * d + j] = v;
+    const int j = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (j >= d) return;
+    float4 v;
+    if (emb_rows) {
+        v = *reinterpret_cast<const float4 *>(emb_rows + (size_t)r * d + j);
+    } else if (sizeof(T) == 2) {
+        const uint2 u = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(E) + (size_t)ids[r] * d + j);
+        v = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                        __uint_as_float(u.y & 0xFFFF0000u));
+    } else {
+        v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(E) + (size_t)ids[r] * d + j);
     }
+    if (done) return;
+    float *dst = sizeof(T) == 2 ? x + act_off(r, j, d / 32) : x + (size_t)r * d + j;
+    *reinterpret_cast<float4 *>(dst) = v;
 }
 
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
@@ -130,9 +141,9 @@ int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_ro
 {
     const int d = m->cfg.d_model;
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, dim3(rows), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, x, st);
+        SJD_LAUNCH(embed_kernel<float>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, x, st);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, x, st);
+        SJD_LAUNCH(embed_kernel<bf16_t>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, x, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
