@@ -193,7 +193,8 @@ int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_
 
 /* Tuning aid: average microseconds per launch of the bf16 projection kernel (plain-store epilogue) at
  * shape M x N x K over `iters` back-to-back launches on zero-filled operands.  `tn` = output tiles
- * per workgroup (1..4), wk = waves splitting K (8), u = k-steps per prefetch stage (2 or 4).
+ * per workgroup (1..3), wk = waves splitting K (8 or 4; 0 = the choice the model makes), u = k-steps per
+ * prefetch stage (2).
  * A negative `iters` times |iters| launches that rotate through more than 1 GiB of weight copies,
  * so that no launch finds its weights in the last-level cache (the situation inside a step).
  * SJD_EINVAL for an unsupported combination.                                                     */

@@ -116,7 +116,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
     };
     // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
     auto linear = [&](size_t off, int N, int K, int perm, SjdLinear *lin) -> int {
-        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 8; lin->u = 2;
+        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 0; lin->u = 2;
         lin->w = db + off * es;
         const size_t n = (size_t)N * K;
         if (cfg->dtype == 0) {
@@ -216,13 +216,14 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     }
     A(kv->tokens, (size_t)c.max_seq * 4);
     A(kv->state, sizeof(SjdState));
-    A(kv->x, R * d * 4);
+    // bf16 models: every activation matrix is followed by one all-zero operand tile (2 KiB)
+    A(kv->x, R * d * 4 + 2048);
     A(kv->h, c.dtype == 0 ? R * d * 4 : 16);
     A(kv->part, (c.dtype == 0 ? part : 4) * 4);
     A(kv->qact, R * d * 4);
     A(kv->att_part, sjd_attention_part_elems(m) * 4);
-    A(kv->att_out, R * d * 4);
-    A(kv->ffn, R * F * 4);
+    A(kv->att_out, R * d * 4 + 2048);
+    A(kv->ffn, R * F * 4 + 2048);
     A(kv->logits, R * V * 4);
     A(kv->q, (R + 1) * V * 4);
     A(kv->tok_smp, (R + 1) * 4);
@@ -805,10 +806,10 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     hipStream_t s = (hipStream_t)stream;
     const size_t es = elt_size(dtype);
     GemmScratch g;
-    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4));     // rows past M stay zero
+    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4 + 2048));   // rows past M and the tile behind stay zero
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 8; lin.u = 2; lin.w = W;
+    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 0; lin.u = 2; lin.w = W;
     if (dtype == 1) {
         SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
         SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * es));
@@ -839,7 +840,7 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     const size_t wbytes = (size_t)N * K * 2;
     const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
     GemmScratch g;
-    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4));
+    SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4 + 2048));
     SJD_TRY(dev_alloc(&g.Wp, wbytes * copies));
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;

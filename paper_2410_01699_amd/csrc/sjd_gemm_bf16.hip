@@ -64,12 +64,11 @@ __device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, in
     } else if (EPI == SJD_EPI_QKV) {
         const int half = ep.hd >> 1;
         pre.pos = min(n_now + m, ep.max_seq - 1);   // rows past the window are computed but never stored
-        if (n0 < 2 * ep.d) {
-            const int j = ((n0 % ep.d) % ep.hd) >> 1;
-            const float2 cc = *reinterpret_cast<const float2 *>(ep.cosT + (size_t)pre.pos * half + j);
-            const float2 ss = *reinterpret_cast<const float2 *>(ep.sinT + (size_t)pre.pos * half + j);
-            pre.c0 = cc.x; pre.c1 = cc.y; pre.s0 = ss.x; pre.s1 = ss.y;
-        }
+        // (V fragments fetch factors they do not use: no branch around the loads)
+        const int j = ((n0 % ep.d) % ep.hd) >> 1;
+        const float2 cc = *reinterpret_cast<const float2 *>(ep.cosT + (size_t)pre.pos * half + j);
+        const float2 ss = *reinterpret_cast<const float2 *>(ep.sinT + (size_t)pre.pos * half + j);
+        pre.c0 = cc.x; pre.c1 = cc.y; pre.s0 = ss.x; pre.s1 = ss.y;
     }
 }
 
@@ -169,29 +168,27 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8, as two float4
     const f32x4 *xp = reinterpret_cast<const f32x4 *>(X) + lane;
     const bf16_t *gp = gain + g * 8;
+    const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(reinterpret_cast<const f32x4 *>(X) + (size_t)2 * KT * 128) + lane;
 
     bf16x8 a0[U][TN], a1[U][TN], g0[U], g1[U];
     f32x4 b0[U][MT][2], b1[U][MT][2];
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
+    // Loads are unconditional (no branch between issue and use, so that the compiler can count
+    // exactly which loads must have landed before a stage is consumed).  A k-step past this wave's
+    // range fetches the all-zero tile that follows every activation matrix, for both operands.
 #define LOAD_STAGE(kbase, a, b, gn)                                                               \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                               \
         const int kq_ = (kbase) + u;                                                              \
-        if (kq_ < kt1) {                                                                          \
-            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                     \
-                a[u][tn] = __builtin_nontemporal_load(wp + ((size_t)kq_ * TN + tn) * 64);         \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                   \
-                const f32x4 *p = xp + ((size_t)mt * KT + kq_) * 128;                              \
-                b[u][mt][0] = p[0];                                                               \
-                b[u][mt][1] = p[64];                                                              \
-            }                                                                                     \
-            if (PRO == SJD_PRO_NORM) gn[u] = *reinterpret_cast<const bf16x8 *>(gp + (size_t)kq_ * 32); \
-        } else {                                                                                  \
-            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) a[u][tn] = zero;                    \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) { b[u][mt][0] = zero4; b[u][mt][1] = zero4; } \
-            gn[u] = zero;                                                                         \
+        const bool ok_ = kq_ < kt1;                                                               \
+        const int kw_ = min(kq_, kt1 - 1);                                                        \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {   /* L2 hits first: they return first */ \
+            const f32x4 *p = xp + (ok_ ? (size_t)mt * KT + kq_ : (size_t)2 * KT) * 128;           \
+            b[u][mt][0] = p[0];                                                                   \
+            b[u][mt][1] = p[64];                                                                  \
         }                                                                                         \
+        _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                         \
+            a[u][tn] = __builtin_nontemporal_load(ok_ ? wp + ((size_t)kq_ * TN + tn) * 64 : zw);  \
+        if (PRO == SJD_PRO_NORM) gn[u] = *reinterpret_cast<const bf16x8 *>(gp + (size_t)kw_ * 32); \
     }
 #define MMA_STAGE(a, b, gn)                                                                       \
     _Pragma("unroll") for (int u = 0; u < U; ++u)                                                 \
@@ -214,19 +211,30 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 
     LOAD_STAGE(kt0, a0, b0, g0)
     if (finished) return;
-    // epilogue fragment of this thread (threads past MT*TN*64 have none): D layout of tile mtn puts
-    // features 4*(l/16) .. +4 of token l%16 in lane l
+    // epilogue fragment of this thread (threads past MT*TN*64 have none and fetch a duplicate): D
+    // layout of tile mtn puts features 4*(l/16) .. +4 of token l%16 in lane l
     const bool has_frag = threadIdx.x < MT * TN * 64;
-    const int f_mtn = threadIdx.x >> 6;
+    const int f_mtn = min((int)(threadIdx.x >> 6), MT * TN - 1);
     const int f_m = (f_mtn / TN) * 16 + c, f_n0 = (tile0 + f_mtn % TN) * 16 + g * 4;
     EpiPre pre;
-    if (has_frag) preload_epilogue<EPI>(ep, N, n_now, f_m, f_n0, pre);
-    for (int kt = kt0; kt < kt1; kt += 2 * U) {
+    preload_epilogue<EPI>(ep, N, n_now, f_m, f_n0, pre);
+    int kt = kt0;
+    // (the scheduling barriers keep the compiler from starting on the previous stage before the next
+    // one's loads are issued, which would drain the memory pipeline once per iteration)
+    for (; kt + 2 * U < kt1; kt += 2 * U) {      // the stage loaded last still lies inside the range
         LOAD_STAGE(kt + U, a1, b1, g1)
+        __builtin_amdgcn_sched_barrier(0);
         MMA_STAGE(a0, b0, g0)
+        __builtin_amdgcn_sched_barrier(0);
         LOAD_STAGE(kt + 2 * U, a0, b0, g0)
+        __builtin_amdgcn_sched_barrier(0);
         MMA_STAGE(a1, b1, g1)
+        __builtin_amdgcn_sched_barrier(0);
     }
+    LOAD_STAGE(kt + U, a1, b1, g1)
+    __builtin_amdgcn_sched_barrier(0);
+    MMA_STAGE(a0, b0, g0)
+    MMA_STAGE(a1, b1, g1)
 #undef LOAD_STAGE
 #undef MMA_STAGE
 
@@ -337,7 +345,7 @@ void sjd_choose_tiles(SjdLinear *lin)
             best_tn = t;
         }
     }
-    lin->tn = best_tn; lin->wk = 8; lin->u = 2;
+    lin->tn = best_tn; lin->wk = 0; lin->u = 2;
 }
 
 template <int MT, int TN, int WK, int U, int PRO>
@@ -370,13 +378,22 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *g
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
     const int tn = lin->tn;               // fixed when the weights were packed
-    if (lin->wk != 8) return SJD_EINVAL;
+    // waves per workgroup: 0 = automatic.  Four waves (longer k-range per wave, two workgroups per CU)
+    // measured 3-15 % faster than eight except on the widest grids; they need one epilogue fragment
+    // per thread to suffice.
+    int wk = lin->wk;
+    if (wk == 0) wk = (mt * tn <= 4 && lin->N / (16 * tn) <= 512) ? 4 : 8;
+    if (wk != 8 && wk != 4) return SJD_EINVAL;
 #define CASE(MT, TN)                                                                                      \
     if (mt == MT && tn == TN) {                                                                           \
-        /* with the norm prologue only the 2-deep prefetch fits the register file */                      \
+        if constexpr (MT * TN <= 4) {                                                                     \
+            if (wk == 4) {                                                                                \
+                if (gain) return launch_epi<MT, TN, 4, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);      \
+                return launch_epi<MT, TN, 4, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);               \
+            }                                                                                             \
+        } else if (wk == 4) return SJD_EINVAL;                                                            \
         if (gain) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);              \
-        return lin->u == 4 ? launch_epi<MT, TN, 8, 4, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s)          \
-                           : launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);         \
+        return launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);                       \
     }
     CASE(1, 1) CASE(1, 2) CASE(1, 3)
     CASE(2, 1) CASE(2, 2) CASE(2, 3)
