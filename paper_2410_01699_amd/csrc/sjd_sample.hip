@@ -7,7 +7,7 @@
 //                        its own draft, a candidate sample from q_i (Eq. 3) and a candidate sample
 //                        from max(0, q_i - p_old_i) (Eq. 2).  Nothing here depends on where the scan
 //                        stops, so all rows run concurrently.
-//   sjd_finalize_kernel  one workgroup per slot of the NEXT window: finds the first rejection, picks
+//   sjd_finalize_kernel  a few workgroups per slot of the NEXT window: finds the first rejection, picks
 //                        the candidates that apply, copies the distributions into next-window order,
 //                        initialises the tail slots and advances the device-resident state.
 //
@@ -89,42 +89,83 @@ __device__ __forceinline__ uint64_t fixed40(float w)
 // ---------------------------------------------------------------------------------------------
 // workgroup-wide helpers (DIST_THREADS threads)
 // ---------------------------------------------------------------------------------------------
+// Wave-wide scans and reductions without LDS traffic: a Hillis-Steele scan inside each row of 16
+// lanes with DPP row shifts (a lane whose source falls outside its row receives the identity), then
+// the four row totals are read from lanes 15/31/47/63 and folded in.
+template <int N>
+__device__ __forceinline__ uint32_t dpp_row_shr(uint32_t identity, uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)x, 0x110 + N, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int l)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l);
+    return ((uint64_t)hi << 32) | lo;
+}
+// inclusive prefix sums over the 64 lanes; `total` is the wave's sum (the same in every lane)
+__device__ __forceinline__ uint64_t wave_scan_u64(uint64_t v, uint64_t &total)
+{
+#define SJD_STEP(N)                                                              \
+    {                                                                            \
+        const uint32_t tl = dpp_row_shr<N>(0u, (uint32_t)v);                     \
+        const uint32_t th = dpp_row_shr<N>(0u, (uint32_t)(v >> 32));             \
+        v += ((uint64_t)th << 32) | tl;                                          \
+    }
+    SJD_STEP(1) SJD_STEP(2) SJD_STEP(4) SJD_STEP(8)
+#undef SJD_STEP
+    const uint64_t r0 = readlane_u64(v, 15), r1 = readlane_u64(v, 31), r2 = readlane_u64(v, 47), r3 = readlane_u64(v, 63);
+    const int row = (threadIdx.x & 63) >> 4;
+    total = r0 + r1 + r2 + r3;
+    return v + (row == 0 ? 0 : row == 1 ? r0 : row == 2 ? r0 + r1 : r0 + r1 + r2);
+}
 __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        uint32_t lo = __shfl_xor((uint32_t)v, o), hi = __shfl_xor((uint32_t)(v >> 32), o);
-        v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
+    uint64_t total;
+    (void)wave_scan_u64(v, total);
+    return total;
 }
-__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int o)
+__device__ __forceinline__ int wave_scan_i32(int v, int &total)
 {
-    uint32_t lo = __shfl_up((uint32_t)v, o), hi = __shfl_up((uint32_t)(v >> 32), o);
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src)
-{
-    uint32_t lo = __shfl((uint32_t)v, src), hi = __shfl((uint32_t)(v >> 32), src);
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { uint32_t t = __shfl_xor(v, o); v = t > v ? t : v; }
-    return v;
+    uint32_t x = (uint32_t)v;
+    x += dpp_row_shr<1>(0u, x); x += dpp_row_shr<2>(0u, x); x += dpp_row_shr<4>(0u, x); x += dpp_row_shr<8>(0u, x);
+    const int r0 = __builtin_amdgcn_readlane((int)x, 15), r1 = __builtin_amdgcn_readlane((int)x, 31);
+    const int r2 = __builtin_amdgcn_readlane((int)x, 47), r3 = __builtin_amdgcn_readlane((int)x, 63);
+    const int row = (threadIdx.x & 63) >> 4;
+    total = r0 + r1 + r2 + r3;
+    return (int)x + (row == 0 ? 0 : row == 1 ? r0 : row == 2 ? r0 + r1 : r0 + r1 + r2);
 }
 __device__ __forceinline__ int wave_sum_i32(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    int total;
+    (void)wave_scan_i32(v, total);
+    return total;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#define SJD_STEP(N) { const uint32_t t = dpp_row_shr<N>(0u, v); v = t > v ? t : v; }
+    SJD_STEP(1) SJD_STEP(2) SJD_STEP(4) SJD_STEP(8)
+#undef SJD_STEP
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15), r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47), r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+    const uint32_t a = r0 > r1 ? r0 : r1, b2 = r2 > r3 ? r2 : r3;
+    return a > b2 ? a : b2;
+}
+__device__ __forceinline__ int wave_min_i32(int v)
+{
+#define SJD_STEP(N) { const int t = (int)dpp_row_shr<N>(0x7FFFFFFFu, (uint32_t)v); v = t < v ? t : v; }
+    SJD_STEP(1) SJD_STEP(2) SJD_STEP(4) SJD_STEP(8)
+#undef SJD_STEP
+    const int r0 = __builtin_amdgcn_readlane(v, 15), r1 = __builtin_amdgcn_readlane(v, 31);
+    const int r2 = __builtin_amdgcn_readlane(v, 47), r3 = __builtin_amdgcn_readlane(v, 63);
+    return min(min(r0, r1), min(r2, r3));
 }
 
 struct DistShared {
     uint64_t wave_tot[DIST_WAVES];
     uint32_t wave_u32[DIST_WAVES];
     int hist[256];
+    int whist[DIST_WAVES][256];   // per-wave digit counts (keeps same-bin LDS atomics inside one wave)
     uint32_t sel_prefix;
     int sel_rank;
     int result;
@@ -132,17 +173,25 @@ struct DistShared {
 
 // Categorical draw from non-negative weights by inverse CDF over 40-bit fixed-point values taken
 // in index order: tau = floor(k32 * C / 2^32), result = first index whose inclusive prefix sum
-// exceeds tau.  The weight of index t is WeightFn(t).  Wave w owns the contiguous index range
-// [w*span, (w+1)*span).  Returns -1 when C == 0.  All threads get the result.
-template <class WeightFn>
+// exceeds tau.  Wave w owns the contiguous index range [w*span, (w+1)*span), span = 64 * ceil(V/1024);
+// inside it lane l owns the indices w*span + 64 j + l, j < EPT (EPT >= ceil(V/1024) at compile time, so
+// that per-thread values can live in registers).  The weight of index t, the j-th of its thread, is
+// weight(j, t).  Returns -1 when C == 0.  All threads get the result.
+template <int EPT, class WeightFn>
 __device__ int block_sample(WeightFn weight, int V, uint32_t k32, DistShared *sh)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int span = ((V + DIST_WAVES * 64 - 1) / (DIST_WAVES * 64)) * 64;  // multiple of 64
     const int beg = wave * span;
     const int end = min(V, beg + span);
+    uint64_t cj[EPT];
     uint64_t local = 0;
-    for (int t = beg + lane; t < end; t += 64) local += fixed40(weight(t));
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int t = beg + j * 64 + lane;
+        cj[j] = t < end ? fixed40(weight(j, t)) : 0;
+        local += cj[j];
+    }
     local = wave_sum_u64(local);
     __syncthreads();                       // protects sh->wave_tot / result from the previous use
     if (lane == 0) sh->wave_tot[wave] = local;
@@ -154,18 +203,19 @@ __device__ int block_sample(WeightFn weight, int V, uint32_t k32, DistShared *sh
         uint64_t tau = __umul64hi((uint64_t)k32 << 32, C);    // (k32 * C) >> 32
         if (tau >= mine && tau < mine + local) {               // exactly one wave
             uint64_t base = mine;
-            for (int g = beg; g < end; g += 64) {
-                int t = g + lane;
-                uint64_t c = t < end ? fixed40(weight(t)) : 0;
-                uint64_t incl = c;
+            bool found = false;
 #pragma unroll
-                for (int o = 1; o < 64; o <<= 1) { uint64_t up = shfl_up_u64(incl, o); if (lane >= o) incl += up; }
-                unsigned long long hit = __ballot(base + incl > tau);
-                if (hit) {
-                    if (lane == 0) sh->result = g + __ffsll(hit) - 1;
-                    break;
+            for (int j = 0; j < EPT; ++j) {
+                if (!found && beg + j * 64 < end) {
+                    uint64_t group_total;
+                    const uint64_t incl = wave_scan_u64(cj[j], group_total);
+                    unsigned long long hit = __ballot(base + incl > tau);
+                    if (hit) {
+                        if (lane == 0) sh->result = beg + j * 64 + __ffsll(hit) - 1;
+                        found = true;
+                    }
+                    base += group_total;
                 }
-                base += shfl_u64(incl, 63);
             }
         }
     }
@@ -177,6 +227,7 @@ __device__ int block_sample(WeightFn weight, int V, uint32_t k32, DistShared *sh
 // caller for writing.  Steps: (1) forced -> one-hot; (2) keep exactly K entries by (value
 // descending, index ascending); (3) e = exp((z - max)/T), Z = sum of e in fixed point,
 // q = e / Z; (4) K == 1 or T == 0 -> one-hot at the arg-max, lowest index on ties.
+template <int EPT>
 __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float T, int forced, uint32_t *buf,
                            DistShared *sh)
 {
@@ -187,12 +238,22 @@ __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float 
         __syncthreads();
         return;
     }
-    // keys into LDS, block max
+    // keys into LDS, block max (all loads of a thread are issued before any is used)
     uint32_t kmax = 0;
-    for (int t = tid; t < V; t += DIST_THREADS) {
-        uint32_t k = order_key(z[t]);
-        buf[t] = k;
-        kmax = k > kmax ? k : kmax;
+    float zr[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int t = tid + j * DIST_THREADS;
+        zr[j] = t < V ? z[t] : 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int t = tid + j * DIST_THREADS;
+        if (t < V) {
+            uint32_t k = order_key(zr[j]);
+            buf[t] = k;
+            kmax = k > kmax ? k : kmax;
+        }
     }
     kmax = wave_max_u32(kmax);
     if (lane == 0) sh->wave_u32[wave] = kmax;
@@ -204,8 +265,7 @@ __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float 
         // lowest index holding the maximum
         int best = 0x7FFFFFFF;
         for (int t = tid; t < V; t += DIST_THREADS) if (buf[t] == kmax) best = min(best, t);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o));
+        best = wave_min_i32(best);
         __syncthreads();
         if (lane == 0) sh->hist[wave] = best;
         __syncthreads();
@@ -225,20 +285,26 @@ __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float 
         uint32_t prefix = 0, mask = 0;
         int rank = top_k;      // we look for the rank-th largest among keys matching the prefix
         for (int shift = 24; shift >= 0; shift -= 8) {
-            if (tid < 256) sh->hist[tid] = 0;
+            for (int b = lane; b < 256; b += 64) sh->whist[wave][b] = 0;
             __syncthreads();
             for (int t = tid; t < V; t += DIST_THREADS) {
                 uint32_t k = buf[t];
-                if ((k & mask) == prefix) atomicAdd(&sh->hist[(k >> shift) & 255u], 1);
+                if ((k & mask) == prefix) atomicAdd(&sh->whist[wave][(k >> shift) & 255u], 1);
+            }
+            __syncthreads();
+            if (tid < 256) {
+                int c = 0;
+#pragma unroll
+                for (int w = 0; w < DIST_WAVES; ++w) c += sh->whist[w][tid];
+                sh->hist[tid] = c;
             }
             __syncthreads();
             if (wave == 0) {
                 // lane l covers digits 255-4l .. 252-4l (descending)
                 int d0 = 255 - 4 * lane;
                 int h0 = sh->hist[d0], h1 = sh->hist[d0 - 1], h2 = sh->hist[d0 - 2], h3 = sh->hist[d0 - 3];
-                int tot = h0 + h1 + h2 + h3, incl = tot;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) { int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
+                int tot = h0 + h1 + h2 + h3, all_;
+                const int incl = wave_scan_i32(tot, all_);
                 int excl = incl - tot;
                 if (excl < rank && rank <= incl) {           // exactly one lane
                     int digit, before;
@@ -284,11 +350,10 @@ __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float 
             for (int g = beg; g < end; g += 64) {
                 int t = g + lane;
                 int f = (t < end && buf[t] == kth) ? 1 : 0;
-                int incl = f;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) { int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
+                int group_total;
+                const int incl = wave_scan_i32(f, group_total);
                 if (f && base + incl > room && kth > 0) buf[t] = kth - 1;
-                base += __shfl(incl, 63);
+                base += group_total;
             }
             __syncthreads();
         }
@@ -302,7 +367,7 @@ __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float 
         bool keep = !cut || k >= kth;
         float e = 0.0f;
         if (keep) {
-            float x = __fdiv_rn(__fsub_rn(z[t], m), T);
+            float x = __fdiv_rn(__fsub_rn(key_to_float(k), m), T);   // the key still holds the logit's bits
             e = exp_fixed(x);
         }
         qb[t] = e;
@@ -350,6 +415,7 @@ struct RowsArgs {
     StepSnap *snap;
 };
 
+template <int EPT>
 __global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
 {
     extern __shared__ uint32_t buf[];
@@ -370,39 +436,61 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
     }
     if (!active || i > L) return;
     const int V = a.V;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int span = ((V + DIST_WAVES * 64 - 1) / (DIST_WAVES * 64)) * 64;
+    const int beg = wave * span, end = min(V, beg + span);
+    // everything this workgroup needs from p_old is requested now and used after the distribution
+    // is done: the thread's share of the row (in block_sample's index order) and, in thread 0, the
+    // entry of the draft token for the accept test
+    const float *po = a.p_old + (size_t)(i < L ? i : 0) * V;
+    float por[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int t = beg + j * 64 + lane;
+        por[j] = (i < L && t < end) ? po[t] : 0.0f;
+    }
+    int x_draft = -1;
+    float po_x = 0.0f;
+    if (threadIdx.x == 0 && i < L) {
+        x_draft = a.draft[i] - a.lo;
+        if (x_draft >= 0 && x_draft < V) po_x = po[x_draft];
+    }
+
     float *qrow = a.q + (size_t)i * V;
     float *qb = reinterpret_cast<float *>(buf);
     if (a.q_in) {
         const float *src = a.q_in + (size_t)i * V;
-        for (int t = threadIdx.x; t < V; t += DIST_THREADS) qb[t] = src[t];
+        float tmp[EPT];
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) { const int t = threadIdx.x + j * DIST_THREADS; tmp[j] = t < V ? src[t] : 0.0f; }
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) { const int t = threadIdx.x + j * DIST_THREADS; if (t < V) qb[t] = tmp[j]; }
         __syncthreads();
     } else {
-        block_dist(a.logits + (size_t)(i - 1) * V, V, a.smp.top_k, a.smp.temperature,
-                   forced_index(a.init, img_pos0 + i, a.lo), buf, &sh);
+        block_dist<EPT>(a.logits + (size_t)(i - 1) * V, V, a.smp.top_k, a.smp.temperature,
+                        forced_index(a.init, img_pos0 + i, a.lo), buf, &sh);
     }
     for (int t = threadIdx.x; t < V; t += DIST_THREADS) qrow[t] = qb[t];
 
     const U4 rnd = philox_draw(a.seed, counter, (uint32_t)i);
     // candidate for Eq. 3 (and for the bonus index L): a plain sample from q_i
-    int s = block_sample([&](int t) { return qb[t]; }, V, rnd.w[2], &sh);
+    int s = block_sample<EPT>([&](int, int t) { return qb[t]; }, V, rnd.w[2], &sh);
     if (threadIdx.x == 0) a.tok_smp[i] = s;
     if (i < L) {
-        const float *po = a.p_old + (size_t)i * V;
         if (threadIdx.x == 0) {
             // Eq. 1: accept iff r < min(1, q_i(x_i) / p_old_i(x_i)); a NaN ratio rejects
-            int x = a.draft[i] - a.lo;
             int ok = 0;
-            if (x >= 0 && x < V) {
-                float ratio = __fdiv_rn(qb[x], po[x]);
+            if (x_draft >= 0 && x_draft < V) {
+                float ratio = __fdiv_rn(qb[x_draft], po_x);
                 float r = u_from_word(rnd.w[0]);
                 ok = (ratio >= 1.0f) || (r < ratio);
             }
             a.acc_flag[i] = ok;
         }
         // candidate for Eq. 2: sample from max(0, q_i - p_old_i); if that vanishes, from q_i
-        int rs = block_sample([&](int t) { float d = __fsub_rn(qb[t], po[t]); return d > 0.0f ? d : 0.0f; }, V,
-                              rnd.w[1], &sh);
-        if (rs < 0) rs = block_sample([&](int t) { return qb[t]; }, V, rnd.w[1], &sh);
+        int rs = block_sample<EPT>([&](int j, int t) { float d = __fsub_rn(qb[t], por[j]); return d > 0.0f ? d : 0.0f; }, V,
+                                   rnd.w[1], &sh);
+        if (rs < 0) rs = block_sample<EPT>([&](int, int t) { return qb[t]; }, V, rnd.w[1], &sh);
         if (threadIdx.x == 0) a.tok_res[i] = rs;
     }
 }
@@ -421,15 +509,22 @@ struct FinalArgs {
     float *p_new;
 };
 
+#define FIN_PARTS 8     // workgroups sharing the copy of one distribution row
 __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
 {
     const StepSnap sn = *a.snap;
     if (!sn.active) return;
     const int L = sn.L_eff, V = a.V, lo = a.lo;
-    const int j = blockIdx.x;
-    // Eq. 1 scan: index 0 is exact by construction; stop at the first rejection
-    int acc = 1;
-    while (acc < L && a.acc_flag[acc]) ++acc;
+    const int j = blockIdx.x, part = blockIdx.y;
+    // this workgroup's slice of row j
+    const int per = (V + FIN_PARTS - 1) / FIN_PARTS;
+    const int t_beg = part * per, t_end = min(V, t_beg + per);
+    // Eq. 1 scan: index 0 is exact by construction; stop at the first rejection.  Every wave loads
+    // all flags at once (lane i holds flag i) and counts the leading run of accepts.
+    const int lane_ = threadIdx.x & 63;
+    const int flag_ = lane_ == 0 ? 1 : (lane_ < L ? a.acc_flag[lane_] : 0);
+    const unsigned long long run_ = __ballot(flag_ != 0);
+    const int acc = __ffsll((long long)~run_) - 1;
     const int n_model = L - acc + 1;
     const int n_hist = sn.img_pos0 + acc;
     const int32_t *hist = a.hist;
@@ -442,10 +537,16 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
             return a.tok_smp[src];
         };
         if (j < n_model) {
-            if (threadIdx.x == 0) a.new_draft[j] = model_tok(j) + lo;
+            if (threadIdx.x == 0 && part == 0) a.new_draft[j] = model_tok(j) + lo;
             const float *src = a.q + (size_t)(acc + j) * V;
             float *dst = a.p_new + (size_t)j * V;
-            for (int t = threadIdx.x; t < V; t += 256) dst[t] = src[t];
+            for (int t0 = t_beg + threadIdx.x; t0 < t_end; t0 += 8 * 256) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { const int t = t0 + u * 256; v[u] = t < t_end ? src[t] : 0.0f; }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { const int t = t0 + u * 256; if (t < t_end) dst[t] = v[u]; }
+            }
         } else {
             // Sec. 4.2 initialisation of image position n_hist + j
             int pos = n_hist + j;
@@ -466,13 +567,13 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
                 tok = (int)(((uint64_t)rnd.w[3] * (uint64_t)V) >> 32);
                 break;
             }
-            if (threadIdx.x == 0) a.new_draft[j] = tok + lo;
+            if (threadIdx.x == 0 && part == 0) a.new_draft[j] = tok + lo;
             float *dst = a.p_new + (size_t)j * V;
             const float u = __fdiv_rn(1.0f, (float)V);
-            for (int t = threadIdx.x; t < V; t += 256) dst[t] = onehot ? (t == tok ? 1.0f : 0.0f) : u;
+            for (int t = t_beg + threadIdx.x; t < t_end; t += 256) dst[t] = onehot ? (t == tok ? 1.0f : 0.0f) : u;
         }
     }
-    if (j == 0 && threadIdx.x == 0) {
+    if (j == 0 && part == 0 && threadIdx.x == 0) {
         if (a.n_accepted) a.n_accepted[0] = acc;
         if (a.state) {
             SjdState *st = a.state;
@@ -491,18 +592,20 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
     }
 }
 
+template <int EPT>
 __global__ __launch_bounds__(DIST_THREADS) void sjd_dist_kernel(const float *logits, int V, sjd_sampler smp,
                                                                 const int32_t *forced, float *q)
 {
     extern __shared__ uint32_t buf[];
     __shared__ DistShared sh;
     const int row = blockIdx.x;
-    block_dist(logits + (size_t)row * V, V, smp.top_k, smp.temperature, forced ? forced[row] : -1, buf, &sh);
+    block_dist<EPT>(logits + (size_t)row * V, V, smp.top_k, smp.temperature, forced ? forced[row] : -1, buf, &sh);
     const float *qb = reinterpret_cast<const float *>(buf);
     for (int t = threadIdx.x; t < V; t += DIST_THREADS) q[(size_t)row * V + t] = qb[t];
 }
 
 // First window (step counter 0): slot 0 ~ q_first, slots 1..L-1 by the init strategy.
+template <int EPT>
 __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const float *q_first, int L, int V, int lo,
                                                                         sjd_init init, uint64_t seed,
                                                                         int32_t *draft, float *p_old)
@@ -517,7 +620,7 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const fl
         for (int t = threadIdx.x; t < V; t += DIST_THREADS) qb[t] = q_first[t];
         __syncthreads();
         U4 rnd = philox_draw(seed, 0, 0);
-        int s = block_sample([&](int t) { return qb[t]; }, V, rnd.w[2], &sh);
+        int s = block_sample<EPT>([&](int, int t) { return qb[t]; }, V, rnd.w[2], &sh);
         if (threadIdx.x == 0) tok0 = s;
         __syncthreads();
     }
@@ -553,21 +656,32 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const fl
 // Dynamic LDS above the default limit has to be enabled per kernel.  The limit is only ever
 // raised, and sjd_sample_setup() raises it when a cache is created, so that launches recorded
 // during graph capture never need to touch function attributes.
-static size_t g_lds_set[3] = {0, 0, 0};
-static int ensure_lds(int which, const void *fn, size_t bytes)
+// Elements per thread are a compile-time bound (per-thread values live in registers): 4, 8, 16 or 32
+// for vocabularies up to 4096, 8192, 16384, 32768.
+static int ept_class(int V) { const int e = (V + DIST_THREADS - 1) / DIST_THREADS; return e <= 4 ? 0 : e <= 8 ? 1 : e <= 16 ? 2 : 3; }
+#define EPT_SWITCH(cls, STMT)                  \
+    switch (cls) {                             \
+        case 0: { constexpr int EPT = 4; STMT; } break;  \
+        case 1: { constexpr int EPT = 8; STMT; } break;  \
+        case 2: { constexpr int EPT = 16; STMT; } break; \
+        default: { constexpr int EPT = 32; STMT; } break; \
+    }
+static size_t g_lds_set[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+static int ensure_lds(int which, int cls, size_t bytes)
 {
-    if (bytes <= 48 * 1024 || bytes <= g_lds_set[which]) return SJD_OK;
+    if (bytes <= 48 * 1024 || bytes <= g_lds_set[which][cls]) return SJD_OK;
+    const void *fn = nullptr;
+    EPT_SWITCH(cls, fn = which == 0 ? (const void *)sjd_rows_kernel<EPT>
+                       : which == 1 ? (const void *)sjd_dist_kernel<EPT> : (const void *)sjd_first_window_kernel<EPT>)
     HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-    g_lds_set[which] = bytes;
+    g_lds_set[which][cls] = bytes;
     return SJD_OK;
 }
 
 int sjd_sample_setup(int32_t V)
 {
     const size_t lds = (size_t)V * 4;
-    SJD_TRY(ensure_lds(0, (const void *)sjd_rows_kernel, lds));
-    SJD_TRY(ensure_lds(1, (const void *)sjd_dist_kernel, lds));
-    SJD_TRY(ensure_lds(2, (const void *)sjd_first_window_kernel, lds));
+    for (int which = 0; which < 3; ++which) SJD_TRY(ensure_lds(which, ept_class(V), lds));
     return SJD_OK;
 }
 
@@ -575,21 +689,21 @@ int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
 {
     if (v->V < 1 || v->V > SJD_MAX_SAMP_VOCAB || v->L < 1 || v->L > SJD_ROWS_MAX) return SJD_EINVAL;
     size_t lds = (size_t)v->V * 4;
-    SJD_TRY(ensure_lds(0, (const void *)sjd_rows_kernel, lds));
+    SJD_TRY(ensure_lds(0, ept_class(v->V), lds));
     RowsArgs r;
     r.logits = v->logits; r.q_in = v->q_in; r.p_old = v->p_old; r.draft = v->draft;
     r.L = v->L; r.V = v->V; r.lo = v->lo; r.smp = v->smp; r.init = v->init; r.seed = v->seed;
     r.state = v->state; r.img_pos0 = v->img_pos0; r.counter = v->counter;
     r.q = v->q; r.tok_smp = v->tok_smp; r.tok_res = v->tok_res; r.acc_flag = v->acc_flag;
     r.draft_snap = v->draft_snap; r.snap = reinterpret_cast<StepSnap *>(v->snap);
-    SJD_LAUNCH(sjd_rows_kernel, dim3(v->L), dim3(DIST_THREADS), lds, s, r);
+    EPT_SWITCH(ept_class(v->V), SJD_LAUNCH(sjd_rows_kernel<EPT>, dim3(v->L), dim3(DIST_THREADS), lds, s, r))
     HIP_TRY(hipGetLastError());
     FinalArgs f;
     f.L = v->L; f.V = v->V; f.lo = v->lo; f.init = v->init; f.seed = v->seed; f.hist = v->hist;
     f.state = v->state; f.kv_tokens = v->kv_tokens; f.q = v->q; f.tok_smp = v->tok_smp; f.tok_res = v->tok_res;
     f.acc_flag = v->acc_flag; f.draft_snap = v->draft_snap; f.snap = reinterpret_cast<const StepSnap *>(v->snap);
     f.n_accepted = v->n_accepted; f.new_draft = v->new_draft; f.p_new = v->p_new;
-    SJD_LAUNCH(sjd_finalize_kernel, dim3(v->L), dim3(256), 0, s, f);
+    SJD_LAUNCH(sjd_finalize_kernel, dim3(v->L, FIN_PARTS), dim3(256), 0, s, f);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -599,8 +713,8 @@ int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_samp
 {
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || rows < 1) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
-    SJD_TRY(ensure_lds(1, (const void *)sjd_dist_kernel, lds));
-    SJD_LAUNCH(sjd_dist_kernel, dim3(rows), dim3(DIST_THREADS), lds, s, logits, V, *smp, forced, q);
+    SJD_TRY(ensure_lds(1, ept_class(V), lds));
+    EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_dist_kernel<EPT>, dim3(rows), dim3(DIST_THREADS), lds, s, logits, V, *smp, forced, q))
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -610,9 +724,9 @@ int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t 
 {
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
-    SJD_TRY(ensure_lds(2, (const void *)sjd_first_window_kernel, lds));
-    SJD_LAUNCH(sjd_first_window_kernel, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo, *init, seed,
-                       draft, p_old);
+    SJD_TRY(ensure_lds(2, ept_class(V), lds));
+    EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_first_window_kernel<EPT>, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo,
+                                        *init, seed, draft, p_old))
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
