@@ -58,12 +58,18 @@ typedef struct {
 } sjd_sampler;
 
 /* Initialisation of new window slots (Sec. 4.2).  mode 0: uniform over the sampling ids;
- * mode 1: strategy (b), repeat the token one grid row above (uniform in the first grid row).
- * eol_id >= 0 forces that id at the last position of every grid row.                          */
+ * mode 1: strategy (b), repeat the token one grid row above (uniform in the first grid row);
+ * mode 2: strategy (a), repeat the token at the previous raster position.
+ * eol_id >= 0 forces that id at the last position of every grid row.
+ * flags bit 0 (SJD_INIT_NO_REFINE): the ablation without refinement (App. "acceleration originates
+ * from the refinement"): only the resampled position survives an iteration, every later slot of the
+ * next window is newly initialised instead of re-drawn by Eq. 3.                                */
+#define SJD_INIT_NO_REFINE 1
 typedef struct {
     int32_t mode;
     int32_t row_stride; /* image tokens per grid row, a row-end token included                 */
     int32_t eol_id;
+    int32_t flags;
 } sjd_init;
 
 typedef struct {

@@ -34,7 +34,7 @@ class Sampler(C.Structure):
 
 
 class Init(C.Structure):
-    _fields_ = [("mode", C.c_int32), ("row_stride", C.c_int32), ("eol_id", C.c_int32)]
+    _fields_ = [("mode", C.c_int32), ("row_stride", C.c_int32), ("eol_id", C.c_int32), ("flags", C.c_int32)]
 
 
 class Config(C.Structure):

@@ -193,6 +193,8 @@ static int32_t forced_index(const orc_init *init, int32_t img_pos, int32_t lo)
  *   uniform           -> uniform row
  *   repeat-above (b)  -> copy of the current token one grid row up, one-hot row; the first
  *                        grid row falls back to uniform.
+ *   repeat-left (a)   -> copy of the current token at the previous raster position, one-hot row
+ *                        (the first column takes the last token of the row before).
  * `cur(pos)` = current token at image position pos: accepted history or the window being built. */
 static int32_t init_slot(const orc_init *init, int32_t V, int32_t lo, int32_t img_pos, uint32_t word,
                          const int32_t *hist, int32_t n_hist, const int32_t *window, float *row)
@@ -202,8 +204,8 @@ static int32_t init_slot(const orc_init *init, int32_t V, int32_t lo, int32_t im
     int onehot;
     if (forced >= 0) {
         tok = forced; onehot = 1;
-    } else if (init->mode == 1 && img_pos - init->row_stride >= 0) {
-        int32_t src = img_pos - init->row_stride;
+    } else if ((init->mode == 1 && img_pos - init->row_stride >= 0) || (init->mode == 2 && img_pos - 1 >= 0)) {
+        int32_t src = img_pos - (init->mode == 1 ? init->row_stride : 1);
         int32_t id = src < n_hist ? hist[src] : window[src - n_hist];
         tok = id - lo; onehot = 1;
     } else {
@@ -266,8 +268,10 @@ int32_t orc_verify_probs(const float *q, const float *p_old, const int32_t *draf
         tok[i] = orc_sample(q + (size_t)i * V, V, w4[2]);
     }
 
-    /* Step 4: next window = unaccepted indices a..L followed by a-1 newly initialised slots */
-    int32_t n_model = L - a + 1;
+    /* Step 4: next window = unaccepted indices a..L followed by a-1 newly initialised slots.
+     * With refinement switched off (the ablation of App. "refinement"), only the resampled index a
+     * survives and every later slot is newly initialised. */
+    int32_t n_model = (init->flags & 1) ? 1 : L - a + 1;
     for (int32_t j = 0; j < n_model; ++j) {
         new_draft[j] = tok[a + j] + lo;
         memcpy(p_new + (size_t)j * V, q + (size_t)(a + j) * V, sizeof(float) * (size_t)V);

@@ -45,9 +45,10 @@ typedef struct {
 } orc_sampler;
 
 typedef struct {
-    int32_t mode;        /* 0 uniform, 1 repeat the token one grid row above */
+    int32_t mode;        /* 0 uniform, 1 repeat the token one grid row above, 2 repeat the left token */
     int32_t row_stride;  /* image tokens per grid row (incl. a row-end token) */
     int32_t eol_id;      /* token id forced at the last position of a row, -1 = none */
+    int32_t flags;       /* bit 0: no refinement (unaccepted drafts are replaced by new slots) */
 } orc_init;
 
 /* One SJD verification (Sec. 4.1 Step 3 + Step 4) from precomputed distributions.

@@ -37,7 +37,7 @@ class sjd_sampler(C.Structure):
 
 
 class sjd_init(C.Structure):
-    _fields_ = [("mode", C.c_int32), ("row_stride", C.c_int32), ("eol_id", C.c_int32)]
+    _fields_ = [("mode", C.c_int32), ("row_stride", C.c_int32), ("eol_id", C.c_int32), ("flags", C.c_int32)]
 
 
 class sjd_stats(C.Structure):

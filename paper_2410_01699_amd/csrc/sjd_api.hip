@@ -485,7 +485,7 @@ extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
         }
     }
     // distribution of the first image token from the last prompt row
-    sjd_init ini = init ? *init : sjd_init{0, 0, -1};
+    sjd_init ini = init ? *init : sjd_init{0, 0, -1, 0};
     SJD_LAUNCH(forced_first_kernel, dim3(1), dim3(1), 0, s, kv->forced, ini, m->cfg.samp_lo);
     HIP_TRY(hipGetLastError());
     return sjd_launch_dist(kv->logits + (size_t)(rows_last - 1) * m->V_s, 1, m->V_s, smp, kv->forced, q_last, s);
@@ -495,7 +495,7 @@ extern "C" int sjd_first_window(const sjd_model *m, const float *q_first, int32_
                                 uint64_t philox_seed, int32_t *draft, float *p_old, void *stream)
 {
     if (!m || !q_first || !init || !draft || !p_old || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
-    if (init->mode < 0 || init->mode > 1 || (init->mode == 1 && init->row_stride < 1)) return SJD_EINVAL;
+    if (init->mode < 0 || init->mode > 2 || (init->mode == 1 && init->row_stride < 1)) return SJD_EINVAL;
     return sjd_launch_first_window(q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, draft, p_old, (hipStream_t)stream);
 }
 
@@ -503,7 +503,7 @@ static int check_sampling(const sjd_sampler *smp, const sjd_init *init, int lo, 
 {
     if (!smp || !init) return SJD_EINVAL;
     if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
-    if (init->mode < 0 || init->mode > 1) return SJD_EINVAL;
+    if (init->mode < 0 || init->mode > 2 || (init->flags & ~SJD_INIT_NO_REFINE)) return SJD_EINVAL;
     if (init->mode == 1 && init->row_stride < 1) return SJD_EINVAL;
     if (init->eol_id >= 0 && (init->eol_id < lo || init->eol_id >= hi || init->row_stride < 1)) return SJD_EINVAL;
     return SJD_OK;
@@ -577,6 +577,7 @@ extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, 
     const bool same = kv->graph_exec && kv->dec_L == L && kv->dec_smp.top_k == smp->top_k &&
                       kv->dec_smp.temperature == smp->temperature && kv->dec_init.mode == init->mode &&
                       kv->dec_init.row_stride == init->row_stride && kv->dec_init.eol_id == init->eol_id &&
+                      kv->dec_init.flags == init->flags &&
                       kv->dec_seed == philox_seed;
     if (!same) drop_graph(kv);          // the captured step has these baked into its kernel arguments
     kv->dec_N = N; kv->dec_L = L; kv->dec_smp = *smp; kv->dec_init = *init; kv->dec_seed = philox_seed;
@@ -746,7 +747,7 @@ static int verify_common(const float *logits, const float *q_in, const float *p_
     if (L < 1 || L > SJD_MAX_WINDOW || V < 1 || V > SJD_MAX_SAMP_VOCAB || img_pos0 < 0) return SJD_EINVAL;
     sjd_sampler sm = smp ? *smp : sjd_sampler{1, 1.0f};
     SJD_TRY(check_sampling(&sm, init, lo, lo + V));
-    if (init->mode == 1 && img_pos0 > 0 && !hist) return SJD_EINVAL;
+    if (init->mode != 0 && img_pos0 > 0 && !hist) return SJD_EINVAL;
     Scratch sc;
     SJD_TRY(dev_alloc((void **)&sc.q, (size_t)(L + 1) * V * 4));
     SJD_TRY(dev_alloc((void **)&sc.ints, (size_t)(L + 1) * 4 * 4));

@@ -525,8 +525,9 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
     const int flag_ = lane_ == 0 ? 1 : (lane_ < L ? a.acc_flag[lane_] : 0);
     const unsigned long long run_ = __ballot(flag_ != 0);
     const int acc = __ffsll((long long)~run_) - 1;
-    const int n_model = L - acc + 1;
+    const int n_model = (a.init.flags & SJD_INIT_NO_REFINE) ? 1 : L - acc + 1;
     const int n_hist = sn.img_pos0 + acc;
+    const int back = a.init.mode == 1 ? a.init.row_stride : a.init.mode == 2 ? 1 : 0;   // repeat-above / -left
     const int32_t *hist = a.hist;
     if (a.kv_tokens) hist = a.kv_tokens + (sn.n - sn.img_pos0);
 
@@ -550,13 +551,13 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
         } else {
             // Sec. 4.2 initialisation of image position n_hist + j
             int pos = n_hist + j;
-            bool onehot = forced_index(a.init, pos, lo) >= 0 || (a.init.mode == 1 && pos - a.init.row_stride >= 0);
+            bool onehot = forced_index(a.init, pos, lo) >= 0 || (back > 0 && pos - back >= 0);
             int tok;
             for (;;) {
                 int f = forced_index(a.init, pos, lo);
                 if (f >= 0) { tok = f; break; }
-                if (a.init.mode == 1 && pos - a.init.row_stride >= 0) {
-                    pos -= a.init.row_stride;
+                if (back > 0 && pos - back >= 0) {
+                    pos -= back;
                     if (pos < sn.img_pos0) { tok = hist[pos] - lo; break; }
                     if (pos < n_hist) { tok = a.draft_snap[pos - sn.img_pos0] - lo; break; }
                     int slot = pos - n_hist;
@@ -614,7 +615,7 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const fl
     __shared__ DistShared sh;
     __shared__ int tok0;
     const int j = blockIdx.x;
-    if (j == 0 || init.mode == 1) {
+    if (j == 0 || init.mode != 0) {
         // slot 0's token (every workgroup that may copy from it recomputes it: same inputs, same bits)
         float *qb = reinterpret_cast<float *>(buf);
         for (int t = threadIdx.x; t < V; t += DIST_THREADS) qb[t] = q_first[t];
@@ -630,13 +631,14 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const fl
         return;
     }
     int pos = j;
-    bool onehot = forced_index(init, pos, lo) >= 0 || (init.mode == 1 && pos - init.row_stride >= 0);
+    const int back = init.mode == 1 ? init.row_stride : init.mode == 2 ? 1 : 0;
+    bool onehot = forced_index(init, pos, lo) >= 0 || (back > 0 && pos - back >= 0);
     int tok;
     for (;;) {
         int f = forced_index(init, pos, lo);
         if (f >= 0) { tok = f; break; }
-        if (init.mode == 1 && pos - init.row_stride >= 0) {
-            pos -= init.row_stride;
+        if (back > 0 && pos - back >= 0) {
+            pos -= back;
             if (pos == 0) { tok = tok0; break; }
             continue;
         }

@@ -197,8 +197,8 @@ def test_step_matches_oracle_given_gpu_logits(B):
         g.close()
 
 
-@pytest.mark.parametrize("L,mode", [(8, 0), (1, 0), (4, 1), (16, 0)])
-def test_generate_tiny_fp32_token_identity(B, L, mode):
+@pytest.mark.parametrize("L,mode,flags", [(8, 0, 0), (1, 0, 0), (4, 1, 0), (16, 0, 0), (8, 2, 0), (8, 0, 1), (4, 2, 1)])
+def test_generate_tiny_fp32_token_identity(B, L, mode, flags):
     w = synth.WORKLOADS["tiny"]
     blob = synth.make_weights(w.shape, seed=0)
     prompt, _ = synth.make_prompt(w)
@@ -206,12 +206,12 @@ def test_generate_tiny_fp32_token_identity(B, L, mode):
     g = Gpu(B, w.shape, blob)
     try:
         for seed in range(3):
-            _say(f"generate tiny L={L} mode={mode} seed={seed}")
-            osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(mode, w.row_stride, -1)
+            _say(f"generate tiny L={L} mode={mode} flags={flags} seed={seed}")
+            osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(mode, w.row_stride, -1, flags)
             lp = om.prefill(prompt)
             want, wst = om.generate_sjd(len(prompt), lp, w.n_image_tokens, L, osmp, oinit, seed)
             got, st = B.sjd_generate(g.m, g.kv, prompt, None, w.n_image_tokens, L, B.sjd_sampler(w.top_k, w.temperature),
-                                     B.sjd_init(mode, w.row_stride, -1), seed)
+                                     B.sjd_init(mode, w.row_stride, -1, flags), seed)
             assert np.array_equal(got, want), (seed, np.nonzero(got != want)[0][:5])
             assert st.steps == wst.steps
             assert list(st.accept_hist) == list(wst.accept_hist)

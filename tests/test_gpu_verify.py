@@ -86,7 +86,7 @@ def _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, seed, counte
     pn = torch.zeros((L, V), dtype=torch.float32, device="cuda")
     h = None if hist is None or len(hist) == 0 else _dev(np.asarray(hist, np.int32))
     B.sjd_verify_probs(_dev(q), _dev(p_old), _dev(np.asarray(draft, np.int32)), L, V, lo,
-                       B.sjd_init(init.mode, init.row_stride, init.eol_id), img_pos0, h, seed, counter, na, nd, pn)
+                       B.sjd_init(init.mode, init.row_stride, init.eol_id, init.flags), img_pos0, h, seed, counter, na, nd, pn)
     torch.cuda.synchronize()
     return int(na.item()), nd.cpu().numpy(), pn.cpu().numpy()
 
@@ -121,8 +121,9 @@ def test_verify_probs_bit_exact(B, L, V, support):
     assert len(set(accepted)) > 1 or L == 2               # the cases do exercise different stopping points
 
 
-@pytest.mark.parametrize("mode,stride,eol", [(1, 8, -1), (1, 3, -1), (0, 7, 13), (1, 5, 13), (1, 1, -1)])
-def test_verify_probs_init_strategies(B, mode, stride, eol):
+@pytest.mark.parametrize("mode,stride,eol,flags", [(1, 8, -1, 0), (1, 3, -1, 0), (0, 7, 13, 0), (1, 5, 13, 0), (1, 1, -1, 0),
+                                                   (2, 8, -1, 0), (2, 5, 13, 0), (0, 8, -1, 1), (2, 5, 13, 1), (1, 3, -1, 1)])
+def test_verify_probs_init_strategies(B, mode, stride, eol, flags):
     rng = np.random.default_rng(mode * 100 + stride)
     L, V, lo = 12, 64, 10
     for case in range(5):
@@ -134,7 +135,7 @@ def test_verify_probs_init_strategies(B, mode, stride, eol):
         for i in range(1, 1 + case * 2):
             q[i] = p_old[i]
         draft = np.array([lo + int(np.argmax(p_old[i])) for i in range(L)], np.int32)
-        init = oracle.Init(mode, stride, eol)
+        init = oracle.Init(mode, stride, eol, flags)
         want = oracle.verify_probs(q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case)
         got = _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case)
         assert got[0] == want[0]
@@ -197,7 +198,7 @@ def test_first_window(B):
     try:
         V, lo = shape.v_s, shape.samp_lo
         q0 = oracle.dist(synth.random_logits(1, V, seed=1)[0], 64, 1.0)
-        for mode, stride, eol, L in [(0, 8, -1, 8), (1, 3, -1, 8), (1, 4, 1000, 16), (0, 5, 7, 32)]:
+        for mode, stride, eol, L in [(0, 8, -1, 8), (1, 3, -1, 8), (1, 4, 1000, 16), (0, 5, 7, 32), (2, 8, -1, 8), (2, 4, 1000, 16)]:
             init = oracle.Init(mode, stride, eol)
             wd, wp = oracle.first_window(q0, L, lo, init, 31)
             d = torch.zeros(L, dtype=torch.int32, device="cuda")

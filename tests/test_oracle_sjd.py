@@ -147,6 +147,39 @@ def test_repeat_above_init_and_forced_row_end():
     assert d0[3] == d0[0] and d0[4] == d0[1] and d0[5] == 29      # pos 3,4 copy pos 0,1
 
 
+def test_repeat_left_init_and_no_refinement():
+    """strategy (a): a new slot copies the current token at the previous raster position (a chain of new
+    slots all copy the last model token), with a one-hot row; without refinement only the resampled
+    index survives and every other slot of the next window is newly initialised"""
+    V, lo, L = 10, 20, 5
+    rng = np.random.default_rng(6)
+    p_old = np.stack([_rand_dist(rng, V) for _ in range(L)])
+    q = np.concatenate([p_old, _rand_dist(rng, V)[None]])
+    draft = np.array([lo + int(np.argmax(p_old[i])) for i in range(L)])
+    hist = np.array([21, 22], np.int32)
+    a, nd, pn = oracle.verify_probs(q, p_old, draft, lo, oracle.Init(2, 4, -1), 2, hist, 9, 2)
+    assert a == L                                        # identical distributions: all accepted
+    assert np.array_equal(pn[0], q[L])                   # slot 0 = bonus index
+    for j in range(1, L):                                # slots 1.. copy slot 0's token, one-hot rows
+        assert nd[j] == nd[0]
+        row = np.zeros(V, np.float32); row[nd[0] - lo] = 1
+        assert np.array_equal(pn[j], row)
+    # a rejection at index 2 (q[2] is disjoint from p_old[2]): with refinement indices 3..L are re-drawn
+    # from q, without it they are initialised afresh (uniform here)
+    q2 = q.copy()
+    q2[2] = 0; q2[2][(int(np.argmax(p_old[2])) + 1) % V] = 1.0
+    p2 = p_old.copy(); p2[2] = 0; p2[2][int(np.argmax(p_old[2]))] = 1.0
+    a1, nd1, pn1 = oracle.verify_probs(q2, p2, draft, lo, oracle.Init(0, 4, -1, 0), 2, hist, 9, 2)
+    a2, nd2, pn2 = oracle.verify_probs(q2, p2, draft, lo, oracle.Init(0, 4, -1, 1), 2, hist, 9, 2)
+    assert a1 == a2 == 2
+    assert nd1[0] == nd2[0] and np.array_equal(pn1[0], pn2[0]) and np.array_equal(pn1[0], q2[2])
+    assert np.array_equal(pn1[1], q2[3]) and np.array_equal(pn1[2], q2[4]) and np.array_equal(pn1[3], q2[5])
+    u = np.full(V, np.float32(1) / np.float32(V), np.float32)
+    for j in range(1, L):
+        assert np.array_equal(pn2[j], u)
+    assert np.array_equal(pn1[4], u)                     # with refinement only a-1 = 1 slot is new
+
+
 # ---------------------------------------------------------------- whole algorithm
 def _tiny():
     shape = synth.ModelShape(n_layers=2, d_model=32, n_heads=2, d_ffn=64, vocab_total=96, samp_lo=32, samp_hi=96,
@@ -262,13 +295,15 @@ def _exact_joint(table, V, depth, smp, init):
     return joint
 
 
-@pytest.mark.parametrize("L,mode,stride,eol", [(2, 0, 2, -1), (3, 0, 2, -1), (4, 0, 2, -1), (2, 1, 2, -1),
-                                               (3, 1, 1, -1), (4, 1, 2, -1), (4, 0, 2, 5), (3, 1, 2, 5)])
-def test_sjd_output_distribution_equals_autoregressive(L, mode, stride, eol):
+@pytest.mark.parametrize("L,mode,stride,eol,flags", [(2, 0, 2, -1, 0), (3, 0, 2, -1, 0), (4, 0, 2, -1, 0), (2, 1, 2, -1, 0),
+                                                     (3, 1, 1, -1, 0), (4, 1, 2, -1, 0), (4, 0, 2, 5, 0), (3, 1, 2, 5, 0),
+                                                     (3, 2, 2, -1, 0), (4, 2, 2, 5, 0),     # repeat-left
+                                                     (4, 0, 2, -1, 1), (3, 2, 2, -1, 1)])   # no refinement
+def test_sjd_output_distribution_equals_autoregressive(L, mode, stride, eol, flags):
     V, depth, runs = 8, 4, 1_000_000
     table = _toy_table(V, depth, seed=100 + L + 10 * mode)
     smp = oracle.Sampler(6, 1.0)                          # top-6 of 8: truncated support is exercised too
-    init = oracle.Init(mode, stride, eol)
+    init = oracle.Init(mode, stride, eol, flags)
     joint = _exact_joint(table, V, depth, smp, init)
     assert abs(joint.sum() - 1) < 1e-9
     hist, steps = oracle.toy_histogram(table, V, depth, L, smp, init, 10_000, runs)
