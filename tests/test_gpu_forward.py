@@ -369,3 +369,48 @@ def test_graph_replay_equals_eager_and_is_deterministic(B):
         assert np.array_equal(toks, ref[1][0]) and st.steps == ref[1][1]
     finally:
         g.close()
+
+
+# ------------------------------------------------------------------ long caches, wide windows, ragged ends
+def test_forward_bf16_long_cache_window32(B):
+    """head size 128, window 32, a cache of ~2300 positions (16 key splits, many 32-position blocks, a
+    ragged last block) and windows that start at every residue of the block size"""
+    shape = synth.ModelShape(2, 512, 4, 1024, 4096, 2048, 4096, 2450, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=11)
+    prompt = synth.random_tokens(2290, 0, 2048, seed=1)
+    toks = synth.random_tokens(160, 2048, 4096, seed=2)
+    windows = [(toks[:32], 1), (toks[32:64], 31), (toks[64:96], 32), (toks[96:113], 17), (toks[113:114], 1),
+               (toks[114:146], 5)]
+    worst = _check_forward(B, shape, blob, prompt, windows, TOL_BF16)
+    _say(f"bf16 long cache worst {worst:.3e}")
+
+
+def test_forward_bf16_7b_dims_two_layers(B):
+    """the 7B layer shapes (d 4096, 32 heads of 128, FFN 11008, 8192 sampled codes at the top of a 65536
+    vocabulary) with two layers, windows of 16 and 32 rows"""
+    shape = synth.ModelShape(2, 4096, 32, 11008, 65536, 57344, 65536, 200, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=0, threads=16)
+    prompt = synth.random_tokens(70, 0, 57344, seed=1)
+    toks = synth.random_tokens(64, 57344, 65536, seed=2)
+    worst = _check_forward(B, shape, blob, prompt, [(toks[:16], 3), (toks[16:48], 32), (toks[48:49], 1)], TOL_BF16)
+    _say(f"7b dims, 2 layers worst {worst:.3e}")
+
+
+@pytest.mark.parametrize("N,L", [(1, 8), (2, 8), (5, 16), (9, 1), (33, 32)])
+def test_generate_ragged_ends_fp32(B, N, L):
+    """images shorter than the window, a single token, window 1: token identity with the oracle"""
+    w = synth.WORKLOADS["tiny"]
+    blob = synth.make_weights(w.shape, seed=0)
+    prompt = synth.random_tokens(1, 0, 1024, seed=5)       # a one-token prompt
+    om = oracle.Model(w.shape, blob)
+    g = Gpu(B, w.shape, blob)
+    try:
+        osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(1, 3, -1)
+        lp = om.prefill(prompt)
+        want, wst = om.generate_sjd(1, lp, N, L, osmp, oinit, 4)
+        got, st = B.sjd_generate(g.m, g.kv, prompt, None, N, L, B.sjd_sampler(w.top_k, w.temperature),
+                                 B.sjd_init(1, 3, -1), 4)
+        assert np.array_equal(got, want)
+        assert st.steps == wst.steps
+    finally:
+        g.close(); om.close()
