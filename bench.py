@@ -75,6 +75,11 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle iterations to time (0 = skip)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--skip-images", action="store_true", help="skip the whole-image SJD / AR runs")
+    ap.add_argument("--window", type=int, default=0, help="override the workload's window size L (1..32)")
+    ap.add_argument("--top-k", type=int, default=0, help="override the workload's top-K (1 = greedy = Jacobi decoding)")
+    ap.add_argument("--init-mode", type=int, default=-1, help="override the initialiser: 0 uniform, 1 above, 2 left")
+    ap.add_argument("--no-refine", action="store_true", help="ablation: no refinement of unaccepted drafts")
+    ap.add_argument("--skip-ar", action="store_true", help="skip the auto-regressive (window 1) image")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -99,6 +104,13 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
         return
     w = synth.WORKLOADS[args.workload]
+    import dataclasses
+    if args.window > 0:
+        w = dataclasses.replace(w, window=args.window)
+    if args.top_k > 0:
+        w = dataclasses.replace(w, top_k=args.top_k)
+    if args.init_mode >= 0:
+        w = dataclasses.replace(w, init_mode=args.init_mode)
     shape = w.shape
     t0 = time.perf_counter()
     blob = synth.make_weights(shape, seed=0, threads=16)
@@ -111,7 +123,7 @@ def main():
     if args.no_graph:
         B.sjd_kv_use_graph(kv, False)
     smp = B.sjd_sampler(w.top_k, w.temperature)
-    init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id)
+    init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id, 1 if args.no_refine else 0)
     N, L = w.n_image_tokens, w.window
     q_first = torch.empty(shape.v_s, dtype=torch.float32, device="cuda")
 
@@ -189,14 +201,17 @@ def main():
         extra["sjd_forwards_per_image"] = st.steps
         extra["sjd_image_seconds"] = st.ms_decode / 1e3
         extra["sjd_image_tokens_per_s"] = N / (st.ms_decode / 1e3)
-        _, sa = B.sjd_generate(m, kv, ids, emb, N, 1, smp, init, args.seed)
-        extra["ar_forwards_per_image"] = sa.steps
-        extra["ar_image_seconds"] = sa.ms_decode / 1e3
-        extra["ar_image_tokens_per_s"] = N / (sa.ms_decode / 1e3)
-        extra["step_compression"] = sa.steps / st.steps
-        extra["latency_speedup_vs_ar"] = sa.ms_decode / st.ms_decode
-        log(f"images: SJD {st.steps} forwards / {st.ms_decode:.0f} ms, AR {sa.steps} forwards / {sa.ms_decode:.0f} ms "
-            f"({time.perf_counter() - t:.1f} s)")
+        if not args.skip_ar:
+            _, sa = B.sjd_generate(m, kv, ids, emb, N, 1, smp, init, args.seed)
+            extra["ar_forwards_per_image"] = sa.steps
+            extra["ar_image_seconds"] = sa.ms_decode / 1e3
+            extra["ar_image_tokens_per_s"] = N / (sa.ms_decode / 1e3)
+            extra["step_compression"] = sa.steps / st.steps
+            extra["latency_speedup_vs_ar"] = sa.ms_decode / st.ms_decode
+            log(f"images: SJD {st.steps} forwards / {st.ms_decode:.0f} ms, AR {sa.steps} forwards / {sa.ms_decode:.0f} ms "
+                f"({time.perf_counter() - t:.1f} s)")
+        else:
+            log(f"image: SJD {st.steps} forwards / {st.ms_decode:.0f} ms")
     B.sjd_kv_free(kv)
     B.sjd_free_model(m)
 
@@ -213,6 +228,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "window_L": L, "top_k": w.top_k, "temperature": w.temperature,
+                   "init_mode": w.init_mode, "no_refine": bool(args.no_refine),
                    "image_tokens_N": N, "prompt_positions": len(ids) + len(emb), "layers": shape.n_layers,
                    "d_model": shape.d_model, "sampling_vocab": shape.v_s, "hip_graph": not args.no_graph,
                    "tokens_fixed_per_step": toks / args.steps, "step_hbm_floor_ms": step_floor_ms,
