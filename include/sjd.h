@@ -101,6 +101,17 @@ int sjd_kv_set_len(sjd_kv *kv, int32_t n);        /* roll the cache back/forward
 int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
                 int32_t n_embeds, const sjd_sampler *smp, const sjd_init *init, float *q_last, void *stream);
 
+/* Classifier-free guidance (Sec. 5.1 runs its text-to-image models with guidance weight 3; the
+ * mechanism is the usual one in logit space): right after sjd_prefill, pre-fill a second,
+ * unconditional prompt into a second cache of the same handle.  From then on every window forward
+ * runs both contexts on the same draft tokens (one pass over the weights, 2 x L rows) and Step 3
+ * works on z = z_uncond + guidance * (z_cond - z_uncond); both caches advance by the accepted
+ * count.  q_last is overwritten with the guided distribution of the first image token.  Windows are
+ * limited to 16 tokens while guidance is on; the next sjd_prefill switches it off.                */
+int sjd_prefill_uncond(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                       int32_t n_embeds, float guidance, const sjd_sampler *smp, const sjd_init *init, float *q_last,
+                       void *stream);
+
 /* First Jacobi window (Sec. 4.1 "starts with a sequence of initialized candidate tokens"):
  * slot 0 is sampled from q_first (dev [V_s]) and carries it as its distribution; slots 1..L-1
  * follow `init`.  Uses step counter 0.  draft dev [L], p_old dev [L x V_s].                   */
@@ -127,6 +138,12 @@ int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const float *p_old,
 int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
                  int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
                  uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats);
+
+/* sjd_generate with classifier-free guidance: both prompts, then the guided loop (L <= 16).      */
+int sjd_generate_cfg(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                     int32_t n_embeds, const int32_t *uncond_ids, int32_t n_uncond_ids, const float *uncond_embeds,
+                     int32_t n_uncond_embeds, float guidance, int32_t N, int32_t L, const sjd_sampler *smp,
+                     const sjd_init *init, uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats);
 
 /* The same loop in pieces, with the loop state (cache length, image position, Philox counter,
  * window, its distributions) resident on the device so that iterations can be enqueued without
@@ -168,7 +185,7 @@ int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *ou
 
 /* ---- pieces of the step, exported for parity tests and profiling --------------------------- */
 /* Step 2 alone: forward `L` tokens (dev ids) at positions n..n+L-1, write their K/V rows, return
- * logits dev [L x V_s] fp32.  Does not advance n.                                              */
+ * logits dev [L x V_s] fp32 (the guided logits while guidance is on).  Does not advance n.     */
 int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream);
 
 /* Step 3 + Step 4 alone, from logits (row s belongs to window index s+1).  hist: dev ids of the

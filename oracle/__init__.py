@@ -68,6 +68,7 @@ def lib():
             "orc_draw": (None, [u64, u64, u32, vp]),
             "orc_u_acc": (f32, [u32]),
             "orc_exp": (f32, [f32]),
+            "orc_guide": (None, [vp, vp, f32, i64, vp]),
             "orc_dist": (None, [vp, i32, i32, f32, i32, vp]),
             "orc_sample": (i32, [vp, i32, u32]),
             "orc_verify_probs": (i32, [vp, vp, vp, i32, i32, i32, P(Init), i32, vp, u64, u64, vp, vp]),
@@ -131,6 +132,13 @@ def u_acc(word):
 
 def exp(x):
     return float(lib().orc_exp(float(np.float32(x))))
+
+
+def guide(z_cond, z_uncond, w):
+    zc = _f32(z_cond); zu = _f32(z_uncond); out = np.empty_like(zc)
+    assert zc.shape == zu.shape
+    lib().orc_guide(_p(zc), _p(zu), float(w), zc.size, _p(out))
+    return out
 
 
 def dist(z, top_k, temperature, forced=-1):

@@ -180,6 +180,17 @@ int32_t orc_sample(const float *w, int32_t V, uint32_t k32)
     return -1; /* unreachable: tau < C */
 }
 
+/* Classifier-free guidance (Sec. 5.1 gives the weight, the usual logit-space mechanism is assumed):
+ * z = z_uncond + w * (z_cond - z_uncond), three separately rounded fp32 operations.             */
+void orc_guide(const float *z_cond, const float *z_uncond, float w, int64_t n, float *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float diff = z_cond[i] - z_uncond[i];
+        float scaled = w * diff;
+        out[i] = z_uncond[i] + scaled;
+    }
+}
+
 /* position-dependent allowed set: the last position of every grid row is the row-end token */
 static int32_t forced_index(const orc_init *init, int32_t img_pos, int32_t lo)
 {

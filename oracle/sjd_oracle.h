@@ -28,6 +28,9 @@ void orc_philox4x32_10(const uint32_t key[2], const uint32_t ctr[4], uint32_t ou
 void orc_draw(uint64_t seed, uint64_t c, uint32_t i, uint32_t out[4]);
 float orc_u_acc(uint32_t word);                 /* top 24 bits -> [0, 1-2^-24] */
 
+/* guided logits of classifier-free guidance: out = z_uncond + w * (z_cond - z_uncond) */
+void orc_guide(const float *z_cond, const float *z_uncond, float w, int64_t n, float *out);
+
 /* ---- sampler pieces ---------------------------------------------------------------- */
 float orc_exp(float x);                         /* the fixed fp32 exp recipe, x <= 0 */
 

@@ -21,7 +21,8 @@ SJD_MAX_SAMP_VOCAB = 32768
 EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "sjd_kv_reset", "sjd_kv_len",
            "sjd_kv_set_len", "sjd_prefill", "sjd_first_window", "sjd_step", "sjd_generate", "sjd_forward_logits",
            "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror", "sjd_decode_begin",
-           "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps", "sjd_gemm_bench"]
+           "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps", "sjd_gemm_bench",
+           "sjd_prefill_uncond", "sjd_generate_cfg"]
 
 PROF_KINDS = ("gemm", "attention", "elementwise", "verify")
 
@@ -72,6 +73,9 @@ _SIG = {
     "sjd_kv_len": (C.c_int, [_vp, _P(_i32)]),
     "sjd_kv_set_len": (C.c_int, [_vp, _i32]),
     "sjd_prefill": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _P(sjd_sampler), _P(sjd_init), _vp, _vp]),
+    "sjd_prefill_uncond": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, C.c_float, _P(sjd_sampler), _P(sjd_init), _vp, _vp]),
+    "sjd_generate_cfg": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _vp, _i32, C.c_float, _i32, _i32,
+                                   _P(sjd_sampler), _P(sjd_init), _u64, _vp, _P(sjd_stats)]),
     "sjd_first_window": (C.c_int, [_vp, _vp, _i32, _P(sjd_init), _u64, _vp, _vp, _vp]),
     "sjd_step": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _u64, _u64, _vp, _vp, _vp,
                            _vp]),
@@ -175,6 +179,22 @@ def sjd_prefill(m, kv, ids, embeds, smp: sjd_sampler, init: sjd_init, q_last, st
     ids, n_ids, embeds, n_emb = _ids_embeds(ids, embeds)
     _check(_lib.sjd_prefill(m, kv, _host(ids), n_ids, _host(embeds), n_emb, C.byref(smp), C.byref(init), _dev(q_last),
                             _stream(stream)))
+
+
+def sjd_prefill_uncond(m, kv, ids, embeds, guidance: float, smp: sjd_sampler, init: sjd_init, q_last, stream=None):
+    ids, n_ids, embeds, n_emb = _ids_embeds(ids, embeds)
+    _check(_lib.sjd_prefill_uncond(m, kv, _host(ids), n_ids, _host(embeds), n_emb, guidance, C.byref(smp), C.byref(init),
+                                   _dev(q_last), _stream(stream)))
+
+
+def sjd_generate_cfg(m, kv, ids, embeds, uncond_ids, uncond_embeds, guidance, N, L, smp, init, seed):
+    ids, n_ids, embeds, n_emb = _ids_embeds(ids, embeds)
+    u_ids, n_u_ids, u_embeds, n_u_emb = _ids_embeds(uncond_ids, uncond_embeds)
+    out = np.empty(N, np.int32)
+    st = sjd_stats()
+    _check(_lib.sjd_generate_cfg(m, kv, _host(ids), n_ids, _host(embeds), n_emb, _host(u_ids), n_u_ids, _host(u_embeds),
+                                 n_u_emb, guidance, N, L, C.byref(smp), C.byref(init), seed, _host(out), C.byref(st)))
+    return out, st
 
 
 def sjd_first_window(m, q_first, L, init: sjd_init, seed, draft, p_old, stream=None):

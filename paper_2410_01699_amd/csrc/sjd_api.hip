@@ -176,7 +176,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
 extern "C" void sjd_kv_free(sjd_kv *kv)
 {
     if (!kv) return;
-    void *ptrs[] = {kv->k, kv->v, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
+    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
                     kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
                     kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
     for (void *p : ptrs) if (p) (void)hipFree(p);
@@ -238,6 +238,7 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     A(kv->g_p, R * V * 4);
     A(kv->g_nacc, 16);
     A(kv->q_first, V * 4);
+    A(kv->logits_last, V * 4);
 #undef A
     if (rc == SJD_OK) rc = sjd_sample_setup(m->V_s);
     if (rc != SJD_OK) { sjd_kv_free(kv); return rc; }
@@ -266,7 +267,9 @@ extern "C" int sjd_kv_reset(sjd_kv *kv)
     SjdState st;
     memset(&st, 0, sizeof(st));
     kv->n_upper = 0;
+    kv->n_upper_u = 0;
     kv->dec_active = 0;
+    kv->cfg_on = 0;
     return state_write(kv, st, 0);
 }
 
@@ -285,10 +288,22 @@ extern "C" int sjd_kv_set_len(sjd_kv *kv, int32_t n)
     if (!kv || n < 0 || n > kv->m->cfg.max_seq) return SJD_EINVAL;
     SjdState st;
     SJD_TRY(state_read(kv, &st));
+    if (kv->cfg_on) {                   // both streams hold the same image tokens: move them together
+        const int n_u = st.n_u + (n - st.n);
+        if (n_u < 0 || n_u > kv->m->cfg.max_seq) return SJD_EINVAL;
+        st.n_u = n_u;
+        kv->n_upper_u = n_u;
+    }
     st.n = n;
     st.done = 0;
     kv->n_upper = n;
     return state_write(kv, st, 0);
+}
+
+static void drop_graph(sjd_kv *kv)
+{
+    if (kv->graph_exec) { (void)hipGraphExecDestroy(kv->graph_exec); kv->graph_exec = nullptr; }
+    if (kv->graph) { (void)hipGraphDestroy(kv->graph); kv->graph = nullptr; }
 }
 
 // ---- optional per-kernel timing -------------------------------------------------------------
@@ -345,17 +360,20 @@ struct SjdProfiler {
 // rows = rows computed (<= 32), rows_valid = rows whose K/V are written.  Inputs already in kv->x.
 static double lin_bytes(const sjd_model *m, const SjdLinear &l) { return (double)l.N * l.K * elt_size(m->cfg.dtype); }
 
-static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+// `stream` selects the cache and the cache length the rows are positioned with (0 conditional,
+// 1 unconditional).
+static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, int32_t stream, float *logits,
+                            hipStream_t s)
 {
     const SjdState *st = kv->state;
     const SjdLinear *prev = nullptr;   // GEMM whose output still has to be added to x
-    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * m->cfg.d_model * 4;   // upper bound
+    const double kv_bytes_layer = 2.0 * ((stream ? kv->n_upper_u : kv->n_upper) + rows) * m->cfg.d_model * 4;   // upper bound
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? 1 : 0, 0, L.g1, rows, kv->h, st, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm(0, &L.qkv, kv->h, rows, kv->part, st, s));
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rope_kv(m, kv, l, kv->part, 1, 0, rows, rows_valid, s));
-        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rope_kv(m, kv, l, stream, kv->part, 1, 0, rows, rows_valid, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, stream, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm(0, &L.o, kv->att_out, rows, kv->part, st, s));
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, 1, 0, L.g2, rows, kv->h, st, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm(0, &L.gu, kv->h, rows, kv->part, st, s));
@@ -368,52 +386,76 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
     return SJD_OK;
 }
 
-// bf16: RMSNorm, residual adds, SiLU*up, RoPE and the cache write happen inside the projection kernel
-static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+// bf16: RMSNorm, residual adds, SiLU*up, RoPE and the cache write happen inside the projection kernel.
+// stream_mode 0 / 1: `rows` rows of that stream; 2: both streams, `rows` (<= 16) rows each, stream 1 in
+// rows 16.. of every activation matrix and of `logits`.
+static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, int32_t stream_mode,
+                             float *logits, hipStream_t s)
 {
     const SjdState *st = kv->state;
     const int d = m->cfg.d_model, F = m->cfg.d_ffn;
     const float eps = m->cfg.rms_eps;
+    const bool dual = stream_mode == 2;
+    const int grows = dual ? SJD_STREAM_ROWS + rows : rows;      // rows the projections compute
     // upper bound of the K/V bytes one layer's attention reads (hi + lo planes)
-    const double kv_bytes_layer = 2.0 * (kv->n_upper + rows) * d * 4;
+    const double kv_bytes_layer = 2.0 * ((stream_mode == 1 ? kv->n_upper_u : kv->n_upper) + rows) * d * 4 +
+                                  (dual ? 2.0 * (kv->n_upper_u + rows) * d * 4 : 0.0);
     SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
     memset(&e_qkv, 0, sizeof(e_qkv));
     e_qkv.st = st;
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
     e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid; e_qkv.max_seq = m->cfg.max_seq;
+    e_qkv.dual = dual; e_qkv.stream = stream_mode == 1;
     e_res.kind = SJD_EPI_RESID; e_res.out = kv->x;
     e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (float *)kv->ffn; e_silu.F = F;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
     const float *x = kv->x, *att = (const float *)kv->att_out, *ffn = (const float *)kv->ffn;
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
-        e_qkv.kvc = (bf16_t *)kv->k + l * kv->k_layer_stride;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, (const bf16_t *)L.g1, eps, rows, e_qkv, s));
-        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, nullptr, 0.f, rows, e_res, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, (const bf16_t *)L.g2, eps, rows, e_silu, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, nullptr, 0.f, rows, e_res, s));
+        e_qkv.kvc = (bf16_t *)(stream_mode == 1 ? kv->k_u : kv->k) + l * kv->k_layer_stride;
+        e_qkv.kvc_u = dual ? (bf16_t *)kv->k_u + l * kv->k_layer_stride : nullptr;
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, (const bf16_t *)L.g1, eps, grows, e_qkv, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, stream_mode, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, nullptr, 0.f, grows, e_res, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, (const bf16_t *)L.g2, eps, grows, e_silu, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, nullptr, 0.f, grows, e_res, s));
     }
-    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, (const bf16_t *)m->gf, eps, rows, e_lm, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, (const bf16_t *)m->gf, eps, grows, e_lm, s));
     return SJD_OK;
 }
 
-static int forward_rows(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, float *logits, hipStream_t s)
+// Embedding + decoder stack for one window or prompt chunk.  ids (device) or emb_rows (device fp32
+// rows), `rows` of them; stream_mode as above.  Two streams see the same rows; their logits land in
+// rows 0.. and SJD_STREAM_ROWS.. of `logits`.
+static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const float *emb_rows, int32_t rows,
+                          int32_t rows_valid, int32_t stream_mode, float *logits, hipStream_t s)
 {
-    return m->cfg.dtype == 0 ? forward_rows_f32(m, kv, rows, rows_valid, logits, s)
-                             : forward_rows_bf16(m, kv, rows, rows_valid, logits, s);
+    if (stream_mode == 2 && rows > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (m->cfg.dtype == 1) {
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, emb_rows, rows, stream_mode == 2, kv->x, kv->state, s));
+        return forward_rows_bf16(m, kv, rows, rows_valid, stream_mode, logits, s);
+    }
+    // fp32 models are launch-bound toys: two streams are two forwards
+    for (int stream = (stream_mode == 1 ? 1 : 0); stream <= (stream_mode == 0 ? 0 : 1); ++stream) {
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, emb_rows, rows, 0, kv->x, kv->state, s));
+        SJD_TRY(forward_rows_f32(m, kv, rows, rows_valid, stream,
+                                 logits + (stream_mode == 2 && stream ? (size_t)SJD_STREAM_ROWS * m->V_s : 0), s));
+    }
+    return SJD_OK;
 }
 
 // n lives on the device; the host keeps an upper bound and only synchronises to refresh it when
 // the bound (not necessarily n itself) would run past max_seq.
 static int check_room(sjd_kv *kv, int32_t L)
 {
-    if (kv->n_upper + L <= kv->m->cfg.max_seq) return SJD_OK;
+    const int ms = kv->m->cfg.max_seq;
+    if (kv->n_upper + L <= ms && (!kv->cfg_on || kv->n_upper_u + L <= ms)) return SJD_OK;
     SjdState st;
     SJD_TRY(state_read(kv, &st));
     kv->n_upper = st.n;
-    if (st.n + L > kv->m->cfg.max_seq) return SJD_ESEQ;
+    kv->n_upper_u = st.n_u;
+    if (st.n + L > ms || (kv->cfg_on && st.n_u + L > ms)) return SJD_ESEQ;
     return SJD_OK;
 }
 
@@ -422,16 +464,24 @@ __global__ void clear_done_kernel(SjdState *st) { st->done = 0; }
 extern "C" int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream)
 {
     if (!m || !kv || kv->m != m || !tokens || !logits || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
     SJD_TRY(check_room(kv, L));
     hipStream_t s = (hipStream_t)stream;
     SJD_LAUNCH(clear_done_kernel, dim3(1), dim3(1), 0, s, kv->state);
     HIP_TRY(hipGetLastError());
-    SJD_TRY(sjd_launch_embed(m, tokens, nullptr, L, kv->x, kv->state, s));
-    return forward_rows(m, kv, L, L, logits, s);
+    if (!kv->cfg_on) return forward_window(m, kv, tokens, nullptr, L, L, 0, logits, s);
+    SJD_TRY(forward_window(m, kv, tokens, nullptr, L, L, 2, kv->logits, s));
+    return sjd_launch_guide(kv->logits, kv->logits + (size_t)SJD_STREAM_ROWS * m->V_s, kv->cfg_scale, (size_t)L * m->V_s,
+                            logits, s);
 }
 
-__global__ void advance_n_kernel(SjdState *st, int32_t *tokens, const int32_t *ids, int rows)
+// rows appended to stream `stream`; the ids of stream 0 are recorded for the repeat initialisers
+__global__ void advance_n_kernel(SjdState *st, int32_t *tokens, const int32_t *ids, int rows, int stream)
 {
+    if (stream) {
+        if (threadIdx.x == 0) st->n_u += rows;
+        return;
+    }
     const int n = st->n;
     for (int r = threadIdx.x; r < rows; r += blockDim.x) tokens[n + r] = ids ? ids[r] : -1;
     __syncthreads();
@@ -443,19 +493,12 @@ __global__ void forced_first_kernel(int32_t *forced, sjd_init init, int lo)
     forced[0] = (init.eol_id >= 0 && init.row_stride == 1) ? init.eol_id - lo : -1;
 }
 
-extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
-                           int32_t n_embeds, const sjd_sampler *smp, const sjd_init *init, float *q_last, void *stream)
+// the prompt of one stream, in chunks of up to SJD_ROWS_MAX positions; leaves the raw logits of the
+// last position in kv->logits row *rows_last - 1
+static int prefill_stream(sjd_model *m, sjd_kv *kv, int32_t stream_id, const int32_t *ids, int32_t n_ids,
+                          const float *embeds, int32_t n_embeds, int *rows_last, hipStream_t s)
 {
-    if (!m || !kv || kv->m != m || !smp || !q_last || n_ids < 0 || n_embeds < 0 || n_ids + n_embeds < 1) return SJD_EINVAL;
-    if ((n_ids && !ids) || (n_embeds && !embeds)) return SJD_EINVAL;
-    if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
-    const int P = n_ids + n_embeds;
-    if (P + 1 > m->cfg.max_seq) return SJD_ESEQ;
-    for (int i = 0; i < n_ids; ++i) if (ids[i] < 0 || ids[i] >= m->cfg.vocab_total) return SJD_EINVAL;
-    hipStream_t s = (hipStream_t)stream;
-    SJD_TRY(sjd_kv_reset(kv));
-    const int d = m->cfg.d_model;
-    int rows_last = 0;
+    const int P = n_ids + n_embeds, d = m->cfg.d_model;
     for (int p0 = 0; p0 < P; p0 += SJD_ROWS_MAX) {
         const int rows = std::min(SJD_ROWS_MAX, P - p0);
         const int id_rows = std::max(0, std::min(rows, n_ids - p0));   // leading rows that are ids
@@ -467,28 +510,85 @@ extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
             if (is_id) {
                 HIP_TRY(hipMemcpyAsync(kv->ids_stage, ids + p0 + done_rows, (size_t)cnt * 4, hipMemcpyHostToDevice, s));
                 HIP_TRY(hipStreamSynchronize(s));
-                SJD_TRY(sjd_launch_embed(m, kv->ids_stage, nullptr, cnt, kv->x, kv->state, s));
+                SJD_TRY(forward_window(m, kv, kv->ids_stage, nullptr, cnt, cnt, stream_id, kv->logits, s));
             } else {
                 HIP_TRY(hipMemcpyAsync(kv->emb_stage, embeds + (size_t)(p0 + done_rows - n_ids) * d, (size_t)cnt * d * 4,
                                        hipMemcpyHostToDevice, s));
                 HIP_TRY(hipStreamSynchronize(s));
-                SJD_TRY(sjd_launch_embed(m, nullptr, kv->emb_stage, cnt, kv->x, kv->state, s));
+                SJD_TRY(forward_window(m, kv, nullptr, kv->emb_stage, cnt, cnt, stream_id, kv->logits, s));
             }
-            SJD_TRY(forward_rows(m, kv, cnt, cnt, kv->logits, s));
             SJD_LAUNCH(advance_n_kernel, dim3(1), dim3(64), 0, s, kv->state, kv->tokens,
-                               is_id ? kv->ids_stage : (const int32_t *)nullptr, cnt);
+                               is_id ? kv->ids_stage : (const int32_t *)nullptr, cnt, stream_id);
             HIP_TRY(hipGetLastError());
             HIP_TRY(hipStreamSynchronize(s));   // staging buffers are reused by the next chunk
-            kv->n_upper += cnt;
+            if (stream_id) kv->n_upper_u += cnt; else kv->n_upper += cnt;
             done_rows += cnt;
-            rows_last = cnt;
+            *rows_last = cnt;
         }
     }
+    return SJD_OK;
+}
+
+static int check_prompt(const sjd_model *m, const int32_t *ids, int32_t n_ids, const float *embeds, int32_t n_embeds)
+{
+    if (n_ids < 0 || n_embeds < 0 || n_ids + n_embeds < 1) return SJD_EINVAL;
+    if ((n_ids && !ids) || (n_embeds && !embeds)) return SJD_EINVAL;
+    if (n_ids + n_embeds + 1 > m->cfg.max_seq) return SJD_ESEQ;
+    for (int i = 0; i < n_ids; ++i) if (ids[i] < 0 || ids[i] >= m->cfg.vocab_total) return SJD_EINVAL;
+    return SJD_OK;
+}
+
+extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                           int32_t n_embeds, const sjd_sampler *smp, const sjd_init *init, float *q_last, void *stream)
+{
+    if (!m || !kv || kv->m != m || !smp || !q_last) return SJD_EINVAL;
+    if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
+    SJD_TRY(check_prompt(m, ids, n_ids, embeds, n_embeds));
+    hipStream_t s = (hipStream_t)stream;
+    SJD_TRY(sjd_kv_reset(kv));          // also switches guidance off
+    int rows_last = 0;
+    SJD_TRY(prefill_stream(m, kv, 0, ids, n_ids, embeds, n_embeds, &rows_last, s));
+    HIP_TRY(hipMemcpyAsync(kv->logits_last, kv->logits + (size_t)(rows_last - 1) * m->V_s, (size_t)m->V_s * 4,
+                           hipMemcpyDeviceToDevice, s));
     // distribution of the first image token from the last prompt row
     sjd_init ini = init ? *init : sjd_init{0, 0, -1, 0};
     SJD_LAUNCH(forced_first_kernel, dim3(1), dim3(1), 0, s, kv->forced, ini, m->cfg.samp_lo);
     HIP_TRY(hipGetLastError());
-    return sjd_launch_dist(kv->logits + (size_t)(rows_last - 1) * m->V_s, 1, m->V_s, smp, kv->forced, q_last, s);
+    return sjd_launch_dist(kv->logits_last, nullptr, 0.f, 1, m->V_s, smp, kv->forced, q_last, s);
+}
+
+static int alloc_uncond_cache(sjd_kv *kv)
+{
+    if (kv->k_u) return SJD_OK;
+    const sjd_config &c = kv->m->cfg;
+    if (c.dtype == 1) {
+        SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 2));
+    } else {
+        SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 4));
+        SJD_TRY(dev_alloc(&kv->v_u, (size_t)c.n_layers * kv->v_layer_stride * 4));
+    }
+    return SJD_OK;
+}
+
+extern "C" int sjd_prefill_uncond(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                                  int32_t n_embeds, float guidance, const sjd_sampler *smp, const sjd_init *init,
+                                  float *q_last, void *stream)
+{
+    if (!m || !kv || kv->m != m || !smp || !q_last || !(guidance == guidance)) return SJD_EINVAL;
+    if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
+    if (kv->n_upper < 1 || kv->cfg_on || kv->dec_active) return SJD_EINVAL;    // right after sjd_prefill only
+    SJD_TRY(check_prompt(m, ids, n_ids, embeds, n_embeds));
+    hipStream_t s = (hipStream_t)stream;
+    SJD_TRY(alloc_uncond_cache(kv));
+    int rows_last = 0;
+    SJD_TRY(prefill_stream(m, kv, 1, ids, n_ids, embeds, n_embeds, &rows_last, s));
+    kv->cfg_on = 1;
+    kv->cfg_scale = guidance;
+    sjd_init ini = init ? *init : sjd_init{0, 0, -1, 0};
+    SJD_LAUNCH(forced_first_kernel, dim3(1), dim3(1), 0, s, kv->forced, ini, m->cfg.samp_lo);
+    HIP_TRY(hipGetLastError());
+    return sjd_launch_dist(kv->logits_last, kv->logits + (size_t)(rows_last - 1) * m->V_s, guidance, 1, m->V_s, smp,
+                           kv->forced, q_last, s);
 }
 
 extern "C" int sjd_first_window(const sjd_model *m, const float *q_first, int32_t L, const sjd_init *init,
@@ -519,10 +619,10 @@ static int enqueue_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
                         const sjd_sampler *smp, const sjd_init *init, uint64_t seed, int32_t *n_accepted,
                         int32_t *new_draft, float *p_new, hipStream_t s)
 {
-    PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, draft, nullptr, L, kv->x, kv->state, s));
-    SJD_TRY(forward_rows(m, kv, L, L, kv->logits, s));
+    SJD_TRY(forward_window(m, kv, draft, nullptr, L, L, kv->cfg_on ? 2 : 0, kv->logits, s));
     SjdVerifyArgs v;
     memset(&v, 0, sizeof(v));
+    if (kv->cfg_on) { v.logits_u = kv->logits + (size_t)SJD_STREAM_ROWS * m->V_s; v.cfg_scale = kv->cfg_scale; }
     v.logits = kv->logits; v.p_old = p_old; v.draft = draft; v.L = L; v.V = m->V_s; v.lo = m->cfg.samp_lo;
     v.smp = *smp; v.init = *init; v.seed = seed; v.state = kv->state; v.kv_tokens = kv->tokens;
     v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new;
@@ -538,6 +638,7 @@ extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
 {
     if (!m || !kv || kv->m != m || !draft || !p_old || !n_accepted || !new_draft || !p_new) return SJD_EINVAL;
     if (L < 1 || L > SJD_MAX_WINDOW || img_pos0 < 0) return SJD_EINVAL;
+    if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
     SJD_TRY(check_room(kv, L));
     hipStream_t s = (hipStream_t)stream;
@@ -546,6 +647,7 @@ extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
     HIP_TRY(hipGetLastError());
     SJD_TRY(enqueue_step(m, kv, draft, p_old, L, smp, init, philox_seed, n_accepted, new_draft, p_new, s));
     kv->n_upper += L;
+    kv->n_upper_u += L;
     return SJD_OK;
 }
 
@@ -557,28 +659,24 @@ __global__ void begin_generate_kernel(SjdState *st, int N, int L)
 }
 
 // ---- device-resident decoding loop -----------------------------------------------------------
-static void drop_graph(sjd_kv *kv)
-{
-    if (kv->graph_exec) { (void)hipGraphExecDestroy(kv->graph_exec); kv->graph_exec = nullptr; }
-    if (kv->graph) { (void)hipGraphDestroy(kv->graph); kv->graph = nullptr; }
-}
-
 extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, int32_t N, int32_t L,
                                 const sjd_sampler *smp, const sjd_init *init, uint64_t philox_seed, void *stream)
 {
     if (!m || !kv || kv->m != m || !q_first || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
-    if (kv->n_upper + N + L > m->cfg.max_seq) {
-        int32_t n;
-        SJD_TRY(sjd_kv_len(kv, &n));
-        if (n + N + L > m->cfg.max_seq) return SJD_ESEQ;
+    if (kv->n_upper + N + L > m->cfg.max_seq || (kv->cfg_on && kv->n_upper_u + N + L > m->cfg.max_seq)) {
+        SjdState st;
+        SJD_TRY(state_read(kv, &st));
+        kv->n_upper = st.n; kv->n_upper_u = st.n_u;
+        if (st.n + N + L > m->cfg.max_seq || (kv->cfg_on && st.n_u + N + L > m->cfg.max_seq)) return SJD_ESEQ;
     }
     hipStream_t s = (hipStream_t)stream;
     const bool same = kv->graph_exec && kv->dec_L == L && kv->dec_smp.top_k == smp->top_k &&
                       kv->dec_smp.temperature == smp->temperature && kv->dec_init.mode == init->mode &&
                       kv->dec_init.row_stride == init->row_stride && kv->dec_init.eol_id == init->eol_id &&
-                      kv->dec_init.flags == init->flags &&
-                      kv->dec_seed == philox_seed;
+                      kv->dec_init.flags == init->flags && kv->dec_seed == philox_seed &&
+                      kv->graph_cfg_on == kv->cfg_on && (!kv->cfg_on || kv->graph_cfg_scale == kv->cfg_scale);
     if (!same) drop_graph(kv);          // the captured step has these baked into its kernel arguments
     kv->dec_N = N; kv->dec_L = L; kv->dec_smp = *smp; kv->dec_init = *init; kv->dec_seed = philox_seed;
     kv->dec_active = 1;
@@ -586,6 +684,7 @@ extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, 
     SJD_LAUNCH(begin_generate_kernel, dim3(1), dim3(1), 0, s, kv->state, N, L);
     HIP_TRY(hipGetLastError());
     kv->n_upper += N;                    // the loop never fixes more than N tokens
+    kv->n_upper_u += N;
     return SJD_OK;
 }
 
@@ -617,6 +716,7 @@ extern "C" int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void 
         (void)hipStreamDestroy(cs);
         if (rc != SJD_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
         kv->graph = g;
+        kv->graph_cfg_on = kv->cfg_on; kv->graph_cfg_scale = kv->cfg_scale;
         e = hipGraphInstantiate(&kv->graph_exec, g, nullptr, nullptr, 0);
         if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_graph(kv); return SJD_EHIP; }
     }
@@ -660,17 +760,20 @@ extern "C" int sjd_kv_use_graph(sjd_kv *kv, int32_t on)
     return SJD_OK;
 }
 
-extern "C" int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
-                            int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
-                            uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats)
+static int generate_common(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                           int32_t n_embeds, bool guided, const int32_t *u_ids, int32_t n_u_ids, const float *u_embeds,
+                           int32_t n_u_embeds, float guidance, int32_t N, int32_t L, const sjd_sampler *smp,
+                           const sjd_init *init, uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats)
 {
     if (!m || !kv || kv->m != m || !out_tokens || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    if (guided && L > SJD_STREAM_ROWS) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
-    const int P = n_ids + n_embeds;
-    if (P + N + L > m->cfg.max_seq) return SJD_ESEQ;
+    if (n_ids + n_embeds + N + L > m->cfg.max_seq) return SJD_ESEQ;
+    if (guided && n_u_ids + n_u_embeds + N + L > m->cfg.max_seq) return SJD_ESEQ;
     hipStream_t s = 0;
     auto t0 = std::chrono::steady_clock::now();
     SJD_TRY(sjd_prefill(m, kv, ids, n_ids, embeds, n_embeds, smp, init, kv->q_first, s));
+    if (guided) SJD_TRY(sjd_prefill_uncond(m, kv, u_ids, n_u_ids, u_embeds, n_u_embeds, guidance, smp, init, kv->q_first, s));
     SJD_TRY(sjd_decode_begin(m, kv, kv->q_first, N, L, smp, init, philox_seed, s));
     HIP_TRY(hipStreamSynchronize(s));
     auto t1 = std::chrono::steady_clock::now();
@@ -690,6 +793,24 @@ extern "C" int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_
         stats->ms_decode = std::chrono::duration<float, std::milli>(t2 - t1).count();
     }
     return SJD_OK;
+}
+
+extern "C" int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                            int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
+                            uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats)
+{
+    return generate_common(m, kv, ids, n_ids, embeds, n_embeds, false, nullptr, 0, nullptr, 0, 0.f, N, L, smp, init,
+                           philox_seed, out_tokens, stats);
+}
+
+extern "C" int sjd_generate_cfg(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
+                                int32_t n_embeds, const int32_t *uncond_ids, int32_t n_uncond_ids,
+                                const float *uncond_embeds, int32_t n_uncond_embeds, float guidance, int32_t N, int32_t L,
+                                const sjd_sampler *smp, const sjd_init *init, uint64_t philox_seed, int32_t *out_tokens,
+                                sjd_stats *stats)
+{
+    return generate_common(m, kv, ids, n_ids, embeds, n_embeds, true, uncond_ids, n_uncond_ids, uncond_embeds,
+                           n_uncond_embeds, guidance, N, L, smp, init, philox_seed, out_tokens, stats);
 }
 
 // ---- per-kernel-class timing of eager iterations (HIP events on the launch stream) ------------
@@ -789,7 +910,7 @@ extern "C" int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sj
 {
     if (!logits || !smp || !q || rows < 1) return SJD_EINVAL;
     if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
-    return sjd_launch_dist(logits, rows, V_s, smp, forced, q, (hipStream_t)stream);
+    return sjd_launch_dist(logits, nullptr, 0.f, rows, V_s, smp, forced, q, (hipStream_t)stream);
 }
 
 struct GemmScratch {

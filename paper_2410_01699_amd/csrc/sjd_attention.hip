@@ -21,7 +21,8 @@ template <typename T, int HD>
 __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(const float *__restrict__ qact, const T *__restrict__ kc,
                                                                    const T *__restrict__ vc, int d, int max_seq,
                                                                    int rows, int v_transposed, int splits,
-                                                                   float *__restrict__ part, const SjdState *st)
+                                                                   float *__restrict__ part, int stream,
+                                                                   const SjdState *st)
 {
     if (st->done) return;
     constexpr int ROWS = SJD_ROWS_MAX;
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(const float *
     __shared__ float m_run[ROWS], l_run[ROWS], scale_old[ROWS];
 
     const int head = blockIdx.x, split = blockIdx.y, tid = threadIdx.x;
-    const int n = st->n;
+    const int n = state_n(st, stream);
     const int total = n + rows;
     int chunk = (total + splits - 1) / splits;
     chunk = (chunk + ATT_TILE - 1) / ATT_TILE * ATT_TILE;
@@ -174,11 +175,19 @@ __device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &
 // partial record of (head, split): O[MT*16][HD] unnormalised, then m[MT*16], then l[MT*16]
 template <int HD, int MT>
 __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__restrict__ qact,
-                                                            const bf16_t *__restrict__ kvc, int d, int nblk_cache,
-                                                            int rows, int splits, float *__restrict__ part,
-                                                            const SjdState *st)
+                                                            const bf16_t *__restrict__ kvc0,
+                                                            const bf16_t *__restrict__ kvc1, int stream0, int d,
+                                                            int nblk_cache, int rows, int splits,
+                                                            float *__restrict__ part, const SjdState *st)
 {
     if (st->done) return;
+    // blockIdx.z = 0: stream `stream0` with cache kvc0, queries in rows 0..; blockIdx.z = 1 (two-stream
+    // forward): stream 1 with cache kvc1, queries in rows SJD_STREAM_ROWS..
+    const int second = blockIdx.z;
+    const int stream = second ? 1 : stream0;
+    const bf16_t *__restrict__ kvc = second ? kvc1 : kvc0;
+    qact += (size_t)second * SJD_STREAM_ROWS * d;
+    part += (size_t)second * gridDim.x * splits * (MT * 16 * HD + 2 * MT * 16);
     constexpr int KS = HD / 32;      // k-steps of the score product
     constexpr int DT = HD / 16;      // output dim tiles
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     __shared__ bf16x8 q_lds[MT][KS][2][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     const int head = blockIdx.x, split = blockIdx.y;
-    const int n = st->n;
+    const int n = state_n(st, stream);
     const int total = n + rows;
     const int nblk = (total + 31) >> 5;
     const int bps = (nblk + splits - 1) / splits;
@@ -338,8 +347,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
 {
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
-    const int head = blockIdx.x;
-    const float *base = part + (size_t)head * splits * REC;
+    const int head = blockIdx.x, second = blockIdx.z;
+    const float *base = part + ((size_t)second * gridDim.x + head) * splits * REC;
     const int u = blockIdx.y * 256 + threadIdx.x;
     if (u >= rows * Q4) return;
     const int q = u / Q4, j4 = u % Q4;
@@ -365,7 +374,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         num += w * os[s];
         den += w * ls[s];
     }
-    *reinterpret_cast<f32x4 *>(out + act_off(q, head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
+    *reinterpret_cast<f32x4 *>(out + act_off(q + second * SJD_STREAM_ROWS, head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -387,17 +396,19 @@ int32_t sjd_attention_splits(const sjd_model *m)
 
 size_t sjd_attention_part_elems(const sjd_model *m)
 {
+    // (two streams of 16 rows need the same space as one stream of 32)
     return (size_t)m->cfg.n_heads * sjd_attention_splits(m) * (SJD_ROWS_MAX * m->hd + 2 * SJD_ROWS_MAX);
 }
 
 template <typename T, int HD>
-static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
+static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream, hipStream_t s)
 {
     const int d = m->cfg.d_model, ms = m->cfg.max_seq, H = m->cfg.n_heads;
+    const T *kc = (const T *)(stream ? kv->k_u : kv->k), *vc = (const T *)(stream ? kv->v_u : kv->v);
     SJD_LAUNCH((attn_partial_kernel<T, HD>), dim3(H, kv->att_splits), dim3(ATT_THREADS), 0, s,
-                       kv->qact, (const T *)kv->k + (size_t)layer * kv->k_layer_stride,
-                       (const T *)kv->v + (size_t)layer * kv->v_layer_stride, d, ms, rows, 0, kv->att_splits,
-                       kv->att_part, kv->state);
+                       kv->qact, kc + (size_t)layer * kv->k_layer_stride,
+                       vc + (size_t)layer * kv->v_layer_stride, d, ms, rows, 0, kv->att_splits,
+                       kv->att_part, stream, kv->state);
     HIP_TRY(hipGetLastError());
     SJD_LAUNCH((attn_combine_kernel<T, HD>), dim3(H), dim3(256), 0, s, kv->att_part, kv->att_splits, d, rows,
                        (T *)kv->att_out, kv->state);
@@ -406,39 +417,47 @@ static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows,
 }
 
 template <int HD, int MT>
-static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
+static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s)
 {
     const int d = m->cfg.d_model, H = m->cfg.n_heads;
-    const bf16_t *kvc = (const bf16_t *)kv->k + (size_t)layer * kv->k_layer_stride;
-    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits), dim3(64 * AW), 0, s, kv->qact, kvc, d,
-                       kv->nblk, rows, kv->att_splits, kv->att_part, kv->state);
+    const size_t off = (size_t)layer * kv->k_layer_stride;
+    const bf16_t *c0 = (const bf16_t *)(stream_mode == 1 ? kv->k_u : kv->k) + off;
+    const bf16_t *c1 = stream_mode == 2 ? (const bf16_t *)kv->k_u + off : c0;
+    const int streams = stream_mode == 2 ? 2 : 1;
+    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits, streams), dim3(64 * AW), 0, s, kv->qact, c0, c1,
+                       stream_mode == 1 ? 1 : 0, d, kv->nblk, rows, kv->att_splits, kv->att_part, kv->state);
     HIP_TRY(hipGetLastError());
-    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256), dim3(256), 0, s, kv->att_part,
+    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256, streams), dim3(256), 0, s, kv->att_part,
                        kv->att_splits, d, rows, (float *)kv->att_out, kv->state);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 
 template <int HD>
-static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
+static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s)
 {
-    return rows <= 16 ? launch_mfma_t<HD, 1>(m, kv, layer, rows, s) : launch_mfma_t<HD, 2>(m, kv, layer, rows, s);
+    if (stream_mode == 2) {
+        if (rows > SJD_STREAM_ROWS) return SJD_EINVAL;
+        return launch_mfma_t<HD, 1>(m, kv, layer, rows, 2, s);
+    }
+    return rows <= 16 ? launch_mfma_t<HD, 1>(m, kv, layer, rows, stream_mode, s)
+                      : launch_mfma_t<HD, 2>(m, kv, layer, rows, stream_mode, s);
 }
 
-int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s)
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s)
 {
     const int hd = m->hd;
     if (m->cfg.dtype == 1) {
-        if (hd == 32) return launch_mfma<32>(m, kv, layer, rows, s);
-        if (hd == 64) return launch_mfma<64>(m, kv, layer, rows, s);
-        if (hd == 128) return launch_mfma<128>(m, kv, layer, rows, s);
+        if (hd == 32) return launch_mfma<32>(m, kv, layer, rows, stream_mode, s);
+        if (hd == 64) return launch_mfma<64>(m, kv, layer, rows, stream_mode, s);
+        if (hd == 128) return launch_mfma<128>(m, kv, layer, rows, stream_mode, s);
         return SJD_EINVAL;
     }
-    if (m->cfg.dtype == 0) {
-        if (hd == 16) return launch_t<float, 16>(m, kv, layer, rows, s);
-        if (hd == 32) return launch_t<float, 32>(m, kv, layer, rows, s);
-        if (hd == 64) return launch_t<float, 64>(m, kv, layer, rows, s);
-        if (hd == 128) return launch_t<float, 128>(m, kv, layer, rows, s);
+    if (m->cfg.dtype == 0 && stream_mode < 2) {
+        if (hd == 16) return launch_t<float, 16>(m, kv, layer, rows, stream_mode, s);
+        if (hd == 32) return launch_t<float, 32>(m, kv, layer, rows, stream_mode, s);
+        if (hd == 64) return launch_t<float, 64>(m, kv, layer, rows, stream_mode, s);
+        if (hd == 128) return launch_t<float, 128>(m, kv, layer, rows, stream_mode, s);
     }
     return SJD_EINVAL;
 }

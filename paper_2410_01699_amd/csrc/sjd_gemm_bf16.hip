@@ -53,17 +53,22 @@ __device__ __forceinline__ uint32_t pack_hi2(float a, float b, float &ra, float 
 struct EpiPre {
     f32x4 x;                  // RESID: current residual values
     float c0, s0, c1, s1;     // QKV: RoPE factors of this thread's two pairs
-    int pos;                  // QKV: absolute position n + m
+    int pos;                  // QKV: absolute position of row m in its stream's cache
+    int stream;               // QKV: 0 or 1
+    int row;                  // QKV: row index inside the stream
 };
 
 template <int EPI>
-__device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, int n_now, int m, int n0, EpiPre &pre)
+__device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, int n_now, int n_now_u, int m, int n0,
+                                                 EpiPre &pre)
 {
     if (EPI == SJD_EPI_RESID) {
         pre.x = *reinterpret_cast<const f32x4 *>(ep.out + act_off(m, n0, N / 32));
     } else if (EPI == SJD_EPI_QKV) {
         const int half = ep.hd >> 1;
-        pre.pos = min(n_now + m, ep.max_seq - 1);   // rows past the window are computed but never stored
+        pre.stream = ep.dual ? (m >= SJD_STREAM_ROWS) : ep.stream;
+        pre.row = ep.dual ? (m & (SJD_STREAM_ROWS - 1)) : m;
+        pre.pos = min((pre.stream ? n_now_u : n_now) + pre.row, ep.max_seq - 1);   // rows past the window are computed but never stored
         // (V fragments fetch factors they do not use: no branch around the loads)
         const int j = ((n0 % ep.d) % ep.hd) >> 1;
         const float2 cc = *reinterpret_cast<const float2 *>(ep.cosT + (size_t)pre.pos * half + j);
@@ -103,8 +108,8 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
                 float *q = ep.qact + (size_t)m * d + head * hd + j;
                 *reinterpret_cast<float2 *>(q) = make_float2(r0, r1);
                 *reinterpret_cast<float2 *>(q + half) = make_float2(r0p, r1p);
-            } else if (m < ep.rows_valid) {
-                bf16_t *rec = ep.kvc + kv_block_off(head, pos >> 5, ep.nblk, hd);
+            } else if (pre.row < ep.rows_valid) {
+                bf16_t *rec = (pre.stream && ep.dual ? ep.kvc_u : ep.kvc) + kv_block_off(head, pos >> 5, ep.nblk, hd);
                 const int kk = pos & 31;
                 float la, lb, dummy0, dummy1;
                 uint32_t hi = pack_hi2(r0, r1, la, lb);
@@ -114,11 +119,11 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
                 *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 0)) = hi;
                 *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 1)) = pack_hi2(la, lb, dummy0, dummy1);
             }
-        } else if (m < ep.rows_valid) {
+        } else if (pre.row < ep.rows_valid) {
             // V: natural feature order
             const int col = n0 - 2 * d;
             const int head = col / hd, dim = col % hd;
-            bf16_t *rec = ep.kvc + kv_block_off(head, pos >> 5, ep.nblk, hd);
+            bf16_t *rec = (pre.stream && ep.dual ? ep.kvc_u : ep.kvc) + kv_block_off(head, pos >> 5, ep.nblk, hd);
             const int kk = pos & 31;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -143,7 +148,9 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 {
     // the finished flag is only needed before anything is written: its load overlaps the first stage
     const int finished = ep.st ? ep.st->done : 0;
-    const int n_now = (EPI == SJD_EPI_QKV) ? ep.st->n : 0;
+    // cache lengths of both streams (one stream: its own length is passed as the first)
+    const int n_now = (EPI == SJD_EPI_QKV) ? state_n(ep.st, ep.dual ? 0 : ep.stream) : 0;
+    const int n_now_u = (EPI == SJD_EPI_QKV) ? ep.st->n_u : 0;
     static_assert(MT * TN * 64 <= 64 * WK, "one epilogue fragment per thread");
     __shared__ f32x4 red[WK][MT * TN][64];
     __shared__ float ssq[WK][MT * 16];
@@ -217,7 +224,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     const int f_mtn = min((int)(threadIdx.x >> 6), MT * TN - 1);
     const int f_m = (f_mtn / TN) * 16 + c, f_n0 = (tile0 + f_mtn % TN) * 16 + g * 4;
     EpiPre pre;
-    preload_epilogue<EPI>(ep, N, n_now, f_m, f_n0, pre);
+    preload_epilogue<EPI>(ep, N, n_now, n_now_u, f_m, f_n0, pre);
     int kt = kt0;
     // (the scheduling barriers keep the compiler from starting on the previous stage before the next
     // one's loads are issued, which would drain the memory pipeline once per iteration)

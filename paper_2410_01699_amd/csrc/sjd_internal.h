@@ -71,7 +71,12 @@ struct SjdState {
     int32_t done;       // generation finished: later steps are no-ops
     int32_t steps;      // window forwards executed
     int32_t accept_hist[65];
+    int32_t n_u;        // length of the second (unconditional) cache when guidance is on
 };
+// Two token streams share one window forward when classifier-free guidance is on: stream 0 is the
+// conditional context (cache length n), stream 1 the unconditional one (cache length n_u).
+__device__ __forceinline__ int state_n(const SjdState *st, int stream) { return stream ? st->n_u : st->n; }
+#define SJD_STREAM_ROWS 16   // rows per stream in a two-stream forward (stream 1 starts at row 16)
 
 // bf16 models keep every activation the projections consume (residual stream, attention output, FFN
 // hidden) as fp32 in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a wave fetches the
@@ -131,6 +136,9 @@ struct SjdGemmEpi {
     float *out;                  // STORE / RESID: [rows][N]
     float *ffn; int32_t F;                                        // SILU: [rows][F]
     float *qact; bf16_t *kvc; const float *cosT, *sinT;           // QKV: kvc = this layer's cache
+    bf16_t *kvc_u;                // QKV, two streams: stream 1's cache of this layer
+    int32_t stream;               // QKV, one stream: which cache length positions the rows
+    int32_t dual;                 // QKV: rows 0..15 belong to stream 0, rows 16..31 to stream 1
     int32_t d, hd, nblk, rows_valid, max_seq;
 };
 
@@ -154,6 +162,11 @@ struct sjd_kv {
     const sjd_model *m;
     void *k, *v;          // fp32 models: K and V as [layer][pos][d]; bf16 models: k holds the blocked
                           // hi/lo cache described above ([layer][head][block][128*hd]), v is unused
+    void *k_u, *v_u;      // the same for the unconditional stream (allocated when guidance is first used)
+    int32_t cfg_on;       // a second stream is pre-filled: forwards run both, logits are guided
+    float cfg_scale;
+    int32_t n_upper_u;    // host-side upper bound of n_u
+    float *logits_last;   // [V_s] raw logits of the last prompt position (stream 0), for guidance
     size_t k_layer_stride, v_layer_stride;   // elements
     int32_t nblk;         // bf16 models: 32-position blocks per head
     int32_t *tokens;      // [max_seq] ids of cached positions (-1 for raw-embedding rows)
@@ -190,16 +203,19 @@ struct sjd_kv {
     int32_t use_graph;
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
+    int32_t graph_cfg_on;   // stream mode and guidance weight the captured iteration was recorded with
+    float graph_cfg_scale;
     void *prof;           // SjdProfiler* while sjd_profile_steps runs, else NULL
 };
 
 // ---- kernel launchers (each returns SJD_OK or an SJD_E* code) --------------------------------
 // `st` (device) lets a kernel skip its work once a generation has finished; NULL = always run.
-int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, float *x,
+// dup != 0: every row is also written SJD_STREAM_ROWS rows further down (second stream, same tokens)
+int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, int32_t dup, float *x,
                      const SjdState *st, hipStream_t s);
 int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
-int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const float *part, int32_t n_part,
+int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
                        size_t part_stride, int32_t rows, int32_t rows_valid, hipStream_t s);
 int sjd_launch_silu_mul(const sjd_model *m, const float *part, int32_t n_part, size_t part_stride, int32_t rows,
                         void *ffn, const SjdState *st, hipStream_t s);
@@ -214,12 +230,16 @@ void sjd_choose_tiles(SjdLinear *lin);
 int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s);
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
-int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, hipStream_t s);
+// stream_mode 0 / 1: one stream (rows 0..rows-1) against that stream's cache; 2: both streams, `rows`
+// rows each (stream 1 in rows 16..), bf16 models only
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s);
 int32_t sjd_attention_splits(const sjd_model *m);
 size_t sjd_attention_part_elems(const sjd_model *m);
 // sampling / verification
 struct SjdVerifyArgs {
     const float *logits;     // [L][V] or NULL when q rows are given
+    const float *logits_u;   // [L][V] unconditional logits, or NULL: z = z_u + cfg_scale * (z - z_u)
+    float cfg_scale;
     const float *q_in;       // [(L+1)][V] precomputed distributions or NULL
     const float *p_old;      // [L][V]
     const int32_t *draft;    // [L]
@@ -243,7 +263,8 @@ struct SjdVerifyArgs {
 };
 int sjd_launch_verify(const SjdVerifyArgs *a, hipStream_t s);
 int sjd_sample_setup(int32_t V);   // raise the dynamic-LDS limit of the sampling kernels for vocabulary V
-int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_sampler *smp, const int32_t *forced,
-                    float *q, hipStream_t s);
+int sjd_launch_dist(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
+                    const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s);
+int sjd_launch_guide(const float *logits, const float *logits_u, float cfg_scale, size_t n, float *out, hipStream_t s);
 int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t lo, const sjd_init *init,
                             uint64_t seed, int32_t *draft, float *p_old, hipStream_t s);

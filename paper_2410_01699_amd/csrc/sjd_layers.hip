@@ -16,8 +16,8 @@ template <> struct Act<bf16_t> {
 // x[r][:] = E[ids[r]][:]  (or the given raw embedding row); bf16 models keep x in act_off order.
 // One thread per 4 consecutive features; grid (rows, d / 1024).
 template <typename T>
-__global__ __launch_bounds__(256) void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, float *x,
-                                                    const SjdState *st)
+__global__ __launch_bounds__(256) void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, int dup,
+                                                    float *x, const SjdState *st)
 {
     const int done = st->done;
     const int r = blockIdx.x;
@@ -36,6 +36,11 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *E, const int32_t *i
     if (done) return;
     float *dst = sizeof(T) == 2 ? x + act_off(r, j, d / 32) : x + (size_t)r * d + j;
     *reinterpret_cast<float4 *>(dst) = v;
+    if (dup) {   // the second stream sees the same tokens
+        const int r2 = r + SJD_STREAM_ROWS;
+        dst = sizeof(T) == 2 ? x + act_off(r2, j, d / 32) : x + (size_t)r2 * d + j;
+        *reinterpret_cast<float4 *>(dst) = v;
+    }
 }
 
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
@@ -69,11 +74,11 @@ template <typename T>
 __global__ __launch_bounds__(256) void rope_kv_kernel(const float *part, int n_part, size_t part_stride, int d, int hd,
                                                       int max_seq, const float *cosT, const float *sinT, float *qact,
                                                       T *kc, T *vc, int v_transposed, int rows_valid,
-                                                      const SjdState *st)
+                                                      int stream, const SjdState *st)
 {
     if (st->done) return;
     const int r = blockIdx.x;
-    const int pos = st->n + r;
+    const int pos = state_n(st, stream) + r;
     const int half = hd / 2;
     const size_t row = (size_t)r * 3 * d;
     for (int e = threadIdx.x; e < d / 2; e += 256) {
@@ -136,14 +141,15 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *part, int
 // ---------------------------------------------------------------------------------------------
 #define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
 
-int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, float *x,
+int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, int32_t dup, float *x,
                      const SjdState *st, hipStream_t s)
 {
+    if (dup && rows > SJD_STREAM_ROWS) return SJD_EINVAL;
     const int d = m->cfg.d_model;
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, x, st);
+        SJD_LAUNCH(embed_kernel<float>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, dup, x, st);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, x, st);
+        SJD_LAUNCH(embed_kernel<bf16_t>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, dup, x, st);
     LAUNCH_CHECK();
     return SJD_OK;
 }
@@ -159,14 +165,15 @@ int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t 
     return SJD_OK;
 }
 
-int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, const float *part, int32_t n_part,
+int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
                        size_t part_stride, int32_t rows, int32_t rows_valid, hipStream_t s)
 {
     const int d = m->cfg.d_model, ms = m->cfg.max_seq;
     if (m->cfg.dtype != 0) return SJD_EINVAL;   // bf16 models do this in the QKV GEMM epilogue
+    float *kc = (float *)(stream ? kv->k_u : kv->k), *vc = (float *)(stream ? kv->v_u : kv->v);
     SJD_LAUNCH(rope_kv_kernel<float>, dim3(rows), dim3(256), 0, s, part, n_part, part_stride, d, m->hd, ms,
-                       m->rope_cos, m->rope_sin, kv->qact, (float *)kv->k + (size_t)layer * kv->k_layer_stride,
-                       (float *)kv->v + (size_t)layer * kv->v_layer_stride, 0, rows_valid, kv->state);
+                       m->rope_cos, m->rope_sin, kv->qact, kc + (size_t)layer * kv->k_layer_stride,
+                       vc + (size_t)layer * kv->v_layer_stride, 0, rows_valid, stream, kv->state);
     LAUNCH_CHECK();
     return SJD_OK;
 }

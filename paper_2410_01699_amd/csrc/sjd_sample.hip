@@ -227,9 +227,13 @@ __device__ int block_sample(WeightFn weight, int V, uint32_t k32, DistShared *sh
 // caller for writing.  Steps: (1) forced -> one-hot; (2) keep exactly K entries by (value
 // descending, index ascending); (3) e = exp((z - max)/T), Z = sum of e in fixed point,
 // q = e / Z; (4) K == 1 or T == 0 -> one-hot at the arg-max, lowest index on ties.
+// Classifier-free guidance (the paper's Sec. 5.1 names the weight, not the mechanism; the usual
+// logit-space form is used): z = z_u + w * (z_c - z_u), three separately rounded fp32 operations.
+__device__ __forceinline__ float guide(float zc, float zu, float w) { return __fadd_rn(zu, __fmul_rn(w, __fsub_rn(zc, zu))); }
+
 template <int EPT>
-__device__ void block_dist(const float *__restrict__ z, int V, int top_k, float T, int forced, uint32_t *buf,
-                           DistShared *sh)
+__device__ void block_dist(const float *__restrict__ z, const float *__restrict__ z_u, float cfg_scale, int V, int top_k,
+                           float T, int forced, uint32_t *buf, DistShared *sh)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float *qb = reinterpret_cast<float *>(buf);
@@ -245,6 +249,16 @@ __device__ void block_dist(const float *__restrict__ z, int V, int top_k, float 
     for (int j = 0; j < EPT; ++j) {
         const int t = tid + j * DIST_THREADS;
         zr[j] = t < V ? z[t] : 0.0f;
+    }
+    if (z_u) {
+        float zu[EPT];
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            const int t = tid + j * DIST_THREADS;
+            zu[j] = t < V ? z_u[t] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) zr[j] = guide(zr[j], zu[j], cfg_scale);
     }
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
@@ -401,7 +415,8 @@ struct StepSnap {       // per-step scalars frozen by the rows kernel for the fi
 };
 
 struct RowsArgs {
-    const float *logits, *q_in, *p_old;
+    const float *logits, *logits_u, *q_in, *p_old;
+    float cfg_scale;
     const int32_t *draft;
     int32_t L, V, lo;
     sjd_sampler smp;
@@ -467,8 +482,8 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
         for (int j = 0; j < EPT; ++j) { const int t = threadIdx.x + j * DIST_THREADS; if (t < V) qb[t] = tmp[j]; }
         __syncthreads();
     } else {
-        block_dist<EPT>(a.logits + (size_t)(i - 1) * V, V, a.smp.top_k, a.smp.temperature,
-                        forced_index(a.init, img_pos0 + i, a.lo), buf, &sh);
+        block_dist<EPT>(a.logits + (size_t)(i - 1) * V, a.logits_u ? a.logits_u + (size_t)(i - 1) * V : nullptr, a.cfg_scale,
+                        V, a.smp.top_k, a.smp.temperature, forced_index(a.init, img_pos0 + i, a.lo), buf, &sh);
     }
     for (int t = threadIdx.x; t < V; t += DIST_THREADS) qrow[t] = qb[t];
 
@@ -580,6 +595,7 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
             SjdState *st = a.state;
             if (a.kv_tokens) for (int i = 0; i < acc; ++i) a.kv_tokens[sn.n + i] = a.draft_snap[i];
             st->n = sn.n + acc;
+            st->n_u += acc;              // the unconditional stream (if any) takes the same tokens
             st->img_pos0 = sn.img_pos0 + acc;
             st->counter = sn.counter + 1;
             st->steps += 1;
@@ -594,13 +610,14 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
 }
 
 template <int EPT>
-__global__ __launch_bounds__(DIST_THREADS) void sjd_dist_kernel(const float *logits, int V, sjd_sampler smp,
-                                                                const int32_t *forced, float *q)
+__global__ __launch_bounds__(DIST_THREADS) void sjd_dist_kernel(const float *logits, const float *logits_u, float cfg_scale,
+                                                                int V, sjd_sampler smp, const int32_t *forced, float *q)
 {
     extern __shared__ uint32_t buf[];
     __shared__ DistShared sh;
     const int row = blockIdx.x;
-    block_dist<EPT>(logits + (size_t)row * V, V, smp.top_k, smp.temperature, forced ? forced[row] : -1, buf, &sh);
+    block_dist<EPT>(logits + (size_t)row * V, logits_u ? logits_u + (size_t)row * V : nullptr, cfg_scale, V, smp.top_k,
+                    smp.temperature, forced ? forced[row] : -1, buf, &sh);
     const float *qb = reinterpret_cast<const float *>(buf);
     for (int t = threadIdx.x; t < V; t += DIST_THREADS) q[(size_t)row * V + t] = qb[t];
 }
@@ -693,7 +710,8 @@ int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
     size_t lds = (size_t)v->V * 4;
     SJD_TRY(ensure_lds(0, ept_class(v->V), lds));
     RowsArgs r;
-    r.logits = v->logits; r.q_in = v->q_in; r.p_old = v->p_old; r.draft = v->draft;
+    r.logits = v->logits; r.logits_u = v->logits_u; r.cfg_scale = v->cfg_scale; r.q_in = v->q_in; r.p_old = v->p_old;
+    r.draft = v->draft;
     r.L = v->L; r.V = v->V; r.lo = v->lo; r.smp = v->smp; r.init = v->init; r.seed = v->seed;
     r.state = v->state; r.img_pos0 = v->img_pos0; r.counter = v->counter;
     r.q = v->q; r.tok_smp = v->tok_smp; r.tok_res = v->tok_res; r.acc_flag = v->acc_flag;
@@ -710,13 +728,13 @@ int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
     return SJD_OK;
 }
 
-int sjd_launch_dist(const float *logits, int32_t rows, int32_t V, const sjd_sampler *smp, const int32_t *forced,
-                    float *q, hipStream_t s)
+int sjd_launch_dist(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
+                    const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s)
 {
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || rows < 1) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
     SJD_TRY(ensure_lds(1, ept_class(V), lds));
-    EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_dist_kernel<EPT>, dim3(rows), dim3(DIST_THREADS), lds, s, logits, V, *smp, forced, q))
+    EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_dist_kernel<EPT>, dim3(rows), dim3(DIST_THREADS), lds, s, logits, logits_u, cfg_scale, V, *smp, forced, q))
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -729,6 +747,20 @@ int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t 
     SJD_TRY(ensure_lds(2, ept_class(V), lds));
     EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_first_window_kernel<EPT>, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo,
                                         *init, seed, draft, p_old))
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+// out[e] = guided logits of two rows sets (parity hook of the two-stream forward)
+__global__ void sjd_guide_kernel(const float *zc, const float *zu, float w, size_t n, float *out)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x)
+        out[e] = guide(zc[e], zu[e], w);
+}
+
+int sjd_launch_guide(const float *logits, const float *logits_u, float cfg_scale, size_t n, float *out, hipStream_t s)
+{
+    SJD_LAUNCH(sjd_guide_kernel, dim3(256), dim3(256), 0, s, logits, logits_u, cfg_scale, n, out);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }

@@ -197,3 +197,24 @@ def test_sample_onehot_is_deterministic():
     w = np.zeros(64, np.float32); w[37] = 1.0
     for k in (0, 1, 2**31, 2**32 - 1):
         assert oracle.sample(w, k) == 37
+
+
+def test_guidance_combination():
+    """z = z_u + w (z_c - z_u): exact special cases and the fp64 value within the rounding of three fp32
+    operations; applied to distributions it moves mass towards the conditional one"""
+    rng = np.random.default_rng(11)
+    zc = (rng.standard_normal(4096) * 1.3).astype(np.float32)
+    zu = (rng.standard_normal(4096) * 1.3).astype(np.float32)
+    assert np.array_equal(oracle.guide(zc, zu, 0.0), zu)                  # no guidance: unconditional
+    assert np.array_equal(oracle.guide(zc, zc, 3.0), zc)                  # identical contexts: unchanged
+    for w in (1.0, 3.0, 7.5, -0.5):
+        got = oracle.guide(zc, zu, w).astype(np.float64)
+        ref = zu.astype(np.float64) + w * (zc.astype(np.float64) - zu.astype(np.float64))
+        scale = np.abs(zu) + abs(w) * np.abs(zc.astype(np.float64) - zu) + np.abs(ref)
+        assert np.all(np.abs(got - ref) <= 2.0 ** -22 * scale)
+    # w = 1 is the conditional logits up to that rounding; w > 1 extrapolates past them
+    assert np.max(np.abs(oracle.guide(zc, zu, 1.0) - zc)) < 1e-6
+    j = int(np.argmax(zc - zu))
+    p1 = oracle.dist(oracle.guide(zc, zu, 1.0), 4096, 1.0)
+    p3 = oracle.dist(oracle.guide(zc, zu, 3.0), 4096, 1.0)
+    assert p3[j] > p1[j]
