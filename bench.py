@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--top-k", type=int, default=0, help="override the workload's top-K (1 = greedy = Jacobi decoding)")
     ap.add_argument("--init-mode", type=int, default=-1, help="override the initialiser: 0 uniform, 1 above, 2 left")
     ap.add_argument("--no-refine", action="store_true", help="ablation: no refinement of unaccepted drafts")
+    ap.add_argument("--cfg", type=float, default=None,
+                    help="classifier-free guidance weight: run a second (unconditional) context in every forward")
     ap.add_argument("--skip-ar", action="store_true", help="skip the auto-regressive (window 1) image")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reference for scaling HBM traffic counters)")
@@ -126,11 +128,19 @@ def main():
     init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id, 1 if args.no_refine else 0)
     N, L = w.n_image_tokens, w.window
     q_first = torch.empty(shape.v_s, dtype=torch.float32, device="cuda")
+    guided = args.cfg is not None
+    # the unconditional context: a short synthetic prompt of its own (a quarter of the conditional one)
+    u_ids = synth.random_tokens(max(1, (len(ids) + len(emb)) // 4), 0, shape.samp_lo or shape.vocab_total, seed=77)
+    if guided and L > 16:
+        print("bench.py: --cfg needs a window of at most 16 tokens", file=sys.stderr)
+        sys.exit(2)
 
     image = [args.seed]
 
     def new_image():
         B.sjd_prefill(m, kv, ids, emb, smp, init, q_first)
+        if guided:
+            B.sjd_prefill_uncond(m, kv, u_ids, None, args.cfg, smp, init, q_first)
         B.sjd_decode_begin(m, kv, q_first, N, L, smp, init, image[0])
         image[0] += 1
         torch.cuda.synchronize()
@@ -195,14 +205,20 @@ def main():
 
     # ---- whole images: forward passes per image, SJD vs ordinary AR (window 1) ----
     extra = {}
+
+    def generate(window):
+        if guided:
+            return B.sjd_generate_cfg(m, kv, ids, emb, u_ids, None, args.cfg, N, window, smp, init, args.seed)
+        return B.sjd_generate(m, kv, ids, emb, N, window, smp, init, args.seed)
+
     if not args.skip_images:
         t = time.perf_counter()
-        _, st = B.sjd_generate(m, kv, ids, emb, N, L, smp, init, args.seed)
+        _, st = generate(L)
         extra["sjd_forwards_per_image"] = st.steps
         extra["sjd_image_seconds"] = st.ms_decode / 1e3
         extra["sjd_image_tokens_per_s"] = N / (st.ms_decode / 1e3)
         if not args.skip_ar:
-            _, sa = B.sjd_generate(m, kv, ids, emb, N, 1, smp, init, args.seed)
+            _, sa = generate(1)
             extra["ar_forwards_per_image"] = sa.steps
             extra["ar_image_seconds"] = sa.ms_decode / 1e3
             extra["ar_image_tokens_per_s"] = N / (sa.ms_decode / 1e3)
@@ -219,6 +235,8 @@ def main():
     if cpu_steps < 0:
         cpu_steps = 2 if shape.n_params() > 2e9 else (6 if shape.n_params() > 1e8 else 40)
     cpu = None
+    if guided:
+        cpu_steps = 0          # the CPU leg times the unguided path only
     if cpu_steps > 0:
         log("timing the CPU oracle on a bounded sample ...")
         cpu = cpu_baseline(w, blob, ids, emb, args.seed, cpu_steps)
@@ -228,7 +246,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "window_L": L, "top_k": w.top_k, "temperature": w.temperature,
-                   "init_mode": w.init_mode, "no_refine": bool(args.no_refine),
+                   "init_mode": w.init_mode, "no_refine": bool(args.no_refine), "cfg_weight": args.cfg,
+                   "uncond_prompt_positions": len(u_ids) if guided else None,
                    "image_tokens_N": N, "prompt_positions": len(ids) + len(emb), "layers": shape.n_layers,
                    "d_model": shape.d_model, "sampling_vocab": shape.v_s, "hip_graph": not args.no_graph,
                    "tokens_fixed_per_step": toks / args.steps, "step_hbm_floor_ms": step_floor_ms,
