@@ -71,8 +71,8 @@ def lib():
             "orc_guide": (None, [vp, vp, f32, i64, vp]),
             "orc_dist": (None, [vp, i32, i32, f32, i32, vp]),
             "orc_sample": (i32, [vp, i32, u32]),
-            "orc_verify_probs": (i32, [vp, vp, vp, i32, i32, i32, P(Init), i32, vp, u64, u64, vp, vp]),
-            "orc_verify": (i32, [vp, vp, vp, i32, i32, i32, P(Sampler), P(Init), i32, vp, u64, u64, vp, vp]),
+            "orc_verify_probs": (i32, [vp, vp, vp, i32, i32, i32, P(Init), i32, vp, u64, u64, vp, vp, vp]),
+            "orc_verify": (i32, [vp, vp, vp, i32, i32, i32, P(Sampler), P(Init), i32, vp, u64, u64, vp, vp, vp]),
             "orc_first_window": (None, [vp, i32, i32, i32, P(Init), u64, vp, vp]),
             "orc_model_create": (vp, [P(Config), vp]),
             "orc_model_free": (None, [vp]),
@@ -152,25 +152,34 @@ def sample(w, k32):
     return int(lib().orc_sample(_p(w), w.size, int(k32)))
 
 
-def verify_probs(q, p_old, draft, lo, init, img_pos0, hist, seed, counter):
+def _ring_arg(init, ring, V):
+    """sample-above keeps [row_stride x V] recorded distributions in a caller-owned array, updated in place"""
+    if init.mode != 4:
+        return None
+    assert ring is not None and ring.dtype == np.float32 and ring.flags.c_contiguous
+    assert ring.shape == (init.row_stride, V)
+    return _p(ring)
+
+
+def verify_probs(q, p_old, draft, lo, init, img_pos0, hist, seed, counter, ring=None):
     q = _f32(q); p_old = _f32(p_old); draft = _i32(draft)
     L, V = p_old.shape
     assert q.shape == (L + 1, V)
     hist = _i32(hist if hist is not None else np.zeros(0))
     nd = np.empty(L, np.int32); pn = np.empty((L, V), np.float32)
     a = lib().orc_verify_probs(_p(q), _p(p_old), _p(draft), L, V, lo, C.byref(init), img_pos0, _p(hist), seed,
-                               counter, _p(nd), _p(pn))
+                               counter, _ring_arg(init, ring, V), _p(nd), _p(pn))
     return a, nd, pn
 
 
-def verify(logits, p_old, draft, lo, sampler, init, img_pos0, hist, seed, counter):
+def verify(logits, p_old, draft, lo, sampler, init, img_pos0, hist, seed, counter, ring=None):
     logits = _f32(logits); p_old = _f32(p_old); draft = _i32(draft)
     L, V = p_old.shape
     assert logits.shape == (L, V)
     hist = _i32(hist if hist is not None else np.zeros(0))
     nd = np.empty(L, np.int32); pn = np.empty((L, V), np.float32)
     a = lib().orc_verify(_p(logits), _p(p_old), _p(draft), L, V, lo, C.byref(sampler), C.byref(init), img_pos0,
-                         _p(hist), seed, counter, _p(nd), _p(pn))
+                         _p(hist), seed, counter, _ring_arg(init, ring, V), _p(nd), _p(pn))
     return a, nd, pn
 
 

@@ -9,6 +9,7 @@
 #include "sjd_oracle.h"
 
 #include <math.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
@@ -206,22 +207,48 @@ static int32_t forced_index(const orc_init *init, int32_t img_pos, int32_t lo)
  *                        grid row falls back to uniform.
  *   repeat-left (a)   -> copy of the current token at the previous raster position, one-hot row
  *                        (the first column takes the last token of the row before).
- * `cur(pos)` = current token at image position pos: accepted history or the window being built. */
+ *   sample-left (c)   -> a fresh draw from the distribution recorded for the nearest slot to the left
+ *                        in the window being built that is not a forced row-end slot; that row is
+ *                        the new slot's row too.  No such slot -> uniform.
+ *   sample-above (d)  -> a fresh draw from the distribution recorded for the position one grid row up:
+ *                        `ring` for an accepted position, the window's row otherwise; first grid row
+ *                        -> uniform.
+ * `cur(pos)` = current token at image position pos: accepted history or the window being built.
+ * `rows` = distributions of the window being built (slot s at rows + s*V; slots left of this one are
+ * final), `ring` = [row_stride x V] distributions of accepted positions, entry pos % row_stride.  */
 static int32_t init_slot(const orc_init *init, int32_t V, int32_t lo, int32_t img_pos, uint32_t word,
-                         const int32_t *hist, int32_t n_hist, const int32_t *window, float *row)
+                         const int32_t *hist, int32_t n_hist, const int32_t *window, const float *rows,
+                         const float *ring, float *row)
 {
     int32_t forced = forced_index(init, img_pos, lo);
-    int32_t tok;
-    int onehot;
+    int32_t tok = -1;
+    int onehot = 0;
     if (forced >= 0) {
         tok = forced; onehot = 1;
     } else if ((init->mode == 1 && img_pos - init->row_stride >= 0) || (init->mode == 2 && img_pos - 1 >= 0)) {
         int32_t src = img_pos - (init->mode == 1 ? init->row_stride : 1);
         int32_t id = src < n_hist ? hist[src] : window[src - n_hist];
         tok = id - lo; onehot = 1;
-    } else {
-        tok = (int32_t)(((uint64_t)word * (uint64_t)V) >> 32); onehot = 0;
+    } else if (init->mode == 3 || init->mode == 4) {
+        const float *src = NULL;
+        if (init->mode == 3) {
+            int32_t s = img_pos - n_hist - 1;                       /* slot to the left */
+            while (s >= 0 && forced_index(init, n_hist + s, lo) >= 0) --s;
+            if (s >= 0) src = rows + (size_t)s * V;
+        } else {
+            int32_t up = img_pos - init->row_stride;
+            if (up >= n_hist) src = rows + (size_t)(up - n_hist) * V;
+            else if (up >= 0) src = ring + (size_t)(up % init->row_stride) * V;
+        }
+        if (src) {
+            tok = orc_sample(src, V, word);
+            if (tok >= 0) {
+                memcpy(row, src, sizeof(float) * (size_t)V);
+                return tok;
+            }
+        }
     }
+    if (tok < 0) tok = (int32_t)(((uint64_t)word * (uint64_t)V) >> 32);
     if (onehot) {
         for (int32_t t = 0; t < V; ++t) row[t] = 0.0f;
         row[tok] = 1.0f;
@@ -237,8 +264,9 @@ static int32_t init_slot(const orc_init *init, int32_t V, int32_t lo, int32_t im
 /* ===================================================================================== */
 int32_t orc_verify_probs(const float *q, const float *p_old, const int32_t *draft, int32_t L, int32_t V,
                          int32_t lo, const orc_init *init, int32_t img_pos0, const int32_t *hist,
-                         uint64_t seed, uint64_t counter, int32_t *new_draft, float *p_new)
+                         uint64_t seed, uint64_t counter, float *ring, int32_t *new_draft, float *p_new)
 {
+    if (init->mode == 4 && !ring) { fprintf(stderr, "orc_verify: sample-above needs the ring\n"); abort(); }
     uint32_t w4[4];
 
     /* Eq. 1: scan left to right.  Window index 0 follows an all-accepted prefix, so its
@@ -287,6 +315,12 @@ int32_t orc_verify_probs(const float *q, const float *p_old, const int32_t *draf
         new_draft[j] = tok[a + j] + lo;
         memcpy(p_new + (size_t)j * V, q + (size_t)(a + j) * V, sizeof(float) * (size_t)V);
     }
+    /* sample-above: record the distribution of every accepted position, in position order.  Index 0
+     * carries its (exact) row from the last iteration, the others this iteration's rows. */
+    if (init->mode == 4)
+        for (int32_t i = 0; i < a; ++i)
+            memcpy(ring + (size_t)((img_pos0 + i) % init->row_stride) * V, i == 0 ? p_old : q + (size_t)i * V,
+                   sizeof(float) * (size_t)V);
     /* accepted history seen by repeat-above: hist[0..img_pos0) then draft[0..a) */
     int32_t n_hist = img_pos0 + a;
     int32_t *h2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_hist > 0 ? n_hist : 1));
@@ -294,7 +328,8 @@ int32_t orc_verify_probs(const float *q, const float *p_old, const int32_t *draf
     for (int32_t p = 0; p < a; ++p) h2[img_pos0 + p] = draft[p];
     for (int32_t j = n_model; j < L; ++j) {
         orc_draw(seed, counter, (uint32_t)(L + 1 + (j - n_model)), w4);
-        int32_t t = init_slot(init, V, lo, n_hist + j, w4[3], h2, n_hist, new_draft, p_new + (size_t)j * V);
+        int32_t t = init_slot(init, V, lo, n_hist + j, w4[3], h2, n_hist, new_draft, p_new, ring,
+                              p_new + (size_t)j * V);
         new_draft[j] = t + lo;
     }
     free(h2);
@@ -304,14 +339,16 @@ int32_t orc_verify_probs(const float *q, const float *p_old, const int32_t *draf
 
 int32_t orc_verify(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V,
                    int32_t lo, const orc_sampler *smp, const orc_init *init, int32_t img_pos0,
-                   const int32_t *hist, uint64_t seed, uint64_t counter, int32_t *new_draft, float *p_new)
+                   const int32_t *hist, uint64_t seed, uint64_t counter, float *ring, int32_t *new_draft,
+                   float *p_new)
 {
     float *q = (float *)malloc(sizeof(float) * (size_t)(L + 1) * V);
     memcpy(q, p_old, sizeof(float) * (size_t)V);
     for (int32_t i = 1; i <= L; ++i)
         orc_dist(logits + (size_t)(i - 1) * V, V, smp->top_k, smp->temperature,
                  forced_index(init, img_pos0 + i, lo), q + (size_t)i * V);
-    int32_t a = orc_verify_probs(q, p_old, draft, L, V, lo, init, img_pos0, hist, seed, counter, new_draft, p_new);
+    int32_t a = orc_verify_probs(q, p_old, draft, L, V, lo, init, img_pos0, hist, seed, counter, ring, new_draft,
+                                 p_new);
     free(q);
     return a;
 }
@@ -325,7 +362,7 @@ void orc_first_window(const float *q_first, int32_t L, int32_t V, int32_t lo, co
     memcpy(p_old, q_first, sizeof(float) * (size_t)V);
     for (int32_t j = 1; j < L; ++j) {
         orc_draw(seed, 0, (uint32_t)j, w4);
-        int32_t t = init_slot(init, V, lo, j, w4[3], NULL, 0, draft, p_old + (size_t)j * V);
+        int32_t t = init_slot(init, V, lo, j, w4[3], NULL, 0, draft, p_old, NULL, p_old + (size_t)j * V);
         draft[j] = t + lo;
     }
 }
@@ -563,6 +600,7 @@ void orc_generate_sjd(orc_forward_fn fwd, void *ctx, int32_t n_prompt, const flo
     float *p_new = (float *)malloc(sizeof(float) * (size_t)L * V);
     float *logits = (float *)malloc(sizeof(float) * (size_t)L * V);
     float *q0 = (float *)malloc(sizeof(float) * (size_t)V);
+    float *ring = init->mode == 4 ? (float *)calloc((size_t)init->row_stride * V, sizeof(float)) : NULL;
     if (stats) memset(stats, 0, sizeof(*stats));
 
     /* Step 1 for the very first window: index 0 from the prompt's exact distribution */
@@ -575,7 +613,7 @@ void orc_generate_sjd(orc_forward_fn fwd, void *ctx, int32_t n_prompt, const flo
         ++c;
         int32_t Le = L < N - n_acc ? L : N - n_acc;      /* window clipped at the image end */
         fwd(ctx, n_prompt + n_acc, draft, Le, logits);   /* Step 2 */
-        int32_t a = orc_verify(logits, p_old, draft, Le, V, lo, smp, init, n_acc, out, seed, c, next, p_new);
+        int32_t a = orc_verify(logits, p_old, draft, Le, V, lo, smp, init, n_acc, out, seed, c, ring, next, p_new);
         for (int32_t i = 0; i < a; ++i) out[n_acc + i] = draft[i];
         n_acc += a;
         memcpy(draft, next, sizeof(int32_t) * (size_t)Le);
@@ -584,7 +622,7 @@ void orc_generate_sjd(orc_forward_fn fwd, void *ctx, int32_t n_prompt, const flo
     }
     if (n_acc == N - 1) out[N - 1] = draft[0];           /* pending index 0 is exact */
 
-    free(q0); free(logits); free(p_new); free(p_old); free(next); free(draft);
+    free(ring); free(q0); free(logits); free(p_new); free(p_old); free(next); free(draft);
 }
 
 void orc_generate_ar(orc_forward_fn fwd, void *ctx, int32_t n_prompt, const float *logits_prompt, int32_t V,

@@ -48,7 +48,8 @@ typedef struct {
 } orc_sampler;
 
 typedef struct {
-    int32_t mode;        /* 0 uniform, 1 repeat the token one grid row above, 2 repeat the left token */
+    int32_t mode;        /* 0 uniform, 1 repeat the token one grid row above, 2 repeat the left token,
+                            3 sample from the left slot's distribution, 4 from the one a grid row above */
     int32_t row_stride;  /* image tokens per grid row (incl. a row-end token) */
     int32_t eol_id;      /* token id forced at the last position of a row, -1 = none */
     int32_t flags;       /* bit 0: no refinement (unaccepted drafts are replaced by new slots) */
@@ -60,15 +61,18 @@ typedef struct {
  *   p_old  [L x V]      distributions the drafts were drawn from
  *   draft  [L]          token ids (global ids, lo <= id < lo+V)
  *   hist   [img_pos0]   image tokens accepted so far (needed by repeat-above init)
+ *   ring   [row_stride x V]  mode 4 only (else may be NULL), in/out: distribution recorded for the
+ *                       accepted position p at entry p % row_stride; this call adds its accepted ones
  * Outputs: new_draft[L], p_new[L x V] in next-window layout; returns n_accepted in [1, L]. */
 int32_t orc_verify_probs(const float *q, const float *p_old, const int32_t *draft, int32_t L, int32_t V,
                          int32_t lo, const orc_init *init, int32_t img_pos0, const int32_t *hist,
-                         uint64_t seed, uint64_t counter, int32_t *new_draft, float *p_new);
+                         uint64_t seed, uint64_t counter, float *ring, int32_t *new_draft, float *p_new);
 
 /* Same from logits: logits[L x V], row s belongs to window index s+1. */
 int32_t orc_verify(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V,
                    int32_t lo, const orc_sampler *smp, const orc_init *init, int32_t img_pos0,
-                   const int32_t *hist, uint64_t seed, uint64_t counter, int32_t *new_draft, float *p_new);
+                   const int32_t *hist, uint64_t seed, uint64_t counter, float *ring, int32_t *new_draft,
+                   float *p_new);
 
 /* Initial window (step counter 0): slot 0 ~ q_first, slots 1.. by the init strategy. */
 void orc_first_window(const float *q_first, int32_t L, int32_t V, int32_t lo, const orc_init *init,

@@ -180,6 +180,88 @@ def test_repeat_left_init_and_no_refinement():
     assert np.array_equal(pn1[4], u)                     # with refinement only a-1 = 1 slot is new
 
 
+def test_sample_left_and_sample_above_initialisers():
+    """strategies (c) and (d): a new slot is a fresh draw (its own random word, the same fixed-point
+    sampler) from a distribution already on record, and carries that row: (c) the nearest slot to the
+    left that is not a forced row end, (d) the position one grid row up, from the ring of accepted
+    positions or from the window itself"""
+    V, lo, L = 10, 20, 5
+    rng = np.random.default_rng(8)
+    p_old = np.stack([_rand_dist(rng, V) for _ in range(L)])
+    q = np.concatenate([p_old, _rand_dist(rng, V)[None]])
+    draft = np.array([lo + int(np.argmax(p_old[i])) for i in range(L)])
+    hist = np.array([21, 22], np.int32)
+    seed, ctr = 9, 2
+
+    def word(j, n_model):                                # init word of next-window slot j
+        return oracle.draw(seed, ctr, L + 1 + (j - n_model))[3]
+
+    # (c), everything accepted: the only model slot is the bonus index, all new slots draw from its row
+    a, nd, pn = oracle.verify_probs(q, p_old, draft, lo, oracle.Init(3, 4, -1), 2, hist, seed, ctr)
+    assert a == L and np.array_equal(pn[0], q[L])
+    for j in range(1, L):
+        assert np.array_equal(pn[j], q[L])
+        assert nd[j] == lo + oracle.sample(q[L], word(j, 1))
+    assert len({int(t) for t in nd[1:]}) > 1             # independent draws, not copies
+    # (c) with a forced row end inside the run of new slots: next window = positions 7..11, stride 5
+    # forces position 9 (slot 2); slots 3 and 4 look past it
+    a, nd, pn = oracle.verify_probs(q, p_old, draft, lo, oracle.Init(3, 5, 29), 2, hist, seed, ctr)
+    onehot = np.zeros(V, np.float32); onehot[29 - lo] = 1
+    assert nd[2] == 29 and np.array_equal(pn[2], onehot)
+    for j in (1, 3, 4):
+        assert np.array_equal(pn[j], q[L]) and nd[j] == lo + oracle.sample(q[L], word(j, 1))
+    # (c) when every slot to the left is a forced row end (stride 4 forces position 7 = slot 0): uniform,
+    # and a draw from a uniform row is the uniform initialiser's token
+    a, nd, pn = oracle.verify_probs(q, p_old, draft, lo, oracle.Init(3, 4, 29), 2, hist, seed, ctr)
+    u = np.full(V, np.float32(1) / np.float32(V), np.float32)
+    for j in (1, 2, 3):
+        assert np.array_equal(pn[j], u) and nd[j] == lo + ((int(word(j, 1)) * V) >> 32)
+    assert nd[4] == 29 and np.array_equal(pn[4], onehot)
+    # (c) after a rejection at index 2: model slots are indices 2..L, one new slot at the end, which
+    # draws from the bonus row (its left neighbour)
+    q2 = q.copy(); q2[2] = 0; q2[2][(int(np.argmax(p_old[2])) + 1) % V] = 1.0
+    p2 = p_old.copy(); p2[2] = 0; p2[2][int(np.argmax(p_old[2]))] = 1.0
+    a, nd, pn = oracle.verify_probs(q2, p2, draft, lo, oracle.Init(3, 4, -1), 2, hist, seed, ctr)
+    assert a == 2
+    assert np.array_equal(pn[3], q2[5]) and np.array_equal(pn[4], q2[5])
+    assert nd[4] == lo + oracle.sample(q2[5], word(4, 4))
+
+    # (d), stride 3, window at image positions 2..6, all accepted -> ring holds positions 2..6 (the last
+    # writer of an entry wins), next window = positions 7..11
+    stride = 3
+    ring = np.full((stride, V), -1.0, np.float32)
+    ring[1] = _rand_dist(rng, V)                         # position 1, accepted earlier (entry 1 % 3)
+    ring0 = ring.copy()
+    a, nd, pn = oracle.verify_probs(q, p_old, draft, lo, oracle.Init(4, stride, -1), 2, hist, seed, ctr, ring=ring)
+    assert a == L
+    rec = {2: p_old[0], 3: q[1], 4: q[2], 5: q[3], 6: q[4]}     # index 0 keeps the row it carried
+    for pos in (4, 5, 6):
+        assert np.array_equal(ring[pos % stride], rec[pos])
+    # slot j is position 7 + j; above = 4 + j: positions 5, 6 are on the ring, 7 (slot 0) and 8 (slot 1,
+    # itself new) are in the window
+    assert np.array_equal(pn[1], rec[5]) and nd[1] == lo + oracle.sample(rec[5], word(1, 1))
+    assert np.array_equal(pn[2], rec[6]) and nd[2] == lo + oracle.sample(rec[6], word(2, 1))
+    assert np.array_equal(pn[3], q[L]) and nd[3] == lo + oracle.sample(q[L], word(3, 1))
+    assert np.array_equal(pn[4], pn[1]) and nd[4] == lo + oracle.sample(rec[5], word(4, 1))
+    # only one accepted (rejection at index 1): position 2 goes on the ring, nothing else changes
+    q3 = q.copy(); q3[1] = 0; q3[1][(int(np.argmax(p_old[1])) + 1) % V] = 1.0
+    p3 = p_old.copy(); p3[1] = 0; p3[1][int(np.argmax(p_old[1]))] = 1.0
+    ring = ring0.copy()
+    a, nd, pn = oracle.verify_probs(q3, p3, draft, lo, oracle.Init(4, stride, -1), 2, hist, seed, ctr, ring=ring)
+    assert a == 1
+    assert np.array_equal(ring[2], p3[0]) and np.array_equal(ring[1], ring0[1]) and np.array_equal(ring[0], ring0[0])
+    # first window: the first grid row has nothing above (uniform); later slots draw from the row above
+    qf = _rand_dist(rng, V)
+    d0, p0 = oracle.first_window(qf, 5, lo, oracle.Init(4, 3, -1), 4)
+    u = np.full(V, np.float32(1) / np.float32(V), np.float32)
+    assert np.array_equal(p0[1], u) and np.array_equal(p0[2], u)
+    assert np.array_equal(p0[3], qf) and d0[3] == lo + oracle.sample(qf, oracle.draw(4, 0, 3)[3])
+    assert np.array_equal(p0[4], u)
+    d1, p1 = oracle.first_window(qf, 4, lo, oracle.Init(3, 3, -1), 4)
+    for j in (1, 2, 3):
+        assert np.array_equal(p1[j], qf) and d1[j] == lo + oracle.sample(qf, oracle.draw(4, 0, j)[3])
+
+
 # ---------------------------------------------------------------- whole algorithm
 def _tiny():
     shape = synth.ModelShape(n_layers=2, d_model=32, n_heads=2, d_ffn=64, vocab_total=96, samp_lo=32, samp_hi=96,
@@ -211,7 +293,7 @@ def _greedy_ar(om, prompt, N):
     return np.array(seq[len(prompt):], np.int32)
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 3, 4])
 @pytest.mark.parametrize("L", [2, 5, 16])
 def test_greedy_sjd_equals_greedy_autoregressive(L, mode):
     shape, blob = _tiny()
@@ -298,7 +380,12 @@ def _exact_joint(table, V, depth, smp, init):
 @pytest.mark.parametrize("L,mode,stride,eol,flags", [(2, 0, 2, -1, 0), (3, 0, 2, -1, 0), (4, 0, 2, -1, 0), (2, 1, 2, -1, 0),
                                                      (3, 1, 1, -1, 0), (4, 1, 2, -1, 0), (4, 0, 2, 5, 0), (3, 1, 2, 5, 0),
                                                      (3, 2, 2, -1, 0), (4, 2, 2, 5, 0),     # repeat-left
-                                                     (4, 0, 2, -1, 1), (3, 2, 2, -1, 1)])   # no refinement
+                                                     (4, 0, 2, -1, 1), (3, 2, 2, -1, 1),    # no refinement
+                                                     (2, 3, 2, -1, 0), (3, 3, 2, -1, 0), (4, 3, 2, 5, 0),   # sample-left
+                                                     (3, 3, 2, -1, 1),
+                                                     (2, 4, 2, -1, 0), (2, 4, 1, -1, 0), (3, 4, 2, -1, 0),  # sample-above
+                                                     (4, 4, 1, -1, 0), (4, 4, 2, 5, 0), (3, 4, 3, -1, 0),
+                                                     (2, 4, 2, -1, 1)])
 def test_sjd_output_distribution_equals_autoregressive(L, mode, stride, eol, flags):
     V, depth, runs = 8, 4, 1_000_000
     table = _toy_table(V, depth, seed=100 + L + 10 * mode)
