@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--skip-images", action="store_true", help="skip the whole-image SJD / AR runs")
     ap.add_argument("--window", type=int, default=0, help="override the workload's window size L (1..32)")
     ap.add_argument("--top-k", type=int, default=0, help="override the workload's top-K (1 = greedy = Jacobi decoding)")
-    ap.add_argument("--init-mode", type=int, default=-1, help="override the initialiser: 0 uniform, 1 above, 2 left")
+    ap.add_argument("--init-mode", type=int, default=-1, help="override the initialiser: 0 uniform, 1 repeat above, 2 repeat left, 3 sample left, 4 sample above")
     ap.add_argument("--no-refine", action="store_true", help="ablation: no refinement of unaccepted drafts")
     ap.add_argument("--cfg", type=float, default=None,
                     help="classifier-free guidance weight: run a second (unconditional) context in every forward")

@@ -59,7 +59,12 @@ typedef struct {
 
 /* Initialisation of new window slots (Sec. 4.2).  mode 0: uniform over the sampling ids;
  * mode 1: strategy (b), repeat the token one grid row above (uniform in the first grid row);
- * mode 2: strategy (a), repeat the token at the previous raster position.
+ * mode 2: strategy (a), repeat the token at the previous raster position;
+ * mode 3: strategy (c), a fresh draw from the distribution on record for the nearest slot to the left
+ *         that is not a forced row end (a run of new slots all draw from the last model row);
+ * mode 4: strategy (d), a fresh draw from the distribution on record for the position one grid row
+ *         up (the cache handle keeps the distributions of the last row_stride accepted positions;
+ *         uniform in the first grid row).  The row drawn from is the slot's row in Eq. 1.
  * eol_id >= 0 forces that id at the last position of every grid row.
  * flags bit 0 (SJD_INIT_NO_REFINE): the ablation without refinement (App. "acceleration originates
  * from the refinement"): only the resampled position survives an iteration, every later slot of the
@@ -189,17 +194,19 @@ int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *ou
 int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream);
 
 /* Step 3 + Step 4 alone, from logits (row s belongs to window index s+1).  hist: dev ids of the
- * image tokens fixed so far [img_pos0] (may be NULL when init->mode == 0 or img_pos0 == 0).
- * V_s <= SJD_MAX_SAMP_VOCAB.                                                                   */
+ * image tokens fixed so far [img_pos0] (may be NULL when init->mode is 0 or 3, or img_pos0 == 0).
+ * ring: dev [row_stride x V_s], in/out, init->mode == 4 only (else may be NULL): entry p % row_stride
+ * holds the distribution on record for accepted image position p; the call adds the positions it
+ * accepts.  V_s <= SJD_MAX_SAMP_VOCAB.                                                          */
 int sjd_verify(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
                int32_t samp_lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
-               const int32_t *hist, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
+               const int32_t *hist, float *ring, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
                int32_t *new_draft, float *p_new, void *stream);
 
 /* Same from precomputed distributions q dev [(L+1) x V_s] (row 0 ignored, row L = the bonus
  * distribution of the position just past the window).                                          */
 int sjd_verify_probs(const float *q, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
-                     int32_t samp_lo, const sjd_init *init, int32_t img_pos0, const int32_t *hist,
+                     int32_t samp_lo, const sjd_init *init, int32_t img_pos0, const int32_t *hist, float *ring,
                      uint64_t philox_seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
                      float *p_new, void *stream);
 

@@ -82,9 +82,9 @@ _SIG = {
     "sjd_generate": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _u64, _vp,
                                _P(sjd_stats)]),
     "sjd_forward_logits": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _vp]),
-    "sjd_verify": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _vp, _u64, _u64,
+    "sjd_verify": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _vp, _vp, _u64, _u64,
                              _vp, _vp, _vp, _vp]),
-    "sjd_verify_probs": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_init), _i32, _vp, _u64, _u64, _vp, _vp,
+    "sjd_verify_probs": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_init), _i32, _vp, _vp, _u64, _u64, _vp, _vp,
                                    _vp, _vp]),
     "sjd_dist": (C.c_int, [_vp, _i32, _i32, _P(sjd_sampler), _vp, _vp, _vp]),
     "sjd_gemm_test": (C.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp]),
@@ -220,16 +220,16 @@ def sjd_forward_logits(m, kv, tokens, L, logits, stream=None):
 
 
 def sjd_verify(logits, p_old, draft, L, V_s, samp_lo, smp, init, img_pos0, hist, seed, counter, n_accepted, new_draft,
-               p_new, stream=None):
+               p_new, stream=None, ring=None):
     _check(_lib.sjd_verify(_dev(logits), _dev(p_old), _dev(draft), L, V_s, samp_lo, C.byref(smp), C.byref(init),
-                           img_pos0, _dev(hist), seed, counter, _dev(n_accepted), _dev(new_draft), _dev(p_new),
-                           _stream(stream)))
+                           img_pos0, _dev(hist), _dev(ring), seed, counter, _dev(n_accepted), _dev(new_draft),
+                           _dev(p_new), _stream(stream)))
 
 
 def sjd_verify_probs(q, p_old, draft, L, V_s, samp_lo, init, img_pos0, hist, seed, counter, n_accepted, new_draft,
-                     p_new, stream=None):
+                     p_new, stream=None, ring=None):
     _check(_lib.sjd_verify_probs(_dev(q), _dev(p_old), _dev(draft), L, V_s, samp_lo, C.byref(init), img_pos0,
-                                 _dev(hist), seed, counter, _dev(n_accepted), _dev(new_draft), _dev(p_new),
+                                 _dev(hist), _dev(ring), seed, counter, _dev(n_accepted), _dev(new_draft), _dev(p_new),
                                  _stream(stream)))
 
 

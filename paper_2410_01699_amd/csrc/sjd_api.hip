@@ -176,7 +176,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
 extern "C" void sjd_kv_free(sjd_kv *kv)
 {
     if (!kv) return;
-    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
+    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->ring, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
                     kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
                     kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
     for (void *p : ptrs) if (p) (void)hipFree(p);
@@ -595,7 +595,7 @@ extern "C" int sjd_first_window(const sjd_model *m, const float *q_first, int32_
                                 uint64_t philox_seed, int32_t *draft, float *p_old, void *stream)
 {
     if (!m || !q_first || !init || !draft || !p_old || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
-    if (init->mode < 0 || init->mode > 2 || (init->mode == 1 && init->row_stride < 1)) return SJD_EINVAL;
+    if (init->mode < 0 || init->mode > 4 || ((init->mode == 1 || init->mode == 4) && init->row_stride < 1)) return SJD_EINVAL;
     return sjd_launch_first_window(q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, draft, p_old, (hipStream_t)stream);
 }
 
@@ -603,8 +603,8 @@ static int check_sampling(const sjd_sampler *smp, const sjd_init *init, int lo, 
 {
     if (!smp || !init) return SJD_EINVAL;
     if (smp->top_k < 1 || !(smp->temperature >= 0.f)) return SJD_EINVAL;
-    if (init->mode < 0 || init->mode > 2 || (init->flags & ~SJD_INIT_NO_REFINE)) return SJD_EINVAL;
-    if (init->mode == 1 && init->row_stride < 1) return SJD_EINVAL;
+    if (init->mode < 0 || init->mode > 4 || (init->flags & ~SJD_INIT_NO_REFINE)) return SJD_EINVAL;
+    if ((init->mode == 1 || init->mode == 4) && init->row_stride < 1) return SJD_EINVAL;
     if (init->eol_id >= 0 && (init->eol_id < lo || init->eol_id >= hi || init->row_stride < 1)) return SJD_EINVAL;
     return SJD_OK;
 }
@@ -612,6 +612,17 @@ static int check_sampling(const sjd_sampler *smp, const sjd_init *init, int lo, 
 __global__ void set_step_kernel(SjdState *st, int img_pos0, uint64_t counter, int L)
 {
     st->img_pos0 = img_pos0; st->counter = counter; st->L_eff = L; st->n_image = 0; st->done = 0;
+}
+
+// initialiser (d) keeps the distributions of the last row_stride accepted image positions
+static int ensure_ring(sjd_kv *kv, const sjd_init *init)
+{
+    if (init->mode != 4 || kv->ring_rows >= init->row_stride) return SJD_OK;
+    if (kv->ring) { HIP_TRY(hipDeviceSynchronize()); (void)hipFree(kv->ring); kv->ring = nullptr; kv->ring_rows = 0; }
+    drop_graph(kv);                      // a captured iteration holds the old address
+    SJD_TRY(dev_alloc((void **)&kv->ring, (size_t)init->row_stride * kv->m->V_s * 4));
+    kv->ring_rows = init->row_stride;
+    return SJD_OK;
 }
 
 // forward + verification of one window, everything stream-ordered, state device-resident
@@ -625,7 +636,7 @@ static int enqueue_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
     if (kv->cfg_on) { v.logits_u = kv->logits + (size_t)SJD_STREAM_ROWS * m->V_s; v.cfg_scale = kv->cfg_scale; }
     v.logits = kv->logits; v.p_old = p_old; v.draft = draft; v.L = L; v.V = m->V_s; v.lo = m->cfg.samp_lo;
     v.smp = *smp; v.init = *init; v.seed = seed; v.state = kv->state; v.kv_tokens = kv->tokens;
-    v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new;
+    v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new; v.ring = kv->ring;
     v.q = kv->q; v.tok_smp = kv->tok_smp; v.tok_res = kv->tok_res; v.acc_flag = kv->acc_flag;
     v.draft_snap = kv->draft_snap; v.snap = kv->snap;
     PROF(kv, SJD_PROF_VERIFY, 3.0 * L * m->V_s * 4, sjd_launch_verify(&v, s));
@@ -641,6 +652,7 @@ extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
     if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
     SJD_TRY(check_room(kv, L));
+    SJD_TRY(ensure_ring(kv, init));
     hipStream_t s = (hipStream_t)stream;
     kv->dec_active = 0;
     SJD_LAUNCH(set_step_kernel, dim3(1), dim3(1), 0, s, kv->state, img_pos0, counter, L);
@@ -665,6 +677,7 @@ extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, 
     if (!m || !kv || kv->m != m || !q_first || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
     if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
+    SJD_TRY(ensure_ring(kv, init));
     if (kv->n_upper + N + L > m->cfg.max_seq || (kv->cfg_on && kv->n_upper_u + N + L > m->cfg.max_seq)) {
         SjdState st;
         SJD_TRY(state_read(kv, &st));
@@ -861,14 +874,15 @@ struct Scratch {
 
 static int verify_common(const float *logits, const float *q_in, const float *p_old, const int32_t *draft, int32_t L,
                          int32_t V, int32_t lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
-                         const int32_t *hist, uint64_t seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
-                         float *p_new, hipStream_t s)
+                         const int32_t *hist, float *ring, uint64_t seed, uint64_t counter, int32_t *n_accepted,
+                         int32_t *new_draft, float *p_new, hipStream_t s)
 {
     if (!p_old || !draft || !n_accepted || !new_draft || !p_new || !init) return SJD_EINVAL;
+    if (init->mode == 4 && !ring) return SJD_EINVAL;
     if (L < 1 || L > SJD_MAX_WINDOW || V < 1 || V > SJD_MAX_SAMP_VOCAB || img_pos0 < 0) return SJD_EINVAL;
     sjd_sampler sm = smp ? *smp : sjd_sampler{1, 1.0f};
     SJD_TRY(check_sampling(&sm, init, lo, lo + V));
-    if (init->mode != 0 && img_pos0 > 0 && !hist) return SJD_EINVAL;
+    if ((init->mode == 1 || init->mode == 2) && img_pos0 > 0 && !hist) return SJD_EINVAL;
     Scratch sc;
     SJD_TRY(dev_alloc((void **)&sc.q, (size_t)(L + 1) * V * 4));
     SJD_TRY(dev_alloc((void **)&sc.ints, (size_t)(L + 1) * 4 * 4));
@@ -876,7 +890,7 @@ static int verify_common(const float *logits, const float *q_in, const float *p_
     SjdVerifyArgs v;
     memset(&v, 0, sizeof(v));
     v.logits = logits; v.q_in = q_in; v.p_old = p_old; v.draft = draft; v.L = L; v.V = V; v.lo = lo;
-    v.smp = sm; v.init = *init; v.hist = hist; v.seed = seed; v.img_pos0 = img_pos0; v.counter = counter;
+    v.smp = sm; v.init = *init; v.hist = hist; v.ring = ring; v.seed = seed; v.img_pos0 = img_pos0; v.counter = counter;
     v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new; v.q = sc.q;
     v.tok_smp = sc.ints; v.tok_res = sc.ints + (L + 1); v.acc_flag = sc.ints + 2 * (L + 1);
     v.draft_snap = sc.ints + 3 * (L + 1); v.snap = sc.snap;
@@ -887,21 +901,21 @@ static int verify_common(const float *logits, const float *q_in, const float *p_
 
 extern "C" int sjd_verify(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
                           int32_t samp_lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
-                          const int32_t *hist, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
-                          int32_t *new_draft, float *p_new, void *stream)
+                          const int32_t *hist, float *ring, uint64_t philox_seed, uint64_t counter,
+                          int32_t *n_accepted, int32_t *new_draft, float *p_new, void *stream)
 {
     if (!logits || !smp) return SJD_EINVAL;
-    return verify_common(logits, nullptr, p_old, draft, L, V_s, samp_lo, smp, init, img_pos0, hist, philox_seed, counter,
+    return verify_common(logits, nullptr, p_old, draft, L, V_s, samp_lo, smp, init, img_pos0, hist, ring, philox_seed, counter,
                          n_accepted, new_draft, p_new, (hipStream_t)stream);
 }
 
 extern "C" int sjd_verify_probs(const float *q, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
                                 int32_t samp_lo, const sjd_init *init, int32_t img_pos0, const int32_t *hist,
-                                uint64_t philox_seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
-                                float *p_new, void *stream)
+                                float *ring, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
+                                int32_t *new_draft, float *p_new, void *stream)
 {
     if (!q) return SJD_EINVAL;
-    return verify_common(nullptr, q, p_old, draft, L, V_s, samp_lo, nullptr, init, img_pos0, hist, philox_seed, counter,
+    return verify_common(nullptr, q, p_old, draft, L, V_s, samp_lo, nullptr, init, img_pos0, hist, ring, philox_seed, counter,
                          n_accepted, new_draft, p_new, (hipStream_t)stream);
 }
 

@@ -203,6 +203,8 @@ struct sjd_kv {
     int32_t use_graph;
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
+    float *ring;          // [ring_rows][V_s] distributions of accepted image positions (initialiser (d))
+    int32_t ring_rows;
     int32_t graph_cfg_on;   // stream mode and guidance weight the captured iteration was recorded with
     float graph_cfg_scale;
     void *prof;           // SjdProfiler* while sjd_profile_steps runs, else NULL
@@ -242,6 +244,7 @@ struct SjdVerifyArgs {
     float cfg_scale;
     const float *q_in;       // [(L+1)][V] precomputed distributions or NULL
     const float *p_old;      // [L][V]
+    float *ring;             // [row_stride][V] distributions of accepted positions (init mode 4), else NULL
     const int32_t *draft;    // [L]
     int32_t L, V, lo;
     sjd_sampler smp;

@@ -518,6 +518,8 @@ struct FinalArgs {
     SjdState *state;              // advanced by workgroup 0 when non-NULL
     int32_t *kv_tokens;           // cache-position-indexed ids (with state), or NULL
     const float *q;
+    const float *p_old;           // row 0 = the distribution index 0 carried (may alias p_new)
+    float *ring;                  // initialiser (d): [row_stride][V] distributions of accepted positions
     const int32_t *tok_smp, *tok_res, *acc_flag, *draft_snap;
     const StepSnap *snap;
     int32_t *n_accepted, *new_draft;
@@ -545,6 +547,16 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
     const int back = a.init.mode == 1 ? a.init.row_stride : a.init.mode == 2 ? 1 : 0;   // repeat-above / -left
     const int32_t *hist = a.hist;
     if (a.kv_tokens) hist = a.kv_tokens + (sn.n - sn.img_pos0);
+
+    // initialiser (d): put the distribution of accepted index j on record (entry position % row_stride;
+    // of several accepted positions sharing an entry the last one writes).  Index 0 records the row it
+    // carried, read here before the next window's row 0 may overwrite it (p_new may be p_old).
+    if (a.init.mode == 4 && j < acc && j + a.init.row_stride >= acc) {
+        const float *src = j == 0 ? a.p_old : a.q + (size_t)j * V;
+        float *dst = a.ring + (size_t)((sn.img_pos0 + j) % a.init.row_stride) * V;
+        for (int t = t_beg + threadIdx.x; t < t_end; t += 256) dst[t] = src[t];
+        __syncthreads();
+    }
 
     if (j < L) {
         auto model_tok = [&](int slot) {   // token of next-window slot < n_model (local index)
@@ -609,6 +621,68 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
     }
 }
 
+// Initialisers (c) and (d) of Sec. 4.2, run after the finalize kernel (which has given every new slot
+// the uniform initialisation): a new slot that finds a recorded distribution becomes a fresh draw from
+// it and carries that row.
+//   (c) the nearest slot to the left in the next window that is neither a forced row end nor itself
+//       new (a run of new slots all draw from the last model row, each with its own random word);
+//   (d) the position one grid row up: accepted (before or in this iteration) -> ring[pos % row_stride],
+//       which the finalize kernel has brought up to date; in the next window -> that slot's row, or,
+//       if that slot is new as well, whatever it resolves to.
+// No source (first grid row, only forced slots to the left) leaves the uniform initialisation.
+struct TailArgs {
+    int32_t V, lo;
+    sjd_init init;
+    uint64_t seed;
+    const float *q;
+    const float *ring;
+    const int32_t *acc_flag;
+    const StepSnap *snap;
+    int32_t *new_draft;
+    float *p_new;
+};
+
+template <int EPT>
+__global__ __launch_bounds__(DIST_THREADS) void sjd_tail_kernel(TailArgs a)
+{
+    __shared__ DistShared sh;
+    const StepSnap sn = *a.snap;
+    if (!sn.active) return;
+    const int L = sn.L_eff, V = a.V, lo = a.lo, j = blockIdx.x;
+    if (j >= L) return;
+    const int lane_ = threadIdx.x & 63;
+    const int flag_ = lane_ == 0 ? 1 : (lane_ < L ? a.acc_flag[lane_] : 0);
+    const unsigned long long run_ = __ballot(flag_ != 0);
+    const int acc = __ffsll((long long)~run_) - 1;
+    const int n_model = (a.init.flags & SJD_INIT_NO_REFINE) ? 1 : L - acc + 1;
+    const int n_hist = sn.img_pos0 + acc;
+    const int stride = a.init.row_stride;
+    if (j < n_model) return;
+    const int pos = n_hist + j;
+    if (forced_index(a.init, pos, lo) >= 0) return;
+    const float *src = nullptr;
+    if (a.init.mode == 3) {
+        for (int p = pos - 1; p >= n_hist; --p) {
+            if (forced_index(a.init, p, lo) >= 0) continue;
+            const int slot = p - n_hist;
+            if (slot < n_model) { src = a.q + (size_t)(acc + slot) * V; break; }
+        }
+    } else {
+        for (int p = pos - stride; p >= 0; p -= stride) {
+            if (p < n_hist) { src = a.ring + (size_t)(p % stride) * V; break; }
+            const int slot = p - n_hist;
+            if (slot < n_model) { src = a.q + (size_t)(acc + slot) * V; break; }
+        }
+    }
+    if (!src) return;
+    const U4 rnd = philox_draw(a.seed, sn.counter, (uint32_t)(L + 1 + (j - n_model)));
+    const int tok = block_sample<EPT>([&](int, int t) { return src[t]; }, V, rnd.w[3], &sh);
+    if (tok < 0) return;
+    if (threadIdx.x == 0) a.new_draft[j] = tok + lo;
+    float *dst = a.p_new + (size_t)j * V;
+    for (int t = threadIdx.x; t < V; t += DIST_THREADS) dst[t] = src[t];
+}
+
 template <int EPT>
 __global__ __launch_bounds__(DIST_THREADS) void sjd_dist_kernel(const float *logits, const float *logits_u, float cfg_scale,
                                                                 int V, sjd_sampler smp, const int32_t *forced, float *q)
@@ -632,7 +706,24 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_first_window_kernel(const fl
     __shared__ DistShared sh;
     __shared__ int tok0;
     const int j = blockIdx.x;
-    if (j == 0 || init.mode != 0) {
+    if (j > 0 && (init.mode == 3 || init.mode == 4) && forced_index(init, j, lo) < 0) {
+        // sampled initialisers: the only recorded distribution in the first window is slot 0's
+        // (every other slot is new and looked through): (c) reaches it unless it is a forced row end,
+        // (d) when the chain of positions above ends at 0
+        const bool from_first = init.mode == 3 ? forced_index(init, 0, lo) < 0
+                                               : (init.row_stride > 0 && j % init.row_stride == 0);
+        if (from_first) {
+            const U4 rnd = philox_draw(seed, 0, (uint32_t)j);
+            const int tok = block_sample<EPT>([&](int, int t) { return q_first[t]; }, V, rnd.w[3], &sh);
+            if (tok >= 0) {
+                if (threadIdx.x == 0) draft[j] = tok + lo;
+                float *dst = p_old + (size_t)j * V;
+                for (int t = threadIdx.x; t < V; t += DIST_THREADS) dst[t] = q_first[t];
+                return;
+            }
+        }
+    }
+    if (j == 0 || init.mode == 1 || init.mode == 2) {
         // slot 0's token (every workgroup that may copy from it recomputes it: same inputs, same bits)
         float *qb = reinterpret_cast<float *>(buf);
         for (int t = threadIdx.x; t < V; t += DIST_THREADS) qb[t] = q_first[t];
@@ -723,8 +814,18 @@ int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
     f.state = v->state; f.kv_tokens = v->kv_tokens; f.q = v->q; f.tok_smp = v->tok_smp; f.tok_res = v->tok_res;
     f.acc_flag = v->acc_flag; f.draft_snap = v->draft_snap; f.snap = reinterpret_cast<const StepSnap *>(v->snap);
     f.n_accepted = v->n_accepted; f.new_draft = v->new_draft; f.p_new = v->p_new;
+    if (v->init.mode == 4 && (!v->ring || v->init.row_stride < 1)) return SJD_EINVAL;
+    f.p_old = v->p_old; f.ring = v->ring;
     SJD_LAUNCH(sjd_finalize_kernel, dim3(v->L, FIN_PARTS), dim3(256), 0, s, f);
     HIP_TRY(hipGetLastError());
+    if (v->init.mode == 3 || v->init.mode == 4) {
+        TailArgs t;
+        t.V = v->V; t.lo = v->lo; t.init = v->init; t.seed = v->seed; t.q = v->q; t.ring = v->ring;
+        t.acc_flag = v->acc_flag; t.snap = reinterpret_cast<const StepSnap *>(v->snap); t.new_draft = v->new_draft;
+        t.p_new = v->p_new;
+        EPT_SWITCH(ept_class(v->V), SJD_LAUNCH(sjd_tail_kernel<EPT>, dim3(v->L), dim3(DIST_THREADS), 0, s, t))
+        HIP_TRY(hipGetLastError());
+    }
     return SJD_OK;
 }
 

@@ -197,7 +197,8 @@ def test_step_matches_oracle_given_gpu_logits(B):
         g.close()
 
 
-@pytest.mark.parametrize("L,mode,flags", [(8, 0, 0), (1, 0, 0), (4, 1, 0), (16, 0, 0), (8, 2, 0), (8, 0, 1), (4, 2, 1)])
+@pytest.mark.parametrize("L,mode,flags", [(8, 0, 0), (1, 0, 0), (4, 1, 0), (16, 0, 0), (8, 2, 0), (8, 0, 1), (4, 2, 1),
+                                          (8, 3, 0), (8, 4, 0), (16, 4, 0), (5, 4, 1), (16, 3, 1)])
 def test_generate_tiny_fp32_token_identity(B, L, mode, flags):
     w = synth.WORKLOADS["tiny"]
     blob = synth.make_weights(w.shape, seed=0)
@@ -367,6 +368,30 @@ def test_graph_replay_equals_eager_and_is_deterministic(B):
             assert guard < 200
         toks, st = B.sjd_decode_result(g.kv, 200)
         assert np.array_equal(toks, ref[1][0]) and st.steps == ref[1][1]
+    finally:
+        g.close()
+
+
+def test_sampled_initialisers_graph_replay(B):
+    """initialisers (c) and (d) inside the captured iteration (the ring of recorded distributions lives
+    on the handle): replay == kernel-by-kernel, and switching initialisers re-captures"""
+    shape = synth.ModelShape(2, 256, 4, 512, 2048, 1024, 2048, 300, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=8)
+    g = Gpu(B, shape, blob)
+    try:
+        prompt = synth.random_tokens(20, 0, 1024, seed=1)
+        smp = B.sjd_sampler(300, 1.0)
+        res = {}
+        for use_graph in (True, False):
+            B.sjd_kv_use_graph(g.kv, use_graph)
+            for mode, stride in ((4, 9), (3, 9), (4, 20), (0, 9)):
+                _say(f"graph={use_graph} init mode={mode} stride={stride}")
+                toks, st = B.sjd_generate(g.m, g.kv, prompt, None, 9 * 20, 16, smp, B.sjd_init(mode, stride, 2047), 3)
+                res[(use_graph, mode, stride)] = (toks, st.steps)
+                assert np.all(toks[stride - 1::stride] == 2047)
+        for mode, stride in ((4, 9), (3, 9), (4, 20), (0, 9)):
+            a, b = res[(True, mode, stride)], res[(False, mode, stride)]
+            assert np.array_equal(a[0], b[0]) and a[1] == b[1], (mode, stride)
     finally:
         g.close()
 

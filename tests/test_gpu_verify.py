@@ -79,15 +79,31 @@ def _rand_rows(rng, rows, V, support):
     return out
 
 
-def _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, seed, counter):
+def _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, seed, counter, ring=None, alias=False):
+    """ring (numpy [row_stride, V], sample-above only) is updated in place like the oracle's; alias: the
+    next window is written over the current one, as the device-resident loop does"""
     L, V = p_old.shape
+    dring = None if ring is None else _dev(ring)
+    if alias:
+        na = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nd = _dev(np.asarray(draft, np.int32)); pn = _dev(p_old)
+        h = None if hist is None or len(hist) == 0 else _dev(np.asarray(hist, np.int32))
+        B.sjd_verify_probs(_dev(q), pn, nd, L, V, lo, B.sjd_init(init.mode, init.row_stride, init.eol_id, init.flags),
+                           img_pos0, h, seed, counter, na, nd, pn, ring=dring)
+        torch.cuda.synchronize()
+        if ring is not None:
+            ring[...] = dring.cpu().numpy()
+        return int(na.item()), nd.cpu().numpy(), pn.cpu().numpy()
     na = torch.zeros(1, dtype=torch.int32, device="cuda")
     nd = torch.zeros(L, dtype=torch.int32, device="cuda")
     pn = torch.zeros((L, V), dtype=torch.float32, device="cuda")
     h = None if hist is None or len(hist) == 0 else _dev(np.asarray(hist, np.int32))
     B.sjd_verify_probs(_dev(q), _dev(p_old), _dev(np.asarray(draft, np.int32)), L, V, lo,
-                       B.sjd_init(init.mode, init.row_stride, init.eol_id, init.flags), img_pos0, h, seed, counter, na, nd, pn)
+                       B.sjd_init(init.mode, init.row_stride, init.eol_id, init.flags), img_pos0, h, seed, counter, na, nd, pn,
+                       ring=dring)
     torch.cuda.synchronize()
+    if ring is not None:
+        ring[...] = dring.cpu().numpy()
     return int(na.item()), nd.cpu().numpy(), pn.cpu().numpy()
 
 
@@ -122,7 +138,10 @@ def test_verify_probs_bit_exact(B, L, V, support):
 
 
 @pytest.mark.parametrize("mode,stride,eol,flags", [(1, 8, -1, 0), (1, 3, -1, 0), (0, 7, 13, 0), (1, 5, 13, 0), (1, 1, -1, 0),
-                                                   (2, 8, -1, 0), (2, 5, 13, 0), (0, 8, -1, 1), (2, 5, 13, 1), (1, 3, -1, 1)])
+                                                   (2, 8, -1, 0), (2, 5, 13, 0), (0, 8, -1, 1), (2, 5, 13, 1), (1, 3, -1, 1),
+                                                   (3, 8, -1, 0), (3, 5, 13, 0), (3, 4, 13, 1), (3, 2, 13, 0),
+                                                   (4, 8, -1, 0), (4, 3, -1, 0), (4, 5, 13, 0), (4, 1, -1, 0),
+                                                   (4, 3, -1, 1), (4, 16, -1, 0), (4, 2, 13, 1)])
 def test_verify_probs_init_strategies(B, mode, stride, eol, flags):
     rng = np.random.default_rng(mode * 100 + stride)
     L, V, lo = 12, 64, 10
@@ -136,11 +155,25 @@ def test_verify_probs_init_strategies(B, mode, stride, eol, flags):
             q[i] = p_old[i]
         draft = np.array([lo + int(np.argmax(p_old[i])) for i in range(L)], np.int32)
         init = oracle.Init(mode, stride, eol, flags)
-        want = oracle.verify_probs(q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case)
-        got = _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case)
+        ring_o = ring_g = None
+        if mode == 4:                                      # distributions on record for earlier positions
+            ring_o = _rand_rows(rng, stride, V, 20); ring_g = ring_o.copy()
+        want = oracle.verify_probs(q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case, ring=ring_o)
+        got = _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case, ring=ring_g)
         assert got[0] == want[0]
         assert np.array_equal(got[1], want[1])
         assert np.array_equal(got[2].view(np.uint32), want[2].view(np.uint32))
+        if mode == 4:
+            assert np.array_equal(ring_g.view(np.uint32), ring_o.view(np.uint32))
+        if mode >= 3:                                      # in place: index 0's carried row is recorded first
+            ring_a = None if mode == 3 else _rand_rows(np.random.default_rng(mode * 100 + stride + 1000 * case), stride, V, 20)
+            ring_b = None if ring_a is None else ring_a.copy()
+            want = oracle.verify_probs(q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case, ring=ring_a)
+            got = _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, 77, 5 + case, ring=ring_b, alias=True)
+            assert got[0] == want[0] and np.array_equal(got[1], want[1])
+            assert np.array_equal(got[2].view(np.uint32), want[2].view(np.uint32))
+            if mode == 4:
+                assert np.array_equal(ring_b.view(np.uint32), ring_a.view(np.uint32))
 
 
 @pytest.mark.parametrize("L,V,K", [(8, 1024, 64), (16, 8192, 2000), (32, 8192, 2000), (16, 16384, 2000)])
@@ -198,7 +231,9 @@ def test_first_window(B):
     try:
         V, lo = shape.v_s, shape.samp_lo
         q0 = oracle.dist(synth.random_logits(1, V, seed=1)[0], 64, 1.0)
-        for mode, stride, eol, L in [(0, 8, -1, 8), (1, 3, -1, 8), (1, 4, 1000, 16), (0, 5, 7, 32), (2, 8, -1, 8), (2, 4, 1000, 16)]:
+        for mode, stride, eol, L in [(0, 8, -1, 8), (1, 3, -1, 8), (1, 4, 1000, 16), (0, 5, 7, 32), (2, 8, -1, 8), (2, 4, 1000, 16),
+                                     (3, 8, -1, 8), (3, 4, 1000, 16), (3, 1, 1000, 4), (4, 3, -1, 8), (4, 4, 1000, 16),
+                                     (4, 40, -1, 16), (4, 1, -1, 8)]:
             init = oracle.Init(mode, stride, eol)
             wd, wp = oracle.first_window(q0, L, lo, init, 31)
             d = torch.zeros(L, dtype=torch.int32, device="cuda")
@@ -224,5 +259,9 @@ def test_argument_errors(B):
     with pytest.raises(B.SjdError):
         B.sjd_verify(z, z, d, L, B.SJD_MAX_SAMP_VOCAB + 1, 0, B.sjd_sampler(5, 1.0), B.sjd_init(0, 0, -1), 0, None, 1, 1,
                      na, d, z)
+    with pytest.raises(B.SjdError):                       # sample-above needs the ring
+        B.sjd_verify(z, z, d, L, V, 0, B.sjd_sampler(5, 1.0), B.sjd_init(4, 8, -1), 0, None, 1, 1, na, d, z)
+    with pytest.raises(B.SjdError):                       # unknown initialiser
+        B.sjd_verify(z, z, d, L, V, 0, B.sjd_sampler(5, 1.0), B.sjd_init(5, 8, -1), 0, None, 1, 1, na, d, z)
     with pytest.raises(B.SjdError):                       # repeat-above needs the history
         B.sjd_verify(z, z, d, L, V, 0, B.sjd_sampler(5, 1.0), B.sjd_init(1, 8, -1), 9, None, 1, 1, na, d, z)
