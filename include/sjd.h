@@ -188,10 +188,38 @@ typedef struct {
 } sjd_profile;
 int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream);
 
+/* ---- batched decoding --------------------------------------------------------------------------
+ * B independent images share every window forward (Sec. 4.1 Step 2 for B windows at once): one pass
+ * over the weights serves B x L rows, so an iteration costs little more than for one image and the
+ * throughput grows almost B-fold.  Each image keeps its own handle (cache, loop state, random
+ * stream); Steps 3 and 4 run per image exactly as in sjd_decode_steps.  bf16 models, no guidance;
+ * the B windows must fit the 32 rows of one projection launch: L <= 16 for B = 2, L <= 8 for
+ * B <= 4, L <= 4 for B <= 8.  The first handle lends its activation buffers and, with graphs on,
+ * holds the captured iteration (re-captured when the set of handles or their settings change).
+ *
+ * sjd_decode_steps_batch: every handle has been through sjd_prefill + sjd_decode_begin with the same
+ * L, sampler and initialiser (seeds may differ); poll and collect per handle with
+ * sjd_decode_status / sjd_decode_result.  A handle whose image is complete sits out further
+ * iterations.  kvs: host array of B distinct handles.                                          */
+int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_steps, void *stream);
+
+/* Prompts to images for B handles.  ids / embeds: host arrays of B host pointers (embeds and
+ * n_embeds may be NULL), out_tokens host [B x N], stats host [B] or NULL (times are the batch's). */
+int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *const *ids, const int32_t *n_ids,
+                       const float *const *embeds, const int32_t *n_embeds, int32_t N, int32_t L,
+                       const sjd_sampler *smp, const sjd_init *init, const uint64_t *philox_seeds, int32_t *out_tokens,
+                       sjd_stats *stats);
+
 /* ---- pieces of the step, exported for parity tests and profiling --------------------------- */
 /* Step 2 alone: forward `L` tokens (dev ids) at positions n..n+L-1, write their K/V rows, return
  * logits dev [L x V_s] fp32 (the guided logits while guidance is on).  Does not advance n.     */
 int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream);
+
+/* The same for B handles in one forward: tokens dev [B x L], logits dev [B x L x V_s].  A handle
+ * inside a generation (sjd_decode_begin) whose image is complete is skipped: its rows of `logits`
+ * are left as they are.                                                                          */
+int sjd_forward_logits_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *tokens, int32_t L,
+                             float *logits, void *stream);
 
 /* Step 3 + Step 4 alone, from logits (row s belongs to window index s+1).  hist: dev ids of the
  * image tokens fixed so far [img_pos0] (may be NULL when init->mode is 0 or 3, or img_pos0 == 0).

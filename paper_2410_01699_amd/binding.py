@@ -22,7 +22,8 @@ EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "
            "sjd_kv_set_len", "sjd_prefill", "sjd_first_window", "sjd_step", "sjd_generate", "sjd_forward_logits",
            "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror", "sjd_decode_begin",
            "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps", "sjd_gemm_bench",
-           "sjd_prefill_uncond", "sjd_generate_cfg"]
+           "sjd_prefill_uncond", "sjd_generate_cfg", "sjd_decode_steps_batch", "sjd_forward_logits_batch",
+           "sjd_generate_batch"]
 
 PROF_KINDS = ("gemm", "attention", "elementwise", "verify")
 
@@ -82,6 +83,10 @@ _SIG = {
     "sjd_generate": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _u64, _vp,
                                _P(sjd_stats)]),
     "sjd_forward_logits": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _vp]),
+    "sjd_forward_logits_batch": (C.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp]),
+    "sjd_decode_steps_batch": (C.c_int, [_vp, _vp, _i32, _i32, _vp]),
+    "sjd_generate_batch": (C.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _vp,
+                                     _vp, _vp]),
     "sjd_verify": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _vp, _vp, _u64, _u64,
                              _vp, _vp, _vp, _vp]),
     "sjd_verify_probs": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_init), _i32, _vp, _vp, _u64, _u64, _vp, _vp,
@@ -213,6 +218,36 @@ def sjd_generate(m, kv, ids, embeds, N, L, smp, init, seed):
     _check(_lib.sjd_generate(m, kv, _host(ids), n_ids, _host(embeds), n_emb, N, L, C.byref(smp), C.byref(init), seed,
                              _host(out), C.byref(st)))
     return out, st
+
+
+def _handles(kvs):
+    """host array of cache handles"""
+    return (C.c_void_p * len(kvs))(*[kv.value for kv in kvs])
+
+
+def sjd_decode_steps_batch(m, kvs, n_steps, stream=None):
+    _check(_lib.sjd_decode_steps_batch(m, _handles(kvs), len(kvs), n_steps, _stream(stream)))
+
+
+def sjd_forward_logits_batch(m, kvs, tokens, L, logits, stream=None):
+    """tokens: device int32 [B, L]; logits: device fp32 [B, L, V_s]"""
+    _check(_lib.sjd_forward_logits_batch(m, _handles(kvs), len(kvs), _dev(tokens), L, _dev(logits), _stream(stream)))
+
+
+def sjd_generate_batch(m, kvs, ids_list, embeds_list, N, L, smp, init, seeds):
+    """ids_list / embeds_list: one prompt per handle (embeds_list may be None); returns tokens [B, N], stats list"""
+    B = len(kvs)
+    prm = [_ids_embeds(ids_list[b], None if embeds_list is None else embeds_list[b]) for b in range(B)]
+    idp = (C.c_void_p * B)(*[None if p[0] is None else p[0].ctypes.data for p in prm])
+    nid = (C.c_int32 * B)(*[p[1] for p in prm])
+    emp = (C.c_void_p * B)(*[None if p[2] is None else p[2].ctypes.data for p in prm])
+    nem = (C.c_int32 * B)(*[p[3] for p in prm])
+    sd = (C.c_uint64 * B)(*[int(x) for x in seeds])
+    out = np.empty((B, N), np.int32)
+    st = (sjd_stats * B)()
+    _check(_lib.sjd_generate_batch(m, _handles(kvs), B, idp, nid, emp, nem, N, L, C.byref(smp), C.byref(init), sd,
+                                   _host(out), st))
+    return out, list(st)
 
 
 def sjd_forward_logits(m, kv, tokens, L, logits, stream=None):

@@ -182,6 +182,8 @@ extern "C" void sjd_kv_free(sjd_kv *kv)
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (kv->graph_exec) (void)hipGraphExecDestroy(kv->graph_exec);
     if (kv->graph) (void)hipGraphDestroy(kv->graph);
+    if (kv->bgraph_exec) (void)hipGraphExecDestroy(kv->bgraph_exec);
+    if (kv->bgraph) (void)hipGraphDestroy(kv->bgraph);
     delete kv;
 }
 
@@ -306,6 +308,13 @@ static void drop_graph(sjd_kv *kv)
     if (kv->graph) { (void)hipGraphDestroy(kv->graph); kv->graph = nullptr; }
 }
 
+static void drop_batch_graph(sjd_kv *kv)
+{
+    if (kv->bgraph_exec) { (void)hipGraphExecDestroy(kv->bgraph_exec); kv->bgraph_exec = nullptr; }
+    if (kv->bgraph) { (void)hipGraphDestroy(kv->bgraph); kv->bgraph = nullptr; }
+    memset(&kv->bkey, 0, sizeof(kv->bkey));
+}
+
 // ---- optional per-kernel timing -------------------------------------------------------------
 thread_local SjdLaunchHook *sjd_launch_hook = nullptr;
 
@@ -373,7 +382,7 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? 1 : 0, 0, L.g1, rows, kv->h, st, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm(0, &L.qkv, kv->h, rows, kv->part, st, s));
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rope_kv(m, kv, l, stream, kv->part, 1, 0, rows, rows_valid, s));
-        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, stream, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention_f32(m, kv, l, rows, stream, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm(0, &L.o, kv->att_out, rows, kv->part, st, s));
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, kv->part, 1, 0, L.g2, rows, kv->h, st, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm(0, &L.gu, kv->h, rows, kv->part, st, s));
@@ -386,37 +395,51 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
     return SJD_OK;
 }
 
-// bf16: RMSNorm, residual adds, SiLU*up, RoPE and the cache write happen inside the projection kernel.
-// stream_mode 0 / 1: `rows` rows of that stream; 2: both streams, `rows` (<= 16) rows each, stream 1 in
-// rows 16.. of every activation matrix and of `logits`.
-static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows_valid, int32_t stream_mode,
-                             float *logits, hipStream_t s)
+// the streams of one handle: its conditional context alone (mode 0), its unconditional one alone (1),
+// or both in rows 0.. and SJD_STREAM_ROWS.. (2)
+static SjdStreams handle_streams(const sjd_kv *kv, int32_t stream_mode)
 {
+    SjdStreams sm;
+    memset(&sm, 0, sizeof(sm));
     const SjdState *st = kv->state;
+    sm.count = stream_mode == 2 ? 2 : 1;
+    sm.shift = stream_mode == 2 ? 4 : 5;
+    for (int i = 0; i < sm.count; ++i) {
+        const bool uncond = stream_mode == 1 || i == 1;
+        sm.n[i] = uncond ? &st->n_u : &st->n;
+        sm.done[i] = &st->done;
+        sm.kvc[i] = (bf16_t *)(uncond ? kv->k_u : kv->k);
+    }
+    return sm;
+}
+
+// bf16: RMSNorm, residual adds, SiLU*up, RoPE and the cache write happen inside the projection kernel.
+// `rows` rows per stream of `sm` (inputs already in kv->x, stream i at row i << sm.shift; the logits
+// land in the same rows of `logits`).  The activation buffers are kv's; the caches are the streams'.
+// kv_tokens_upper: upper bound of the cached positions all streams together read (profiling only).
+static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int32_t rows, int32_t rows_valid,
+                             double kv_tokens_upper, float *logits, hipStream_t s)
+{
     const int d = m->cfg.d_model, F = m->cfg.d_ffn;
     const float eps = m->cfg.rms_eps;
-    const bool dual = stream_mode == 2;
-    const int grows = dual ? SJD_STREAM_ROWS + rows : rows;      // rows the projections compute
+    const int grows = ((sm.count - 1) << sm.shift) + rows;      // rows the projections compute
     // upper bound of the K/V bytes one layer's attention reads (hi + lo planes)
-    const double kv_bytes_layer = 2.0 * ((stream_mode == 1 ? kv->n_upper_u : kv->n_upper) + rows) * d * 4 +
-                                  (dual ? 2.0 * (kv->n_upper_u + rows) * d * 4 : 0.0);
+    const double kv_bytes_layer = 2.0 * kv_tokens_upper * d * 4;
     SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
     memset(&e_qkv, 0, sizeof(e_qkv));
-    e_qkv.st = st;
+    e_qkv.sm = sm;
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
     e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid; e_qkv.max_seq = m->cfg.max_seq;
-    e_qkv.dual = dual; e_qkv.stream = stream_mode == 1;
     e_res.kind = SJD_EPI_RESID; e_res.out = kv->x;
     e_silu.kind = SJD_EPI_SILU; e_silu.ffn = (float *)kv->ffn; e_silu.F = F;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
     const float *x = kv->x, *att = (const float *)kv->att_out, *ffn = (const float *)kv->ffn;
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
-        e_qkv.kvc = (bf16_t *)(stream_mode == 1 ? kv->k_u : kv->k) + l * kv->k_layer_stride;
-        e_qkv.kvc_u = dual ? (bf16_t *)kv->k_u + l * kv->k_layer_stride : nullptr;
+        e_qkv.layer_off = (size_t)l * kv->k_layer_stride;
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, (const bf16_t *)L.g1, eps, grows, e_qkv, s));
-        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, stream_mode, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, nullptr, 0.f, grows, e_res, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, (const bf16_t *)L.g2, eps, grows, e_silu, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, nullptr, 0.f, grows, e_res, s));
@@ -425,20 +448,25 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t row
     return SJD_OK;
 }
 
-// Embedding + decoder stack for one window or prompt chunk.  ids (device) or emb_rows (device fp32
-// rows), `rows` of them; stream_mode as above.  Two streams see the same rows; their logits land in
-// rows 0.. and SJD_STREAM_ROWS.. of `logits`.
+// Embedding + decoder stack for one window or prompt chunk of one handle.  ids (device) or emb_rows
+// (device fp32 rows), `rows` of them; stream_mode as in handle_streams.  Two streams see the same
+// rows; their logits land in rows 0.. and SJD_STREAM_ROWS.. of `logits`.
 static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const float *emb_rows, int32_t rows,
                           int32_t rows_valid, int32_t stream_mode, float *logits, hipStream_t s)
 {
     if (stream_mode == 2 && rows > SJD_STREAM_ROWS) return SJD_EINVAL;
     if (m->cfg.dtype == 1) {
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, emb_rows, rows, stream_mode == 2, kv->x, kv->state, s));
-        return forward_rows_bf16(m, kv, rows, rows_valid, stream_mode, logits, s);
+        const SjdStreams sm = handle_streams(kv, stream_mode);
+        const int32_t *idv[SJD_MAX_STREAMS] = {ids, ids};
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, s));
+        const double toks = (stream_mode == 1 ? 0 : kv->n_upper + rows) + (stream_mode == 0 ? 0 : kv->n_upper_u + rows);
+        return forward_rows_bf16(m, kv, sm, rows, rows_valid, toks, logits, s);
     }
     // fp32 models are launch-bound toys: two streams are two forwards
+    const SjdStreams one = handle_streams(kv, 0);     // (only the finished flag is used by the embedding)
+    const int32_t *idv[SJD_MAX_STREAMS] = {ids};
     for (int stream = (stream_mode == 1 ? 1 : 0); stream <= (stream_mode == 0 ? 0 : 1); ++stream) {
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, emb_rows, rows, 0, kv->x, kv->state, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, s));
         SJD_TRY(forward_rows_f32(m, kv, rows, rows_valid, stream,
                                  logits + (stream_mode == 2 && stream ? (size_t)SJD_STREAM_ROWS * m->V_s : 0), s));
     }
@@ -734,6 +762,197 @@ extern "C" int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void 
         if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_graph(kv); return SJD_EHIP; }
     }
     for (int i = 0; i < n_steps; ++i) HIP_TRY(hipGraphLaunch(kv->graph_exec, s));
+    return SJD_OK;
+}
+
+// ---- batched decoding: B handles share every window forward --------------------------------------
+// rows reserved per handle: the smallest power of two that holds the window, such that all fit in
+// the 32 rows one projection launch computes
+static int batch_shift(int32_t B, int32_t L)
+{
+    for (int shift = 0; shift <= 5; ++shift)
+        if ((1 << shift) >= L) return (B << shift) <= SJD_ROWS_MAX ? shift : -1;
+    return -1;
+}
+
+static int check_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t L, bool decoding)
+{
+    if (!m || !kvs || B < 1 || B > SJD_MAX_STREAMS || m->cfg.dtype != 1) return SJD_EINVAL;
+    for (int b = 0; b < B; ++b) {
+        sjd_kv *kv = kvs[b];
+        if (!kv || kv->m != m || kv->cfg_on) return SJD_EINVAL;
+        for (int c = 0; c < b; ++c) if (kvs[c] == kv) return SJD_EINVAL;
+        if (decoding) {
+            const sjd_kv *k0 = kvs[0];
+            if (!kv->dec_active || kv->dec_L != L) return SJD_EINVAL;
+            if (kv->dec_smp.top_k != k0->dec_smp.top_k || kv->dec_smp.temperature != k0->dec_smp.temperature ||
+                memcmp(&kv->dec_init, &k0->dec_init, sizeof(sjd_init)) != 0)
+                return SJD_EINVAL;
+        }
+    }
+    return batch_shift(B, L) < 0 ? SJD_EINVAL : SJD_OK;
+}
+
+static SjdStreams batch_streams(sjd_kv *const *kvs, int32_t B, int32_t L)
+{
+    SjdStreams sm;
+    memset(&sm, 0, sizeof(sm));
+    sm.count = B; sm.shift = batch_shift(B, L);
+    for (int b = 0; b < B; ++b) {
+        sm.n[b] = &kvs[b]->state->n; sm.done[b] = &kvs[b]->state->done; sm.kvc[b] = (bf16_t *)kvs[b]->k;
+    }
+    return sm;
+}
+
+// one window forward for all handles: handle b's tokens ids[b] (device), rows b << shift of the
+// first handle's activation buffers and of its logits buffer
+static int forward_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *const *ids, int32_t L, hipStream_t s)
+{
+    sjd_kv *kv0 = kvs[0];
+    const SjdStreams sm = batch_streams(kvs, B, L);
+    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, s));
+    double toks = 0;
+    for (int b = 0; b < B; ++b) toks += kvs[b]->n_upper + L;
+    return forward_rows_bf16(m, kv0, sm, L, L, toks, kv0->logits, s);
+}
+
+static int decode_one_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, hipStream_t s)
+{
+    sjd_kv *kv0 = kvs[0];
+    const int L = kv0->dec_L, shift = batch_shift(B, L);
+    const int32_t *ids[SJD_MAX_STREAMS] = {};
+    for (int b = 0; b < B; ++b) ids[b] = kvs[b]->g_draft;
+    SJD_TRY(forward_batch(m, kvs, B, ids, L, s));
+    for (int b = 0; b < B; ++b) {
+        sjd_kv *kv = kvs[b];
+        SjdVerifyArgs v;
+        memset(&v, 0, sizeof(v));
+        v.logits = kv0->logits + ((size_t)b << shift) * m->V_s; v.p_old = kv->g_p; v.draft = kv->g_draft; v.L = L;
+        v.V = m->V_s; v.lo = m->cfg.samp_lo; v.smp = kv->dec_smp; v.init = kv->dec_init; v.seed = kv->dec_seed;
+        v.state = kv->state; v.kv_tokens = kv->tokens; v.n_accepted = kv->g_nacc; v.new_draft = kv->g_draft;
+        v.p_new = kv->g_p; v.ring = kv->ring; v.q = kv->q; v.tok_smp = kv->tok_smp; v.tok_res = kv->tok_res;
+        v.acc_flag = kv->acc_flag; v.draft_snap = kv->draft_snap; v.snap = kv->snap;
+        PROF(kv0, SJD_PROF_VERIFY, 3.0 * L * m->V_s * 4, sjd_launch_verify(&v, s));
+    }
+    return SJD_OK;
+}
+
+extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_steps, void *stream)
+{
+    if (!kvs || B < 1 || !kvs[0] || n_steps < 0) return SJD_EINVAL;
+    sjd_kv *kv0 = kvs[0];
+    SJD_TRY(check_batch(m, kvs, B, kv0->dec_L, true));
+    hipStream_t s = (hipStream_t)stream;
+    if (!kv0->use_graph) {
+        for (int i = 0; i < n_steps; ++i) SJD_TRY(decode_one_batch(m, kvs, B, s));
+        return SJD_OK;
+    }
+    sjd_kv::BatchKey key;
+    memset(&key, 0, sizeof(key));
+    key.B = B; key.L = kv0->dec_L; key.smp = kv0->dec_smp; key.init = kv0->dec_init;
+    for (int b = 0; b < B; ++b) {
+        key.kv[b] = kvs[b]; key.state[b] = kvs[b]->state; key.cache[b] = kvs[b]->k; key.ring[b] = kvs[b]->ring;
+        key.seed[b] = kvs[b]->dec_seed;
+    }
+    if (kv0->bgraph_exec && memcmp(&key, &kv0->bkey, sizeof(key)) != 0) drop_batch_graph(kv0);
+    if (!kv0->bgraph_exec) {
+        // one iteration of all handles; what varies between iterations lives in device memory
+        hipStream_t cs;
+        HIP_TRY(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+        hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
+        int rc = SJD_OK;
+        if (e != hipSuccess) { sjd_set_hip_error(e, "hipStreamBeginCapture"); rc = SJD_EHIP; }
+        if (rc == SJD_OK) rc = decode_one_batch(m, kvs, B, cs);
+        hipGraph_t g = nullptr;
+        e = hipStreamEndCapture(cs, &g);
+        if (rc == SJD_OK && e != hipSuccess) { sjd_set_hip_error(e, "hipStreamEndCapture"); rc = SJD_EHIP; }
+        (void)hipStreamDestroy(cs);
+        if (rc != SJD_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+        kv0->bgraph = g;
+        e = hipGraphInstantiate(&kv0->bgraph_exec, g, nullptr, nullptr, 0);
+        if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_batch_graph(kv0); return SJD_EHIP; }
+        kv0->bkey = key;
+    }
+    for (int i = 0; i < n_steps; ++i) HIP_TRY(hipGraphLaunch(kv0->bgraph_exec, s));
+    return SJD_OK;
+}
+
+__global__ void clear_done_batch_kernel(SjdStreams sm)
+{
+    if ((int)threadIdx.x < sm.count) *const_cast<int32_t *>(sm.done[threadIdx.x]) = 0;
+}
+
+extern "C" int sjd_forward_logits_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *tokens, int32_t L,
+                                        float *logits, void *stream)
+{
+    if (!tokens || !logits || L < 1) return SJD_EINVAL;
+    SJD_TRY(check_batch(m, kvs, B, L, false));
+    for (int b = 0; b < B; ++b) SJD_TRY(check_room(kvs[b], L));
+    hipStream_t s = (hipStream_t)stream;
+    const SjdStreams sm = batch_streams(kvs, B, L);
+    // a handle that is not inside a generation computes regardless of how its last one ended; one that
+    // is keeps its finished flag (its rows are skipped once its image is complete)
+    SjdStreams idle = sm;
+    idle.count = 0;
+    for (int b = 0; b < B; ++b) if (!kvs[b]->dec_active) idle.done[idle.count++] = sm.done[b];
+    if (idle.count) {
+        SJD_LAUNCH(clear_done_batch_kernel, dim3(1), dim3(64), 0, s, idle);
+        HIP_TRY(hipGetLastError());
+    }
+    const int32_t *ids[SJD_MAX_STREAMS] = {};
+    for (int b = 0; b < B; ++b) ids[b] = tokens + (size_t)b * L;
+    SJD_TRY(forward_batch(m, kvs, B, ids, L, s));
+    // rows b << shift .. of the shared logits buffer -> [B][L][V_s]
+    const size_t V = m->V_s;
+    for (int b = 0; b < B; ++b)
+        HIP_TRY(hipMemcpyAsync(logits + (size_t)b * L * V, kvs[0]->logits + ((size_t)b << sm.shift) * V, (size_t)L * V * 4,
+                               hipMemcpyDeviceToDevice, s));
+    return SJD_OK;
+}
+
+extern "C" int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *const *ids,
+                                  const int32_t *n_ids, const float *const *embeds, const int32_t *n_embeds, int32_t N,
+                                  int32_t L, const sjd_sampler *smp, const sjd_init *init, const uint64_t *philox_seeds,
+                                  int32_t *out_tokens, sjd_stats *stats)
+{
+    if (!ids || !n_ids || !philox_seeds || !out_tokens || N < 1) return SJD_EINVAL;
+    SJD_TRY(check_batch(m, kvs, B, L, false));
+    SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
+    for (int b = 0; b < B; ++b)
+        if (n_ids[b] + (n_embeds ? n_embeds[b] : 0) + N + L > m->cfg.max_seq) return SJD_ESEQ;
+    hipStream_t s = 0;
+    auto t0 = std::chrono::steady_clock::now();
+    for (int b = 0; b < B; ++b) {
+        sjd_kv *kv = kvs[b];
+        SJD_TRY(sjd_prefill(m, kv, ids[b], n_ids[b], embeds ? embeds[b] : nullptr, n_embeds ? n_embeds[b] : 0, smp, init,
+                            kv->q_first, s));
+        SJD_TRY(sjd_decode_begin(m, kv, kv->q_first, N, L, smp, init, philox_seeds[b], s));
+    }
+    HIP_TRY(hipStreamSynchronize(s));
+    auto t1 = std::chrono::steady_clock::now();
+    // iterations are enqueued eight at a time; a handle whose image is complete sits out the rest
+    // (its rows are still computed, its kernels of the verification return at once)
+    int enq = 0, all_done = 0;
+    while (!all_done) {
+        SJD_TRY(sjd_decode_steps_batch(m, kvs, B, 8, s));
+        enq += 8;
+        all_done = 1;
+        for (int b = 0; b < B; ++b) {
+            int done = 0;
+            SJD_TRY(sjd_decode_status(kvs[b], nullptr, nullptr, &done));
+            all_done &= done;
+        }
+        if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every iteration fixes at least one token per image
+    }
+    auto t2 = std::chrono::steady_clock::now();
+    for (int b = 0; b < B; ++b) {
+        sjd_stats *st = stats ? stats + b : nullptr;
+        SJD_TRY(sjd_decode_result(kvs[b], out_tokens + (size_t)b * N, st));
+        if (st) {
+            st->ms_prefill = std::chrono::duration<float, std::milli>(t1 - t0).count();
+            st->ms_decode = std::chrono::duration<float, std::milli>(t2 - t1).count();
+        }
+    }
     return SJD_OK;
 }
 

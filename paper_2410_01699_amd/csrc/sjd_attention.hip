@@ -8,6 +8,8 @@
 // LDS as fp32, plain FMA arithmetic) and an MFMA one for the blocked hi/lo cache of bf16 models.
 #include "sjd_internal.h"
 
+#include <algorithm>
+
 #define ATT_TILE 64
 #define ATT_THREADS 256
 
@@ -174,20 +176,16 @@ __device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &
 #define AW 4
 // partial record of (head, split): O[MT*16][HD] unnormalised, then m[MT*16], then l[MT*16]
 template <int HD, int MT>
-__global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__restrict__ qact,
-                                                            const bf16_t *__restrict__ kvc0,
-                                                            const bf16_t *__restrict__ kvc1, int stream0, int d,
-                                                            int nblk_cache, int rows, int splits,
-                                                            float *__restrict__ part, const SjdState *st)
+__global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__restrict__ qact, SjdStreams sm,
+                                                            size_t layer_off, int d, int nblk_cache, int rows,
+                                                            int splits, float *__restrict__ part)
 {
-    if (st->done) return;
-    // blockIdx.z = 0: stream `stream0` with cache kvc0, queries in rows 0..; blockIdx.z = 1 (two-stream
-    // forward): stream 1 with cache kvc1, queries in rows SJD_STREAM_ROWS..
-    const int second = blockIdx.z;
-    const int stream = second ? 1 : stream0;
-    const bf16_t *__restrict__ kvc = second ? kvc1 : kvc0;
-    qact += (size_t)second * SJD_STREAM_ROWS * d;
-    part += (size_t)second * gridDim.x * splits * (MT * 16 * HD + 2 * MT * 16);
+    // blockIdx.z = stream: its own cache and cache length, queries in rows (stream << shift)..
+    const int stream = blockIdx.z;
+    if (*sm.done[stream]) return;
+    const bf16_t *__restrict__ kvc = sm.kvc[stream] + layer_off;
+    const int row0 = stream << sm.shift;
+    part += (size_t)stream * gridDim.x * splits * (MT * 16 * HD + 2 * MT * 16);
     constexpr int KS = HD / 32;      // k-steps of the score product
     constexpr int DT = HD / 16;      // output dim tiles
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
@@ -196,7 +194,7 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     __shared__ bf16x8 q_lds[MT][KS][2][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     const int head = blockIdx.x, split = blockIdx.y;
-    const int n = state_n(st, stream);
+    const int n = *sm.n[stream];
     const int total = n + rows;
     const int nblk = (total + 31) >> 5;
     const int bps = (nblk + splits - 1) / splits;
@@ -227,7 +225,9 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     for (int u = threadIdx.x; u < MT * KS * 64; u += 64 * AW) {
         const int l = u & 63, ks = (u >> 6) % KS, mt = (u >> 6) / KS;
         float x[8];
-        const float4 *src = reinterpret_cast<const float4 *>(qact + (size_t)(mt * 16 + (l & 15)) * d + head * HD + ks * 32 + (l >> 4) * 8);
+        // (query rows past the stream's `rows` are masked below; the clamp keeps their loads inside qact)
+        const int qr = min(row0 + mt * 16 + (l & 15), SJD_ROWS_MAX - 1);
+        const float4 *src = reinterpret_cast<const float4 *>(qact + (size_t)qr * d + head * HD + ks * 32 + (l >> 4) * 8);
         const float4 x0 = src[0], x1 = src[1];
         x[0] = x0.x * scale; x[1] = x0.y * scale; x[2] = x0.z * scale; x[3] = x0.w * scale;
         x[4] = x1.x * scale; x[5] = x1.y * scale; x[6] = x1.z * scale; x[7] = x1.w * scale;
@@ -343,18 +343,18 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
 #define ATT_MAX_SPLITS 16
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
-                                                        float *__restrict__ out, const SjdState *st)
+                                                        float *__restrict__ out, SjdStreams sm)
 {
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
-    const int head = blockIdx.x, second = blockIdx.z;
-    const float *base = part + ((size_t)second * gridDim.x + head) * splits * REC;
+    const int head = blockIdx.x, stream = blockIdx.z;
+    const float *base = part + ((size_t)stream * gridDim.x + head) * splits * REC;
     const int u = blockIdx.y * 256 + threadIdx.x;
     if (u >= rows * Q4) return;
     const int q = u / Q4, j4 = u % Q4;
     float ms[ATT_MAX_SPLITS], ls[ATT_MAX_SPLITS];
     f32x4 os[ATT_MAX_SPLITS];
-    const int done = st->done;
+    const int done = *sm.done[stream];
 #pragma unroll
     for (int s = 0; s < ATT_MAX_SPLITS; ++s) {
         const float *p = base + (size_t)(s < splits ? s : 0) * REC;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         num += w * os[s];
         den += w * ls[s];
     }
-    *reinterpret_cast<f32x4 *>(out + act_off(q + second * SJD_STREAM_ROWS, head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
+    *reinterpret_cast<f32x4 *>(out + act_off(q + (stream << sm.shift), head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -396,8 +396,10 @@ int32_t sjd_attention_splits(const sjd_model *m)
 
 size_t sjd_attention_part_elems(const sjd_model *m)
 {
-    // (two streams of 16 rows need the same space as one stream of 32)
-    return (size_t)m->cfg.n_heads * sjd_attention_splits(m) * (SJD_ROWS_MAX * m->hd + 2 * SJD_ROWS_MAX);
+    // one stream of 32 rows at the full number of key splits; two streams of 16 rows need the same, and
+    // up to SJD_MAX_STREAMS streams split their keys less finely (never below one split each)
+    const int splits = std::max(sjd_attention_splits(m), SJD_MAX_STREAMS / 2);
+    return (size_t)m->cfg.n_heads * splits * (SJD_ROWS_MAX * m->hd + 2 * SJD_ROWS_MAX);
 }
 
 template <typename T, int HD>
@@ -417,47 +419,48 @@ static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows,
 }
 
 template <int HD, int MT>
-static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s)
+static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)
 {
     const int d = m->cfg.d_model, H = m->cfg.n_heads;
     const size_t off = (size_t)layer * kv->k_layer_stride;
-    const bf16_t *c0 = (const bf16_t *)(stream_mode == 1 ? kv->k_u : kv->k) + off;
-    const bf16_t *c1 = stream_mode == 2 ? (const bf16_t *)kv->k_u + off : c0;
-    const int streams = stream_mode == 2 ? 2 : 1;
-    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, kv->att_splits, streams), dim3(64 * AW), 0, s, kv->qact, c0, c1,
-                       stream_mode == 1 ? 1 : 0, d, kv->nblk, rows, kv->att_splits, kv->att_part, kv->state);
+    // the partial-record buffer is sized for one stream of 32 rows at att_splits key splits; more than
+    // two streams (of at most 16 rows each) share it by splitting their keys less finely
+    const int splits = sm.count <= 2 ? kv->att_splits : std::max(1, 2 * kv->att_splits / sm.count);
+    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, splits, sm.count), dim3(64 * AW), 0, s, kv->qact, sm, off, d,
+                       kv->nblk, rows, splits, kv->att_part);
     HIP_TRY(hipGetLastError());
-    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256, streams), dim3(256), 0, s, kv->att_part,
-                       kv->att_splits, d, rows, (float *)kv->att_out, kv->state);
+    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256, sm.count), dim3(256), 0, s, kv->att_part,
+                       splits, d, rows, (float *)kv->att_out, sm);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 
 template <int HD>
-static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s)
+static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)
 {
-    if (stream_mode == 2) {
-        if (rows > SJD_STREAM_ROWS) return SJD_EINVAL;
-        return launch_mfma_t<HD, 1>(m, kv, layer, rows, 2, s);
-    }
-    return rows <= 16 ? launch_mfma_t<HD, 1>(m, kv, layer, rows, stream_mode, s)
-                      : launch_mfma_t<HD, 2>(m, kv, layer, rows, stream_mode, s);
+    if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows > (1 << sm.shift) || (sm.count << sm.shift) > SJD_ROWS_MAX)
+        return SJD_EINVAL;
+    if (sm.count > 1 || rows <= 16) return launch_mfma_t<HD, 1>(m, kv, layer, rows, sm, s);
+    return launch_mfma_t<HD, 2>(m, kv, layer, rows, sm, s);
 }
 
-int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s)
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)
 {
     const int hd = m->hd;
-    if (m->cfg.dtype == 1) {
-        if (hd == 32) return launch_mfma<32>(m, kv, layer, rows, stream_mode, s);
-        if (hd == 64) return launch_mfma<64>(m, kv, layer, rows, stream_mode, s);
-        if (hd == 128) return launch_mfma<128>(m, kv, layer, rows, stream_mode, s);
-        return SJD_EINVAL;
-    }
-    if (m->cfg.dtype == 0 && stream_mode < 2) {
-        if (hd == 16) return launch_t<float, 16>(m, kv, layer, rows, stream_mode, s);
-        if (hd == 32) return launch_t<float, 32>(m, kv, layer, rows, stream_mode, s);
-        if (hd == 64) return launch_t<float, 64>(m, kv, layer, rows, stream_mode, s);
-        if (hd == 128) return launch_t<float, 128>(m, kv, layer, rows, stream_mode, s);
-    }
+    if (m->cfg.dtype != 1) return SJD_EINVAL;
+    if (hd == 32) return launch_mfma<32>(m, kv, layer, rows, sm, s);
+    if (hd == 64) return launch_mfma<64>(m, kv, layer, rows, sm, s);
+    if (hd == 128) return launch_mfma<128>(m, kv, layer, rows, sm, s);
+    return SJD_EINVAL;
+}
+
+int sjd_launch_attention_f32(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream, hipStream_t s)
+{
+    const int hd = m->hd;
+    if (m->cfg.dtype != 0 || stream < 0 || stream > 1) return SJD_EINVAL;
+    if (hd == 16) return launch_t<float, 16>(m, kv, layer, rows, stream, s);
+    if (hd == 32) return launch_t<float, 32>(m, kv, layer, rows, stream, s);
+    if (hd == 64) return launch_t<float, 64>(m, kv, layer, rows, stream, s);
+    if (hd == 128) return launch_t<float, 128>(m, kv, layer, rows, stream, s);
     return SJD_EINVAL;
 }

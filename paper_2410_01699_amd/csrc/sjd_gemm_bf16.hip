@@ -54,21 +54,29 @@ struct EpiPre {
     f32x4 x;                  // RESID: current residual values
     float c0, s0, c1, s1;     // QKV: RoPE factors of this thread's two pairs
     int pos;                  // QKV: absolute position of row m in its stream's cache
-    int stream;               // QKV: 0 or 1
     int row;                  // QKV: row index inside the stream
+    bf16_t *cache;            // QKV: this layer of the stream's cache (NULL: the row belongs to no stream)
 };
 
 template <int EPI>
-__device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, int n_now, int n_now_u, int m, int n0,
-                                                 EpiPre &pre)
+__device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, int m, int n0, EpiPre &pre)
 {
     if (EPI == SJD_EPI_RESID) {
         pre.x = *reinterpret_cast<const f32x4 *>(ep.out + act_off(m, n0, N / 32));
     } else if (EPI == SJD_EPI_QKV) {
         const int half = ep.hd >> 1;
-        pre.stream = ep.dual ? (m >= SJD_STREAM_ROWS) : ep.stream;
-        pre.row = ep.dual ? (m & (SJD_STREAM_ROWS - 1)) : m;
-        pre.pos = min((pre.stream ? n_now_u : n_now) + pre.row, ep.max_seq - 1);   // rows past the window are computed but never stored
+        // the stream that owns row m: its cache length and cache (the loop index is uniform, so the
+        // table reads are scalar loads; the selection is per lane)
+        const int stream = m >> ep.sm.shift;
+        pre.row = m & ((1 << ep.sm.shift) - 1);
+        int n_s = 0;
+        pre.cache = nullptr;
+        for (int s = 0; s < ep.sm.count; ++s) {
+            const int n_here = *ep.sm.n[s];
+            bf16_t *c_here = ep.sm.kvc[s];
+            if (s == stream) { n_s = n_here; pre.cache = c_here + ep.layer_off; }
+        }
+        pre.pos = min(n_s + pre.row, ep.max_seq - 1);   // rows past the window are computed but never stored
         // (V fragments fetch factors they do not use: no branch around the loads)
         const int j = ((n0 % ep.d) % ep.hd) >> 1;
         const float2 cc = *reinterpret_cast<const float2 *>(ep.cosT + (size_t)pre.pos * half + j);
@@ -108,8 +116,8 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
                 float *q = ep.qact + (size_t)m * d + head * hd + j;
                 *reinterpret_cast<float2 *>(q) = make_float2(r0, r1);
                 *reinterpret_cast<float2 *>(q + half) = make_float2(r0p, r1p);
-            } else if (pre.row < ep.rows_valid) {
-                bf16_t *rec = (pre.stream && ep.dual ? ep.kvc_u : ep.kvc) + kv_block_off(head, pos >> 5, ep.nblk, hd);
+            } else if (pre.row < ep.rows_valid && pre.cache) {
+                bf16_t *rec = pre.cache + kv_block_off(head, pos >> 5, ep.nblk, hd);
                 const int kk = pos & 31;
                 float la, lb, dummy0, dummy1;
                 uint32_t hi = pack_hi2(r0, r1, la, lb);
@@ -119,11 +127,11 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
                 *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 0)) = hi;
                 *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 1)) = pack_hi2(la, lb, dummy0, dummy1);
             }
-        } else if (pre.row < ep.rows_valid) {
+        } else if (pre.row < ep.rows_valid && pre.cache) {
             // V: natural feature order
             const int col = n0 - 2 * d;
             const int head = col / hd, dim = col % hd;
-            bf16_t *rec = (pre.stream && ep.dual ? ep.kvc_u : ep.kvc) + kv_block_off(head, pos >> 5, ep.nblk, hd);
+            bf16_t *rec = pre.cache + kv_block_off(head, pos >> 5, ep.nblk, hd);
             const int kk = pos & 31;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -146,11 +154,6 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
                                                             const bf16_t *__restrict__ gain, float eps, int N, int K,
                                                             SjdGemmEpi ep)
 {
-    // the finished flag is only needed before anything is written: its load overlaps the first stage
-    const int finished = ep.st ? ep.st->done : 0;
-    // cache lengths of both streams (one stream: its own length is passed as the first)
-    const int n_now = (EPI == SJD_EPI_QKV) ? state_n(ep.st, ep.dual ? 0 : ep.stream) : 0;
-    const int n_now_u = (EPI == SJD_EPI_QKV) ? ep.st->n_u : 0;
     static_assert(MT * TN * 64 <= 64 * WK, "one epilogue fragment per thread");
     __shared__ f32x4 red[WK][MT * TN][64];
     __shared__ float ssq[WK][MT * 16];
@@ -217,6 +220,11 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         }
 
     LOAD_STAGE(kt0, a0, b0, g0)
+    // the finished flags (every stream's generation is over: nothing to do) are only needed before
+    // anything is written; read behind the first stage's loads so that those are not held up
+    __builtin_amdgcn_sched_barrier(0);
+    int finished = ep.sm.count > 0;
+    for (int s = 0; s < ep.sm.count; ++s) finished &= *ep.sm.done[s];
     if (finished) return;
     // epilogue fragment of this thread (threads past MT*TN*64 have none and fetch a duplicate): D
     // layout of tile mtn puts features 4*(l/16) .. +4 of token l%16 in lane l
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     const int f_mtn = min((int)(threadIdx.x >> 6), MT * TN - 1);
     const int f_m = (f_mtn / TN) * 16 + c, f_n0 = (tile0 + f_mtn % TN) * 16 + g * 4;
     EpiPre pre;
-    preload_epilogue<EPI>(ep, N, n_now, n_now_u, f_m, f_n0, pre);
+    preload_epilogue<EPI>(ep, N, f_m, f_n0, pre);
     int kt = kt0;
     // (the scheduling barriers keep the compiler from starting on the previous stage before the next
     // one's loads are issued, which would drain the memory pipeline once per iteration)

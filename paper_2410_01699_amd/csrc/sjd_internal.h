@@ -78,6 +78,19 @@ struct SjdState {
 __device__ __forceinline__ int state_n(const SjdState *st, int stream) { return stream ? st->n_u : st->n; }
 #define SJD_STREAM_ROWS 16   // rows per stream in a two-stream forward (stream 1 starts at row 16)
 
+// Token streams that share one window forward of a bf16 model: the two contexts of one image under
+// classifier-free guidance, or one context per image in batched decoding.  Stream s owns rows
+// [s << shift, (s + 1) << shift) of every activation matrix (count << shift <= 32), has its own cache
+// and its own cache length; the weights are streamed once for all of them.
+#define SJD_MAX_STREAMS 8
+struct SjdStreams {
+    int32_t count;                          // 0 (no device state: kernel test hooks) .. SJD_MAX_STREAMS
+    int32_t shift;                          // log2 of the rows reserved per stream
+    const int32_t *n[SJD_MAX_STREAMS];      // device: the stream's cache length
+    const int32_t *done[SJD_MAX_STREAMS];   // device: its generation has finished (kernels skip its work)
+    bf16_t *kvc[SJD_MAX_STREAMS];           // its cache, layer 0 (kernels add the layer offset)
+};
+
 // bf16 models keep every activation the projections consume (residual stream, attention output, FFN
 // hidden) as fp32 in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a wave fetches the
 // 16 x 32 tile of a k-step with two contiguous 1 KiB loads; the projection kernel splits the values
@@ -132,14 +145,12 @@ struct SjdLinear {
 #define SJD_EPI_QKV 3     // RoPE on q,k at position n+m; q -> qact, k,v -> cache
 struct SjdGemmEpi {
     int32_t kind;
-    const SjdState *st;          // device state (n, done); may be NULL for STORE
+    SjdStreams sm;               // who owns which rows; every kind uses the finished flags
+    size_t layer_off;            // QKV: element offset of this layer inside every stream's cache
     float *out;                  // STORE / RESID: [rows][N]
     float *ffn; int32_t F;                                        // SILU: [rows][F]
-    float *qact; bf16_t *kvc; const float *cosT, *sinT;           // QKV: kvc = this layer's cache
-    bf16_t *kvc_u;                // QKV, two streams: stream 1's cache of this layer
-    int32_t stream;               // QKV, one stream: which cache length positions the rows
-    int32_t dual;                 // QKV: rows 0..15 belong to stream 0, rows 16..31 to stream 1
-    int32_t d, hd, nblk, rows_valid, max_seq;
+    float *qact; const float *cosT, *sinT;                        // QKV
+    int32_t d, hd, nblk, rows_valid, max_seq;                     // rows_valid: rows per stream whose K/V are stored
 };
 
 struct SjdLayer {
@@ -203,6 +214,16 @@ struct sjd_kv {
     int32_t use_graph;
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
+    // batched decoding led by this handle: one captured iteration for a fixed set of handles
+    hipGraph_t bgraph;
+    hipGraphExec_t bgraph_exec;
+    struct BatchKey {
+        int32_t B, L;
+        sjd_sampler smp;
+        sjd_init init;
+        const void *kv[SJD_MAX_STREAMS], *state[SJD_MAX_STREAMS], *cache[SJD_MAX_STREAMS], *ring[SJD_MAX_STREAMS];
+        uint64_t seed[SJD_MAX_STREAMS];
+    } bkey;
     float *ring;          // [ring_rows][V_s] distributions of accepted image positions (initialiser (d))
     int32_t ring_rows;
     int32_t graph_cfg_on;   // stream mode and guidance weight the captured iteration was recorded with
@@ -212,9 +233,10 @@ struct sjd_kv {
 
 // ---- kernel launchers (each returns SJD_OK or an SJD_E* code) --------------------------------
 // `st` (device) lets a kernel skip its work once a generation has finished; NULL = always run.
-// dup != 0: every row is also written SJD_STREAM_ROWS rows further down (second stream, same tokens)
-int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, int32_t dup, float *x,
-                     const SjdState *st, hipStream_t s);
+// bf16 models: `rows` rows per stream, stream s from ids[s] (device ids; all streams share emb_rows when
+// that is given instead), written at row s << sm.shift.  fp32 models: one stream, ids[0].
+int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
+                     const SjdStreams &sm, float *x, hipStream_t s);
 int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
 int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
@@ -232,9 +254,10 @@ void sjd_choose_tiles(SjdLinear *lin);
 int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s);
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
-// stream_mode 0 / 1: one stream (rows 0..rows-1) against that stream's cache; 2: both streams, `rows`
-// rows each (stream 1 in rows 16..), bf16 models only
-int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream_mode, hipStream_t s);
+// fp32 models: `stream` 0 / 1 selects the cache and length of the handle
+int sjd_launch_attention_f32(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream, hipStream_t s);
+// bf16 models: `rows` query rows per stream of sm against that stream's cache
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s);
 int32_t sjd_attention_splits(const sjd_model *m);
 size_t sjd_attention_part_elems(const sjd_model *m);
 // sampling / verification

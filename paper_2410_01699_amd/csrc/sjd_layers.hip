@@ -13,13 +13,16 @@ template <> struct Act<bf16_t> {
     __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 };
 
-// x[r][:] = E[ids[r]][:]  (or the given raw embedding row); bf16 models keep x in act_off order.
-// One thread per 4 consecutive features; grid (rows, d / 1024).
+// x[row][:] = E[id][:]  (or the given raw embedding row); bf16 models keep x in act_off order.  Stream
+// blockIdx.z takes its ids from ids.p[stream] and writes rows (stream << shift)..; one thread per 4
+// consecutive features; grid (rows per stream, d / 1024, streams).
+struct EmbedIds { const int32_t *p[SJD_MAX_STREAMS]; };
 template <typename T>
-__global__ __launch_bounds__(256) void embed_kernel(const T *E, const int32_t *ids, const float *emb_rows, int d, int dup,
-                                                    float *x, const SjdState *st)
+__global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, const float *emb_rows, int d, SjdStreams sm,
+                                                    float *x)
 {
-    const int done = st->done;
+    const int stream = blockIdx.z;
+    const int done = *sm.done[stream];
     const int r = blockIdx.x;
     const int j = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (j >= d) return;
@@ -27,20 +30,17 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *E, const int32_t *i
     if (emb_rows) {
         v = *reinterpret_cast<const float4 *>(emb_rows + (size_t)r * d + j);
     } else if (sizeof(T) == 2) {
-        const uint2 u = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(E) + (size_t)ids[r] * d + j);
+        const int id = ids.p[stream][r];
+        const uint2 u = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(E) + (size_t)id * d + j);
         v = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
                         __uint_as_float(u.y & 0xFFFF0000u));
     } else {
-        v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(E) + (size_t)ids[r] * d + j);
+        v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(E) + (size_t)ids.p[stream][r] * d + j);
     }
     if (done) return;
-    float *dst = sizeof(T) == 2 ? x + act_off(r, j, d / 32) : x + (size_t)r * d + j;
+    const int row = (stream << sm.shift) + r;
+    float *dst = sizeof(T) == 2 ? x + act_off(row, j, d / 32) : x + (size_t)row * d + j;
     *reinterpret_cast<float4 *>(dst) = v;
-    if (dup) {   // the second stream sees the same tokens
-        const int r2 = r + SJD_STREAM_ROWS;
-        dst = sizeof(T) == 2 ? x + act_off(r2, j, d / 32) : x + (size_t)r2 * d + j;
-        *reinterpret_cast<float4 *>(dst) = v;
-    }
 }
 
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
@@ -141,15 +141,21 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *part, int
 // ---------------------------------------------------------------------------------------------
 #define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
 
-int sjd_launch_embed(const sjd_model *m, const int32_t *ids, const float *emb_rows, int32_t rows, int32_t dup, float *x,
-                     const SjdState *st, hipStream_t s)
+int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
+                     const SjdStreams &sm, float *x, hipStream_t s)
 {
-    if (dup && rows > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows < 1 || rows > (1 << sm.shift) ||
+        (sm.count << sm.shift) > SJD_ROWS_MAX)
+        return SJD_EINVAL;
+    if (m->cfg.dtype == 0 && sm.count != 1) return SJD_EINVAL;
     const int d = m->cfg.d_model;
+    EmbedIds e;
+    for (int i = 0; i < SJD_MAX_STREAMS; ++i) e.p[i] = (ids && i < sm.count) ? ids[i] : nullptr;
+    const dim3 grid(rows, (d + 1023) / 1024, sm.count);
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const float *)m->E, ids, emb_rows, d, dup, x, st);
+        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm, x);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, dim3(rows, (d + 1023) / 1024), dim3(256), 0, s, (const bf16_t *)m->E, ids, emb_rows, d, dup, x, st);
+        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm, x);
     LAUNCH_CHECK();
     return SJD_OK;
 }
