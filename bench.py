@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--no-refine", action="store_true", help="ablation: no refinement of unaccepted drafts")
     ap.add_argument("--cfg", type=float, default=None,
                     help="classifier-free guidance weight: run a second (unconditional) context in every forward")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="images decoded together, one pass over the weights per iteration (window x batch <= 32 rows)")
     ap.add_argument("--skip-ar", action="store_true", help="skip the auto-regressive (window 1) image")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reference for scaling HBM traffic counters)")
@@ -121,6 +123,8 @@ def main():
     t0 = time.perf_counter()
     m = B.sjd_init_model(B.config_from_shape(shape), blob)
     kv = B.sjd_kv_create(m)
+    nb = args.batch
+    kvs = [kv] + [B.sjd_kv_create(m) for _ in range(nb - 1)]
     log(f"model on device in {time.perf_counter() - t0:.1f} s")
     if args.no_graph:
         B.sjd_kv_use_graph(kv, False)
@@ -134,20 +138,38 @@ def main():
     if guided and L > 16:
         print("bench.py: --cfg needs a window of at most 16 tokens", file=sys.stderr)
         sys.exit(2)
+    if nb > 1 and (guided or shape.dtype != 1 or nb > 8 or nb * (1 << max(0, (L - 1).bit_length())) > 32):
+        print("bench.py: --batch needs a bf16 model, no --cfg, and window x batch within 32 rows", file=sys.stderr)
+        sys.exit(2)
+    # every image of a batch has its own prompt (same length, different ids)
+    prompts = [ids] + [synth.random_tokens(len(ids), 0, shape.samp_lo or shape.vocab_total, seed=200 + b)
+                       for b in range(1, nb)]
 
     image = [args.seed]
 
     def new_image():
-        B.sjd_prefill(m, kv, ids, emb, smp, init, q_first)
-        if guided:
-            B.sjd_prefill_uncond(m, kv, u_ids, None, args.cfg, smp, init, q_first)
-        B.sjd_decode_begin(m, kv, q_first, N, L, smp, init, image[0])
-        image[0] += 1
+        for b, h in enumerate(kvs):
+            B.sjd_prefill(m, h, prompts[b] if len(ids) else ids, emb, smp, init, q_first)
+            if guided:
+                B.sjd_prefill_uncond(m, h, u_ids, None, args.cfg, smp, init, q_first)
+            B.sjd_decode_begin(m, h, q_first, N, L, smp, init, image[0])
+            image[0] += 1
         torch.cuda.synchronize()
 
     def safe_steps():
-        fixed, _, done = B.sjd_decode_status(kv)
-        return 0 if done else (N - 2 - fixed) // L, fixed
+        """iterations every image can still run without finishing, tokens fixed so far (all images)"""
+        safe, fixed_all = 1 << 30, 0
+        for h in kvs:
+            fixed, _, done = B.sjd_decode_status(h)
+            safe = min(safe, 0 if done else (N - 2 - fixed) // L)
+            fixed_all += fixed
+        return safe, fixed_all
+
+    def steps(k):
+        if nb > 1:
+            B.sjd_decode_steps_batch(m, kvs, k)
+        else:
+            B.sjd_decode_steps(m, kv, k)
 
     def run_steps(k, timed):
         """exactly k iterations of a live generation; returns (seconds, tokens fixed)"""
@@ -160,10 +182,10 @@ def main():
             seg = min(k, safe)
             torch.cuda.synchronize()
             t = time.perf_counter()
-            B.sjd_decode_steps(m, kv, seg)
+            steps(seg)
             torch.cuda.synchronize()
             secs += time.perf_counter() - t
-            fixed1, _, _ = B.sjd_decode_status(kv)
+            _, fixed1 = safe_steps()
             toks += fixed1 - fixed0
             k -= seg
         return secs, toks
@@ -179,7 +201,7 @@ def main():
     safe, _ = safe_steps()
     if safe < prof_steps:
         new_image()
-    p = B.sjd_profile_steps(m, kv, prof_steps)
+    p = B.sjd_profile_steps_batch(m, kvs, prof_steps) if nb > 1 else B.sjd_profile_steps(m, kv, prof_steps)
     classes = {}
     for i, name in enumerate(B.PROF_KINDS):
         ms, by, n = p.ms[i], p.bytes[i], p.launches[i]
@@ -192,7 +214,8 @@ def main():
     g["ms_per_step_back_to_back"] = p.ms_gemm_back_to_back / prof_steps
     g["us_per_launch"] = p.ms_gemm_back_to_back * 1e3 / p.launches[0]
     g["GBps"] = (p.bytes[0] / 1e9) / (p.ms_gemm_back_to_back / 1e3)
-    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload)
+    # (the counter runs were made on the default configuration only)
+    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload) if nb == 1 and not guided and args.window == 0 else None
     roofline = {"bound": "hbm", "kernel": "gemm_fused_kernel (all projections + LM head)" if shape.dtype == 1
                 else "gemm_f32_kernel", "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
@@ -207,6 +230,10 @@ def main():
     extra = {}
 
     def generate(window):
+        if nb > 1:
+            t, sts = B.sjd_generate_batch(m, kvs, prompts, None if not len(emb) else [emb] * nb, N, window, smp, init,
+                                          [args.seed + b for b in range(nb)])
+            return t, sts[0]
         if guided:
             return B.sjd_generate_cfg(m, kv, ids, emb, u_ids, None, args.cfg, N, window, smp, init, args.seed)
         return B.sjd_generate(m, kv, ids, emb, N, window, smp, init, args.seed)
@@ -216,27 +243,28 @@ def main():
         _, st = generate(L)
         extra["sjd_forwards_per_image"] = st.steps
         extra["sjd_image_seconds"] = st.ms_decode / 1e3
-        extra["sjd_image_tokens_per_s"] = N / (st.ms_decode / 1e3)
+        extra["sjd_image_tokens_per_s"] = nb * N / (st.ms_decode / 1e3)
         if not args.skip_ar:
             _, sa = generate(1)
             extra["ar_forwards_per_image"] = sa.steps
             extra["ar_image_seconds"] = sa.ms_decode / 1e3
-            extra["ar_image_tokens_per_s"] = N / (sa.ms_decode / 1e3)
+            extra["ar_image_tokens_per_s"] = nb * N / (sa.ms_decode / 1e3)
             extra["step_compression"] = sa.steps / st.steps
             extra["latency_speedup_vs_ar"] = sa.ms_decode / st.ms_decode
             log(f"images: SJD {st.steps} forwards / {st.ms_decode:.0f} ms, AR {sa.steps} forwards / {sa.ms_decode:.0f} ms "
                 f"({time.perf_counter() - t:.1f} s)")
         else:
             log(f"image: SJD {st.steps} forwards / {st.ms_decode:.0f} ms")
-    B.sjd_kv_free(kv)
+    for h in kvs:
+        B.sjd_kv_free(h)
     B.sjd_free_model(m)
 
     cpu_steps = args.cpu_steps
     if cpu_steps < 0:
         cpu_steps = 2 if shape.n_params() > 2e9 else (6 if shape.n_params() > 1e8 else 40)
     cpu = None
-    if guided:
-        cpu_steps = 0          # the CPU leg times the unguided path only
+    if guided or nb > 1:
+        cpu_steps = 0          # the CPU leg times the unguided single-image path only
     if cpu_steps > 0:
         log("timing the CPU oracle on a bounded sample ...")
         cpu = cpu_baseline(w, blob, ids, emb, args.seed, cpu_steps)
@@ -246,7 +274,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "window_L": L, "top_k": w.top_k, "temperature": w.temperature,
-                   "init_mode": w.init_mode, "no_refine": bool(args.no_refine), "cfg_weight": args.cfg,
+                   "init_mode": w.init_mode, "no_refine": bool(args.no_refine), "cfg_weight": args.cfg, "batch_images": nb,
                    "uncond_prompt_positions": len(u_ids) if guided else None,
                    "image_tokens_N": N, "prompt_positions": len(ids) + len(emb), "layers": shape.n_layers,
                    "d_model": shape.d_model, "sampling_vocab": shape.v_s, "hip_graph": not args.no_graph,

@@ -187,6 +187,9 @@ typedef struct {
     double ms_gemm_back_to_back;
 } sjd_profile;
 int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream);
+/* the same for iterations of sjd_decode_steps_batch */
+int sjd_profile_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_steps, sjd_profile *out,
+                            void *stream);
 
 /* ---- batched decoding --------------------------------------------------------------------------
  * B independent images share every window forward (Sec. 4.1 Step 2 for B windows at once): one pass

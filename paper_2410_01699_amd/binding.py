@@ -23,7 +23,7 @@ EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "
            "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror", "sjd_decode_begin",
            "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps", "sjd_gemm_bench",
            "sjd_prefill_uncond", "sjd_generate_cfg", "sjd_decode_steps_batch", "sjd_forward_logits_batch",
-           "sjd_generate_batch"]
+           "sjd_generate_batch", "sjd_profile_steps_batch"]
 
 PROF_KINDS = ("gemm", "attention", "elementwise", "verify")
 
@@ -85,6 +85,7 @@ _SIG = {
     "sjd_forward_logits": (C.c_int, [_vp, _vp, _vp, _i32, _vp, _vp]),
     "sjd_forward_logits_batch": (C.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp]),
     "sjd_decode_steps_batch": (C.c_int, [_vp, _vp, _i32, _i32, _vp]),
+    "sjd_profile_steps_batch": (C.c_int, [_vp, _vp, _i32, _i32, _P(sjd_profile), _vp]),
     "sjd_generate_batch": (C.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _vp,
                                      _vp, _vp]),
     "sjd_verify": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _vp, _vp, _u64, _u64,
@@ -305,6 +306,12 @@ def sjd_kv_use_graph(kv, on: bool):
 def sjd_profile_steps(m, kv, n_steps, stream=None) -> sjd_profile:
     p = sjd_profile()
     _check(_lib.sjd_profile_steps(m, kv, n_steps, C.byref(p), _stream(stream)))
+    return p
+
+
+def sjd_profile_steps_batch(m, kvs, n_steps, stream=None) -> sjd_profile:
+    p = sjd_profile()
+    _check(_lib.sjd_profile_steps_batch(m, _handles(kvs), len(kvs), n_steps, C.byref(p), _stream(stream)))
     return p
 
 

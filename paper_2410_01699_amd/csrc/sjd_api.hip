@@ -1046,10 +1046,11 @@ extern "C" int sjd_generate_cfg(sjd_model *m, sjd_kv *kv, const int32_t *ids, in
 }
 
 // ---- per-kernel-class timing of eager iterations (HIP events on the launch stream) ------------
-extern "C" int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream)
+// kvs[0] carries the profiler; B == 0: the single-handle iteration of kvs[0]
+static int profile_steps(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_steps, sjd_profile *out, hipStream_t s)
 {
-    if (!m || !kv || kv->m != m || n_steps < 1 || !out || !kv->dec_active) return SJD_EINVAL;
-    hipStream_t s = (hipStream_t)stream;
+    sjd_kv *kv = kvs[0];
+    auto one = [&]() { return B ? decode_one_batch(m, kvs, B, s) : decode_one(m, kv, s); };
     memset(out, 0, sizeof(*out));
     SjdProfiler prof;
     prof.hook.next = SjdProfiler::next; prof.hook.self = &prof; prof.hook.cur_kind = 0; prof.hook.only_kind = -1;
@@ -1057,7 +1058,7 @@ extern "C" int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_
     sjd_launch_hook = &prof.hook;
     int rc = SJD_OK;
     for (int i = 0; i < n_steps && rc == SJD_OK; ++i) {
-        rc = decode_one(m, kv, s);
+        rc = one();
         if (rc == SJD_OK) rc = prof.drain(out, s);
     }
     // second pass: the projections of n_steps iterations alone, back to back, inside one event pair
@@ -1067,9 +1068,9 @@ extern "C" int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_
         hipEvent_t e0 = nullptr, e1 = nullptr;
         prof.hook.next = nullptr; prof.hook.only_kind = SJD_PROF_GEMM;
         if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) rc = SJD_EHIP;
-        if (rc == SJD_OK) rc = decode_one(m, kv, s);                       // warm-up
+        if (rc == SJD_OK) rc = one();                                      // warm-up
         if (rc == SJD_OK && hipEventRecord(e0, s) != hipSuccess) rc = SJD_EHIP;
-        for (int i = 0; i < n_steps && rc == SJD_OK; ++i) rc = decode_one(m, kv, s);
+        for (int i = 0; i < n_steps && rc == SJD_OK; ++i) rc = one();
         if (rc == SJD_OK && hipEventRecord(e1, s) != hipSuccess) rc = SJD_EHIP;
         if (rc == SJD_OK && hipEventSynchronize(e1) != hipSuccess) rc = SJD_EHIP;
         float ms = 0.f;
@@ -1083,6 +1084,21 @@ extern "C" int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_
     prof.destroy();
     out->steps = n_steps;
     return rc;
+}
+
+extern "C" int sjd_profile_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, sjd_profile *out, void *stream)
+{
+    if (!m || !kv || kv->m != m || n_steps < 1 || !out || !kv->dec_active) return SJD_EINVAL;
+    sjd_kv *one[1] = {kv};
+    return profile_steps(m, one, 0, n_steps, out, (hipStream_t)stream);
+}
+
+extern "C" int sjd_profile_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_steps, sjd_profile *out,
+                                       void *stream)
+{
+    if (!kvs || B < 1 || !kvs[0] || n_steps < 1 || !out) return SJD_EINVAL;
+    SJD_TRY(check_batch(m, kvs, B, kvs[0]->dec_L, true));
+    return profile_steps(m, kvs, B, n_steps, out, (hipStream_t)stream);
 }
 
 // ---- hooks ----------------------------------------------------------------------------------
