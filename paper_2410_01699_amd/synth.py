@@ -103,6 +103,7 @@ def _shape(layers, d, heads, ffn, vocab, lo, hi, max_seq, dtype):
 
 _SHAPE_7B_SHORT = _shape(32, 4096, 32, 11008, 65536, 57344, 65536, 64 + 1024 + 32, DTYPE_BF16)
 _SHAPE_7B_LONG = _shape(32, 4096, 32, 11008, 65536, 57344, 65536, 64 + 2352 + 32, DTYPE_BF16)
+_SHAPE_7B_1024 = _shape(32, 4096, 32, 11008, 65536, 57344, 65536, 64 + 4160 + 32, DTYPE_BF16)
 
 WORKLOADS = {
     # Tiny: 2 layers, d=128, vocab 1024 all image codes, 8x8 grid.
@@ -118,6 +119,8 @@ WORKLOADS = {
     # same with drafts initialised from the token one grid row above.
     "7b_48x48_above": Workload("7b_48x48_above", _SHAPE_7B_LONG, 64, 0, 2352, 32, 2000, 1.0,
                                INIT_REPEAT_ABOVE, 49, 65535),
+    # 7B, 64x64 grid (a 1024 x 1024 image at 16 x 16 pixels per code) + row-end tokens: 4160 tokens.
+    "7b_64x64": Workload("7b_64x64", _SHAPE_7B_1024, 64, 0, 4160, 16, 2000, 1.0, INIT_UNIFORM, 65, 65535),
 }
 
 

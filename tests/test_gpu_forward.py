@@ -396,6 +396,18 @@ def test_sampled_initialisers_graph_replay(B):
         g.close()
 
 
+def test_forward_bf16_cache_of_a_1024_image(B):
+    """a cache as long as the 64 x 64 grid needs (about 4200 positions: 132 blocks of 32 per head, 16 key
+    splits of 8-9 blocks), windows of 16 at its far end"""
+    shape = synth.ModelShape(2, 512, 4, 1024, 4096, 2048, 4096, 4256, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=12)
+    prompt = synth.random_tokens(4190, 0, 2048, seed=1)
+    toks = synth.random_tokens(64, 2048, 4096, seed=2)
+    windows = [(toks[:16], 16), (toks[16:32], 3), (toks[32:48], 16), (toks[48:64], 1)]
+    worst = _check_forward(B, shape, blob, prompt, windows, TOL_BF16)
+    _say(f"bf16 4200-position cache worst {worst:.3e}")
+
+
 # ------------------------------------------------------------------ long caches, wide windows, ragged ends
 def test_forward_bf16_long_cache_window32(B):
     """head size 128, window 32, a cache of ~2300 positions (16 key splits, many 32-position blocks, a
