@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--batch", type=int, default=1,
                     help="images decoded together, one pass over the weights per iteration (window x batch <= 32 rows)")
     ap.add_argument("--skip-ar", action="store_true", help="skip the auto-regressive (window 1) image")
+    ap.add_argument("--also", default=None,
+                    help="a second workload measured afterwards in a child process and summarised under "
+                         "config.also_measured ('none' = skip; default: 775m when the 7B default runs unmodified)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -282,6 +285,29 @@ def main():
                    "step_weight_stream_GBps": weight_bytes / 1e9 / (ms_per_step / 1e3), **extra},
         "roofline": roofline, "kernel_classes": classes, "cpu_baseline": cpu,
     }
+    also = args.also
+    if also is None:
+        plain = (args.workload == "7b_32x32" and nb == 1 and not guided and args.window == 0 and args.top_k == 0
+                 and args.init_mode < 0 and not args.no_refine and not args.no_graph)
+        also = "775m" if plain else "none"
+    if also != "none":
+        # the class-conditional configuration, same measurement without the CPU leg, in a process of its own
+        # (this one has released the GPU memory; its line is parsed, not re-printed)
+        import subprocess
+        log(f"measuring workload {also} in a child process ...")
+        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", also, "--also", "none", "--cpu-steps", "0",
+                            "--steps", str(args.steps), "--warmup", str(args.warmup)], capture_output=True, text=True)
+        line = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+        if r.returncode == 0 and line:
+            o = json.loads(line[-1])
+            out["config"]["also_measured"] = {also: {
+                "value": o["value"], "unit": o["unit"], "ms_per_step": o["ms_per_step"], "dtype": o["dtype"],
+                "window_L": o["config"]["window_L"], "tokens_fixed_per_step": o["config"]["tokens_fixed_per_step"],
+                "sjd_forwards_per_image": o["config"].get("sjd_forwards_per_image"),
+                "ar_forwards_per_image": o["config"].get("ar_forwards_per_image"),
+                "roofline": {k: o["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac")}}}
+        else:
+            out["config"]["also_measured"] = {also: {"error": (r.stderr or "no output")[-300:]}}
     print(json.dumps(out), flush=True)
 
 

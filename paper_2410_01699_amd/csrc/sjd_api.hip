@@ -176,7 +176,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
 extern "C" void sjd_kv_free(sjd_kv *kv)
 {
     if (!kv) return;
-    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->ring, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
+    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->ring, kv->cfg_tab, kv->btab, kv->tokens, kv->state, kv->x, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
                     kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
                     kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
     for (void *p : ptrs) if (p) (void)hipFree(p);
@@ -241,6 +241,8 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     A(kv->g_nacc, 16);
     A(kv->q_first, V * 4);
     A(kv->logits_last, V * 4);
+    A(kv->cfg_tab, 2 * sizeof(SjdStreamEntry));
+    A(kv->btab, SJD_MAX_STREAMS * sizeof(SjdStreamEntry));
 #undef A
     if (rc == SJD_OK) rc = sjd_sample_setup(m->V_s);
     if (rc != SJD_OK) { sjd_kv_free(kv); return rc; }
@@ -397,19 +399,24 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
 
 // the streams of one handle: its conditional context alone (mode 0), its unconditional one alone (1),
 // or both in rows 0.. and SJD_STREAM_ROWS.. (2)
+static SjdStreamEntry handle_entry(const sjd_kv *kv, bool uncond)
+{
+    const SjdState *st = kv->state;
+    SjdStreamEntry e;
+    e.n = uncond ? &st->n_u : &st->n;
+    e.done = &st->done;
+    e.kvc = (bf16_t *)(uncond ? kv->k_u : kv->k);
+    return e;
+}
+
 static SjdStreams handle_streams(const sjd_kv *kv, int32_t stream_mode)
 {
     SjdStreams sm;
     memset(&sm, 0, sizeof(sm));
-    const SjdState *st = kv->state;
     sm.count = stream_mode == 2 ? 2 : 1;
     sm.shift = stream_mode == 2 ? 4 : 5;
-    for (int i = 0; i < sm.count; ++i) {
-        const bool uncond = stream_mode == 1 || i == 1;
-        sm.n[i] = uncond ? &st->n_u : &st->n;
-        sm.done[i] = &st->done;
-        sm.kvc[i] = (bf16_t *)(uncond ? kv->k_u : kv->k);
-    }
+    sm.first = handle_entry(kv, stream_mode == 1);
+    sm.table = stream_mode == 2 ? kv->cfg_tab : nullptr;     // filled when the second cache is allocated
     return sm;
 }
 
@@ -587,14 +594,19 @@ extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
 
 static int alloc_uncond_cache(sjd_kv *kv)
 {
-    if (kv->k_u) return SJD_OK;
     const sjd_config &c = kv->m->cfg;
-    if (c.dtype == 1) {
-        SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 2));
-    } else {
-        SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 4));
-        SJD_TRY(dev_alloc(&kv->v_u, (size_t)c.n_layers * kv->v_layer_stride * 4));
+    if (!kv->k_u) {
+        if (c.dtype == 1) {
+            SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 2));
+        } else {
+            SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 4));
+            if (!kv->v_u) SJD_TRY(dev_alloc(&kv->v_u, (size_t)c.n_layers * kv->v_layer_stride * 4));
+        }
     }
+    if (c.dtype == 0 && !kv->v_u) SJD_TRY(dev_alloc(&kv->v_u, (size_t)c.n_layers * kv->v_layer_stride * 4));
+    // the table of the handle's two contexts, read by the kernels of a two-stream forward
+    const SjdStreamEntry two[2] = {handle_entry(kv, false), handle_entry(kv, true)};
+    HIP_TRY(hipMemcpy(kv->cfg_tab, two, sizeof(two), hipMemcpyHostToDevice));
     return SJD_OK;
 }
 
@@ -793,14 +805,29 @@ static int check_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t L, b
     return batch_shift(B, L) < 0 ? SJD_EINVAL : SJD_OK;
 }
 
+// The table of the batch lives in the first handle; it is rewritten (after the stream has drained:
+// kernels in flight may still read it) only when the set of handles changes.  Not to be called
+// while a stream is being captured.
+static int prepare_batch_table(sjd_kv *const *kvs, int32_t B, hipStream_t s)
+{
+    sjd_kv *kv0 = kvs[0];
+    SjdStreamEntry want[SJD_MAX_STREAMS];
+    memset(want, 0, sizeof(want));
+    for (int b = 0; b < B; ++b) want[b] = handle_entry(kvs[b], false);
+    if (memcmp(want, kv0->btab_host, sizeof(want)) == 0) return SJD_OK;
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipMemcpy(kv0->btab, want, sizeof(want), hipMemcpyHostToDevice));
+    memcpy(kv0->btab_host, want, sizeof(want));
+    return SJD_OK;
+}
+
 static SjdStreams batch_streams(sjd_kv *const *kvs, int32_t B, int32_t L)
 {
     SjdStreams sm;
     memset(&sm, 0, sizeof(sm));
     sm.count = B; sm.shift = batch_shift(B, L);
-    for (int b = 0; b < B; ++b) {
-        sm.n[b] = &kvs[b]->state->n; sm.done[b] = &kvs[b]->state->done; sm.kvc[b] = (bf16_t *)kvs[b]->k;
-    }
+    sm.first = handle_entry(kvs[0], false);
+    sm.table = kvs[0]->btab;
     return sm;
 }
 
@@ -843,6 +870,7 @@ extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t 
     sjd_kv *kv0 = kvs[0];
     SJD_TRY(check_batch(m, kvs, B, kv0->dec_L, true));
     hipStream_t s = (hipStream_t)stream;
+    SJD_TRY(prepare_batch_table(kvs, B, s));
     if (!kv0->use_graph) {
         for (int i = 0; i < n_steps; ++i) SJD_TRY(decode_one_batch(m, kvs, B, s));
         return SJD_OK;
@@ -877,9 +905,10 @@ extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t 
     return SJD_OK;
 }
 
-__global__ void clear_done_batch_kernel(SjdStreams sm)
+struct DoneFlags { int32_t *p[SJD_MAX_STREAMS]; int32_t count; };
+__global__ void clear_done_batch_kernel(DoneFlags f)
 {
-    if ((int)threadIdx.x < sm.count) *const_cast<int32_t *>(sm.done[threadIdx.x]) = 0;
+    if ((int)threadIdx.x < f.count) *f.p[threadIdx.x] = 0;
 }
 
 extern "C" int sjd_forward_logits_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *tokens, int32_t L,
@@ -889,12 +918,13 @@ extern "C" int sjd_forward_logits_batch(sjd_model *m, sjd_kv *const *kvs, int32_
     SJD_TRY(check_batch(m, kvs, B, L, false));
     for (int b = 0; b < B; ++b) SJD_TRY(check_room(kvs[b], L));
     hipStream_t s = (hipStream_t)stream;
+    SJD_TRY(prepare_batch_table(kvs, B, s));
     const SjdStreams sm = batch_streams(kvs, B, L);
     // a handle that is not inside a generation computes regardless of how its last one ended; one that
     // is keeps its finished flag (its rows are skipped once its image is complete)
-    SjdStreams idle = sm;
-    idle.count = 0;
-    for (int b = 0; b < B; ++b) if (!kvs[b]->dec_active) idle.done[idle.count++] = sm.done[b];
+    DoneFlags idle;
+    memset(&idle, 0, sizeof(idle));
+    for (int b = 0; b < B; ++b) if (!kvs[b]->dec_active) idle.p[idle.count++] = &kvs[b]->state->done;
     if (idle.count) {
         SJD_LAUNCH(clear_done_batch_kernel, dim3(1), dim3(64), 0, s, idle);
         HIP_TRY(hipGetLastError());
@@ -930,17 +960,21 @@ extern "C" int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, c
     }
     HIP_TRY(hipStreamSynchronize(s));
     auto t1 = std::chrono::steady_clock::now();
-    // iterations are enqueued eight at a time; a handle whose image is complete sits out the rest
-    // (its rows are still computed, its kernels of the verification return at once)
-    int enq = 0, all_done = 0;
+    // iterations are enqueued a few at a time, never more than the image furthest from its end can
+    // still take; a handle whose image is complete sits out the rest (its rows are still computed, its
+    // attention and verification kernels return at once)
+    int enq = 0, all_done = 0, most_left = N - 1;
     while (!all_done) {
-        SJD_TRY(sjd_decode_steps_batch(m, kvs, B, 8, s));
-        enq += 8;
+        const int k = std::max(1, std::min(8, (most_left + L - 1) / L));
+        SJD_TRY(sjd_decode_steps_batch(m, kvs, B, k, s));
+        enq += k;
         all_done = 1;
+        most_left = 0;
         for (int b = 0; b < B; ++b) {
-            int done = 0;
-            SJD_TRY(sjd_decode_status(kvs[b], nullptr, nullptr, &done));
+            int done = 0, fixed = 0;
+            SJD_TRY(sjd_decode_status(kvs[b], &fixed, nullptr, &done));
             all_done &= done;
+            if (!done) most_left = std::max(most_left, N - 1 - fixed);
         }
         if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every iteration fixes at least one token per image
     }
@@ -1009,13 +1043,14 @@ static int generate_common(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
     SJD_TRY(sjd_decode_begin(m, kv, kv->q_first, N, L, smp, init, philox_seed, s));
     HIP_TRY(hipStreamSynchronize(s));
     auto t1 = std::chrono::steady_clock::now();
-    // Iterations are enqueued in batches; the kernels of an iteration that starts after the
-    // generation has finished return at once (state->done), so over-enqueueing is harmless.
-    int enq = 0, done = 0;
+    // Iterations are enqueued a few at a time, never more than the image can still take (an iteration
+    // fixes at most L tokens): the forward of an iteration past the end would be wasted work.
+    int enq = 0, done = 0, fixed = 0;
     while (!done) {
-        SJD_TRY(sjd_decode_steps(m, kv, 8, s));
-        enq += 8;
-        SJD_TRY(sjd_decode_status(kv, nullptr, nullptr, &done));
+        const int k = std::max(1, std::min(8, (N - 1 - fixed + L - 1) / L));
+        SJD_TRY(sjd_decode_steps(m, kv, k, s));
+        enq += k;
+        SJD_TRY(sjd_decode_status(kv, &fixed, nullptr, &done));
         if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every iteration fixes at least one token
     }
     auto t2 = std::chrono::steady_clock::now();
@@ -1098,6 +1133,7 @@ extern "C" int sjd_profile_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t
 {
     if (!kvs || B < 1 || !kvs[0] || n_steps < 1 || !out) return SJD_EINVAL;
     SJD_TRY(check_batch(m, kvs, B, kvs[0]->dec_L, true));
+    SJD_TRY(prepare_batch_table(kvs, B, (hipStream_t)stream));
     return profile_steps(m, kvs, B, n_steps, out, (hipStream_t)stream);
 }
 

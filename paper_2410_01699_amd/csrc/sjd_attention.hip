@@ -182,8 +182,10 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
 {
     // blockIdx.z = stream: its own cache and cache length, queries in rows (stream << shift)..
     const int stream = blockIdx.z;
-    if (*sm.done[stream]) return;
-    const bf16_t *__restrict__ kvc = sm.kvc[stream] + layer_off;
+    const SjdStreamEntry ent = stream_entry(sm, stream);
+    if (*ent.done) return;
+    const int n = *ent.n;
+    const bf16_t *__restrict__ kvc = ent.kvc + layer_off;
     const int row0 = stream << sm.shift;
     part += (size_t)stream * gridDim.x * splits * (MT * 16 * HD + 2 * MT * 16);
     constexpr int KS = HD / 32;      // k-steps of the score product
@@ -194,7 +196,6 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     __shared__ bf16x8 q_lds[MT][KS][2][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     const int head = blockIdx.x, split = blockIdx.y;
-    const int n = *sm.n[stream];
     const int total = n + rows;
     const int nblk = (total + 31) >> 5;
     const int bps = (nblk + splits - 1) / splits;
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
 #define ATT_MAX_SPLITS 16
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
-                                                        float *__restrict__ out, SjdStreams sm)
+                                                        float *__restrict__ out, int shift)
 {
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
@@ -354,7 +355,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
     const int q = u / Q4, j4 = u % Q4;
     float ms[ATT_MAX_SPLITS], ls[ATT_MAX_SPLITS];
     f32x4 os[ATT_MAX_SPLITS];
-    const int done = *sm.done[stream];
 #pragma unroll
     for (int s = 0; s < ATT_MAX_SPLITS; ++s) {
         const float *p = base + (size_t)(s < splits ? s : 0) * REC;
@@ -362,7 +362,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         ls[s] = p[MT * 16 * HD + MT * 16 + q];
         os[s] = *reinterpret_cast<const f32x4 *>(p + (size_t)q * HD + j4 * 4);
     }
-    if (done) return;
     float M = -INFINITY;
 #pragma unroll
     for (int s = 0; s < ATT_MAX_SPLITS; ++s) if (s < splits) M = fmaxf(M, ms[s]);
@@ -374,7 +373,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         num += w * os[s];
         den += w * ls[s];
     }
-    *reinterpret_cast<f32x4 *>(out + act_off(q + (stream << sm.shift), head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
+    *reinterpret_cast<f32x4 *>(out + act_off(q + (stream << shift), head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -430,7 +429,7 @@ static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
                        kv->nblk, rows, splits, kv->att_part);
     HIP_TRY(hipGetLastError());
     SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256, sm.count), dim3(256), 0, s, kv->att_part,
-                       splits, d, rows, (float *)kv->att_out, sm);
+                       splits, d, rows, (float *)kv->att_out, sm.shift);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }

@@ -69,12 +69,12 @@ __device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, in
         // table reads are scalar loads; the selection is per lane)
         const int stream = m >> ep.sm.shift;
         pre.row = m & ((1 << ep.sm.shift) - 1);
-        int n_s = 0;
-        pre.cache = nullptr;
-        for (int s = 0; s < ep.sm.count; ++s) {
-            const int n_here = *ep.sm.n[s];
-            bf16_t *c_here = ep.sm.kvc[s];
-            if (s == stream) { n_s = n_here; pre.cache = c_here + ep.layer_off; }
+        int n_s = ep.sm.count > 0 ? *ep.sm.first.n : 0;
+        pre.cache = (stream == 0 && ep.sm.count > 0) ? ep.sm.first.kvc + ep.layer_off : nullptr;
+        for (int s = 1; s < ep.sm.count; ++s) {            // uniform index: scalar table reads
+            const SjdStreamEntry e = ep.sm.table[s];
+            const int n_here = *e.n;
+            if (s == stream) { n_s = n_here; pre.cache = e.kvc + ep.layer_off; }
         }
         pre.pos = min(n_s + pre.row, ep.max_seq - 1);   // rows past the window are computed but never stored
         // (V fragments fetch factors they do not use: no branch around the loads)
@@ -219,13 +219,11 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
             }                                                                                     \
         }
 
+    // (An iteration enqueued after its generation has finished is not skipped here: it recomputes rows
+    // nobody reads, inside the buffers and the cache, and the verification that follows leaves the
+    // loop state alone.  Reading a finished flag first would put a dependent scalar load in front of
+    // every launch's first weight loads.)
     LOAD_STAGE(kt0, a0, b0, g0)
-    // the finished flags (every stream's generation is over: nothing to do) are only needed before
-    // anything is written; read behind the first stage's loads so that those are not held up
-    __builtin_amdgcn_sched_barrier(0);
-    int finished = ep.sm.count > 0;
-    for (int s = 0; s < ep.sm.count; ++s) finished &= *ep.sm.done[s];
-    if (finished) return;
     // epilogue fragment of this thread (threads past MT*TN*64 have none and fetch a duplicate): D
     // layout of tile mtn puts features 4*(l/16) .. +4 of token l%16 in lane l
     const bool has_frag = threadIdx.x < MT * TN * 64;

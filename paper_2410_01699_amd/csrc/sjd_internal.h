@@ -83,13 +83,25 @@ __device__ __forceinline__ int state_n(const SjdState *st, int stream) { return 
 // [s << shift, (s + 1) << shift) of every activation matrix (count << shift <= 32), has its own cache
 // and its own cache length; the weights are streamed once for all of them.
 #define SJD_MAX_STREAMS 8
-struct SjdStreams {
-    int32_t count;                          // 0 (no device state: kernel test hooks) .. SJD_MAX_STREAMS
-    int32_t shift;                          // log2 of the rows reserved per stream
-    const int32_t *n[SJD_MAX_STREAMS];      // device: the stream's cache length
-    const int32_t *done[SJD_MAX_STREAMS];   // device: its generation has finished (kernels skip its work)
-    bf16_t *kvc[SJD_MAX_STREAMS];           // its cache, layer 0 (kernels add the layer offset)
+struct SjdStreamEntry {
+    const int32_t *n;       // device: the stream's cache length
+    const int32_t *done;    // device: its generation has finished (kernels skip its work)
+    bf16_t *kvc;            // its cache, layer 0 (kernels add the layer offset)
 };
+// Passed to kernels by value, so it is kept small (every kernel waits for its arguments): stream 0
+// travels inside, the others are looked up in a table in device memory.
+struct SjdStreams {
+    int32_t count;                  // 0 (no device state: kernel test hooks) .. SJD_MAX_STREAMS
+    int32_t shift;                  // log2 of the rows reserved per stream
+    SjdStreamEntry first;           // stream 0
+    const SjdStreamEntry *table;    // device [count]: every stream (entry 0 repeats `first`); unused when count <= 1
+};
+// entry of stream s, s uniform across the wave
+__device__ __forceinline__ SjdStreamEntry stream_entry(const SjdStreams &sm, int s)
+{
+    if (s == 0) return sm.first;
+    return sm.table[s];
+}
 
 // bf16 models keep every activation the projections consume (residual stream, attention output, FFN
 // hidden) as fp32 in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a wave fetches the
@@ -224,6 +236,9 @@ struct sjd_kv {
         const void *kv[SJD_MAX_STREAMS], *state[SJD_MAX_STREAMS], *cache[SJD_MAX_STREAMS], *ring[SJD_MAX_STREAMS];
         uint64_t seed[SJD_MAX_STREAMS];
     } bkey;
+    SjdStreamEntry *cfg_tab;                   // device [2]: the two contexts of this handle under guidance
+    SjdStreamEntry *btab;                      // device [SJD_MAX_STREAMS]: handles of the batch this one leads
+    SjdStreamEntry btab_host[SJD_MAX_STREAMS]; // what btab holds
     float *ring;          // [ring_rows][V_s] distributions of accepted image positions (initialiser (d))
     int32_t ring_rows;
     int32_t graph_cfg_on;   // stream mode and guidance weight the captured iteration was recorded with

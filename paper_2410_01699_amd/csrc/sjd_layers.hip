@@ -18,11 +18,10 @@ template <> struct Act<bf16_t> {
 // consecutive features; grid (rows per stream, d / 1024, streams).
 struct EmbedIds { const int32_t *p[SJD_MAX_STREAMS]; };
 template <typename T>
-__global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, const float *emb_rows, int d, SjdStreams sm,
+__global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, const float *emb_rows, int d, int shift,
                                                     float *x)
 {
     const int stream = blockIdx.z;
-    const int done = *sm.done[stream];
     const int r = blockIdx.x;
     const int j = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (j >= d) return;
@@ -37,8 +36,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, co
     } else {
         v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(E) + (size_t)ids.p[stream][r] * d + j);
     }
-    if (done) return;
-    const int row = (stream << sm.shift) + r;
+    const int row = (stream << shift) + r;
     float *dst = sizeof(T) == 2 ? x + act_off(row, j, d / 32) : x + (size_t)row * d + j;
     *reinterpret_cast<float4 *>(dst) = v;
 }
@@ -153,9 +151,9 @@ int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float 
     for (int i = 0; i < SJD_MAX_STREAMS; ++i) e.p[i] = (ids && i < sm.count) ? ids[i] : nullptr;
     const dim3 grid(rows, (d + 1023) / 1024, sm.count);
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm, x);
+        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm, x);
+        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x);
     LAUNCH_CHECK();
     return SJD_OK;
 }
