@@ -18,6 +18,9 @@ LIB = os.path.join(HERE, "libsjd_hip.so")
 # packed-fp32 instructions are switched off for every device compile (a known hazard on the test machines)
 COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          # leading kernel arguments arrive in SGPRs with the dispatch (no scalar load in front of a
+          # kernel's first memory accesses); kernels keep a fallback prologue for firmware without it
+          "-mllvm", "-amdgpu-kernarg-preload-count=16",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # the sampling file needs every fp32 operation rounded separately (bit-exact contract)
 PER_FILE = {"sjd_sample.hip": ["-ffp-contract=off"]}
