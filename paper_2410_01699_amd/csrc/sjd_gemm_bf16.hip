@@ -163,6 +163,13 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     const int kps = (KT + WK - 1) / WK;
     const int kt0 = wave * kps;
     const int kt1 = min(KT, kt0 + kps);
+    // Workgroups walk their k-range from different starting points (and wrap around): all workgroups
+    // of a launch read the same activation tiles, and in lockstep they would all want the same few
+    // cache lines at the same moment.  The starting point depends on the workgroup index only, so the
+    // summation order of a given output is the same in every launch.
+    const int klen = max(kt1 - kt0, 1);
+    // (short walks gain nothing from it)
+    const int rot = klen >= 16 ? (int)(((((blockIdx.x >> 3) * 0x9E3779B1u) >> 16) * (unsigned)klen) >> 16) : 0;   // in [0, klen)
 
     f32x4 acc[MT][TN];
     float ss[MT];
@@ -188,8 +195,10 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     // range fetches the all-zero tile that follows every activation matrix, for both operands.
 #define LOAD_STAGE(kbase, a, b, gn)                                                               \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                               \
-        const int kq_ = (kbase) + u;                                                              \
-        const bool ok_ = kq_ < kt1;                                                               \
+        const int ki_ = (kbase) + u;              /* position in this wave's walk */              \
+        const bool ok_ = ki_ < kt1;                                                               \
+        const int kr_ = ki_ + rot;                                                                \
+        const int kq_ = kr_ >= kt1 ? kr_ - klen : kr_;                                            \
         const int kw_ = min(kq_, kt1 - 1);                                                        \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {   /* L2 hits first: they return first */ \
             const f32x4 *p = xp + (ok_ ? (size_t)mt * KT + kq_ : (size_t)2 * KT) * 128;           \
