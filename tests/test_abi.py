@@ -39,3 +39,23 @@ def test_error_strings_and_argument_checks_without_gpu():
     assert lib.sjd_init_model(ctypes.byref(cfg), None, ctypes.c_size_t(0), ctypes.byref(out)) == binding.SJD_EINVAL
     assert lib.sjd_kv_create(None, ctypes.byref(out)) == binding.SJD_EINVAL
     assert lib.sjd_step(None, None, None, None, 4, None, None, 0, 0, 0, None, None, None, None) == binding.SJD_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """one GPU only: asking for more exits with a message instead of launching anything"""
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
+
+
+def test_null_arguments_of_the_wider_entry_points_without_gpu():
+    from paper_2410_01699_amd import binding
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    E = binding.SJD_EINVAL
+    assert lib.sjd_prefill_uncond(None, None, None, 0, None, 0, ctypes.c_float(3.0), None, None, None, None) == E
+    assert lib.sjd_decode_steps_batch(None, None, 2, 1, None) == E
+    assert lib.sjd_generate_batch(None, None, 2, None, None, None, None, 8, 4, None, None, None, None, None) == E
+    assert lib.sjd_forward_logits_batch(None, None, 2, None, 4, None, None) == E
+    assert lib.sjd_profile_steps_batch(None, None, 2, 1, None, None) == E
+    assert lib.sjd_generate_cfg(None, None, None, 0, None, 0, None, 0, None, 0, ctypes.c_float(3.0), 8, 4, None, None,
+                                ctypes.c_uint64(0), None, None) == E

@@ -126,6 +126,32 @@ def test_guided_window_logits(B, case):
         p.close()
 
 
+def test_guided_logits_with_embedding_row_prompts(B):
+    """class-conditional style contexts: one id + raw embedding rows on the conditional side (crossing a
+    32-position chunk boundary), a single id on the unconditional side"""
+    shape = synth.ModelShape(3, 384, 6, 1024, 4096, 0, 4096, 140, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=3)
+    rng = np.random.default_rng(4)
+    emb = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits((rng.standard_normal((40, 384)) * 0.02).astype(np.float32))).reshape(40, 384)
+    pc = np.array([7], np.int32); pu = np.array([9], np.int32)
+    smp = B.sjd_sampler(8, 1.0); init = B.sjd_init(0, 0, -1)
+    w = 3.0
+    p = Pair(B, shape, blob, pc, pu, w, smp, init, emb_c=emb)
+    try:
+        assert p.Pc == 41 and B.sjd_kv_len(p.kv) == 41
+        toks = synth.random_tokens(32, 0, 4096, seed=5)
+        n_img = 0
+        for lo_, hi_, keep in ((0, 16, 16), (16, 27, 4), (27, 32, 5)):
+            got = p.gpu_logits(toks[lo_:hi_])
+            ref = p.ref_logits(n_img, toks[lo_:hi_])
+            err = float(np.max(np.abs(got - ref)))
+            assert err < TOL_BF16 * _amp(w), (n_img, err)
+            n_img += keep
+            B.sjd_kv_set_len(p.kv, p.Pc + n_img)
+    finally:
+        p.close()
+
+
 def test_guidance_weight_zero_and_one(B):
     """w = 0 gives the unconditional context's logits (an ordinary one-context forward of the second
     prompt), w = 1 the conditional one's"""
