@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     // summation order of a given output is the same in every launch.
     const int klen = max(kt1 - kt0, 1);
     // (short walks gain nothing from it)
-    const int rot = klen >= 16 ? (int)(((((blockIdx.x >> 3) * 0x9E3779B1u) >> 16) * (unsigned)klen) >> 16) : 0;   // in [0, klen)
+    const int rot = klen >= 16 ? (int)((((blockIdx.x >> 3) & 31u) * (unsigned)klen) >> 5) : 0;   // in [0, klen)
 
     f32x4 acc[MT][TN];
     float ss[MT];
