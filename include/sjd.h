@@ -156,7 +156,9 @@ int sjd_generate_cfg(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids
  * where the next window starts, which is a data dependence, not a host decision).
  *   sjd_decode_begin   after sjd_prefill: first window from q_first (dev [V_s]), counters reset.
  *   sjd_decode_steps   enqueue n_steps iterations on `stream` (one HIP-graph replay each);
- *                      iterations that start after the N-th token is fixed do nothing.
+ *                      an iteration that starts after the N-th token is fixed changes nothing
+ *                      (its forward still runs, on rows nobody reads: do not enqueue far past
+ *                      the end; an iteration fixes at most L tokens).
  *   sjd_decode_status  synchronise; image tokens fixed so far, iterations run, finished flag.
  *   sjd_decode_result  after `done`: the N tokens (host) and the step statistics.
  *   sjd_kv_use_graph   0: launch kernels one by one instead of replaying a captured graph.     */

@@ -65,10 +65,10 @@ struct SjdState {
     int32_t n;          // cache length (prompt + accepted tokens)
     int32_t img_pos0;   // image index of window slot 0
     int32_t L_eff;      // slots of the window in use this step
-    int32_t n_snap;     // n at the start of the step (stable while the step runs)
+    int32_t reserved0;
     uint64_t counter;   // Philox step counter
     int32_t n_image;    // N, image tokens to produce (generate loop; 0 = unbounded single steps)
-    int32_t done;       // generation finished: later steps are no-ops
+    int32_t done;       // generation finished: later steps leave the state and the tokens alone
     int32_t steps;      // window forwards executed
     int32_t accept_hist[65];
     int32_t n_u;        // length of the second (unconditional) cache when guidance is on
@@ -85,7 +85,7 @@ __device__ __forceinline__ int state_n(const SjdState *st, int stream) { return 
 #define SJD_MAX_STREAMS 8
 struct SjdStreamEntry {
     const int32_t *n;       // device: the stream's cache length
-    const int32_t *done;    // device: its generation has finished (kernels skip its work)
+    const int32_t *done;    // device: its generation has finished (attention skips the stream)
     bf16_t *kvc;            // its cache, layer 0 (kernels add the layer offset)
 };
 // Passed to kernels by value, so it is kept small (every kernel waits for its arguments): stream 0
@@ -157,7 +157,7 @@ struct SjdLinear {
 #define SJD_EPI_QKV 3     // RoPE on q,k at position n+m; q -> qact, k,v -> cache
 struct SjdGemmEpi {
     int32_t kind;
-    SjdStreams sm;               // who owns which rows; every kind uses the finished flags
+    SjdStreams sm;               // QKV: who owns which rows
     size_t layer_off;            // QKV: element offset of this layer inside every stream's cache
     float *out;                  // STORE / RESID: [rows][N]
     float *ffn; int32_t F;                                        // SILU: [rows][F]
@@ -247,7 +247,7 @@ struct sjd_kv {
 };
 
 // ---- kernel launchers (each returns SJD_OK or an SJD_E* code) --------------------------------
-// `st` (device) lets a kernel skip its work once a generation has finished; NULL = always run.
+// `st` (device, fp32 models' kernels) lets a kernel skip its work once a generation has finished; NULL = always run.
 // bf16 models: `rows` rows per stream, stream s from ids[s] (device ids; all streams share emb_rows when
 // that is given instead), written at row s << sm.shift.  fp32 models: one stream, ids[0].
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
