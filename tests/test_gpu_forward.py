@@ -332,6 +332,36 @@ def test_forward_and_step_7b_full_size(B):
         assert np.array_equal(nd.cpu().numpy(), want[1])
         assert np.array_equal(pn.cpu().numpy().view(np.uint32), want[2].view(np.uint32))
         assert B.sjd_kv_len(g.kv) == len(ids) + want[0]
+
+        # the launch configuration the benchmark times: the device-resident loop replaying its captured
+        # iteration.  Every iteration against the oracle's verification of the same logits (taken with
+        # the forward hook, which leaves the loop state alone), then the finished image token by token.
+        N = 40
+        osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(w.init_mode, w.row_stride, w.eol_id)
+        B.sjd_kv_use_graph(g.kv, True)
+        B.sjd_prefill(g.m, g.kv, ids, None, smp, init, q_last)
+        B.sjd_decode_begin(g.m, g.kv, q_last, N, L, smp, init, 11)
+        torch.cuda.synchronize()
+        d_o, p_o = oracle.first_window(q_last.cpu().numpy(), L, lo, oinit, 11)
+        hist, c, done = [], 0, False
+        while not done:
+            c += 1
+            _say(f"7b: loop iteration {c}, {len(hist)} tokens fixed")
+            lg = g.logits(d_o)
+            Le = min(L, N - len(hist))
+            a, nd, pn = oracle.verify(lg[:Le], p_o[:Le], d_o[:Le], lo, osmp, oinit, len(hist), np.array(hist, np.int32), 11, c)
+            hist += [int(t) for t in d_o[:a]]
+            d_o = np.concatenate([nd, d_o[Le:]]).astype(np.int32); p_o = np.concatenate([pn, p_o[Le:]])
+            done = len(hist) >= N - 1
+            B.sjd_decode_steps(g.m, g.kv, 1)
+            fixed, steps, gdone = B.sjd_decode_status(g.kv)
+            assert fixed == len(hist) and steps == c and gdone == done, (c, fixed, len(hist))
+            assert c < 2 * N
+        toks, st = B.sjd_decode_result(g.kv, N)
+        want_toks = np.array(hist[:N], np.int32)
+        if len(want_toks) < N:
+            want_toks = np.append(want_toks, d_o[0]).astype(np.int32)
+        assert np.array_equal(toks, want_toks) and st.steps == c
     finally:
         g.close(); om.close()
 
