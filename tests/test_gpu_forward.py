@@ -402,6 +402,42 @@ def test_graph_replay_equals_eager_and_is_deterministic(B):
         g.close()
 
 
+def test_two_handles_on_two_streams(B):
+    """two generations of one model, each on its own stream with its own handle, enqueued alternately
+    without waiting: the weights are shared and read-only, everything else is per handle, so both must
+    produce what they produce alone"""
+    shape = synth.ModelShape(3, 512, 8, 1024, 4096, 2048, 4096, 300, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=9)
+    m = B.sjd_init_model(B.config_from_shape(shape), blob)
+    kvs = [B.sjd_kv_create(m) for _ in range(2)]
+    try:
+        prompts = [synth.random_tokens(30 + 11 * i, 0, 2048, seed=20 + i) for i in range(2)]
+        smp = B.sjd_sampler(500, 1.0); init = B.sjd_init(4, 12, 4095)
+        N, L = 12 * 10, 16
+        alone = [B.sjd_generate(m, kvs[i], prompts[i], None, N, L, smp, init, 5 + i)[0] for i in range(2)]
+        streams = [torch.cuda.Stream() for _ in range(2)]
+        q = [torch.empty(shape.v_s, dtype=torch.float32, device="cuda") for _ in range(2)]
+        for i in range(2):
+            B.sjd_prefill(m, kvs[i], prompts[i], None, smp, init, q[i], stream=streams[i])
+            B.sjd_decode_begin(m, kvs[i], q[i], N, L, smp, init, 5 + i, stream=streams[i])
+        done, rounds = [False, False], 0
+        while not all(done):
+            for i in range(2):                       # a few iterations each, no synchronisation in between
+                if not done[i]:
+                    B.sjd_decode_steps(m, kvs[i], 3, stream=streams[i])
+            for i in range(2):
+                done[i] = B.sjd_decode_status(kvs[i])[2]
+            rounds += 1
+            assert rounds < 200
+        for i in range(2):
+            toks, _ = B.sjd_decode_result(kvs[i], N)
+            assert np.array_equal(toks, alone[i]), i
+    finally:
+        for kv in kvs:
+            B.sjd_kv_free(kv)
+        B.sjd_free_model(m)
+
+
 def test_sampled_initialisers_graph_replay(B):
     """initialisers (c) and (d) inside the captured iteration (the ring of recorded distributions lives
     on the handle): replay == kernel-by-kernel, and switching initialisers re-captures"""
