@@ -327,6 +327,43 @@ def test_at_least_one_token_per_forward_and_step_accounting():
             assert out.min() >= 32 and out.max() < 96
 
 
+def test_log_probability_statistics_match_autoregressive_sampling():
+    """The statistic of the paper's Tab. "logit-sta": mean and standard deviation of log p(token) over
+    generated tokens, auto-regressive sampling against SJD, on a transformer (the toy chi-square tests
+    cover the exact joint; this covers a model whose distributions depend on the whole prefix)."""
+    shape, blob = _tiny()
+    om = oracle.Model(shape, blob)
+    prompt = synth.random_tokens(5, 0, 32, seed=4)
+    smp = oracle.Sampler(20, 1.0)
+    N, runs = 20, 150
+
+    def logps(tokens):
+        seq = np.concatenate([prompt, tokens]).astype(np.int32)
+        lg = om.forward_full(om.embed(seq))
+        out = []
+        for i, t in enumerate(tokens):
+            q = oracle.dist(lg[len(prompt) - 1 + i], 20, 1.0)
+            assert q[t - shape.samp_lo] > 0                 # every generated token lies inside the top-K support
+            out.append(np.log(float(q[t - shape.samp_lo])))
+        return out
+
+    ar, sjd = [], []
+    for seed in range(runs):
+        lp = om.prefill(prompt)
+        ar += logps(om.generate_ar(5, lp, N, smp, UNIFORM, 1000 + seed))
+        lp = om.prefill(prompt)
+        sjd += logps(om.generate_sjd(5, lp, N, 6, smp, UNIFORM, 5000 + seed)[0])
+    ar, sjd = np.array(ar), np.array(sjd)
+    n = len(ar)
+    se_mean = np.sqrt(ar.var() / n + sjd.var() / n)
+    assert abs(ar.mean() - sjd.mean()) < 4 * se_mean, (ar.mean(), sjd.mean(), se_mean)
+    # standard error of a standard deviation, from the fourth moment
+    def se_sd(x):
+        m2, m4 = x.var(), np.mean((x - x.mean()) ** 4)
+        return np.sqrt(max(m4 - m2 * m2, 0) / (4 * m2 * len(x)))
+    assert abs(ar.std() - sjd.std()) < 4 * np.hypot(se_sd(ar), se_sd(sjd)), (ar.std(), sjd.std())
+
+
 def test_stepwise_python_loop_reproduces_generate():
     """The step is a pure function of (cache, window, seed, counter): driving it from outside
     (and restarting the model state from scratch every step) gives the same stream."""
