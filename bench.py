@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--skip-images", action="store_true", help="skip the whole-image SJD / AR runs")
     ap.add_argument("--window", type=int, default=0, help="override the workload's window size L (1..32)")
     ap.add_argument("--top-k", type=int, default=0, help="override the workload's top-K (1 = greedy = Jacobi decoding)")
+    ap.add_argument("--temperature", type=float, default=0.0, help="override the workload's sampling temperature")
     ap.add_argument("--init-mode", type=int, default=-1, help="override the initialiser: 0 uniform, 1 repeat above, 2 repeat left, 3 sample left, 4 sample above")
     ap.add_argument("--no-refine", action="store_true", help="ablation: no refinement of unaccepted drafts")
     ap.add_argument("--cfg", type=float, default=None,
@@ -118,6 +119,8 @@ def main():
         w = dataclasses.replace(w, top_k=args.top_k)
     if args.init_mode >= 0:
         w = dataclasses.replace(w, init_mode=args.init_mode)
+    if args.temperature > 0:
+        w = dataclasses.replace(w, temperature=args.temperature)
     shape = w.shape
     t0 = time.perf_counter()
     blob = synth.make_weights(shape, seed=0, threads=16)
@@ -288,7 +291,7 @@ def main():
     also = args.also
     if also is None:
         plain = (args.workload == "7b_32x32" and nb == 1 and not guided and args.window == 0 and args.top_k == 0
-                 and args.init_mode < 0 and not args.no_refine and not args.no_graph)
+                 and args.temperature == 0 and args.init_mode < 0 and not args.no_refine and not args.no_graph)
         also = "775m" if plain else "none"
     if also != "none":
         # the class-conditional configuration, same measurement without the CPU leg, in a process of its own
