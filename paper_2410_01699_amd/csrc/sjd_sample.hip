@@ -166,8 +166,9 @@ struct DistShared {
     uint32_t wave_u32[DIST_WAVES];
     int hist[256];
     int whist[DIST_WAVES][256];   // per-wave digit counts (keeps same-bin LDS atomics inside one wave)
-    uint32_t sel_prefix;
-    int sel_rank;
+    uint32_t sel_prefix[2];       // result of a radix pass, double-buffered by pass parity
+    int sel_rank[2];
+    int top4[DIST_WAVES][2];      // per-wave counts of the four highest top bytes (two 16-bit fields each)
     int result;
 };
 
@@ -298,9 +299,48 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
     if (cut) {
         uint32_t prefix = 0, mask = 0;
         int rank = top_k;      // we look for the rank-th largest among keys matching the prefix
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            for (int b = lane; b < 256; b += 64) sh->whist[wave][b] = 0;
+        int first_shift = 24;
+        {
+            // Top byte (sign and high exponent bits): the keys crowd into the few highest values that
+            // occur, which is the worst case for a histogram in LDS (every lane on the same counter) and
+            // the best for counting in registers: the four highest top bytes, four 8-bit counters per
+            // thread (at most EPT <= 32 each), widened to 16-bit fields for the sums (at most V <= 32768).
+            const uint32_t dmax = kmax >> 24;
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const int t = tid + j * DIST_THREADS;
+                if (t < V) {
+                    const uint32_t diff = dmax - (buf[t] >> 24);
+                    if (diff < 4u) cnt += 1u << (8 * diff);
+                }
+            }
+            int lo = (int)((cnt & 0xFFu) | ((cnt & 0xFF00u) << 8));               // counts of dmax, dmax - 1
+            int hi = (int)(((cnt >> 16) & 0xFFu) | ((cnt >> 24) << 16));         // counts of dmax - 2, dmax - 3
+            lo = wave_sum_i32(lo);
+            hi = wave_sum_i32(hi);
+            if (lane == 0) { sh->top4[wave][0] = lo; sh->top4[wave][1] = hi; }
             __syncthreads();
+            lo = 0; hi = 0;
+            for (int w = 0; w < DIST_WAVES; ++w) { lo += sh->top4[w][0]; hi += sh->top4[w][1]; }
+            const int c0 = lo & 0xFFFF, c1 = (lo >> 16) & 0xFFFF, c2 = hi & 0xFFFF, c3 = (hi >> 16) & 0xFFFF;
+            int digit = -1, before = 0;
+            if (rank <= c0) { digit = (int)dmax; }
+            else if (rank <= c0 + c1) { digit = (int)dmax - 1; before = c0; }
+            else if (rank <= c0 + c1 + c2) { digit = (int)dmax - 2; before = c0 + c1; }
+            else if (rank <= c0 + c1 + c2 + c3) { digit = (int)dmax - 3; before = c0 + c1 + c2; }
+            if (digit >= 0) {          // (the same decision in every thread)
+                prefix = (uint32_t)digit << 24;
+                rank -= before;
+                mask = 255u << 24;
+                first_shift = 16;
+            }
+        }
+        for (int shift = first_shift; shift >= 0; shift -= 8) {
+            const int par = (shift >> 3) & 1;
+            // a wave clears and fills its own histogram: no workgroup barrier in between (the readers of
+            // the previous pass are behind that pass's barriers)
+            for (int b = lane; b < 256; b += 64) sh->whist[wave][b] = 0;
             for (int t = tid; t < V; t += DIST_THREADS) {
                 uint32_t k = buf[t];
                 if ((k & mask) == prefix) atomicAdd(&sh->whist[wave][(k >> shift) & 255u], 1);
@@ -326,15 +366,14 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
                     else if (rank <= excl + h0 + h1) { digit = d0 - 1; before = excl + h0; }
                     else if (rank <= excl + h0 + h1 + h2) { digit = d0 - 2; before = excl + h0 + h1; }
                     else { digit = d0 - 3; before = excl + h0 + h1 + h2; }
-                    sh->sel_prefix = prefix | ((uint32_t)digit << shift);
-                    sh->sel_rank = rank - before;
+                    sh->sel_prefix[par] = prefix | ((uint32_t)digit << shift);
+                    sh->sel_rank[par] = rank - before;
                 }
             }
             __syncthreads();
-            prefix = sh->sel_prefix;
-            rank = sh->sel_rank;
+            prefix = sh->sel_prefix[par];
+            rank = sh->sel_rank[par];
             mask |= 255u << shift;
-            __syncthreads();
         }
         kth = prefix;
         room = rank;           // = K - #(keys > kth)
