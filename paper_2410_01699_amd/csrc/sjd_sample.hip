@@ -169,6 +169,8 @@ struct DistShared {
     uint32_t sel_prefix[2];       // result of a radix pass, double-buffered by pass parity
     int sel_rank[2];
     int top4[DIST_WAVES][2];      // per-wave counts of the four highest top bytes (two 16-bit fields each)
+    int ncand;                    // keys sharing the 16 resolved bits, and the low halves of the first 64
+    uint32_t cand[64];
     int result;
 };
 
@@ -261,17 +263,23 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
 #pragma unroll
         for (int j = 0; j < EPT; ++j) zr[j] = guide(zr[j], zu[j], cfg_scale);
     }
+    // every thread keeps the keys of its own elements (t = tid + j * DIST_THREADS) in registers; the
+    // copy in LDS serves the steps that walk the row in a different order
+    uint32_t kr[EPT];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int t = tid + j * DIST_THREADS;
+        kr[j] = 0;
         if (t < V) {
             uint32_t k = order_key(zr[j]);
+            kr[j] = k;
             buf[t] = k;
             kmax = k > kmax ? k : kmax;
         }
     }
     kmax = wave_max_u32(kmax);
     if (lane == 0) sh->wave_u32[wave] = kmax;
+    if (tid == 0) sh->ncand = 0;
     __syncthreads();
     kmax = 0;
     for (int w = 0; w < DIST_WAVES; ++w) kmax = sh->wave_u32[w] > kmax ? sh->wave_u32[w] : kmax;
@@ -311,7 +319,7 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
             for (int j = 0; j < EPT; ++j) {
                 const int t = tid + j * DIST_THREADS;
                 if (t < V) {
-                    const uint32_t diff = dmax - (buf[t] >> 24);
+                    const uint32_t diff = dmax - (kr[j] >> 24);
                     if (diff < 4u) cnt += 1u << (8 * diff);
                 }
             }
@@ -338,12 +346,47 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
         }
         for (int shift = first_shift; shift >= 0; shift -= 8) {
             const int par = (shift >> 3) & 1;
+            if (shift == 8) {
+                // 16 bits are resolved: the keys that share them are few (a sliver of the value range).
+                // Up to 64 of them are finished by one wave, each lane ranking its key against the rest.
+#pragma unroll
+                for (int j = 0; j < EPT; ++j) {
+                    const uint32_t k = kr[j];
+                    if (tid + j * DIST_THREADS < V && (k & mask) == prefix) {
+                        const int pos = atomicAdd(&sh->ncand, 1);
+                        if (pos < 64) sh->cand[pos] = k & 0xFFFFu;
+                    }
+                }
+                __syncthreads();
+                const int n = sh->ncand;
+                if (n <= 64) {
+                    if (wave == 0) {
+                        const uint32_t mine = lane < n ? sh->cand[lane] : 0u;
+                        int gt = 0, ge = 0;
+                        for (int i = 0; i < n; ++i) {
+                            const uint32_t other = (uint32_t)__builtin_amdgcn_readlane((int)mine, i);
+                            gt += other > mine;
+                            ge += other >= mine;
+                        }
+                        if (lane < n && gt < rank && rank <= ge) {       // every lane holding that value agrees
+                            sh->sel_prefix[par] = prefix | mine;
+                            sh->sel_rank[par] = rank - gt;
+                        }
+                    }
+                    __syncthreads();
+                    prefix = sh->sel_prefix[par];
+                    rank = sh->sel_rank[par];
+                    mask = 0xFFFFFFFFu;
+                    break;
+                }
+            }
             // a wave clears and fills its own histogram: no workgroup barrier in between (the readers of
             // the previous pass are behind that pass's barriers)
             for (int b = lane; b < 256; b += 64) sh->whist[wave][b] = 0;
-            for (int t = tid; t < V; t += DIST_THREADS) {
-                uint32_t k = buf[t];
-                if ((k & mask) == prefix) atomicAdd(&sh->whist[wave][(k >> shift) & 255u], 1);
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                const uint32_t k = kr[j];
+                if (tid + j * DIST_THREADS < V && (k & mask) == prefix) atomicAdd(&sh->whist[wave][(k >> shift) & 255u], 1);
             }
             __syncthreads();
             if (tid < 256) {
@@ -379,7 +422,8 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
         room = rank;           // = K - #(keys > kth)
         // entries equal to kth: do they all fit?
         int eq = 0;
-        for (int t = tid; t < V; t += DIST_THREADS) eq += buf[t] == kth;
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) eq += (tid + j * DIST_THREADS < V) && kr[j] == kth;
         eq = wave_sum_i32(eq);
         if (lane == 0) sh->hist[wave] = eq;
         __syncthreads();
@@ -409,21 +453,28 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
                 base += group_total;
             }
             __syncthreads();
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {           // the keys of lost ties changed: take them again
+                const int t = tid + j * DIST_THREADS;
+                if (t < V) kr[j] = buf[t];
+            }
         }
     }
 
     // ---- softmax over the survivors ----------------------------------------------------------
     const float m = key_to_float(kmax);
     uint64_t csum = 0;
-    for (int t = tid; t < V; t += DIST_THREADS) {
-        uint32_t k = buf[t];
-        bool keep = !cut || k >= kth;
+    float er[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const uint32_t k = kr[j];
+        const bool keep = tid + j * DIST_THREADS < V && (!cut || k >= kth);
         float e = 0.0f;
         if (keep) {
             float x = __fdiv_rn(__fsub_rn(key_to_float(k), m), T);   // the key still holds the logit's bits
             e = exp_fixed(x);
         }
-        qb[t] = e;
+        er[j] = e;
         csum += fixed40(e);
     }
     csum = wave_sum_u64(csum);
@@ -432,9 +483,10 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
     uint64_t C = 0;
     for (int w = 0; w < DIST_WAVES; ++w) C += sh->wave_tot[w];
     const float Z = __fmul_rn(__ull2float_rn(C), 0x1p-40f);
-    for (int t = tid; t < V; t += DIST_THREADS) {
-        float e = qb[t];
-        qb[t] = (e != 0.0f) ? __fdiv_rn(e, Z) : 0.0f;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int t = tid + j * DIST_THREADS;
+        if (t < V) qb[t] = (er[j] != 0.0f) ? __fdiv_rn(er[j], Z) : 0.0f;     // (over the keys: same storage)
     }
     __syncthreads();
 }
