@@ -163,6 +163,8 @@ __device__ __forceinline__ int wave_min_i32(int v)
 
 struct DistShared {
     uint64_t wave_tot[DIST_WAVES];
+    uint64_t wave_tot2[DIST_WAVES];  // second draw of block_sample2
+    int result2;
     uint32_t wave_u32[DIST_WAVES];
     int hist[256];
     int whist[DIST_WAVES][256];   // per-wave digit counts (keeps same-bin LDS atomics inside one wave)
@@ -224,6 +226,65 @@ __device__ int block_sample(WeightFn weight, int V, uint32_t k32, DistShared *sh
     }
     __syncthreads();
     return sh->result;
+}
+
+// Two draws at once from two weight functions over the same index range (one pass over the row, one
+// pair of barriers): results as block_sample would give them for (w1, k1) and (w2, k2).
+template <int EPT, class W1, class W2>
+__device__ void block_sample2(W1 w1, W2 w2, int V, uint32_t k1, uint32_t k2, DistShared *sh, int &r1, int &r2)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int span = ((V + DIST_WAVES * 64 - 1) / (DIST_WAVES * 64)) * 64;
+    const int beg = wave * span;
+    const int end = min(V, beg + span);
+    uint64_t c1[EPT], c2[EPT];
+    uint64_t loc1 = 0, loc2 = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int t = beg + j * 64 + lane;
+        c1[j] = t < end ? fixed40(w1(j, t)) : 0;
+        c2[j] = t < end ? fixed40(w2(j, t)) : 0;
+        loc1 += c1[j];
+        loc2 += c2[j];
+    }
+    loc1 = wave_sum_u64(loc1);
+    loc2 = wave_sum_u64(loc2);
+    __syncthreads();                       // protects the shared fields from the previous use
+    if (lane == 0) { sh->wave_tot[wave] = loc1; sh->wave_tot2[wave] = loc2; }
+    if (threadIdx.x == 0) { sh->result = -1; sh->result2 = -1; }
+    __syncthreads();
+    uint64_t C1 = 0, C2 = 0, mine1 = 0, mine2 = 0;
+    for (int w = 0; w < DIST_WAVES; ++w) {
+        if (w == wave) { mine1 = C1; mine2 = C2; }
+        C1 += sh->wave_tot[w];
+        C2 += sh->wave_tot2[w];
+    }
+    auto find = [&](const uint64_t (&cj)[EPT], uint64_t C, uint64_t mine, uint64_t local, uint32_t k32, int *out) {
+        if (C == 0) return;
+        const uint64_t tau = __umul64hi((uint64_t)k32 << 32, C);    // (k32 * C) >> 32
+        if (tau >= mine && tau < mine + local) {                   // exactly one wave
+            uint64_t base = mine;
+            bool found = false;
+#pragma unroll
+            for (int j = 0; j < EPT; ++j) {
+                if (!found && beg + j * 64 < end) {
+                    uint64_t group_total;
+                    const uint64_t incl = wave_scan_u64(cj[j], group_total);
+                    unsigned long long hit = __ballot(base + incl > tau);
+                    if (hit) {
+                        if (lane == 0) *out = beg + j * 64 + __ffsll(hit) - 1;
+                        found = true;
+                    }
+                    base += group_total;
+                }
+            }
+        }
+    };
+    find(c1, C1, mine1, loc1, k1, &sh->result);
+    find(c2, C2, mine2, loc2, k2, &sh->result2);
+    __syncthreads();
+    r1 = sh->result;
+    r2 = sh->result2;
 }
 
 // The sampling distribution of one logits row, left in `buf` (LDS, V floats) and returned to the
@@ -579,8 +640,18 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
     for (int t = threadIdx.x; t < V; t += DIST_THREADS) qrow[t] = qb[t];
 
     const U4 rnd = philox_draw(a.seed, counter, (uint32_t)i);
-    // candidate for Eq. 3 (and for the bonus index L): a plain sample from q_i
-    int s = block_sample<EPT>([&](int, int t) { return qb[t]; }, V, rnd.w[2], &sh);
+    // candidate for Eq. 3 (and for the bonus index L): a plain sample from q_i; candidate for Eq. 2: a
+    // sample from max(0, q_i - p_old_i), or, if that vanishes, from q_i with the same random word
+    int s, rs = -1;
+    auto w_q = [&](int, int t) { return qb[t]; };
+    auto w_res = [&](int j, int t) { float d = __fsub_rn(qb[t], por[j]); return d > 0.0f ? d : 0.0f; };
+    if constexpr (EPT <= 8) {            // both draws in one pass where their fixed-point values fit the registers
+        if (i < L) block_sample2<EPT>(w_q, w_res, V, rnd.w[2], rnd.w[1], &sh, s, rs);
+        else s = block_sample<EPT>(w_q, V, rnd.w[2], &sh);
+    } else {
+        s = block_sample<EPT>(w_q, V, rnd.w[2], &sh);
+        if (i < L) rs = block_sample<EPT>(w_res, V, rnd.w[1], &sh);
+    }
     if (threadIdx.x == 0) a.tok_smp[i] = s;
     if (i < L) {
         if (threadIdx.x == 0) {
@@ -593,9 +664,6 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
             }
             a.acc_flag[i] = ok;
         }
-        // candidate for Eq. 2: sample from max(0, q_i - p_old_i); if that vanishes, from q_i
-        int rs = block_sample<EPT>([&](int j, int t) { float d = __fsub_rn(qb[t], por[j]); return d > 0.0f ? d : 0.0f; }, V,
-                                   rnd.w[1], &sh);
         if (rs < 0) rs = block_sample<EPT>([&](int, int t) { return qb[t]; }, V, rnd.w[1], &sh);
         if (threadIdx.x == 0) a.tok_res[i] = rs;
     }
