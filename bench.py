@@ -67,8 +67,9 @@ def cpu_baseline(w, blob, prompt_ids, prompt_emb, seed, budget_steps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--steps", type=int, default=1024,
+                    help="timed iterations (the default spans more than one whole image of the 7B workload, so every cache length counts)")
+    ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="7b_32x32")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--profile-steps", type=int, default=24)
