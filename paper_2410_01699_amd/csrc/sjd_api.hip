@@ -111,7 +111,8 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
 
     // copy a tensor as is; returns its device pointer
     auto plain = [&](size_t off, size_t n) -> const void * {
-        if (hipMemcpy(db + off * es, hb + off * es, n * es, hipMemcpyHostToDevice) != hipSuccess) return nullptr;
+        const hipError_t e = hipMemcpy(db + off * es, hb + off * es, n * es, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { sjd_set_hip_error(e, "weight upload"); return nullptr; }
         return db + off * es;
     };
     // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
@@ -595,14 +596,8 @@ extern "C" int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
 static int alloc_uncond_cache(sjd_kv *kv)
 {
     const sjd_config &c = kv->m->cfg;
-    if (!kv->k_u) {
-        if (c.dtype == 1) {
-            SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 2));
-        } else {
-            SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * 4));
-            if (!kv->v_u) SJD_TRY(dev_alloc(&kv->v_u, (size_t)c.n_layers * kv->v_layer_stride * 4));
-        }
-    }
+    // same layout as the first cache: bf16 K and V blocked together, fp32 K and V apart
+    if (!kv->k_u) SJD_TRY(dev_alloc(&kv->k_u, (size_t)c.n_layers * kv->k_layer_stride * (c.dtype == 1 ? 2 : 4)));
     if (c.dtype == 0 && !kv->v_u) SJD_TRY(dev_alloc(&kv->v_u, (size_t)c.n_layers * kv->v_layer_stride * 4));
     // the table of the handle's two contexts, read by the kernels of a two-stream forward
     const SjdStreamEntry two[2] = {handle_entry(kv, false), handle_entry(kv, true)};
@@ -899,7 +894,7 @@ extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t 
         kv0->bgraph = g;
         e = hipGraphInstantiate(&kv0->bgraph_exec, g, nullptr, nullptr, 0);
         if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_batch_graph(kv0); return SJD_EHIP; }
-        kv0->bkey = key;
+        memcpy(&kv0->bkey, &key, sizeof(key));    // byte copy: the comparison above is one too
     }
     for (int i = 0; i < n_steps; ++i) HIP_TRY(hipGraphLaunch(kv0->bgraph_exec, s));
     return SJD_OK;
@@ -1255,8 +1250,9 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     SjdGemmEpi ep;
     memset(&ep, 0, sizeof(ep));
     ep.kind = SJD_EPI_STORE; ep.out = g.out;
-    hipEvent_t e0, e1;
-    HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); sjd_set_hip_error(e, "hipEventCreate"); return SJD_EHIP; }
     int rc = SJD_OK;
     for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, (const float *)g.Ap, nullptr, 0.f, M, ep, 0);
     if (rc == SJD_OK) {

@@ -83,7 +83,7 @@ class ModelShape:
 
 @dataclasses.dataclass(frozen=True)
 class Workload:
-    """One BASELINE configuration: a model shape plus the decoding set-up."""
+    """One benchmark configuration: a model shape plus the decoding set-up."""
     name: str
     shape: ModelShape
     n_prompt_ids: int     # prompt token ids fed first
