@@ -250,7 +250,9 @@ int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sjd_sampler *
 
 /* C[M x N] (fp32, dev) = A[M x K] * W[N x K]^T with the kernel the model uses for its projections.
  * dtype as in sjd_config; A and W are dev, row-major, element type per dtype; W is repacked into
- * the library's streaming layout first (not timed separately).  For kernel-level parity tests.  */
+ * the library's streaming layout first (not timed separately).  dtype 2: W bf16 and A fp32, A taken
+ * through the 3-byte form (16 significant bits) in which bf16 models hand the attention output and
+ * the FFN hidden to their projections.  For kernel-level parity tests.                            */
 int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_t N, int32_t K, float *C,
                   void *stream);
 

@@ -338,13 +338,13 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
     }
 }
 
-// out[q][head*HD + :] = sum_s w_s O_s[q][:] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s), written in
-// the operand order the O projection streams.  All loads of a thread are issued before anything
+// out[q][head*HD + :] = sum_s w_s O_s[q][:] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s), written as
+// the hi / lo operand planes the O projection streams (act24_idx).  All loads of a thread are issued before anything
 // depends on them (splits <= ATT_MAX_SPLITS).
 #define ATT_MAX_SPLITS 16
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
-                                                        float *__restrict__ out, int shift)
+                                                        void *__restrict__ out, int shift)
 {
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
@@ -373,7 +373,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         num += w * os[s];
         den += w * ls[s];
     }
-    *reinterpret_cast<f32x4 *>(out + act_off(q + (stream << shift), head * HD + j4 * 4, d / 32)) = num * (1.0f / den);
+    const f32x4 o = num * (1.0f / den);
+    act24_store4(out, q + (stream << shift), head * HD + j4 * 4, d / 32, o[0], o[1], o[2], o[3]);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -429,7 +430,7 @@ static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
                        kv->nblk, rows, splits, kv->att_part);
     HIP_TRY(hipGetLastError());
     SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256, sm.count), dim3(256), 0, s, kv->att_part,
-                       splits, d, rows, (float *)kv->att_out, sm.shift);
+                       splits, d, rows, kv->att_out, sm.shift);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }

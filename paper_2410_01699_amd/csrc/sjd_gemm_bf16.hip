@@ -7,11 +7,14 @@
 //
 //  - W is pre-packed (sjd_repack_bf16) into 16x32 tiles in the exact A-operand register order of
 //    v_mfma_f32_16x16x32_bf16: one 16-byte load per lane fetches 1 KiB of contiguous HBM per wave.
-//  - The activations are the B operand (tokens on the 16 columns).  They are fp32 in L2, stored by
-//    their producers in B-operand order (act_off); each lane loads the 8 values of its token and
-//    k-group and splits them into hi = bf16(x) and lo = bf16(x - hi), which are multiplied
-//    separately: ~16 significant bits of activation.  A wave reuses each activation tile for its TN
-//    weight tiles, so TN sets the L2-to-HBM traffic ratio.
+//  - The activations are the B operand (tokens on the 16 columns), multiplied as a pair of bf16
+//    operands hi + lo: ~16 significant bits.  Inside the model they arrive from L2 in 3 bytes per
+//    value, stored by their producers in B-operand order (act24_idx): the bf16 hi plane is the first
+//    operand as stored, the second is rebuilt from the byte plane (with a normalisation in front, the
+//    value is rebuilt, scaled by the gain and split again).  The hooks that time or test the kernel
+//    alone pass fp32 values in the same order (act_off), split on the fly into hi = bf16(x) and
+//    lo = bf16(x - hi).  A wave reuses each activation tile for its TN weight tiles, so TN sets the
+//    ratio of L2 to HBM traffic.
 //  - RMSNorm in front of a projection is folded in: the values are multiplied by the gain before the
 //    split, every workgroup accumulates the sum of squares of the rows it streams anyway, and the
 //    factor rsqrt(mean(x^2) + eps) of each token is applied to the final sums (it is constant along
@@ -93,14 +96,13 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
     if (EPI == SJD_EPI_STORE) {
         *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
     } else if (EPI == SJD_EPI_RESID) {
-        *reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32)) = pre.x + v;
+        const f32x4 y = pre.x + v;
+        *reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32)) = y;
+        if (ep.out24) act24_store4(ep.out24, m, n0, N / 32, y[0], y[1], y[2], y[3]);
     } else if (EPI == SJD_EPI_SILU) {
         // packed rows: (gate f, up f, gate f+1, up f+1)
         const int f = n0 >> 1;
-        float2 y;
-        y.x = v[0] / (1.0f + __expf(-v[0])) * v[1];
-        y.y = v[2] / (1.0f + __expf(-v[2])) * v[3];
-        *reinterpret_cast<float2 *>(ep.ffn + act_off(m, f, ep.F / 32)) = y;
+        act24_store2(ep.ffn, m, f, ep.F / 32, v[0] / (1.0f + __expf(-v[0])) * v[1], v[2] / (1.0f + __expf(-v[2])) * v[3]);
     } else {   // SJD_EPI_QKV
         const int d = ep.d, hd = ep.hd, half = hd >> 1;
         const int pos = pre.pos;
@@ -146,11 +148,12 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
 // ---------------------------------------------------------------------------------------------
 // in-workgroup split-K
 // ---------------------------------------------------------------------------------------------
-#define SJD_PRO_PLAIN 0
-#define SJD_PRO_NORM 1
+#define SJD_PRO_PLAIN 0     // fp32 activations as they are
+#define SJD_PRO_NORM 1      // activations in hi / lo planes (3 bytes per value), RMSNorm folded in
+#define SJD_PRO_A24 2       // activations in hi / lo planes, as they are
 template <int MT, int TN, int WK, int U, int EPI, int PRO>
 __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__restrict__ Wp,
-                                                            const float *__restrict__ X,
+                                                            const void *__restrict__ Xv,
                                                             const bf16_t *__restrict__ gain, float eps, int N, int K,
                                                             SjdGemmEpi ep)
 {
@@ -182,10 +185,15 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 
     // weights: the TN tiles of a k-step are adjacent (in 16-byte units)
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)blockIdx.x * KT * TN * 64 + lane;
-    // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8, as two float4
-    const f32x4 *xp = reinterpret_cast<const f32x4 *>(X) + lane;
+    // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8, as two float4, or as
+    // 8 bf16 of the hi plane and 8 bytes of the lo plane
+    constexpr bool A24 = PRO != SJD_PRO_PLAIN;
+    const f32x4 *xp = reinterpret_cast<const f32x4 *>(Xv) + lane;
+    const uint2 *xl = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
     const bf16_t *gp = gain + g * 8;
-    const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(reinterpret_cast<const f32x4 *>(X) + (size_t)2 * KT * 128) + lane;
+    // an all-zero weight tile: the tile behind the activations (fp32: tile 2 KT of 2 KiB; planes: tile
+    // 2 KT of the hi plane, 1 KiB)
+    const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(xp + (size_t)2 * KT * (A24 ? 64 : 128));
 
     bf16x8 a0[U][TN], a1[U][TN], g0[U], g1[U];
     f32x4 b0[U][MT][2], b1[U][MT][2];
@@ -201,9 +209,15 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         const int kq_ = kr_ >= kt1 ? kr_ - klen : kr_;                                            \
         const int kw_ = min(kq_, kt1 - 1);                                                        \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {   /* L2 hits first: they return first */ \
-            const f32x4 *p = xp + (ok_ ? (size_t)mt * KT + kq_ : (size_t)2 * KT) * 128;           \
-            b[u][mt][0] = p[0];                                                                   \
-            b[u][mt][1] = p[64];                                                                  \
+            const size_t tix_ = ok_ ? (size_t)mt * KT + kq_ : (size_t)2 * KT;                     \
+            if (A24) {                                                                            \
+                b[u][mt][0] = xp[tix_ * 64];                          /* 8 bf16 of the hi plane */ \
+                const uint2 l_ = xl[tix_ * 64];                                                   \
+                b[u][mt][1][0] = __uint_as_float(l_.x); b[u][mt][1][1] = __uint_as_float(l_.y);   \
+            } else {                                                                              \
+                b[u][mt][0] = xp[tix_ * 128];                                                     \
+                b[u][mt][1] = xp[tix_ * 128 + 64];                                                \
+            }                                                                                     \
         }                                                                                         \
         _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                         \
             a[u][tn] = __builtin_nontemporal_load(ok_ ? wp + ((size_t)kq_ * TN + tn) * 64 : zw);  \
@@ -212,16 +226,30 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
 #define MMA_STAGE(a, b, gn)                                                                       \
     _Pragma("unroll") for (int u = 0; u < U; ++u)                                                 \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                       \
-            float x_[8];                                                                          \
-            _Pragma("unroll") for (int e = 0; e < 8; ++e) x_[e] = b[u][mt][e >> 2][e & 3];        \
-            if (PRO == SJD_PRO_NORM) {                                                            \
-                _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                   \
-                    ss[mt] = fmaf(x_[e], x_[e], ss[mt]);                                          \
-                    x_[e] *= (float)gn[u][e];                                                     \
-                }                                                                                 \
-            }                                                                                     \
             bf16x8 bh_, bl_;                                                                      \
-            split8(x_, bh_, bl_);                                                                 \
+            if (A24) {                                                                            \
+                /* value = hi bits | lo byte << 8 (as fp32); second operand = value - hi, exact */ \
+                float x_[8];                                                                      \
+                _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                   \
+                    const uint32_t hw_ = __float_as_uint(b[u][mt][0][e >> 1]);                    \
+                    const uint32_t lw_ = __float_as_uint(b[u][mt][1][e >> 2]);                    \
+                    const uint32_t hb_ = (e & 1) ? (hw_ & 0xFFFF0000u) : (hw_ << 16);             \
+                    const uint32_t lb_ = ((lw_ >> (8 * (e & 3))) & 0xFFu) << 8;                   \
+                    if (PRO == SJD_PRO_NORM) {                                                    \
+                        x_[e] = __uint_as_float(hb_ | lb_);                                       \
+                        ss[mt] = fmaf(x_[e], x_[e], ss[mt]);                                      \
+                        x_[e] *= (float)gn[u][e];                                                 \
+                    } else {                                                                      \
+                        bl_[e] = (__bf16)(__uint_as_float(hb_ | lb_) - __uint_as_float(hb_));     \
+                    }                                                                             \
+                }                                                                                 \
+                if (PRO == SJD_PRO_NORM) split8(x_, bh_, bl_);                                    \
+                else bh_ = __builtin_bit_cast(bf16x8, b[u][mt][0]);                               \
+            } else {                                                                              \
+                float x_[8];                                                                      \
+                _Pragma("unroll") for (int e = 0; e < 8; ++e) x_[e] = b[u][mt][e >> 2][e & 3];    \
+                split8(x_, bh_, bl_);                                                             \
+            }                                                                                     \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                   \
                 acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], bh_, acc[mt][tn], 0, 0, 0); \
                 acc[mt][tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][tn], bl_, acc[mt][tn], 0, 0, 0); \
@@ -339,6 +367,26 @@ __global__ void bf16_rows_to_f32_kernel(const bf16_t *__restrict__ src, size_t n
         dst[act_off((int)(e / K), (int)(e % K), K / 32)] = bf16_to_f32(src[e]);
 }
 
+// row-major fp32 [rows][K] -> hi / lo planes (test hook)
+__global__ void f32_rows_to_act24_kernel(const float *__restrict__ src, size_t n, int K, void *__restrict__ dst)
+{
+    const int KT = K / 32;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const uint32_t v = f32_to_act24(src[e]);
+        const size_t i = act24_idx((int)(e / K), (int)(e % K), KT);
+        ((bf16_t *)dst)[i] = (bf16_t)(v >> 16);
+        ((uint8_t *)dst)[act24_lo_base(KT) + i] = (uint8_t)(v >> 8);
+    }
+}
+
+int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s)
+{
+    if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
+    SJD_LAUNCH(f32_rows_to_act24_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s)
 {
     if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
@@ -371,19 +419,28 @@ void sjd_choose_tiles(SjdLinear *lin)
 }
 
 template <int MT, int TN, int WK, int U, int PRO>
-static int launch_epi(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, const SjdGemmEpi &ep,
+static int launch_epi(const SjdLinear *lin, const void *act, const bf16_t *gain, float eps, const SjdGemmEpi &ep,
                       hipStream_t s)
 {
     if constexpr (WK * MT * TN * 1024 + WK * MT * 64 <= 65536) {
         dim3 grid(lin->N / (16 * TN)), block(64 * WK);
         const bf16_t *W = (const bf16_t *)lin->w;
 #define GO(EPI) SJD_LAUNCH((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, gain, eps, lin->N, lin->K, ep)
-        switch (ep.kind) {
-            case SJD_EPI_STORE: GO(SJD_EPI_STORE); break;
-            case SJD_EPI_RESID: GO(SJD_EPI_RESID); break;
-            case SJD_EPI_SILU: GO(SJD_EPI_SILU); break;
-            case SJD_EPI_QKV: GO(SJD_EPI_QKV); break;
-            default: return SJD_EINVAL;
+        if constexpr (PRO == SJD_PRO_A24) {
+            // (the plane activations feed the residual projections; the plain store serves the test hook)
+            switch (ep.kind) {
+                case SJD_EPI_STORE: GO(SJD_EPI_STORE); break;
+                case SJD_EPI_RESID: GO(SJD_EPI_RESID); break;
+                default: return SJD_EINVAL;
+            }
+        } else {
+            switch (ep.kind) {
+                case SJD_EPI_STORE: GO(SJD_EPI_STORE); break;
+                case SJD_EPI_RESID: GO(SJD_EPI_RESID); break;
+                case SJD_EPI_SILU: GO(SJD_EPI_SILU); break;
+                case SJD_EPI_QKV: GO(SJD_EPI_QKV); break;
+                default: return SJD_EINVAL;
+            }
         }
 #undef GO
         HIP_TRY(hipGetLastError());
@@ -393,10 +450,10 @@ static int launch_epi(const SjdLinear *lin, const float *act, const bf16_t *gain
     }
 }
 
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const bf16_t *gain, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s)
 {
-    if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (rows < 1 || rows > SJD_ROWS_MAX || (gain && !act24)) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
     const int tn = lin->tn;               // fixed when the weights were packed
@@ -411,10 +468,12 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *g
         if constexpr (MT * TN <= 4) {                                                                     \
             if (wk == 4) {                                                                                \
                 if (gain) return launch_epi<MT, TN, 4, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);      \
+                if (act24) return launch_epi<MT, TN, 4, 2, SJD_PRO_A24>(lin, act, gain, eps, ep, s);      \
                 return launch_epi<MT, TN, 4, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);               \
             }                                                                                             \
         } else if (wk == 4) return SJD_EINVAL;                                                            \
         if (gain) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);              \
+        if (act24) return launch_epi<MT, TN, 8, 2, SJD_PRO_A24>(lin, act, gain, eps, ep, s);              \
         return launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);                       \
     }
     CASE(1, 1) CASE(1, 2) CASE(1, 3)

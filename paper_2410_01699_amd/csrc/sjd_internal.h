@@ -114,6 +114,47 @@ __host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
     return (((size_t)(m >> 4) * KT + (k >> 5)) * 2 + ((k >> 2) & 1)) * 256 + ((((k & 31) >> 3) * 16 + (m & 15)) << 2) + (k & 3);
 }
 //
+// What the projections of the decoder stack actually stream is a 3-byte form of those activations:
+// the fp32 value rounded to 16 significant bits (the precision the hi + lo operand pair carries
+// anyway), its upper 16 bits in a bf16 "hi" plane that IS the first MFMA operand, the next 8 bits in a
+// byte "lo" plane from which the projection rebuilds the second operand.  The attention output and
+// the FFN hidden exist in this form only; the residual stream is accumulated in fp32 (act_off order,
+// read and written by the residual epilogues) and every writer also leaves its planes.  Every byte a projection reads passes through its CU's vector memory
+// pipeline at the same cost, whether it comes from HBM or from L2, so a quarter less activation
+// traffic is time saved on the shapes whose workgroups read more activation than weight bytes.
+// Plane layout for a [32 x K] matrix: tiles (m/16, k/32) of 512 values, value index act24_idx(); the
+// hi plane holds 2*K/32 tiles plus one all-zero tile, the lo plane follows it.
+__host__ __device__ __forceinline__ size_t act24_idx(int m, int k, int KT)
+{
+    return (((size_t)(m >> 4) * KT + (k >> 5)) << 9) + ((((k & 31) >> 3) * 16 + (m & 15)) << 3) + (k & 7);
+}
+__host__ __device__ __forceinline__ size_t act24_lo_base(int KT) { return (size_t)(2 * KT + 1) * 1024; }   // bytes
+__host__ __device__ __forceinline__ size_t act24_bytes(int KT) { return (size_t)(2 * KT + 1) * 1536; }
+// fp32 -> 16 significant bits (round to nearest even), returned in fp32 position: bits 31..16 are the
+// hi plane entry, bits 15..8 the lo plane entry
+__device__ __forceinline__ uint32_t f32_to_act24(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    u += 0x7Fu + ((u >> 8) & 1u);
+    return u & 0xFFFFFF00u;
+}
+// planes of 4 consecutive values (k a multiple of 4) / of 2 (k even) of row m
+__device__ __forceinline__ void act24_store4(void *base, int m, int k, int KT, float v0, float v1, float v2, float v3)
+{
+    const uint32_t a = f32_to_act24(v0), b = f32_to_act24(v1), c = f32_to_act24(v2), d = f32_to_act24(v3);
+    const size_t i = act24_idx(m, k, KT);
+    *reinterpret_cast<uint2 *>((bf16_t *)base + i) = make_uint2((a >> 16) | (b & 0xFFFF0000u), (c >> 16) | (d & 0xFFFF0000u));
+    *reinterpret_cast<uint32_t *>((uint8_t *)base + act24_lo_base(KT) + i) =
+        ((a >> 8) & 0xFFu) | (b & 0xFF00u) | ((c << 8) & 0xFF0000u) | ((d << 16) & 0xFF000000u);
+}
+__device__ __forceinline__ void act24_store2(void *base, int m, int k, int KT, float v0, float v1)
+{
+    const uint32_t a = f32_to_act24(v0), b = f32_to_act24(v1);
+    const size_t i = act24_idx(m, k, KT);
+    *reinterpret_cast<uint32_t *>((bf16_t *)base + i) = (a >> 16) | (b & 0xFFFF0000u);
+    *reinterpret_cast<uint16_t *>((uint8_t *)base + act24_lo_base(KT) + i) = (uint16_t)(((a >> 8) & 0xFFu) | (b & 0xFF00u));
+}
+//
 // KV cache of bf16 models: per layer, per head, per block of 32 positions one contiguous record of
 // 128*hd bf16 values, laid out as the MFMA operands the attention kernel consumes, each value kept
 // as hi = bf16(v) and lo = bf16(v - hi) (two "planes"):
@@ -160,7 +201,8 @@ struct SjdGemmEpi {
     SjdStreams sm;               // QKV: who owns which rows
     size_t layer_off;            // QKV: element offset of this layer inside every stream's cache
     float *out;                  // STORE / RESID: [rows][N]
-    float *ffn; int32_t F;                                        // SILU: [rows][F]
+    void *out24;                 // RESID: hi / lo planes of the updated rows (or NULL)
+    void *ffn; int32_t F;                                         // SILU: [rows][F] in act24 planes
     float *qact; const float *cosT, *sinT;                        // QKV
     int32_t d, hd, nblk, rows_valid, max_seq;                     // rows_valid: rows per stream whose K/V are stored
 };
@@ -196,14 +238,15 @@ struct sjd_kv {
     SjdState *state;      // device
     // ---- scratch for one forward over <= SJD_ROWS_MAX rows ----
     float *x;             // [rows][d] residual stream
+    void *x24;            // bf16 models: its hi / lo planes (what the projections read)
     void *h;              // fp32 models: [rows][d] normalised activations
     float *part;          // fp32 models: GEMM output
     size_t part_elems;
     float *qact;          // [rows][d] rotated queries (fp32)
     float *att_part;      // attention partials per (head, split): [rows][hd] + m,l
     int32_t att_splits;
-    void *att_out;        // [rows][d] fp32
-    void *ffn;            // [rows][F] fp32
+    void *att_out;        // [rows][d] fp32; bf16 models: hi / lo planes
+    void *ffn;            // [rows][F] fp32; bf16 models: hi / lo planes
     float *logits;        // [rows][V_s]
     // ---- scratch for verification ----
     float *q;             // [(rows+1)][V_s]
@@ -251,7 +294,7 @@ struct sjd_kv {
 // bf16 models: `rows` rows per stream, stream s from ids[s] (device ids; all streams share emb_rows when
 // that is given instead), written at row s << sm.shift.  fp32 models: one stream, ids[0].
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, hipStream_t s);
+                     const SjdStreams &sm, float *x, void *x24, hipStream_t s);
 int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
 int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
@@ -265,10 +308,12 @@ int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_
 int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t tn, int32_t perm, int32_t d,
                     int32_t hd, hipStream_t s);
 void sjd_choose_tiles(SjdLinear *lin);
-// bf16 projection: act = fp32 [SJD_ROWS_MAX x K] in act_off order; gain != NULL fuses RMSNorm(act; gain, eps) in front
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const float *act, const bf16_t *gain, float eps, int32_t rows,
+// bf16 projection: act = the 3-byte planes described at act24_idx() (act24 set; gain != NULL fuses
+// RMSNorm(act; gain, eps) in front) or fp32 [SJD_ROWS_MAX x K] in act_off order (no gain then)
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const bf16_t *gain, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s);
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
+int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s);
 // fp32 models: `stream` 0 / 1 selects the cache and length of the handle
 int sjd_launch_attention_f32(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream, hipStream_t s);
 // bf16 models: `rows` query rows per stream of sm against that stream's cache

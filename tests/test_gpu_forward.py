@@ -57,7 +57,10 @@ class Gpu:
 @pytest.mark.parametrize("dtype,M,N,K", [(0, 8, 384, 128), (0, 16, 100, 512), (0, 32, 37, 260), (0, 3, 1024, 128),
                                          (1, 16, 4608, 1536), (1, 16, 1536, 4096), (1, 32, 256, 320), (1, 5, 48, 64),
                                          (1, 16, 12288, 4096), (1, 32, 4096, 11008), (1, 16, 22016, 4096),
-                                         (1, 16, 8192, 4096)])
+                                         (1, 16, 8192, 4096),
+                                         # bf16 weights, fp32 activations handed over in 3 bytes per value
+                                         (2, 16, 4096, 11008), (2, 32, 4096, 4096), (2, 7, 48, 96), (2, 32, 1536, 4096),
+                                         (2, 21, 256, 320)])
 def test_gemm_against_fp64(B, dtype, M, N, K):
     _say(f"gemm dtype={dtype} M={M} N={N} K={K}")
     rng = np.random.default_rng(N + K)
@@ -67,6 +70,16 @@ def test_gemm_against_fp64(B, dtype, M, N, K):
         A16, W16 = synth.f32_to_bf16_bits(A).reshape(M, K), synth.f32_to_bf16_bits(W).reshape(N, K)
         A, W = synth.bf16_bits_to_f32(A16).reshape(M, K), synth.bf16_bits_to_f32(W16).reshape(N, K)
         dA, dW = _dev(A16.view(np.int16)), _dev(W16.view(np.int16))
+    elif dtype == 2:
+        # a few values whose rounding carries into the upper 16 bits or the exponent, and tiny ones
+        A[0, :6] = np.array([0x3F7FFFC0, 0x3F80FF80, 0xBFFFFFFF, 0x3F800080, 0x3F800180, 0x00800000],
+                            np.uint32).view(np.float32)
+        W16 = synth.f32_to_bf16_bits(W).reshape(N, K)
+        W = synth.bf16_bits_to_f32(W16).reshape(N, K)
+        dA, dW = _dev(A), _dev(W16.view(np.int16))
+        # what the kernel multiplies: A rounded to 16 significant bits, ties to even
+        u = A.view(np.uint32).astype(np.uint64)
+        A = ((u + 0x7F + ((u >> 8) & 1)) & 0xFFFFFF00).astype(np.uint32).view(np.float32)
     else:
         dA, dW = _dev(A), _dev(W)
     C = torch.empty((M, N), dtype=torch.float32, device="cuda")
