@@ -257,7 +257,8 @@ int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_
                   void *stream);
 
 /* Tuning aid: average microseconds per launch of the bf16 projection kernel (plain-store epilogue) at
- * shape M x N x K over `iters` back-to-back launches on zero-filled operands.  `tn` = output tiles
+ * shape M x N x K over `iters` back-to-back launches on zero-filled operands (activations in the
+ * 3-byte form the model's projections read).  `tn` = output tiles
  * per workgroup (1..3), wk = waves splitting K (8 or 4; 0 = the choice the model makes), u = k-steps per
  * prefetch stage (2).
  * A negative `iters` times |iters| launches that rotate through more than 1 GiB of weight copies,

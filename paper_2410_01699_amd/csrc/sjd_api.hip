@@ -177,7 +177,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
 extern "C" void sjd_kv_free(sjd_kv *kv)
 {
     if (!kv) return;
-    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->ring, kv->cfg_tab, kv->btab, kv->tokens, kv->state, kv->x, kv->x24, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
+    void *ptrs[] = {kv->k, kv->v, kv->k_u, kv->v_u, kv->logits_last, kv->ring, kv->cfg_tab, kv->btab, kv->tokens, kv->state, kv->x, kv->x24, kv->ssq, kv->h, kv->part, kv->qact, kv->att_part, kv->att_out,
                     kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
                     kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
     for (void *p : ptrs) if (p) (void)hipFree(p);
@@ -224,6 +224,7 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     // smaller than the fp32 matrices of the fp32 models these sizes are written for)
     A(kv->x, R * d * 4 + 2048);
     A(kv->x24, c.dtype == 1 ? act24_bytes((int)d / 32) : 16);
+    A(kv->ssq, c.dtype == 1 ? R * ssq_stride((int)d) * 4 : 16);
     A(kv->h, c.dtype == 0 ? R * d * 4 : 16);
     A(kv->part, (c.dtype == 0 ? part : 4) * 4);
     A(kv->qact, R * d * 4);
@@ -442,20 +443,26 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
     e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid; e_qkv.max_seq = m->cfg.max_seq;
-    e_res.kind = SJD_EPI_RESID; e_res.out = kv->x; e_res.out24 = kv->x24;
+    e_res.kind = SJD_EPI_RESID; e_res.out = kv->x; e_res.out24 = kv->x24; e_res.ssq_out = kv->ssq;
     e_silu.kind = SJD_EPI_SILU; e_silu.ffn = kv->ffn; e_silu.F = F;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
     const void *x = kv->x24, *att = kv->att_out, *ffn = kv->ffn;     // hi / lo planes, 3 bytes per value
+    // x24 holds x * (gain of the normalisation the next projection sits behind), kv->ssq its partial
+    // sums of squares: written by the embedding kernel for the first layer, by each residual epilogue
+    // for whatever follows it
+    const float *ssq = kv->ssq;
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
         e_qkv.layer_off = (size_t)l * kv->k_layer_stride;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, true, (const bf16_t *)L.g1, eps, grows, e_qkv, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, true, ssq, eps, grows, e_qkv, s));
         PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, s));
+        e_res.gain_next = (const bf16_t *)L.g2;
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, true, nullptr, 0.f, grows, e_res, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, true, (const bf16_t *)L.g2, eps, grows, e_silu, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, true, ssq, eps, grows, e_silu, s));
+        e_res.gain_next = (const bf16_t *)(l + 1 < m->cfg.n_layers ? m->layers[l + 1].g1 : m->gf);
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, true, nullptr, 0.f, grows, e_res, s));
     }
-    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, true, (const bf16_t *)m->gf, eps, grows, e_lm, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, true, ssq, eps, grows, e_lm, s));
     return SJD_OK;
 }
 
@@ -469,7 +476,7 @@ static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const fl
     if (m->cfg.dtype == 1) {
         const SjdStreams sm = handle_streams(kv, stream_mode);
         const int32_t *idv[SJD_MAX_STREAMS] = {ids, ids};
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, kv->x24, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, kv->x24, kv->ssq, s));
         const double toks = (stream_mode == 1 ? 0 : kv->n_upper + rows) + (stream_mode == 0 ? 0 : kv->n_upper_u + rows);
         return forward_rows_bf16(m, kv, sm, rows, rows_valid, toks, logits, s);
     }
@@ -477,7 +484,7 @@ static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const fl
     const SjdStreams one = handle_streams(kv, 0);     // (only the finished flag is used by the embedding)
     const int32_t *idv[SJD_MAX_STREAMS] = {ids};
     for (int stream = (stream_mode == 1 ? 1 : 0); stream <= (stream_mode == 0 ? 0 : 1); ++stream) {
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, kv->x24, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, kv->x24, kv->ssq, s));
         SJD_TRY(forward_rows_f32(m, kv, rows, rows_valid, stream,
                                  logits + (stream_mode == 2 && stream ? (size_t)SJD_STREAM_ROWS * m->V_s : 0), s));
     }
@@ -835,7 +842,7 @@ static int forward_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int3
 {
     sjd_kv *kv0 = kvs[0];
     const SjdStreams sm = batch_streams(kvs, B, L);
-    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, s));
+    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, s));
     double toks = 0;
     for (int b = 0; b < B; ++b) toks += kvs[b]->n_upper + L;
     return forward_rows_bf16(m, kv0, sm, L, L, toks, kv0->logits, s);
@@ -1258,12 +1265,12 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     HIP_TRY(hipEventCreate(&e0));
     if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); sjd_set_hip_error(e, "hipEventCreate"); return SJD_EHIP; }
     int rc = SJD_OK;
-    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, g.Ap, false, nullptr, 0.f, M, ep, 0);
+    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, g.Ap, true, nullptr, 0.f, M, ep, 0);
     if (rc == SJD_OK) {
         (void)hipEventRecord(e0, 0);
         for (int i = 0; i < iters && rc == SJD_OK; ++i) {
             lin.w = (const char *)g.Wp + (size_t)(i % copies) * wbytes;
-            rc = sjd_launch_gemm_bf16(&lin, g.Ap, false, nullptr, 0.f, M, ep, 0);
+            rc = sjd_launch_gemm_bf16(&lin, g.Ap, true, nullptr, 0.f, M, ep, 0);
         }
         (void)hipEventRecord(e1, 0);
         (void)hipEventSynchronize(e1);

@@ -10,15 +10,17 @@
 //  - The activations are the B operand (tokens on the 16 columns), multiplied as a pair of bf16
 //    operands hi + lo: ~16 significant bits.  Inside the model they arrive from L2 in 3 bytes per
 //    value, stored by their producers in B-operand order (act24_idx): the bf16 hi plane is the first
-//    operand as stored, the second is rebuilt from the byte plane (with a normalisation in front, the
-//    value is rebuilt, scaled by the gain and split again).  The hooks that time or test the kernel
+//    operand as stored, the second is rebuilt from the byte plane.  The hooks that time or test the kernel
 //    alone pass fp32 values in the same order (act_off), split on the fly into hi = bf16(x) and
 //    lo = bf16(x - hi).  A wave reuses each activation tile for its TN weight tiles, so TN sets the
 //    ratio of L2 to HBM traffic.
-//  - RMSNorm in front of a projection is folded in: the values are multiplied by the gain before the
-//    split, every workgroup accumulates the sum of squares of the rows it streams anyway, and the
-//    factor rsqrt(mean(x^2) + eps) of each token is applied to the final sums (it is constant along
-//    the reduction).  All workgroups add the squares in the same order, so they agree bit for bit.
+//  - RMSNorm in front of a projection is folded in and costs the streaming loop nothing: whoever
+//    writes the residual stream (the residual epilogue, the embedding kernel) leaves the planes of
+//    x * gain of the NEXT normalisation, plus the sum of squares of x over its 16 features per
+//    token; the projection behind the normalisation adds those partial sums (every workgroup in the
+//    same order, so they agree bit for bit) and applies rsqrt(mean(x^2) + eps) of each token to its
+//    final sums (the factor is constant along the reduction).  (Rebuilding x, scaling and splitting
+//    it inside the loop instead made the 32-row variants instruction-bound.)
 //  - One workgroup owns TN output tiles (16*TN features) for the WHOLE reduction; its WK waves
 //    split K between them and add their fp32 accumulators through LDS in wave order.  No global
 //    partial sums, no atomics: results are deterministic and the epilogue sees final values.
@@ -55,6 +57,7 @@ __device__ __forceinline__ uint32_t pack_hi2(float a, float b, float &ra, float 
 // What an epilogue needs from memory besides the sums; fetched while the weights stream.
 struct EpiPre {
     f32x4 x;                  // RESID: current residual values
+    uint2 gn;                 // RESID: 4 bf16 gains of the normalisation that follows
     float c0, s0, c1, s1;     // QKV: RoPE factors of this thread's two pairs
     int pos;                  // QKV: absolute position of row m in its stream's cache
     int row;                  // QKV: row index inside the stream
@@ -66,6 +69,7 @@ __device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, in
 {
     if (EPI == SJD_EPI_RESID) {
         pre.x = *reinterpret_cast<const f32x4 *>(ep.out + act_off(m, n0, N / 32));
+        pre.gn = ep.out24 ? *reinterpret_cast<const uint2 *>(ep.gain_next + n0) : make_uint2(0u, 0u);
     } else if (EPI == SJD_EPI_QKV) {
         const int half = ep.hd >> 1;
         // the stream that owns row m: its cache length and cache (the loop index is uniform, so the
@@ -98,7 +102,17 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
     } else if (EPI == SJD_EPI_RESID) {
         const f32x4 y = pre.x + v;
         *reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32)) = y;
-        if (ep.out24) act24_store4(ep.out24, m, n0, N / 32, y[0], y[1], y[2], y[3]);
+        if (ep.out24) {
+            // what the projection behind the next normalisation reads: x * gain in planes, and this
+            // tile's share of sum(x^2) of token m (lanes l, l^16, l^32, l^48 hold its 16 features)
+            act24_store4(ep.out24, m, n0, N / 32, y[0] * __uint_as_float(pre.gn.x << 16),
+                         y[1] * __uint_as_float(pre.gn.x & 0xFFFF0000u), y[2] * __uint_as_float(pre.gn.y << 16),
+                         y[3] * __uint_as_float(pre.gn.y & 0xFFFF0000u));
+            float sq = fmaf(y[0], y[0], fmaf(y[1], y[1], fmaf(y[2], y[2], y[3] * y[3])));
+            sq += __shfl_xor(sq, 16);
+            sq += __shfl_xor(sq, 32);
+            if ((threadIdx.x & 48) == 0) ep.ssq_out[(size_t)m * ssq_stride(N) + (n0 >> 4)] = sq;
+        }
     } else if (EPI == SJD_EPI_SILU) {
         // packed rows: (gate f, up f, gate f+1, up f+1)
         const int f = n0 >> 1;
@@ -149,12 +163,12 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
 // in-workgroup split-K
 // ---------------------------------------------------------------------------------------------
 #define SJD_PRO_PLAIN 0     // fp32 activations as they are
-#define SJD_PRO_NORM 1      // activations in hi / lo planes (3 bytes per value), RMSNorm folded in
+#define SJD_PRO_NORM 1      // planes of x * gain; the token factors rsqrt(mean(x^2) + eps) come from partial sums
 #define SJD_PRO_A24 2       // activations in hi / lo planes, as they are
 template <int MT, int TN, int WK, int U, int EPI, int PRO>
 __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__restrict__ Wp,
                                                             const void *__restrict__ Xv,
-                                                            const bf16_t *__restrict__ gain, float eps, int N, int K,
+                                                            const float *__restrict__ ssq_in, float eps, int N, int K,
                                                             SjdGemmEpi ep)
 {
     static_assert(MT * TN * 64 <= 64 * WK, "one epilogue fragment per thread");
@@ -175,13 +189,10 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     const int rot = klen >= 16 ? (int)((((blockIdx.x >> 3) & 31u) * (unsigned)klen) >> 5) : 0;   // in [0, klen)
 
     f32x4 acc[MT][TN];
-    float ss[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        ss[mt] = 0.f;
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) acc[mt][tn] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    }
 
     // weights: the TN tiles of a k-step are adjacent (in 16-byte units)
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)blockIdx.x * KT * TN * 64 + lane;
@@ -190,24 +201,22 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     constexpr bool A24 = PRO != SJD_PRO_PLAIN;
     const f32x4 *xp = reinterpret_cast<const f32x4 *>(Xv) + lane;
     const uint2 *xl = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
-    const bf16_t *gp = gain + g * 8;
     // an all-zero weight tile: the tile behind the activations (fp32: tile 2 KT of 2 KiB; planes: tile
     // 2 KT of the hi plane, 1 KiB)
     const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(xp + (size_t)2 * KT * (A24 ? 64 : 128));
 
-    bf16x8 a0[U][TN], a1[U][TN], g0[U], g1[U];
+    bf16x8 a0[U][TN], a1[U][TN];
     f32x4 b0[U][MT][2], b1[U][MT][2];
 
     // Loads are unconditional (no branch between issue and use, so that the compiler can count
     // exactly which loads must have landed before a stage is consumed).  A k-step past this wave's
     // range fetches the all-zero tile that follows every activation matrix, for both operands.
-#define LOAD_STAGE(kbase, a, b, gn)                                                               \
+#define LOAD_STAGE(kbase, a, b)                                                                   \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                               \
         const int ki_ = (kbase) + u;              /* position in this wave's walk */              \
         const bool ok_ = ki_ < kt1;                                                               \
         const int kr_ = ki_ + rot;                                                                \
         const int kq_ = kr_ >= kt1 ? kr_ - klen : kr_;                                            \
-        const int kw_ = min(kq_, kt1 - 1);                                                        \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {   /* L2 hits first: they return first */ \
             const size_t tix_ = ok_ ? (size_t)mt * KT + kq_ : (size_t)2 * KT;                     \
             if (A24) {                                                                            \
@@ -221,30 +230,21 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         }                                                                                         \
         _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                         \
             a[u][tn] = __builtin_nontemporal_load(ok_ ? wp + ((size_t)kq_ * TN + tn) * 64 : zw);  \
-        if (PRO == SJD_PRO_NORM) gn[u] = *reinterpret_cast<const bf16x8 *>(gp + (size_t)kw_ * 32); \
     }
-#define MMA_STAGE(a, b, gn)                                                                       \
+#define MMA_STAGE(a, b)                                                                           \
     _Pragma("unroll") for (int u = 0; u < U; ++u)                                                 \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                       \
             bf16x8 bh_, bl_;                                                                      \
             if (A24) {                                                                            \
                 /* value = hi bits | lo byte << 8 (as fp32); second operand = value - hi, exact */ \
-                float x_[8];                                                                      \
+                bh_ = __builtin_bit_cast(bf16x8, b[u][mt][0]);                                    \
                 _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                   \
                     const uint32_t hw_ = __float_as_uint(b[u][mt][0][e >> 1]);                    \
                     const uint32_t lw_ = __float_as_uint(b[u][mt][1][e >> 2]);                    \
                     const uint32_t hb_ = (e & 1) ? (hw_ & 0xFFFF0000u) : (hw_ << 16);             \
                     const uint32_t lb_ = ((lw_ >> (8 * (e & 3))) & 0xFFu) << 8;                   \
-                    if (PRO == SJD_PRO_NORM) {                                                    \
-                        x_[e] = __uint_as_float(hb_ | lb_);                                       \
-                        ss[mt] = fmaf(x_[e], x_[e], ss[mt]);                                      \
-                        x_[e] *= (float)gn[u][e];                                                 \
-                    } else {                                                                      \
-                        bl_[e] = (__bf16)(__uint_as_float(hb_ | lb_) - __uint_as_float(hb_));     \
-                    }                                                                             \
+                    bl_[e] = (__bf16)(__uint_as_float(hb_ | lb_) - __uint_as_float(hb_));         \
                 }                                                                                 \
-                if (PRO == SJD_PRO_NORM) split8(x_, bh_, bl_);                                    \
-                else bh_ = __builtin_bit_cast(bf16x8, b[u][mt][0]);                               \
             } else {                                                                              \
                 float x_[8];                                                                      \
                 _Pragma("unroll") for (int e = 0; e < 8; ++e) x_[e] = b[u][mt][e >> 2][e & 3];    \
@@ -260,7 +260,24 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     // nobody reads, inside the buffers and the cache, and the verification that follows leaves the
     // loop state alone.  Reading a finished flag first would put a dependent scalar load in front of
     // every launch's first weight loads.)
-    LOAD_STAGE(kt0, a0, b0, g0)
+    // sum(x^2) of token c (+16 mt): K/16 partial sums left by whoever wrote x (rows of ssq_stride(K)
+    // floats, zero padded).  Wave w, lane group g fetch every (4 WK)-th float4 of the row before the
+    // first weights are requested (loads return in order: they have landed by the time the first
+    // stage has, without a wait of their own) and add them up after the main loop; groups and waves
+    // are added below in a fixed order.
+    constexpr int PJ = 4;
+    f32x4 pr[MT][PJ];
+    const int NQ = ssq_stride(K) / 4, slice = wave * 4 + g;
+    if (PRO == SJD_PRO_NORM) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const f32x4 *pp = reinterpret_cast<const f32x4 *>(ssq_in + (size_t)(mt * 16 + c) * (NQ * 4));
+#pragma unroll
+            for (int j = 0; j < PJ; ++j)
+                pr[mt][j] = pp[min(slice + j * 4 * WK, NQ - 1)];    // (past the row's end: a duplicate, dropped below)
+        }
+    }
+    LOAD_STAGE(kt0, a0, b0)
     // epilogue fragment of this thread (threads past MT*TN*64 have none and fetch a duplicate): D
     // layout of tile mtn puts features 4*(l/16) .. +4 of token l%16 in lane l
     const bool has_frag = threadIdx.x < MT * TN * 64;
@@ -272,19 +289,19 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     // (the scheduling barriers keep the compiler from starting on the previous stage before the next
     // one's loads are issued, which would drain the memory pipeline once per iteration)
     for (; kt + 2 * U < kt1; kt += 2 * U) {      // the stage loaded last still lies inside the range
-        LOAD_STAGE(kt + U, a1, b1, g1)
+        LOAD_STAGE(kt + U, a1, b1)
         __builtin_amdgcn_sched_barrier(0);
-        MMA_STAGE(a0, b0, g0)
+        MMA_STAGE(a0, b0)
         __builtin_amdgcn_sched_barrier(0);
-        LOAD_STAGE(kt + 2 * U, a0, b0, g0)
+        LOAD_STAGE(kt + 2 * U, a0, b0)
         __builtin_amdgcn_sched_barrier(0);
-        MMA_STAGE(a1, b1, g1)
+        MMA_STAGE(a1, b1)
         __builtin_amdgcn_sched_barrier(0);
     }
-    LOAD_STAGE(kt + U, a1, b1, g1)
+    LOAD_STAGE(kt + U, a1, b1)
     __builtin_amdgcn_sched_barrier(0);
-    MMA_STAGE(a0, b0, g0)
-    MMA_STAGE(a1, b1, g1)
+    MMA_STAGE(a0, b0)
+    MMA_STAGE(a1, b1)
 #undef LOAD_STAGE
 #undef MMA_STAGE
 
@@ -296,7 +313,13 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     if (PRO == SJD_PRO_NORM) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            float t = ss[mt];
+            float t = 0.f;
+#pragma unroll
+            for (int j = 0; j < PJ; ++j)
+                t += slice + j * 4 * WK < NQ ? (pr[mt][j][0] + pr[mt][j][1]) + (pr[mt][j][2] + pr[mt][j][3]) : 0.f;
+            // (rows longer than 4 * PJ * 4 WK partial sums: the rest, latency exposed)
+            const f32x4 *pp = reinterpret_cast<const f32x4 *>(ssq_in + (size_t)(mt * 16 + c) * (NQ * 4));
+            for (int i = slice + PJ * 4 * WK; i < NQ; i += 4 * WK) { const f32x4 v = pp[i]; t += (v[0] + v[1]) + (v[2] + v[3]); }
             t += __shfl_xor(t, 16);
             t += __shfl_xor(t, 32);
             if (g == 0) ssq[wave][mt * 16 + c] = t;
@@ -419,13 +442,13 @@ void sjd_choose_tiles(SjdLinear *lin)
 }
 
 template <int MT, int TN, int WK, int U, int PRO>
-static int launch_epi(const SjdLinear *lin, const void *act, const bf16_t *gain, float eps, const SjdGemmEpi &ep,
+static int launch_epi(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, const SjdGemmEpi &ep,
                       hipStream_t s)
 {
     if constexpr (WK * MT * TN * 1024 + WK * MT * 64 <= 65536) {
         dim3 grid(lin->N / (16 * TN)), block(64 * WK);
         const bf16_t *W = (const bf16_t *)lin->w;
-#define GO(EPI) SJD_LAUNCH((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, gain, eps, lin->N, lin->K, ep)
+#define GO(EPI) SJD_LAUNCH((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, ssq_in, eps, lin->N, lin->K, ep)
         if constexpr (PRO == SJD_PRO_A24) {
             // (the plane activations feed the residual projections; the plain store serves the test hook)
             switch (ep.kind) {
@@ -450,10 +473,11 @@ static int launch_epi(const SjdLinear *lin, const void *act, const bf16_t *gain,
     }
 }
 
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const bf16_t *gain, float eps, int32_t rows,
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const float *ssq_in, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s)
 {
-    if (rows < 1 || rows > SJD_ROWS_MAX || (gain && !act24)) return SJD_EINVAL;
+    if (rows < 1 || rows > SJD_ROWS_MAX || (ssq_in && !act24)) return SJD_EINVAL;
+    if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
     const int tn = lin->tn;               // fixed when the weights were packed
@@ -467,14 +491,14 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, cons
     if (mt == MT && tn == TN) {                                                                           \
         if constexpr (MT * TN <= 4) {                                                                     \
             if (wk == 4) {                                                                                \
-                if (gain) return launch_epi<MT, TN, 4, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);      \
-                if (act24) return launch_epi<MT, TN, 4, 2, SJD_PRO_A24>(lin, act, gain, eps, ep, s);      \
-                return launch_epi<MT, TN, 4, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);               \
+                if (ssq_in) return launch_epi<MT, TN, 4, 2, SJD_PRO_NORM>(lin, act, ssq_in, eps, ep, s);      \
+                if (act24) return launch_epi<MT, TN, 4, 2, SJD_PRO_A24>(lin, act, ssq_in, eps, ep, s);      \
+                return launch_epi<MT, TN, 4, 2, SJD_PRO_PLAIN>(lin, act, ssq_in, eps, ep, s);               \
             }                                                                                             \
         } else if (wk == 4) return SJD_EINVAL;                                                            \
-        if (gain) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM>(lin, act, gain, eps, ep, s);              \
-        if (act24) return launch_epi<MT, TN, 8, 2, SJD_PRO_A24>(lin, act, gain, eps, ep, s);              \
-        return launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, gain, eps, ep, s);                       \
+        if (ssq_in) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM>(lin, act, ssq_in, eps, ep, s);              \
+        if (act24) return launch_epi<MT, TN, 8, 2, SJD_PRO_A24>(lin, act, ssq_in, eps, ep, s);              \
+        return launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, ssq_in, eps, ep, s);                       \
     }
     CASE(1, 1) CASE(1, 2) CASE(1, 3)
     CASE(2, 1) CASE(2, 2) CASE(2, 3)

@@ -119,7 +119,8 @@ __host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
 // anyway), its upper 16 bits in a bf16 "hi" plane that IS the first MFMA operand, the next 8 bits in a
 // byte "lo" plane from which the projection rebuilds the second operand.  The attention output and
 // the FFN hidden exist in this form only; the residual stream is accumulated in fp32 (act_off order,
-// read and written by the residual epilogues) and every writer also leaves its planes.  Every byte a projection reads passes through its CU's vector memory
+// read and written by the residual epilogues) and every writer also leaves the planes of x * gain of
+// the normalisation that follows, plus per-token sums of squares (ssq_stride).  Every byte a projection reads passes through its CU's vector memory
 // pipeline at the same cost, whether it comes from HBM or from L2, so a quarter less activation
 // traffic is time saved on the shapes whose workgroups read more activation than weight bytes.
 // Plane layout for a [32 x K] matrix: tiles (m/16, k/32) of 512 values, value index act24_idx(); the
@@ -138,6 +139,9 @@ __device__ __forceinline__ uint32_t f32_to_act24(float x)
     u += 0x7Fu + ((u >> 8) & 1u);
     return u & 0xFFFFFF00u;
 }
+// Row length (floats) of the per-token partial sums of squares a writer of a [32 x K] residual matrix
+// leaves, one per 16 features; padded (with zeros nobody writes) to whole float4.
+__host__ __device__ __forceinline__ int ssq_stride(int K) { return (K / 16 + 3) & ~3; }
 // planes of 4 consecutive values (k a multiple of 4) / of 2 (k even) of row m
 __device__ __forceinline__ void act24_store4(void *base, int m, int k, int KT, float v0, float v1, float v2, float v3)
 {
@@ -201,7 +205,9 @@ struct SjdGemmEpi {
     SjdStreams sm;               // QKV: who owns which rows
     size_t layer_off;            // QKV: element offset of this layer inside every stream's cache
     float *out;                  // STORE / RESID: [rows][N]
-    void *out24;                 // RESID: hi / lo planes of the updated rows (or NULL)
+    void *out24;                 // RESID: planes of (updated rows) * gain_next, or NULL: none of the three
+    const bf16_t *gain_next;     // RESID: [N] gain of the normalisation that follows
+    float *ssq_out;              // RESID: [rows][ssq_stride(N)] sum of squares of the updated rows per 16 features
     void *ffn; int32_t F;                                         // SILU: [rows][F] in act24 planes
     float *qact; const float *cosT, *sinT;                        // QKV
     int32_t d, hd, nblk, rows_valid, max_seq;                     // rows_valid: rows per stream whose K/V are stored
@@ -238,7 +244,8 @@ struct sjd_kv {
     SjdState *state;      // device
     // ---- scratch for one forward over <= SJD_ROWS_MAX rows ----
     float *x;             // [rows][d] residual stream
-    void *x24;            // bf16 models: its hi / lo planes (what the projections read)
+    void *x24;            // bf16 models: hi / lo planes of x * (gain of the next normalisation)
+    float *ssq;           // bf16 models: [rows][ssq_stride(d)] partial sums of squares of x
     void *h;              // fp32 models: [rows][d] normalised activations
     float *part;          // fp32 models: GEMM output
     size_t part_elems;
@@ -294,7 +301,7 @@ struct sjd_kv {
 // bf16 models: `rows` rows per stream, stream s from ids[s] (device ids; all streams share emb_rows when
 // that is given instead), written at row s << sm.shift.  fp32 models: one stream, ids[0].
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, void *x24, hipStream_t s);
+                     const SjdStreams &sm, float *x, void *x24, float *ssq, hipStream_t s);
 int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
 int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
@@ -308,9 +315,10 @@ int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_
 int sjd_repack_bf16(const bf16_t *src_dev, bf16_t *dst_dev, int32_t N, int32_t K, int32_t tn, int32_t perm, int32_t d,
                     int32_t hd, hipStream_t s);
 void sjd_choose_tiles(SjdLinear *lin);
-// bf16 projection: act = the 3-byte planes described at act24_idx() (act24 set; gain != NULL fuses
-// RMSNorm(act; gain, eps) in front) or fp32 [SJD_ROWS_MAX x K] in act_off order (no gain then)
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const bf16_t *gain, float eps, int32_t rows,
+// bf16 projection: act = the 3-byte planes described at act24_idx() (act24 set) or fp32 [SJD_ROWS_MAX x K]
+// in act_off order.  ssq_in != NULL (planes only): the planes hold x * gain and ssq_in the partial sums
+// of squares of x ([rows][ssq_stride(K)]); the projection applies rsqrt(mean(x^2) + eps) per row.
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const float *ssq_in, float eps, int32_t rows,
                          const SjdGemmEpi &ep, hipStream_t s);
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
 int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s);

@@ -13,19 +13,20 @@ template <> struct Act<bf16_t> {
     __device__ static float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 };
 
-// x[row][:] = E[id][:]  (or the given raw embedding row); bf16 models keep x in act_off order plus its
-// hi / lo planes in x24.  Stream
+// x[row][:] = E[id][:]  (or the given raw embedding row); bf16 models keep x in act_off order and leave
+// what the first projection reads: the hi / lo planes of x * gain (first layer's attention norm) in
+// x24 and the sums of squares of x per 16 features in ssq.  Stream
 // blockIdx.z takes its ids from ids.p[stream] and writes rows (stream << shift)..; one thread per 4
 // consecutive features; grid (rows per stream, d / 1024, streams).
 struct EmbedIds { const int32_t *p[SJD_MAX_STREAMS]; };
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, const float *emb_rows, int d, int shift,
-                                                    float *x, void *x24)
+                                                    float *x, void *x24, const bf16_t *gain, float *ssq)
 {
     const int stream = blockIdx.z;
     const int r = blockIdx.x;
     const int j = (blockIdx.y * 256 + threadIdx.x) * 4;
-    if (j >= d) return;
+    if (j >= d) return;       // (d is a multiple of 32 in bf16 models: whole groups of 4 threads leave)
     float4 v;
     if (emb_rows) {
         v = *reinterpret_cast<const float4 *>(emb_rows + (size_t)r * d + j);
@@ -40,7 +41,15 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, co
     const int row = (stream << shift) + r;
     float *dst = sizeof(T) == 2 ? x + act_off(row, j, d / 32) : x + (size_t)row * d + j;
     *reinterpret_cast<float4 *>(dst) = v;
-    if (sizeof(T) == 2) act24_store4(x24, row, j, d / 32, v.x, v.y, v.z, v.w);
+    if (sizeof(T) == 2) {
+        const uint2 gn = *reinterpret_cast<const uint2 *>(gain + j);
+        act24_store4(x24, row, j, d / 32, v.x * __uint_as_float(gn.x << 16), v.y * __uint_as_float(gn.x & 0xFFFF0000u),
+                     v.z * __uint_as_float(gn.y << 16), v.w * __uint_as_float(gn.y & 0xFFFF0000u));
+        float sq = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w)));
+        sq += __shfl_xor(sq, 1);                      // 4 consecutive threads hold 16 consecutive features
+        sq += __shfl_xor(sq, 2);
+        if ((threadIdx.x & 3) == 0) ssq[(size_t)row * ssq_stride(d) + (j >> 4)] = sq;
+    }
 }
 
 // x[r] += sum_p part[p][r]  (skipped when part == NULL);  h[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * g
@@ -142,21 +151,21 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *part, int
 #define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
 
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, void *x24, hipStream_t s)
+                     const SjdStreams &sm, float *x, void *x24, float *ssq, hipStream_t s)
 {
     if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows < 1 || rows > (1 << sm.shift) ||
         (sm.count << sm.shift) > SJD_ROWS_MAX)
         return SJD_EINVAL;
     if (m->cfg.dtype == 0 && sm.count != 1) return SJD_EINVAL;
-    if (m->cfg.dtype == 1 && !x24) return SJD_EINVAL;
+    if (m->cfg.dtype == 1 && (!x24 || !ssq)) return SJD_EINVAL;
     const int d = m->cfg.d_model;
     EmbedIds e;
     for (int i = 0; i < SJD_MAX_STREAMS; ++i) e.p[i] = (ids && i < sm.count) ? ids[i] : nullptr;
     const dim3 grid(rows, (d + 1023) / 1024, sm.count);
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x, x24);
+        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)nullptr, ssq);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x, x24);
+        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)m->layers[0].g1, ssq);
     LAUNCH_CHECK();
     return SJD_OK;
 }
