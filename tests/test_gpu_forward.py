@@ -160,6 +160,43 @@ def test_forward_small_bf16(B):
     _say(f"small bf16 worst {worst:.3e}")
 
 
+def _random_gains(shape, blob, seed):
+    """the RMSNorm gains of a blob (all ones as generated) replaced by values in [0.5, 1.5)"""
+    rng = np.random.default_rng(seed)
+    for _, (off, shp) in synth.tensor_offsets(shape).items():
+        if len(shp) == 1:
+            g = rng.uniform(0.5, 1.5, shp[0]).astype(np.float32)
+            blob[off:off + shp[0]] = g if shape.dtype == synth.DTYPE_F32 else synth.f32_to_bf16_bits(g)
+    return blob
+
+
+def test_forward_with_non_unit_norm_gains(B):
+    """every normalisation (two per layer and the final one) with its own random gain vector: a gain
+    applied at the wrong place, or the wrong layer's, shows as an error of order one"""
+    shape = synth.ModelShape(3, 64, 4, 96, 300, 44, 300, 120, synth.DTYPE_F32)
+    blob = _random_gains(shape, synth.make_weights(shape, seed=5, std=0.12), 11)
+    prompt = synth.random_tokens(40, 0, 300, seed=1)
+    toks = synth.random_tokens(40, 44, 300, seed=2)
+    worst = _check_forward(B, shape, blob, prompt, [(toks[:32], 7), (toks[3:20], 17), (toks[5:6], 1)], 2e-4)
+    _say(f"fp32 random gains worst {worst:.3e}")
+    shape = synth.ModelShape(4, 256, 4, 512, 2048, 1024, 2048, 200, synth.DTYPE_BF16)
+    blob = _random_gains(shape, synth.make_weights(shape, seed=7), 12)
+    prompt = synth.random_tokens(45, 0, 1024, seed=1)
+    toks = synth.random_tokens(64, 1024, 2048, seed=2)
+    emb = (np.random.default_rng(3).standard_normal((5, 256)) * 0.02).astype(np.float32)
+    emb = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(emb)).reshape(emb.shape)
+    worst = _check_forward(B, shape, blob, prompt, [(toks[:16], 5), (toks[16:48], 32), (toks[50:57], 7)], TOL_BF16,
+                           embeds=emb)
+    _say(f"bf16 random gains worst {worst:.3e}")
+    # d_model = 96: 6 partial sums of squares per token, rows padded to 8
+    shape = synth.ModelShape(2, 96, 3, 160, 512, 0, 512, 100, synth.DTYPE_BF16)
+    blob = _random_gains(shape, synth.make_weights(shape, seed=9, std=0.05), 13)
+    prompt = synth.random_tokens(33, 0, 512, seed=1)
+    toks = synth.random_tokens(40, 0, 512, seed=2)
+    worst = _check_forward(B, shape, blob, prompt, [(toks[:9], 9), (toks[9:40], 31)], TOL_BF16)
+    _say(f"bf16 d=96 random gains worst {worst:.3e}")
+
+
 def test_forward_775m_bf16(B):
     """full size of the class-conditional configuration: prompt = 1 id + 120 embedding rows"""
     w = synth.WORKLOADS["775m"]
