@@ -173,7 +173,9 @@ def _random_gains(shape, blob, seed):
 def test_forward_with_non_unit_norm_gains(B):
     """every normalisation (two per layer and the final one) with its own random gain vector: a gain
     applied at the wrong place, or the wrong layer's, shows as an error of order one"""
-    shape = synth.ModelShape(3, 64, 4, 96, 300, 44, 300, 120, synth.DTYPE_F32)
+    # (also a RoPE base and a normalisation epsilon other than the defaults every other test uses; the
+    # epsilons are of the order of mean(x^2), so that they matter)
+    shape = synth.ModelShape(3, 64, 4, 96, 300, 44, 300, 120, synth.DTYPE_F32, rope_theta=50000.0, rms_eps=1e-2)
     blob = _random_gains(shape, synth.make_weights(shape, seed=5, std=0.12), 11)
     prompt = synth.random_tokens(40, 0, 300, seed=1)
     toks = synth.random_tokens(40, 44, 300, seed=2)
@@ -189,7 +191,7 @@ def test_forward_with_non_unit_norm_gains(B):
                            embeds=emb)
     _say(f"bf16 random gains worst {worst:.3e}")
     # d_model = 96: 6 partial sums of squares per token, rows padded to 8
-    shape = synth.ModelShape(2, 96, 3, 160, 512, 0, 512, 100, synth.DTYPE_BF16)
+    shape = synth.ModelShape(2, 96, 3, 160, 512, 0, 512, 100, synth.DTYPE_BF16, rope_theta=1e6, rms_eps=3e-3)
     blob = _random_gains(shape, synth.make_weights(shape, seed=9, std=0.05), 13)
     prompt = synth.random_tokens(33, 0, 512, seed=1)
     toks = synth.random_tokens(40, 0, 512, seed=2)
