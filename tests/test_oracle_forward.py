@@ -5,6 +5,8 @@ classifier" (Sec. 3.1); the workload configurations fix a Llama-style decoder.  
 pinned against the Hugging Face `LlamaForCausalLM` library implementation in fp64 (an
 independent code base), and its KV-cached window path against its own full-sequence path.
 """
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -65,8 +67,11 @@ def _hf_model(shape, blob):
     return m
 
 
-def test_forward_matches_library_llama():
-    shape = _small_shape()
+@pytest.mark.parametrize("theta,eps", [(10000.0, 1e-5), (500000.0, 2e-2)])
+def test_forward_matches_library_llama(theta, eps):
+    # (the second case: a RoPE base and a normalisation epsilon that are not the defaults; the epsilon is
+    # of the order of mean(x^2), so that dropping it or misplacing it shows)
+    shape = dataclasses.replace(_small_shape(), rope_theta=theta, rms_eps=eps)
     blob = _random_blob(shape, seed=11)
     ids = synth.random_tokens(21, 0, shape.vocab_total, seed=5)
     om = oracle.Model(shape, blob)
