@@ -182,7 +182,9 @@ def test_forward_with_non_unit_norm_gains(B):
     worst = _check_forward(B, shape, blob, prompt, [(toks[:32], 7), (toks[3:20], 17), (toks[5:6], 1)], 2e-4)
     _say(f"fp32 random gains worst {worst:.3e}")
     shape = synth.ModelShape(4, 256, 4, 512, 2048, 1024, 2048, 200, synth.DTYPE_BF16)
-    blob = _random_gains(shape, synth.make_weights(shape, seed=7), 12)
+    # (weights large enough for attention scores of order one: with the 0.02 of the workloads the
+    # softmax is nearly uniform and would hide a wrong score scale)
+    blob = _random_gains(shape, synth.make_weights(shape, seed=7, std=0.08), 12)
     prompt = synth.random_tokens(45, 0, 1024, seed=1)
     toks = synth.random_tokens(64, 1024, 2048, seed=2)
     emb = (np.random.default_rng(3).standard_normal((5, 256)) * 0.02).astype(np.float32)
