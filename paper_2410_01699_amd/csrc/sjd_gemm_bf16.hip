@@ -481,11 +481,11 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, cons
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;
     const int tn = lin->tn;               // fixed when the weights were packed
-    // waves per workgroup: 0 = automatic.  Four waves (longer k-range per wave, two workgroups per CU)
-    // measured 3-15 % faster than eight except on the widest grids; they need one epilogue fragment
-    // per thread to suffice.
+    // waves per workgroup: 0 = automatic.  Four waves (longer k-range per wave, more workgroups per CU, one
+    // of which can run its epilogue while another streams) measured 2-8 % faster inside a 7B iteration
+    // than eight where a workgroup holds at most three accumulator fragments; eight with four or more.
     int wk = lin->wk;
-    if (wk == 0) wk = (mt * tn <= 4 && lin->N / (16 * tn) <= 512) ? 4 : 8;
+    if (wk == 0) wk = mt * tn <= 3 ? 4 : 8;
     if (wk != 8 && wk != 4) return SJD_EINVAL;
 #define CASE(MT, TN)                                                                                      \
     if (mt == MT && tn == TN) {                                                                           \
