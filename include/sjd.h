@@ -260,7 +260,7 @@ int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_
  * shape M x N x K over `iters` back-to-back launches on zero-filled operands (activations in the
  * 3-byte form the model's projections read).  `tn` = output tiles
  * per workgroup (1..3), wk = waves splitting K (8 or 4; 0 = the choice the model makes), u = k-steps per
- * prefetch stage (2).
+ * prefetch stage (2; 4 for wk = 4, M <= 16; 0 = the choice the model makes).
  * A negative `iters` times |iters| launches that rotate through more than 1 GiB of weight copies,
  * so that no launch finds its weights in the last-level cache (the situation inside a step).
  * SJD_EINVAL for an unsupported combination.                                                     */

@@ -117,7 +117,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
     };
     // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
     auto linear = [&](size_t off, int N, int K, int perm, SjdLinear *lin) -> int {
-        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 0; lin->u = 2;
+        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 0; lin->u = 0;
         lin->w = db + off * es;
         const size_t n = (size_t)N * K;
         if (cfg->dtype == 0) {
@@ -1221,7 +1221,7 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4 + 2048));   // rows past M and the tile behind stay zero
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 0; lin.u = 2; lin.w = W;
+    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 0; lin.u = 0; lin.w = W;
     if (dtype >= 1) {
         if (dtype == 1) SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
         else SJD_TRY(sjd_f32_rows_to_act24((const float *)A, M, K, g.Ap, s));     // hi / lo planes
@@ -1249,7 +1249,7 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     const bool cold = iters < 0;
     if (cold) iters = -iters;
     if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
-    if (tn < 1 || N % (16 * tn) || u != 2) return SJD_EINVAL;       // (only two k-steps per stage are built)
+    if (tn < 1 || N % (16 * tn) || (u != 0 && u != 2 && u != 4)) return SJD_EINVAL;       // (0: the model's choice)       // (only two k-steps per stage are built)
     const size_t wbytes = (size_t)N * K * 2;
     const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
     GemmScratch g;

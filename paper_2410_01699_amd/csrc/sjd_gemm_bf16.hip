@@ -438,7 +438,7 @@ void sjd_choose_tiles(SjdLinear *lin)
             best_tn = t;
         }
     }
-    lin->tn = best_tn; lin->wk = 0; lin->u = 2;
+    lin->tn = best_tn; lin->wk = 0; lin->u = 0;
 }
 
 template <int MT, int TN, int WK, int U, int PRO>
@@ -487,6 +487,25 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, cons
     int wk = lin->wk;
     if (wk == 0) wk = mt * tn <= 3 ? 4 : 8;
     if (wk != 8 && wk != 4) return SJD_EINVAL;
+    // k-steps per prefetch stage: 0 = automatic.  Four instead of two: 1 % of a 7B iteration and 1.4 % of a
+    // 775M one, for 16 rows and four waves that each walk at least 32 k-steps (alone on cold weights
+    // only the single-tile shapes gain, 6-7 %, and two-tile ones lose as much; inside an iteration none
+    // loses); shorter walks and 32 rows are 6-29 % slower with four.
+    int u = lin->u;
+    if (u == 0) u = (mt == 1 && wk == 4 && lin->K / 32 / wk >= 32) ? 4 : 2;
+    if (u == 4) {
+        if (mt != 1 || wk != 4) return SJD_EINVAL;       // (the only deep variants built)
+#define DEEP(TN)                                                                                      \
+        if (tn == TN) {                                                                               \
+            if (ssq_in) return launch_epi<1, TN, 4, 4, SJD_PRO_NORM>(lin, act, ssq_in, eps, ep, s);   \
+            if (act24) return launch_epi<1, TN, 4, 4, SJD_PRO_A24>(lin, act, ssq_in, eps, ep, s);     \
+            return launch_epi<1, TN, 4, 4, SJD_PRO_PLAIN>(lin, act, ssq_in, eps, ep, s);              \
+        }
+        DEEP(1) DEEP(2) DEEP(3)
+#undef DEEP
+        return SJD_EINVAL;
+    }
+    if (u != 2) return SJD_EINVAL;
 #define CASE(MT, TN)                                                                                      \
     if (mt == MT && tn == TN) {                                                                           \
         if constexpr (MT * TN <= 4) {                                                                     \

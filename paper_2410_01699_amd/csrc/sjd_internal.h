@@ -192,7 +192,7 @@ struct SjdLinear {
     int32_t N, K;
     int32_t tn;       // bf16: 16-wide output tiles per workgroup
     int32_t wk;       // bf16: waves per workgroup splitting K (0 = chosen at launch)
-    int32_t u;        // bf16: k-steps per prefetch stage
+    int32_t u;        // bf16: k-steps per prefetch stage (0 = chosen at launch)
 };
 
 // what the bf16 GEMM does with its final fp32 values
