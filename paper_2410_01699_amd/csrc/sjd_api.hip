@@ -1249,7 +1249,7 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     const bool cold = iters < 0;
     if (cold) iters = -iters;
     if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
-    if (tn < 1 || N % (16 * tn) || (u != 0 && u != 2 && u != 4)) return SJD_EINVAL;       // (0: the model's choice)       // (only two k-steps per stage are built)
+    if (tn < 1 || N % (16 * tn) || (u != 0 && u != 2 && u != 4)) return SJD_EINVAL;       // (0: the model's choice)
     const size_t wbytes = (size_t)N * K * 2;
     const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
     GemmScratch g;
