@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per projection launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain 1 GiB copy (profiles/projections_<workload>.md hold the runs): read + written
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"7b_32x32": (101062 + 675) * 1024, "775m": (15189 + 262) * 1024}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"7b_32x32": (101109 + 675) * 1024, "775m": (15199 + 262) * 1024}
 
 
 def log(msg):
