@@ -46,7 +46,9 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, d_ffn;
     int32_t vocab_total, samp_lo, samp_hi; /* sampling ids = [samp_lo, samp_hi)                */
     int32_t max_seq;                       /* KV rows; needs prompt + N + L                    */
-    int32_t dtype;                         /* 0 = fp32, 1 = bf16 (weights, activations, cache) */
+    int32_t dtype;                         /* 0 = fp32 throughout; 1 = bf16 weights, activations
+                                              and cache as bf16 operand pairs hi + lo (about 16
+                                              significant bits), fp32 accumulation             */
     float rope_theta, rms_eps;
 } sjd_config;
 
