@@ -10,23 +10,23 @@
 //  - The activations are the B operand (tokens on the 16 columns), multiplied as a pair of bf16
 //    operands hi + lo: ~16 significant bits.  Inside the model they arrive from L2 in 3 bytes per
 //    value, stored by their producers in B-operand order (act24_idx): the bf16 hi plane is the first
-//    operand as stored, the second is rebuilt from the byte plane.  The hooks that time or test the kernel
-//    alone pass fp32 values in the same order (act_off), split on the fly into hi = bf16(x) and
-//    lo = bf16(x - hi).  A wave reuses each activation tile for its TN weight tiles, so TN sets the
-//    ratio of L2 to HBM traffic.
+//    operand as stored, the second is rebuilt from the byte plane.  The test hook can also pass fp32
+//    values in the same order (act_off), split on the fly into hi = bf16(x) and lo = bf16(x - hi).
+//    A wave reuses each activation tile for its TN weight tiles, so TN sets the ratio of L2 to HBM
+//    traffic.
 //  - RMSNorm in front of a projection is folded in and costs the streaming loop nothing: whoever
 //    writes the residual stream (the residual epilogue, the embedding kernel) leaves the planes of
 //    x * gain of the NEXT normalisation, plus the sum of squares of x over its 16 features per
 //    token; the projection behind the normalisation adds those partial sums (every workgroup in the
 //    same order, so they agree bit for bit) and applies rsqrt(mean(x^2) + eps) of each token to its
-//    final sums (the factor is constant along the reduction).  (Rebuilding x, scaling and splitting
-//    it inside the loop instead made the 32-row variants instruction-bound.)
+//    final sums (the factor is constant along the reduction).
 //  - One workgroup owns TN output tiles (16*TN features) for the WHOLE reduction; its WK waves
 //    split K between them and add their fp32 accumulators through LDS in wave order.  No global
 //    partial sums, no atomics: results are deterministic and the epilogue sees final values.
 //    (A stream-K variant that balanced work across waves through global partial tiles and a ticket
 //    counter was measured 2-4x slower here: the device-scope fences it needs write back L2.)
-//  - Each wave keeps U k-steps of loads in flight ahead of the MFMAs (register double buffering).
+//  - Each wave keeps U k-steps of loads in flight ahead of the MFMAs (register double buffering);
+//    U = 2, or 4 for long walks over 16 rows.
 //  - Epilogues see final fp32 values: plain store (LM head logits), residual add into the fp32
 //    stream (O and down projections), SiLU(gate)*up (gate and up rows are interleaved inside each
 //    tile when packed, so a lane holds both), RoPE + KV-cache write (Q/K rows of a head are packed

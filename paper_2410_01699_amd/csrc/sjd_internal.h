@@ -103,28 +103,27 @@ __device__ __forceinline__ SjdStreamEntry stream_entry(const SjdStreams &sm, int
     return sm.table[s];
 }
 
-// bf16 models keep every activation the projections consume (residual stream, attention output, FFN
-// hidden) as fp32 in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a wave fetches the
-// 16 x 32 tile of a k-step with two contiguous 1 KiB loads; the projection kernel splits the values
-// into hi + lo bf16 operands on the fly.  Element (row m, column k) of a [32 x K] matrix lives at
-// act_off(m, k, K/32) floats: tile (m/16, k/32) of 512 floats, inside it two halves (k%8 < 4, >= 4) of
-// 64 lanes x 4 floats, lane = 16 * ((k%32)/8) + m%16.
+// Activations of bf16 models are laid out in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a
+// wave fetches the 16 x 32 tile of a k-step with contiguous loads.  As fp32 (the residual stream, which
+// is accumulated at full precision and read and written by the residual epilogues only; the operands of
+// the hooks that run the projection kernel alone): element (row m, column k) of a [32 x K] matrix
+// lives at act_off(m, k, K/32) floats: tile (m/16, k/32) of 512 floats, inside it two halves (k%8 < 4,
+// >= 4) of 64 lanes x 4 floats, lane = 16 * ((k%32)/8) + m%16.
 __host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
 {
     return (((size_t)(m >> 4) * KT + (k >> 5)) * 2 + ((k >> 2) & 1)) * 256 + ((((k & 31) >> 3) * 16 + (m & 15)) << 2) + (k & 3);
 }
 //
-// What the projections of the decoder stack actually stream is a 3-byte form of those activations:
-// the fp32 value rounded to 16 significant bits (the precision the hi + lo operand pair carries
-// anyway), its upper 16 bits in a bf16 "hi" plane that IS the first MFMA operand, the next 8 bits in a
-// byte "lo" plane from which the projection rebuilds the second operand.  The attention output and
-// the FFN hidden exist in this form only; the residual stream is accumulated in fp32 (act_off order,
-// read and written by the residual epilogues) and every writer also leaves the planes of x * gain of
-// the normalisation that follows, plus per-token sums of squares (ssq_stride).  Every byte a projection reads passes through its CU's vector memory
-// pipeline at the same cost, whether it comes from HBM or from L2, so a quarter less activation
-// traffic is time saved on the shapes whose workgroups read more activation than weight bytes.
-// Plane layout for a [32 x K] matrix: tiles (m/16, k/32) of 512 values, value index act24_idx(); the
-// hi plane holds 2*K/32 tiles plus one all-zero tile, the lo plane follows it.
+// What the projections of the decoder stack stream is a 3-byte form: the fp32 value rounded to 16
+// significant bits (the precision the hi + lo operand pair carries anyway), its upper 16 bits in a
+// bf16 "hi" plane that IS the first MFMA operand, the next 8 bits in a byte "lo" plane from which the
+// projection rebuilds the second operand.  The attention output and the FFN hidden exist in this form
+// only; every writer of the residual stream also leaves the planes of x * gain of the normalisation
+// that follows, plus per-token sums of squares (ssq_stride).  Every byte a projection reads passes
+// through its CU's vector memory pipeline at the same cost, whether it comes from HBM or from L2, so
+// a quarter less activation traffic is time saved on the shapes whose workgroups read more activation
+// than weight bytes.  Plane layout for a [32 x K] matrix: tiles (m/16, k/32) of 512 values, value
+// index act24_idx(); the hi plane holds 2*K/32 tiles plus one all-zero tile, the lo plane follows it.
 __host__ __device__ __forceinline__ size_t act24_idx(int m, int k, int KT)
 {
     return (((size_t)(m >> 4) * KT + (k >> 5)) << 9) + ((((k & 31) >> 3) * 16 + (m & 15)) << 3) + (k & 7);
