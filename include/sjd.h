@@ -33,6 +33,7 @@ extern "C" {
 #define SJD_ENOMEM (-2) /* device or host allocation failed                                    */
 #define SJD_ESEQ (-3)   /* the call would run past max_seq                                     */
 #define SJD_EHIP (-4)   /* a HIP runtime call failed; sjd_strerror() reports the last message  */
+#define SJD_ELIMIT (-5) /* a size exceeds a fixed limit of the entry point; sjd_strerror() says which */
 
 #define SJD_MAX_WINDOW 32     /* largest L accepted by sjd_step / sjd_generate                 */
 #define SJD_MAX_SAMP_VOCAB 32768 /* largest V_s the verification kernels hold in LDS          */
@@ -244,6 +245,21 @@ int sjd_verify_probs(const float *q, const float *p_old, const int32_t *draft, i
                      int32_t samp_lo, const sjd_init *init, int32_t img_pos0, const int32_t *hist, float *ring,
                      uint64_t philox_seed, uint64_t counter, int32_t *n_accepted, int32_t *new_draft,
                      float *p_new, void *stream);
+
+/* sjd_verify for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same outputs, but the scratch that
+ * sjd_verify allocates per call (the distributions of the L + 1 window indices, candidates, flags)
+ * lives in a static device array of the library, SJD_STATIC_VERIFY_FLOATS floats (1.06 MiB, held on
+ * every GPU the library runs on until the process ends).  The call allocates nothing, frees nothing
+ * and does not synchronise: outputs are valid once `stream` has been synchronised.  SJD_ELIMIT when
+ * (L + 1) * V_s exceeds SJD_STATIC_VERIFY_FLOATS (the 7B and 775M workloads fit: 33 x 8192 and
+ * 17 x 16384).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two
+ * streams, two threads) race; run them one after the other.                                      */
+#define SJD_STATIC_VERIFY_FLOATS (17 * 16384)
+int sjd_verify_static(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
+                      int32_t samp_lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
+                      const int32_t *hist, float *ring, uint64_t philox_seed, uint64_t counter, int32_t *n_accepted,
+                      int32_t *new_draft, float *p_new, void *stream);
 
 /* The sampling distribution of Sec. 3.1 for `rows` logits rows: top-K, temperature, softmax.
  * forced: dev [rows] column index to make one-hot, or -1; may be NULL.  q dev [rows x V_s].     */

@@ -14,7 +14,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsjd_hip.so")
 
-SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_ESEQ, SJD_EHIP = 0, -1, -2, -3, -4
+SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_ESEQ, SJD_EHIP, SJD_ELIMIT = 0, -1, -2, -3, -4, -5
+SJD_STATIC_VERIFY_FLOATS = 17 * 16384
 SJD_MAX_WINDOW = 32
 SJD_MAX_SAMP_VOCAB = 32768
 
@@ -23,7 +24,7 @@ EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "
            "sjd_verify", "sjd_verify_probs", "sjd_dist", "sjd_gemm_test", "sjd_strerror", "sjd_decode_begin",
            "sjd_decode_steps", "sjd_decode_status", "sjd_decode_result", "sjd_kv_use_graph", "sjd_profile_steps", "sjd_gemm_bench",
            "sjd_prefill_uncond", "sjd_generate_cfg", "sjd_decode_steps_batch", "sjd_forward_logits_batch",
-           "sjd_generate_batch", "sjd_profile_steps_batch"]
+           "sjd_generate_batch", "sjd_profile_steps_batch", "sjd_verify_static"]
 
 PROF_KINDS = ("gemm", "attention", "elementwise", "verify")
 
@@ -90,6 +91,8 @@ _SIG = {
                                      _vp, _vp]),
     "sjd_verify": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _vp, _vp, _u64, _u64,
                              _vp, _vp, _vp, _vp]),
+    "sjd_verify_static": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_sampler), _P(sjd_init), _i32, _vp, _vp, _u64, _u64,
+                                    _vp, _vp, _vp, _vp]),
     "sjd_verify_probs": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _P(sjd_init), _i32, _vp, _vp, _u64, _u64, _vp, _vp,
                                    _vp, _vp]),
     "sjd_dist": (C.c_int, [_vp, _i32, _i32, _P(sjd_sampler), _vp, _vp, _vp]),
@@ -260,6 +263,13 @@ def sjd_verify(logits, p_old, draft, L, V_s, samp_lo, smp, init, img_pos0, hist,
     _check(_lib.sjd_verify(_dev(logits), _dev(p_old), _dev(draft), L, V_s, samp_lo, C.byref(smp), C.byref(init),
                            img_pos0, _dev(hist), _dev(ring), seed, counter, _dev(n_accepted), _dev(new_draft),
                            _dev(p_new), _stream(stream)))
+
+
+def sjd_verify_static(logits, p_old, draft, L, V_s, samp_lo, smp, init, img_pos0, hist, seed, counter, n_accepted,
+                      new_draft, p_new, stream=None, ring=None):
+    _check(_lib.sjd_verify_static(_dev(logits), _dev(p_old), _dev(draft), L, V_s, samp_lo, C.byref(smp), C.byref(init),
+                                  img_pos0, _dev(hist), _dev(ring), seed, counter, _dev(n_accepted), _dev(new_draft),
+                                  _dev(p_new), _stream(stream)))
 
 
 def sjd_verify_probs(q, p_old, draft, L, V_s, samp_lo, init, img_pos0, hist, seed, counter, n_accepted, new_draft,

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -11,6 +12,7 @@
 
 // ---- errors ---------------------------------------------------------------------------------
 static thread_local char g_hip_msg[256] = "no HIP error recorded";
+static thread_local char g_limit_msg[256] = "a size exceeds a fixed limit of the entry point";
 void sjd_set_hip_error(hipError_t e, const char *what)
 {
     snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
@@ -24,6 +26,7 @@ extern "C" const char *sjd_strerror(int code)
         case SJD_ENOMEM: return "out of memory";
         case SJD_ESEQ: return "sequence would exceed max_seq";
         case SJD_EHIP: return g_hip_msg;
+        case SJD_ELIMIT: return g_limit_msg;
         default: return "unknown error code";
     }
 }
@@ -1193,6 +1196,66 @@ extern "C" int sjd_verify_probs(const float *q, const float *p_old, const int32_
     if (!q) return SJD_EINVAL;
     return verify_common(nullptr, q, p_old, draft, L, V_s, samp_lo, nullptr, init, img_pos0, hist, ring, philox_seed, counter,
                          n_accepted, new_draft, p_new, (hipStream_t)stream);
+}
+
+// ---- Step 3 + Step 4 for callers that cannot allocate ------------------------------------------
+// sjd_verify_static keeps what sjd_verify allocates per call (the distributions q[(L+1) x V_s], the
+// per-index candidates and flags, the frozen step scalars) in one file-scope device array.  In host
+// code the array's name is only a handle for the runtime: its device address is looked up once per
+// device with hipGetSymbolAddress and that pointer is what the kernels are given.
+struct VerifyStatic {
+    float q[SJD_STATIC_VERIFY_FLOATS];
+    int32_t ints[4 * (SJD_MAX_WINDOW + 1)];
+    unsigned char snap[64];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(VerifyStatic)];
+#define SJD_MAX_DEVICES 64
+static VerifyStatic *g_scratch_ptr[SJD_MAX_DEVICES];     // per device: every GPU holds its own copy of the array
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(VerifyStatic **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SJD_MAX_DEVICES) return SJD_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return SJD_EHIP;
+        g_scratch_ptr[dev] = (VerifyStatic *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SJD_OK;
+}
+
+extern "C" int sjd_verify_static(const float *logits, const float *p_old, const int32_t *draft, int32_t L, int32_t V_s,
+                                 int32_t samp_lo, const sjd_sampler *smp, const sjd_init *init, int32_t img_pos0,
+                                 const int32_t *hist, float *ring, uint64_t philox_seed, uint64_t counter,
+                                 int32_t *n_accepted, int32_t *new_draft, float *p_new, void *stream)
+{
+    if (!logits || !smp || !p_old || !draft || !n_accepted || !new_draft || !p_new || !init) return SJD_EINVAL;
+    if (init->mode == 4 && !ring) return SJD_EINVAL;
+    if (L < 1 || L > SJD_MAX_WINDOW || V_s < 1 || V_s > SJD_MAX_SAMP_VOCAB || img_pos0 < 0) return SJD_EINVAL;
+    if ((size_t)(L + 1) * V_s > SJD_STATIC_VERIFY_FLOATS) {
+        snprintf(g_limit_msg, sizeof(g_limit_msg), "sjd_verify_static: (L + 1) * V_s = %zu exceeds the static scratch of %d floats",
+                 (size_t)(L + 1) * V_s, SJD_STATIC_VERIFY_FLOATS);
+        return SJD_ELIMIT;
+    }
+    SJD_TRY(check_sampling(smp, init, samp_lo, samp_lo + V_s));
+    if ((init->mode == 1 || init->mode == 2) && img_pos0 > 0 && !hist) return SJD_EINVAL;
+    VerifyStatic *sc = nullptr;
+    SJD_TRY(static_scratch(&sc));
+    // Nothing in the scratch has to start at zero: the first kernel writes every row, candidate, flag
+    // and scalar the second one reads.  Calls that overlap on one GPU would share it and race.
+    SjdVerifyArgs v;
+    memset(&v, 0, sizeof(v));
+    v.logits = logits; v.p_old = p_old; v.draft = draft; v.L = L; v.V = V_s; v.lo = samp_lo;
+    v.smp = *smp; v.init = *init; v.hist = hist; v.ring = ring; v.seed = philox_seed; v.img_pos0 = img_pos0; v.counter = counter;
+    v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new; v.q = sc->q;
+    v.tok_smp = sc->ints; v.tok_res = sc->ints + (L + 1); v.acc_flag = sc->ints + 2 * (L + 1);
+    v.draft_snap = sc->ints + 3 * (L + 1); v.snap = sc->snap;
+    return sjd_launch_verify(&v, (hipStream_t)stream);
 }
 
 extern "C" int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sjd_sampler *smp, const int32_t *forced,

@@ -59,3 +59,23 @@ def test_null_arguments_of_the_wider_entry_points_without_gpu():
     assert lib.sjd_profile_steps_batch(None, None, 2, 1, None, None) == E
     assert lib.sjd_generate_cfg(None, None, None, 0, None, 0, None, 0, None, 0, ctypes.c_float(3.0), 8, 4, None, None,
                                 ctypes.c_uint64(0), None, None) == E
+
+
+def test_static_verify_checks_its_arguments_and_its_limit_without_gpu():
+    """the entry point that allocates nothing rejects null pointers and sizes beyond its static scratch
+    before it touches the GPU"""
+    from paper_2410_01699_amd import binding
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    lib.sjd_strerror.restype = ctypes.c_char_p
+    u64 = ctypes.c_uint64
+    assert lib.sjd_verify_static(None, None, None, 4, 64, 0, None, None, 0, None, None, u64(0), u64(0), None, None, None,
+                                 None) == binding.SJD_EINVAL
+    dummy = (ctypes.c_float * 4)()           # never dereferenced: the size check comes first
+    p = ctypes.cast(dummy, ctypes.c_void_p)
+    smp, init = binding.sjd_sampler(10, 1.0), binding.sjd_init(0, 0, -1, 0)
+    L, V = 32, 16384
+    assert (L + 1) * V > binding.SJD_STATIC_VERIFY_FLOATS
+    rc = lib.sjd_verify_static(p, p, p, L, V, 0, ctypes.byref(smp), ctypes.byref(init), 0, None, None, u64(1), u64(1), p, p, p,
+                               None)
+    assert rc == binding.SJD_ELIMIT
+    assert b"static scratch" in lib.sjd_strerror(rc)
