@@ -5,11 +5,14 @@
 
 A step is one SJD iteration (window forward + verification + window slide) of a running
 generation, with weights, KV cache, window and loop state resident in HBM.  Prints ONE JSON line:
-image tokens/s over exactly K timed steps, forward passes per image for SJD and for ordinary
-auto-regressive decoding (the same loop with window 1), the roofline position of the dominant
-kernel (the weight-streaming projections) measured inside the library with HIP events that the
-runtime stamps with each kernel's own begin and end, and the CPU
-oracle timed on a bounded sample of the same workload on this host's cores.
+`ms_per_step` over exactly K timed steps; `value` = image tokens/s over WHOLE images (mean of the
+images of seeds 0..4, with its range: the tokens an iteration fixes vary, so a rate taken over a few
+steps of one image swings by 20 %, and late iterations read a longer cache than early ones); forward
+passes per image for SJD and for ordinary auto-regressive decoding (the same loop with window 1); the
+roofline position of the dominant kernel (the weight-streaming projections) measured inside the
+library with HIP events that the runtime stamps with each kernel's own begin and end; the other
+workloads (child processes, summarised under config.also_measured); and the CPU oracle timed on a
+bounded sample of the same workload on this host's cores.
 
 Only one GPU is used; --gpus above 1 is refused.
 """
@@ -25,9 +28,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per projection launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain 1 GiB copy (profiles/projections_<workload>.md hold the runs): read + written
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"7b_32x32": (101109 + 675) * 1024, "775m": (15199 + 262) * 1024}
+
+
+def recorded_traffic(workload):
+    """HBM bytes per projection launch as rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE counted them (scaled by what
+    the same counters read for a plain 1 GiB copy) in the committed run profiles/projections_<workload>.md,
+    which ends in a line `traffic_bytes_per_launch: <read + written>`.  A recorded figure, not one of this run:
+    the JSON names its source.  None when there is no such file."""
+    path = os.path.join(ROOT, "profiles", f"projections_{workload}.md")
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return int(float(ln.split(":")[1].split()[0])), os.path.relpath(path, ROOT)
+    except OSError:
+        pass
+    return None, None
 
 
 def log(msg):
@@ -64,19 +79,25 @@ def cpu_baseline(w, blob, prompt_ids, prompt_emb, seed, budget_steps):
             "s_per_step": dt / budget_steps}
 
 
+def spread(xs):
+    return {"mean": sum(xs) / len(xs), "min": min(xs), "max": max(xs), "n": len(xs)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1024,
-                    help="timed iterations (the default spans more than one whole image of the 7B workload, so every cache length counts)")
+    ap.add_argument("--steps", type=int, default=256, help="timed iterations (ms_per_step)")
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="7b_32x32")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--images", type=int, default=5,
+                    help="whole images generated for `value` (seeds seed .. seed + images - 1; 0 = none: value falls back to "
+                         "the tokens fixed during the timed steps)")
     ap.add_argument("--profile-steps", type=int, default=24)
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle iterations to time (0 = skip)")
     ap.add_argument("--no-graph", action="store_true")
-    ap.add_argument("--skip-images", action="store_true", help="skip the whole-image SJD / AR runs")
-    ap.add_argument("--window", type=int, default=0, help="override the workload's window size L (1..32)")
+    ap.add_argument("--skip-images", action="store_true", help="same as --images 0 --skip-ar")
+    ap.add_argument("--window", type=int, default=0, help="override the workload's window size L")
     ap.add_argument("--top-k", type=int, default=0, help="override the workload's top-K (1 = greedy = Jacobi decoding)")
     ap.add_argument("--temperature", type=float, default=0.0, help="override the workload's sampling temperature")
     ap.add_argument("--init-mode", type=int, default=-1, help="override the initialiser: 0 uniform, 1 repeat above, 2 repeat left, 3 sample left, 4 sample above")
@@ -84,11 +105,14 @@ def main():
     ap.add_argument("--cfg", type=float, default=None,
                     help="classifier-free guidance weight: run a second (unconditional) context in every forward")
     ap.add_argument("--batch", type=int, default=1,
-                    help="images decoded together, one pass over the weights per iteration (window x batch <= 32 rows)")
+                    help="images decoded together, one pass over the weights per iteration")
     ap.add_argument("--skip-ar", action="store_true", help="skip the auto-regressive (window 1) image")
+    ap.add_argument("--compare-init", type=int, default=-1,
+                    help="also generate the images with this initialiser (same seeds) and report both side by side")
     ap.add_argument("--also", default=None,
-                    help="a second workload measured afterwards in a child process and summarised under "
-                         "config.also_measured ('none' = skip; default: 775m when the 7B default runs unmodified)")
+                    help="comma-separated workloads measured afterwards in child processes and summarised under "
+                         "config.also_measured ('none' = skip; default: every other configuration when the 7B default "
+                         "runs unmodified)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -96,6 +120,9 @@ def main():
         print("bench.py: this build runs on ONE GPU (independent images per GPU is how it would scale); "
               "run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.skip_images:
+        args.images = 0
+        args.skip_ar = True
 
     import numpy as np
     import torch
@@ -136,17 +163,19 @@ def main():
     if args.no_graph:
         B.sjd_kv_use_graph(kv, False)
     smp = B.sjd_sampler(w.top_k, w.temperature)
-    init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id, 1 if args.no_refine else 0)
+    flags = 1 if args.no_refine else 0
+    init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id, flags)
     N, L = w.n_image_tokens, w.window
     q_first = torch.empty(shape.v_s, dtype=torch.float32, device="cuda")
     guided = args.cfg is not None
     # the unconditional context: a short synthetic prompt of its own (a quarter of the conditional one)
     u_ids = synth.random_tokens(max(1, (len(ids) + len(emb)) // 4), 0, shape.samp_lo or shape.vocab_total, seed=77)
-    if guided and L > 16:
-        print("bench.py: --cfg needs a window of at most 16 tokens", file=sys.stderr)
-        sys.exit(2)
-    if nb > 1 and (guided or shape.dtype != 1 or nb > 8 or nb * (1 << max(0, (L - 1).bit_length())) > 32):
-        print("bench.py: --batch needs a bf16 model, no --cfg, and window x batch within 32 rows", file=sys.stderr)
+    rows_per_image = (1 << max(0, (L - 1).bit_length())) if nb > 1 else L
+    rows_needed = rows_per_image * nb * (2 if guided else 1)
+    if L > B.SJD_MAX_WINDOW or rows_needed > B.SJD_MAX_ROWS or (nb > 1 and (guided or shape.dtype != 1 or nb > 8)):
+        print(f"bench.py: window {L} x batch {nb}{' x 2 contexts' if guided else ''} does not fit one forward "
+              f"(at most {B.SJD_MAX_ROWS} rows, windows up to {B.SJD_MAX_WINDOW}; batches need a bf16 model and no --cfg)",
+              file=sys.stderr)
         sys.exit(2)
     # every image of a batch has its own prompt (same length, different ids)
     prompts = [ids] + [synth.random_tokens(len(ids), 0, shape.samp_lo or shape.vocab_total, seed=200 + b)
@@ -201,7 +230,7 @@ def main():
     run_steps(args.warmup, False)
     secs, toks = run_steps(args.steps, True)
     ms_per_step = secs / args.steps * 1e3
-    log(f"{args.steps} steps: {ms_per_step:.3f} ms/step, {toks} tokens fixed, {toks / secs:.1f} tokens/s")
+    log(f"{args.steps} steps: {ms_per_step:.3f} ms/step, {toks} tokens fixed, {toks / secs:.1f} tokens/s over these steps")
 
     # ---- roofline of the dominant kernel: HIP events around every launch, same stream ----
     prof_steps = args.profile_steps
@@ -221,11 +250,26 @@ def main():
     g["ms_per_step_back_to_back"] = p.ms_gemm_back_to_back / prof_steps
     g["us_per_launch"] = p.ms_gemm_back_to_back * 1e3 / p.launches[0]
     g["GBps"] = (p.bytes[0] / 1e9) / (p.ms_gemm_back_to_back / 1e3)
-    # (the counter runs were made on the default configuration only)
-    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload) if nb == 1 and not guided and args.window == 0 else None
+    # Attention: the library counts the K/V bytes AS STORED for the positions actually cached during the
+    # profiled iterations (device-resident lengths, read before each one).  bf16 models store every value as
+    # a hi + lo bf16 pair (4 bytes), twice the 2 bytes per value that the plain algorithm's count assumes.
+    at = classes["attention"]
+    stored_over_alg = 2.0 if shape.dtype == 1 else 1.0
+    at["stored_GB_per_step"] = at.pop("algorithmic_GB_per_step")
+    at["GBps_stored"] = at.pop("GBps")
+    at["algorithmic_GB_per_step"] = at["stored_GB_per_step"] / stored_over_alg
+    at["GBps_algorithmic"] = None if at["GBps_stored"] is None else at["GBps_stored"] / stored_over_alg
+    at["stored_over_algorithmic_bytes"] = stored_over_alg
+    at["kv_bytes_per_token_stored"] = 2 * shape.n_layers * shape.d_model * (4 if shape.dtype == 1 else 4)
+    at["kv_bytes_per_token_algorithmic"] = 2 * shape.n_layers * shape.d_model * (2 if shape.dtype == 1 else 4)
+    plain = (nb == 1 and not guided and args.window == 0 and args.top_k == 0 and args.temperature == 0
+             and args.init_mode < 0 and not args.no_refine and not args.no_graph)
+    # (the counter runs were made on the default configuration of a workload only)
+    traffic, traffic_src = recorded_traffic(args.workload) if plain else (None, None)
     roofline = {"bound": "hbm", "kernel": "gemm_fused_kernel (all projections + LM head)" if shape.dtype == 1
                 else "gemm_f32_kernel", "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_source": None if traffic is None else f"recorded rocprofv3 --pmc run, {traffic_src} (not measured by this run)",
                 "bytes_per_launch": g["algorithmic_GB_per_step"] * 1e9 / g["launches_per_step"],
                 "us_per_launch": g["us_per_launch"], "launches_per_step": g["launches_per_step"]}
     weight_bytes = g["algorithmic_GB_per_step"] * 1e9
@@ -233,85 +277,113 @@ def main():
     log(f"gemm: {g['GBps']:.0f} GB/s over {g['launches_per_step']:.0f} launches/step; "
         f"whole step at {weight_bytes / 1e9 / (ms_per_step / 1e3):.0f} GB/s of weight stream")
 
-    # ---- whole images: forward passes per image, SJD vs ordinary AR (window 1) ----
+    # ---- whole images: tokens/s (the headline), forward passes per image, SJD vs ordinary AR (window 1) ----
     extra = {}
 
-    def generate(window):
+    def generate(window, ini, seed):
         if nb > 1:
-            t, sts = B.sjd_generate_batch(m, kvs, prompts, None if not len(emb) else [emb] * nb, N, window, smp, init,
-                                          [args.seed + b for b in range(nb)])
+            t, sts = B.sjd_generate_batch(m, kvs, prompts, None if not len(emb) else [emb] * nb, N, window, smp, ini,
+                                          [seed * nb + b for b in range(nb)])
             return t, sts[0]
         if guided:
-            return B.sjd_generate_cfg(m, kv, ids, emb, u_ids, None, args.cfg, N, window, smp, init, args.seed)
-        return B.sjd_generate(m, kv, ids, emb, N, window, smp, init, args.seed)
+            return B.sjd_generate_cfg(m, kv, ids, emb, u_ids, None, args.cfg, N, window, smp, ini, seed)
+        return B.sjd_generate(m, kv, ids, emb, N, window, smp, ini, seed)
 
-    if not args.skip_images:
+    def images(ini):
+        """args.images whole generations: per-image tokens/s, forwards, tokens fixed per forward"""
+        rate, fwd = [], []
+        for sd in range(args.seed, args.seed + args.images):
+            _, st = generate(L, ini, sd)
+            rate.append(nb * N / (st.ms_decode / 1e3))
+            fwd.append(st.steps)
+        return {"seeds": list(range(args.seed, args.seed + args.images)),
+                "image_tokens_per_s": spread(rate), "forwards_per_image": spread(fwd),
+                "tokens_fixed_per_forward": spread([N / f for f in fwd]),
+                "ms_per_forward_whole_image": spread([nb * N / r * 1e3 / f for r, f in zip(rate, fwd)])}
+
+    value, value_basis = toks / secs, f"tokens fixed during the {args.steps} timed steps (no whole image was generated)"
+    if args.images > 0:
         t = time.perf_counter()
-        _, st = generate(L)
-        extra["sjd_forwards_per_image"] = st.steps
-        extra["sjd_image_seconds"] = st.ms_decode / 1e3
-        extra["sjd_image_tokens_per_s"] = nb * N / (st.ms_decode / 1e3)
-        if not args.skip_ar:
-            _, sa = generate(1)
-            extra["ar_forwards_per_image"] = sa.steps
-            extra["ar_image_seconds"] = sa.ms_decode / 1e3
-            extra["ar_image_tokens_per_s"] = nb * N / (sa.ms_decode / 1e3)
-            extra["step_compression"] = sa.steps / st.steps
-            extra["latency_speedup_vs_ar"] = sa.ms_decode / st.ms_decode
-            log(f"images: SJD {st.steps} forwards / {st.ms_decode:.0f} ms, AR {sa.steps} forwards / {sa.ms_decode:.0f} ms "
-                f"({time.perf_counter() - t:.1f} s)")
-        else:
-            log(f"image: SJD {st.steps} forwards / {st.ms_decode:.0f} ms")
+        im = images(init)
+        extra["whole_images"] = im
+        value = im["image_tokens_per_s"]["mean"]
+        value_basis = (f"whole images: N = {N} image tokens{' x ' + str(nb) + ' images' if nb > 1 else ''} / wall time of the decoding "
+                       f"loop, mean over seeds {im['seeds'][0]}..{im['seeds'][-1]} (prefill excluded, as in the paper's protocol)")
+        extra["sjd_forwards_per_image"] = im["forwards_per_image"]["mean"]
+        log(f"{args.images} images: {value:.1f} tokens/s (min {im['image_tokens_per_s']['min']:.1f}, max "
+            f"{im['image_tokens_per_s']['max']:.1f}), {im['forwards_per_image']['mean']:.0f} forwards/image "
+            f"({time.perf_counter() - t:.1f} s)")
+        if args.compare_init >= 0:
+            other = B.sjd_init(args.compare_init, w.row_stride, w.eol_id, flags)
+            extra["whole_images_init_mode_%d" % args.compare_init] = images(other)
+    if not args.skip_ar:
+        _, sa = generate(1, init, args.seed)
+        extra["ar_forwards_per_image"] = sa.steps
+        extra["ar_image_seconds"] = sa.ms_decode / 1e3
+        extra["ar_image_tokens_per_s"] = nb * N / (sa.ms_decode / 1e3)
+        if args.images > 0:
+            extra["step_compression"] = sa.steps / extra["sjd_forwards_per_image"]
+            extra["latency_speedup_vs_ar"] = value / extra["ar_image_tokens_per_s"]
+        log(f"AR image: {sa.steps} forwards / {sa.ms_decode:.0f} ms")
     for h in kvs:
         B.sjd_kv_free(h)
     B.sjd_free_model(m)
 
     cpu_steps = args.cpu_steps
     if cpu_steps < 0:
-        cpu_steps = 2 if shape.n_params() > 2e9 else (6 if shape.n_params() > 1e8 else 40)
+        cpu_steps = 3 if shape.n_params() > 2e9 else (8 if shape.n_params() > 1e8 else 40)
     cpu = None
     if guided or nb > 1:
         cpu_steps = 0          # the CPU leg times the unguided single-image path only
     if cpu_steps > 0:
         log("timing the CPU oracle on a bounded sample ...")
         cpu = cpu_baseline(w, blob, ids, emb, args.seed, cpu_steps)
+    del blob
 
     out = {
-        "metric": "image_tokens_per_s", "value": toks / secs, "unit": "tokens/s", "n_gpus": 1,
+        "metric": "image_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == 1 else "f32", "data": "synthetic",
+        "value_basis": value_basis,
+        "tokens_per_s_over_timed_steps": toks / secs,
         "config": {"workload": w.name, "window_L": L, "top_k": w.top_k, "temperature": w.temperature,
                    "init_mode": w.init_mode, "no_refine": bool(args.no_refine), "cfg_weight": args.cfg, "batch_images": nb,
                    "uncond_prompt_positions": len(u_ids) if guided else None,
                    "image_tokens_N": N, "prompt_positions": len(ids) + len(emb), "layers": shape.n_layers,
                    "d_model": shape.d_model, "sampling_vocab": shape.v_s, "hip_graph": not args.no_graph,
-                   "tokens_fixed_per_step": toks / args.steps, "step_hbm_floor_ms": step_floor_ms,
+                   "rows_per_forward": rows_needed,
+                   "tokens_fixed_per_step_timed": toks / args.steps, "step_hbm_floor_ms": step_floor_ms,
                    "step_weight_stream_GBps": weight_bytes / 1e9 / (ms_per_step / 1e3), **extra},
         "roofline": roofline, "kernel_classes": classes, "cpu_baseline": cpu,
     }
     also = args.also
     if also is None:
-        plain = (args.workload == "7b_32x32" and nb == 1 and not guided and args.window == 0 and args.top_k == 0
-                 and args.temperature == 0 and args.init_mode < 0 and not args.no_refine and not args.no_graph)
-        also = "775m" if plain else "none"
+        also = "775m,tiny,7b_48x48" if (plain and args.workload == "7b_32x32") else "none"
     if also != "none":
-        # the class-conditional configuration, same measurement without the CPU leg, in a process of its own
-        # (this one has released the GPU memory; its line is parsed, not re-printed)
+        # the other configurations, same measurement without the CPU leg, each in a process of its own (this one
+        # has released the GPU memory; their lines are parsed, not re-printed).  The 48 x 48 workload generates
+        # its images twice: uniform initialisation and repeat-above, same seeds, side by side.
         import subprocess
-        log(f"measuring workload {also} in a child process ...")
-        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", also, "--also", "none", "--cpu-steps", "0",
-                            "--steps", str(args.steps), "--warmup", str(args.warmup)], capture_output=True, text=True)
-        line = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
-        if r.returncode == 0 and line:
-            o = json.loads(line[-1])
-            out["config"]["also_measured"] = {also: {
-                "value": o["value"], "unit": o["unit"], "ms_per_step": o["ms_per_step"], "dtype": o["dtype"],
-                "window_L": o["config"]["window_L"], "tokens_fixed_per_step": o["config"]["tokens_fixed_per_step"],
-                "sjd_forwards_per_image": o["config"].get("sjd_forwards_per_image"),
-                "ar_forwards_per_image": o["config"].get("ar_forwards_per_image"),
-                "roofline": {k: o["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac")}}}
-        else:
-            out["config"]["also_measured"] = {also: {"error": (r.stderr or "no output")[-300:]}}
+        out["config"]["also_measured"] = {}
+        for name in also.split(","):
+            log(f"measuring workload {name} in a child process ...")
+            cmd = [sys.executable, os.path.abspath(__file__), "--workload", name, "--also", "none", "--cpu-steps", "0",
+                   "--steps", str(args.steps), "--warmup", str(args.warmup), "--images", str(args.images)]
+            if name == "7b_48x48":
+                cmd += ["--compare-init", "1"]
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            line = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+            if r.returncode == 0 and line:
+                o = json.loads(line[-1])
+                c = o["config"]
+                keep = {k: c[k] for k in c if k.startswith("whole_images") or k in
+                        ("window_L", "init_mode", "image_tokens_N", "ar_forwards_per_image", "ar_image_tokens_per_s",
+                         "step_compression", "latency_speedup_vs_ar", "tokens_fixed_per_step_timed")}
+                out["config"]["also_measured"][name] = {
+                    "value": o["value"], "unit": o["unit"], "ms_per_step": o["ms_per_step"], "dtype": o["dtype"], **keep,
+                    "roofline": {k: o["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac")}}
+            else:
+                out["config"]["also_measured"][name] = {"error": (r.stderr or "no output")[-300:]}
     print(json.dumps(out), flush=True)
 
 

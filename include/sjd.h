@@ -35,7 +35,9 @@ extern "C" {
 #define SJD_EHIP (-4)   /* a HIP runtime call failed; sjd_strerror() reports the last message  */
 #define SJD_ELIMIT (-5) /* a size exceeds a fixed limit of the entry point; sjd_strerror() says which */
 
-#define SJD_MAX_WINDOW 32     /* largest L accepted by sjd_step / sjd_generate                 */
+#define SJD_MAX_WINDOW 64     /* largest L accepted by sjd_step / sjd_generate                 */
+#define SJD_MAX_ROWS 128      /* rows one window forward computes: L x contexts (2 under guidance) x
+                                 images of a batch, each image's rows rounded up to a power of two  */
 #define SJD_MAX_SAMP_VOCAB 32768 /* largest V_s the verification kernels hold in LDS          */
 
 typedef struct sjd_model sjd_model; /* repacked device weights + tables; immutable after init  */
@@ -279,6 +281,11 @@ int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_
  * 3-byte form the model's projections read).  `tn` = output tiles
  * per workgroup (1..3), wk = waves splitting K (8 or 4; 0 = the choice the model makes), u = k-steps per
  * prefetch stage (2; 4 for wk = 4, M <= 16; 0 = the choice the model makes).
+ * More than 32 rows run the wide kernel (waves split N and share the activations through LDS, K split
+ * across workgroups, a second kernel adds the slices): then wk = K-slices and u = weight groups per wave
+ * (0 = automatic); wk >= 100 asks for the wide kernel at any row count, with wk - 100 K-slices.  M above
+ * SJD_MAX_ROWS is an off-path measurement of the wide kernel's matrix-core rate: the rows are cut into
+ * chunks of SJD_MAX_ROWS, one launch pair each over the same weights.
  * A negative `iters` times |iters| launches that rotate through more than 1 GiB of weight copies,
  * so that no launch finds its weights in the last-level cache (the situation inside a step).
  * SJD_EINVAL for an unsupported combination.                                                     */

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libsjd_hip.so")
 
 SJD_OK, SJD_EINVAL, SJD_ENOMEM, SJD_ESEQ, SJD_EHIP, SJD_ELIMIT = 0, -1, -2, -3, -4, -5
 SJD_STATIC_VERIFY_FLOATS = 17 * 16384
-SJD_MAX_WINDOW = 32
+SJD_MAX_WINDOW = 64
+SJD_MAX_ROWS = 128          # rows one forward computes (window x contexts x images)
 SJD_MAX_SAMP_VOCAB = 32768
 
 EXPORTS = ["sjd_init_model", "sjd_free_model", "sjd_kv_create", "sjd_kv_free", "sjd_kv_reset", "sjd_kv_len",

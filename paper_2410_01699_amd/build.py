@@ -24,7 +24,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # the sampling file needs every fp32 operation rounded separately (bit-exact contract)
 PER_FILE = {"sjd_sample.hip": ["-ffp-contract=off"]}
-SOURCES = ["sjd_api.hip", "sjd_gemm.hip", "sjd_gemm_bf16.hip", "sjd_layers.hip", "sjd_attention.hip", "sjd_sample.hip"]
+SOURCES = ["sjd_api.hip", "sjd_gemm.hip", "sjd_gemm_bf16.hip", "sjd_gemm_wide.hip", "sjd_layers.hip", "sjd_attention.hip", "sjd_sample.hip"]
 
 
 def build(verbose: bool = True) -> str:

@@ -22,7 +22,8 @@ extern "C" const char *sjd_strerror(int code)
 {
     switch (code) {
         case SJD_OK: return "ok";
-        case SJD_EINVAL: return "invalid argument";
+        case SJD_EINVAL: return "invalid argument (host-side check, or a kernel met a token id outside the vocabulary "
+                                "or an image position beyond the cache length)";
         case SJD_ENOMEM: return "out of memory";
         case SJD_ESEQ: return "sequence would exceed max_seq";
         case SJD_EHIP: return g_hip_msg;
@@ -120,7 +121,8 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
     };
     // a linear layer [N][K] starting at element `off`: fp32 as is, bf16 repacked
     auto linear = [&](size_t off, int N, int K, int perm, SjdLinear *lin) -> int {
-        lin->N = N; lin->K = K; lin->tn = 1; lin->wk = 0; lin->u = 0;
+        memset(lin, 0, sizeof(*lin));
+        lin->N = N; lin->K = K; lin->tn = 1;
         lin->w = db + off * es;
         const size_t n = (size_t)N * K;
         if (cfg->dtype == 0) {
@@ -177,6 +179,7 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
 }
 
 // ---- cache + scratch ------------------------------------------------------------------------
+#define SJD_RING_ROWS_DEFAULT 128   // rows of the distribution ring a handle is created with (initialiser (d))
 extern "C" void sjd_kv_free(sjd_kv *kv)
 {
     if (!kv) return;
@@ -184,6 +187,7 @@ extern "C" void sjd_kv_free(sjd_kv *kv)
                     kv->ffn, kv->logits, kv->q, kv->tok_smp, kv->tok_res, kv->acc_flag, kv->draft_snap, kv->snap,
                     kv->forced, kv->ids_stage, kv->emb_stage, kv->g_draft, kv->g_p, kv->g_nacc, kv->q_first};
     for (void *p : ptrs) if (p) (void)hipFree(p);
+    if (kv->state_host) (void)hipHostFree(kv->state_host);
     if (kv->graph_exec) (void)hipGraphExecDestroy(kv->graph_exec);
     if (kv->graph) (void)hipGraphDestroy(kv->graph);
     if (kv->bgraph_exec) (void)hipGraphExecDestroy(kv->bgraph_exec);
@@ -229,7 +233,10 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     A(kv->x24, c.dtype == 1 ? act24_bytes((int)d / 32) : 16);
     A(kv->ssq, c.dtype == 1 ? R * ssq_stride((int)d) * 4 : 16);
     A(kv->h, c.dtype == 0 ? R * d * 4 : 16);
-    A(kv->part, (c.dtype == 0 ? part : 4) * 4);
+    // fp32 models: the output of a linear layer; bf16 models: the fp32 sums of the wide projection kernel's
+    // K-slices (two full outputs' worth: shapes with few output features split K further)
+    if (c.dtype == 1) kv->part_elems = 2 * part;
+    A(kv->part, kv->part_elems * 4);
     A(kv->qact, R * d * 4);
     A(kv->att_part, sjd_attention_part_elems(m) * 4);
     A(kv->att_out, R * d * 4 + 2048);
@@ -249,10 +256,17 @@ extern "C" int sjd_kv_create(const sjd_model *m, sjd_kv **out)
     A(kv->g_nacc, 16);
     A(kv->q_first, V * 4);
     A(kv->logits_last, V * 4);
+    A(kv->ring, (size_t)SJD_RING_ROWS_DEFAULT * V * 4);
+    if (rc == SJD_OK) kv->ring_rows = SJD_RING_ROWS_DEFAULT;
     A(kv->cfg_tab, 2 * sizeof(SjdStreamEntry));
     A(kv->btab, SJD_MAX_STREAMS * sizeof(SjdStreamEntry));
 #undef A
     if (rc == SJD_OK) rc = sjd_sample_setup(m->V_s);
+    if (rc == SJD_OK && c.dtype == 1) rc = sjd_gemm_wide_setup();
+    if (rc == SJD_OK) {
+        const hipError_t e = hipHostMalloc((void **)&kv->state_host, sizeof(SjdState), hipHostMallocDefault);
+        if (e != hipSuccess) { kv->state_host = nullptr; sjd_set_hip_error(e, "hipHostMalloc"); rc = e == hipErrorOutOfMemory ? SJD_ENOMEM : SJD_EHIP; }
+    }
     if (rc != SJD_OK) { sjd_kv_free(kv); return rc; }
     *out = kv;
     return SJD_OK;
@@ -265,11 +279,15 @@ static int state_write(sjd_kv *kv, const SjdState &st, hipStream_t s)
     HIP_TRY(hipStreamSynchronize(s));
     return SJD_OK;
 }
+// Waits for the stream the handle's work was last enqueued on (not for the device: other handles on
+// other streams keep running) and copies the state into the handle's pinned host buffer.  A kernel
+// that met bad device-side input has left a flag in the state: reported here as SJD_EINVAL.
 static int state_read(const sjd_kv *kv, SjdState *st)
 {
-    HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpy(st, kv->state, sizeof(SjdState), hipMemcpyDeviceToHost));
-    return SJD_OK;
+    HIP_TRY(hipMemcpyAsync(kv->state_host, kv->state, sizeof(SjdState), hipMemcpyDeviceToHost, kv->last_stream));
+    HIP_TRY(hipStreamSynchronize(kv->last_stream));
+    *st = *kv->state_host;
+    return st->err ? SJD_EINVAL : SJD_OK;
 }
 
 extern "C" int sjd_kv_reset(sjd_kv *kv)
@@ -375,6 +393,15 @@ struct SjdProfiler {
         SJD_TRY(call);                                                   \
     } while (0)
 
+// rows one forward computes and the largest window: bf16 models SJD_MAX_ROWS / SJD_MAX_WINDOW, the fp32
+// models (launch-bound toys on plain kernels) 32 / 32; under guidance two contexts share the rows
+static int rows_max(const sjd_model *m) { return m->cfg.dtype == 1 ? SJD_ROWS_MAX : SJD_ROWS_F32; }
+static int window_max(const sjd_model *m, bool guided)
+{
+    const int w = std::min(rows_max(m) / (guided ? 2 : 1), SJD_MAX_WINDOW);
+    return m->cfg.dtype == 1 ? w : std::min(w, SJD_ROWS_F32);
+}
+
 // ---- the window forward (Step 2) ------------------------------------------------------------
 // rows = rows computed (<= 32), rows_valid = rows whose K/V are written.  Inputs already in kv->x.
 static double lin_bytes(const sjd_model *m, const SjdLinear &l) { return (double)l.N * l.K * elt_size(m->cfg.dtype); }
@@ -386,7 +413,8 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
 {
     const SjdState *st = kv->state;
     const SjdLinear *prev = nullptr;   // GEMM whose output still has to be added to x
-    const double kv_bytes_layer = 2.0 * ((stream ? kv->n_upper_u : kv->n_upper) + rows) * m->cfg.d_model * 4;   // upper bound
+    const double kv_bytes_layer = kv->prof ? 2.0 * kv->prof_kv_tokens * m->cfg.d_model * 4
+                                           : 2.0 * ((stream ? kv->n_upper_u : kv->n_upper) + rows) * m->cfg.d_model * 4;
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
         PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_rmsnorm(m, kv->x, prev ? kv->part : nullptr, prev ? 1 : 0, 0, L.g1, rows, kv->h, st, s));
@@ -406,7 +434,7 @@ static int forward_rows_f32(sjd_model *m, sjd_kv *kv, int32_t rows, int32_t rows
 }
 
 // the streams of one handle: its conditional context alone (mode 0), its unconditional one alone (1),
-// or both in rows 0.. and SJD_STREAM_ROWS.. (2)
+// or both in rows 0.. and (1 << cfg_shift(rows)).. (2)
 static SjdStreamEntry handle_entry(const sjd_kv *kv, bool uncond)
 {
     const SjdState *st = kv->state;
@@ -417,12 +445,21 @@ static SjdStreamEntry handle_entry(const sjd_kv *kv, bool uncond)
     return e;
 }
 
-static SjdStreams handle_streams(const sjd_kv *kv, int32_t stream_mode)
+// rows reserved per context in a two-context (guided) forward of `rows` window rows: the smallest
+// power of two that holds them, at least one 16-row tile
+static int cfg_shift(int32_t rows)
+{
+    int shift = 4;
+    while ((1 << shift) < rows) ++shift;
+    return shift;
+}
+
+static SjdStreams handle_streams(const sjd_kv *kv, int32_t stream_mode, int32_t rows)
 {
     SjdStreams sm;
     memset(&sm, 0, sizeof(sm));
     sm.count = stream_mode == 2 ? 2 : 1;
-    sm.shift = stream_mode == 2 ? 4 : 5;
+    sm.shift = stream_mode == 2 ? cfg_shift(rows) : 7;
     sm.first = handle_entry(kv, stream_mode == 1);
     sm.table = stream_mode == 2 ? kv->cfg_tab : nullptr;     // filled when the second cache is allocated
     return sm;
@@ -457,39 +494,44 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
         e_qkv.layer_off = (size_t)l * kv->k_layer_stride;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, true, ssq, eps, grows, e_qkv, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, true, ssq, eps, grows, e_qkv, kv->part, kv->part_elems, s));
         PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, s));
         e_res.gain_next = (const bf16_t *)L.g2;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, true, nullptr, 0.f, grows, e_res, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, true, ssq, eps, grows, e_silu, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, true, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, true, ssq, eps, grows, e_silu, kv->part, kv->part_elems, s));
         e_res.gain_next = (const bf16_t *)(l + 1 < m->cfg.n_layers ? m->layers[l + 1].g1 : m->gf);
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, true, nullptr, 0.f, grows, e_res, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, true, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
     }
-    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, true, ssq, eps, grows, e_lm, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, true, ssq, eps, grows, e_lm, kv->part, kv->part_elems, s));
     return SJD_OK;
 }
 
 // Embedding + decoder stack for one window or prompt chunk of one handle.  ids (device) or emb_rows
 // (device fp32 rows), `rows` of them; stream_mode as in handle_streams.  Two streams see the same
-// rows; their logits land in rows 0.. and SJD_STREAM_ROWS.. of `logits`.
+// rows; their logits land in rows 0.. and (1 << cfg_shift(rows)).. of `logits`.
 static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const float *emb_rows, int32_t rows,
                           int32_t rows_valid, int32_t stream_mode, float *logits, hipStream_t s)
 {
-    if (stream_mode == 2 && rows > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (rows > rows_max(m) || (stream_mode == 2 && rows > rows_max(m) / 2)) return SJD_EINVAL;
+    kv->last_stream = s;
     if (m->cfg.dtype == 1) {
-        const SjdStreams sm = handle_streams(kv, stream_mode);
+        const SjdStreams sm = handle_streams(kv, stream_mode, rows);
         const int32_t *idv[SJD_MAX_STREAMS] = {ids, ids};
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, kv->x24, kv->ssq, s));
-        const double toks = (stream_mode == 1 ? 0 : kv->n_upper + rows) + (stream_mode == 0 ? 0 : kv->n_upper_u + rows);
+        int32_t *errv[SJD_MAX_STREAMS] = {&kv->state->err, &kv->state->err};
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, kv->x24, kv->ssq, errv, s));
+        // (only the profiler uses the count: it has read the true lengths before the iteration)
+        const double toks = kv->prof ? kv->prof_kv_tokens
+                                     : (stream_mode == 1 ? 0 : kv->n_upper + rows) + (stream_mode == 0 ? 0 : kv->n_upper_u + rows);
         return forward_rows_bf16(m, kv, sm, rows, rows_valid, toks, logits, s);
     }
     // fp32 models are launch-bound toys: two streams are two forwards
-    const SjdStreams one = handle_streams(kv, 0);     // (only the finished flag is used by the embedding)
+    const SjdStreams one = handle_streams(kv, 0, rows);     // (only the finished flag is used by the embedding)
     const int32_t *idv[SJD_MAX_STREAMS] = {ids};
+    int32_t *errv[SJD_MAX_STREAMS] = {&kv->state->err};
     for (int stream = (stream_mode == 1 ? 1 : 0); stream <= (stream_mode == 0 ? 0 : 1); ++stream) {
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, kv->x24, kv->ssq, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, kv->x24, kv->ssq, errv, s));
         SJD_TRY(forward_rows_f32(m, kv, rows, rows_valid, stream,
-                                 logits + (stream_mode == 2 && stream ? (size_t)SJD_STREAM_ROWS * m->V_s : 0), s));
+                                 logits + (stream_mode == 2 && stream ? ((size_t)1 << cfg_shift(rows)) * m->V_s : 0), s));
     }
     return SJD_OK;
 }
@@ -512,15 +554,15 @@ __global__ void clear_done_kernel(SjdState *st) { st->done = 0; }
 
 extern "C" int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream)
 {
-    if (!m || !kv || kv->m != m || !tokens || !logits || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
-    if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (!m || !kv || kv->m != m || !tokens || !logits || L < 1) return SJD_EINVAL;
+    if (L > rows_max(m) / (kv->cfg_on ? 2 : 1)) return SJD_EINVAL;
     SJD_TRY(check_room(kv, L));
     hipStream_t s = (hipStream_t)stream;
     SJD_LAUNCH(clear_done_kernel, dim3(1), dim3(1), 0, s, kv->state);
     HIP_TRY(hipGetLastError());
     if (!kv->cfg_on) return forward_window(m, kv, tokens, nullptr, L, L, 0, logits, s);
     SJD_TRY(forward_window(m, kv, tokens, nullptr, L, L, 2, kv->logits, s));
-    return sjd_launch_guide(kv->logits, kv->logits + (size_t)SJD_STREAM_ROWS * m->V_s, kv->cfg_scale, (size_t)L * m->V_s,
+    return sjd_launch_guide(kv->logits, kv->logits + ((size_t)1 << cfg_shift(L)) * m->V_s, kv->cfg_scale, (size_t)L * m->V_s,
                             logits, s);
 }
 
@@ -548,8 +590,9 @@ static int prefill_stream(sjd_model *m, sjd_kv *kv, int32_t stream_id, const int
                           const float *embeds, int32_t n_embeds, int *rows_last, hipStream_t s)
 {
     const int P = n_ids + n_embeds, d = m->cfg.d_model;
-    for (int p0 = 0; p0 < P; p0 += SJD_ROWS_MAX) {
-        const int rows = std::min(SJD_ROWS_MAX, P - p0);
+    const int chunk = rows_max(m);
+    for (int p0 = 0; p0 < P; p0 += chunk) {
+        const int rows = std::min(chunk, P - p0);
         const int id_rows = std::max(0, std::min(rows, n_ids - p0));   // leading rows that are ids
         // a chunk is either all ids or all embedding rows; split mixed chunks
         int done_rows = 0;
@@ -642,7 +685,7 @@ extern "C" int sjd_prefill_uncond(sjd_model *m, sjd_kv *kv, const int32_t *ids, 
 extern "C" int sjd_first_window(const sjd_model *m, const float *q_first, int32_t L, const sjd_init *init,
                                 uint64_t philox_seed, int32_t *draft, float *p_old, void *stream)
 {
-    if (!m || !q_first || !init || !draft || !p_old || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    if (!m || !q_first || !init || !draft || !p_old || L < 1 || L > window_max(m, false)) return SJD_EINVAL;
     if (init->mode < 0 || init->mode > 4 || ((init->mode == 1 || init->mode == 4) && init->row_stride < 1)) return SJD_EINVAL;
     return sjd_launch_first_window(q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, draft, p_old, (hipStream_t)stream);
 }
@@ -660,12 +703,23 @@ static int check_sampling(const sjd_sampler *smp, const sjd_init *init, int lo, 
 __global__ void set_step_kernel(SjdState *st, int img_pos0, uint64_t counter, int L)
 {
     st->img_pos0 = img_pos0; st->counter = counter; st->L_eff = L; st->n_image = 0; st->done = 0;
+    // An image position beyond the cache length would make the repeat initialisers look for image
+    // tokens in front of the cache's id record: the step is not executed (its verification kernels
+    // see a finished generation and return) and the handle reports the error when its state is read.
+    if (img_pos0 > st->n) { st->err = SJD_DEVERR_IMG_POS; st->done = 1; }
 }
 
-// initialiser (d) keeps the distributions of the last row_stride accepted image positions
-static int ensure_ring(sjd_kv *kv, const sjd_init *init)
+// initialiser (d) keeps the distributions of the last row_stride accepted image positions: a ring of
+// SJD_RING_ROWS_DEFAULT rows comes with the handle; a wider grid makes sjd_decode_begin (which may
+// allocate) replace it, while sjd_step (which never allocates) refuses with SJD_ELIMIT.
+static int ensure_ring(sjd_kv *kv, const sjd_init *init, bool may_allocate)
 {
     if (init->mode != 4 || kv->ring_rows >= init->row_stride) return SJD_OK;
+    if (!may_allocate) {
+        snprintf(g_limit_msg, sizeof(g_limit_msg), "sjd_step: initialiser (d) with row_stride %d needs a ring of that many rows, the "
+                 "handle holds %d (sjd_decode_begin allocates a larger one)", init->row_stride, kv->ring_rows);
+        return SJD_ELIMIT;
+    }
     if (kv->ring) { HIP_TRY(hipDeviceSynchronize()); (void)hipFree(kv->ring); kv->ring = nullptr; kv->ring_rows = 0; }
     drop_graph(kv);                      // a captured iteration holds the old address
     SJD_TRY(dev_alloc((void **)&kv->ring, (size_t)init->row_stride * kv->m->V_s * 4));
@@ -681,7 +735,7 @@ static int enqueue_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
     SJD_TRY(forward_window(m, kv, draft, nullptr, L, L, kv->cfg_on ? 2 : 0, kv->logits, s));
     SjdVerifyArgs v;
     memset(&v, 0, sizeof(v));
-    if (kv->cfg_on) { v.logits_u = kv->logits + (size_t)SJD_STREAM_ROWS * m->V_s; v.cfg_scale = kv->cfg_scale; }
+    if (kv->cfg_on) { v.logits_u = kv->logits + ((size_t)1 << cfg_shift(L)) * m->V_s; v.cfg_scale = kv->cfg_scale; }
     v.logits = kv->logits; v.p_old = p_old; v.draft = draft; v.L = L; v.V = m->V_s; v.lo = m->cfg.samp_lo;
     v.smp = *smp; v.init = *init; v.seed = seed; v.state = kv->state; v.kv_tokens = kv->tokens;
     v.n_accepted = n_accepted; v.new_draft = new_draft; v.p_new = p_new; v.ring = kv->ring;
@@ -696,11 +750,11 @@ extern "C" int sjd_step(sjd_model *m, sjd_kv *kv, const int32_t *draft, const fl
                         uint64_t counter, int32_t *n_accepted, int32_t *new_draft, float *p_new, void *stream)
 {
     if (!m || !kv || kv->m != m || !draft || !p_old || !n_accepted || !new_draft || !p_new) return SJD_EINVAL;
-    if (L < 1 || L > SJD_MAX_WINDOW || img_pos0 < 0) return SJD_EINVAL;
-    if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (L < 1 || L > window_max(m, kv->cfg_on) || img_pos0 < 0) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
+    if (img_pos0 > kv->n_upper) return SJD_EINVAL;       // (n_upper >= n: surely beyond the cache)
     SJD_TRY(check_room(kv, L));
-    SJD_TRY(ensure_ring(kv, init));
+    SJD_TRY(ensure_ring(kv, init, false));
     hipStream_t s = (hipStream_t)stream;
     kv->dec_active = 0;
     SJD_LAUNCH(set_step_kernel, dim3(1), dim3(1), 0, s, kv->state, img_pos0, counter, L);
@@ -722,10 +776,9 @@ __global__ void begin_generate_kernel(SjdState *st, int N, int L)
 extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, int32_t N, int32_t L,
                                 const sjd_sampler *smp, const sjd_init *init, uint64_t philox_seed, void *stream)
 {
-    if (!m || !kv || kv->m != m || !q_first || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
-    if (kv->cfg_on && L > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (!m || !kv || kv->m != m || !q_first || N < 1 || L < 1 || L > window_max(m, kv->cfg_on)) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
-    SJD_TRY(ensure_ring(kv, init));
+    SJD_TRY(ensure_ring(kv, init, true));
     if (kv->n_upper + N + L > m->cfg.max_seq || (kv->cfg_on && kv->n_upper_u + N + L > m->cfg.max_seq)) {
         SjdState st;
         SJD_TRY(state_read(kv, &st));
@@ -744,6 +797,7 @@ extern "C" int sjd_decode_begin(sjd_model *m, sjd_kv *kv, const float *q_first, 
     SJD_TRY(sjd_launch_first_window(q_first, L, m->V_s, m->cfg.samp_lo, init, philox_seed, kv->g_draft, kv->g_p, s));
     SJD_LAUNCH(begin_generate_kernel, dim3(1), dim3(1), 0, s, kv->state, N, L);
     HIP_TRY(hipGetLastError());
+    kv->last_stream = s;
     kv->n_upper += N;                    // the loop never fixes more than N tokens
     kv->n_upper_u += N;
     return SJD_OK;
@@ -759,6 +813,7 @@ extern "C" int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void 
 {
     if (!m || !kv || kv->m != m || n_steps < 0 || !kv->dec_active) return SJD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
+    kv->last_stream = s;
     if (!kv->use_graph) {
         for (int i = 0; i < n_steps; ++i) SJD_TRY(decode_one(m, kv, s));
         return SJD_OK;
@@ -775,12 +830,14 @@ extern "C" int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void 
         e = hipStreamEndCapture(cs, &g);
         if (rc == SJD_OK && e != hipSuccess) { sjd_set_hip_error(e, "hipStreamEndCapture"); rc = SJD_EHIP; }
         (void)hipStreamDestroy(cs);
+        kv->last_stream = s;
         if (rc != SJD_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
         kv->graph = g;
         kv->graph_cfg_on = kv->cfg_on; kv->graph_cfg_scale = kv->cfg_scale;
         e = hipGraphInstantiate(&kv->graph_exec, g, nullptr, nullptr, 0);
         if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_graph(kv); return SJD_EHIP; }
     }
+    kv->last_stream = s;                // (the capture above went through a stream of its own, gone by now)
     for (int i = 0; i < n_steps; ++i) HIP_TRY(hipGraphLaunch(kv->graph_exec, s));
     return SJD_OK;
 }
@@ -790,7 +847,7 @@ extern "C" int sjd_decode_steps(sjd_model *m, sjd_kv *kv, int32_t n_steps, void 
 // the 32 rows one projection launch computes
 static int batch_shift(int32_t B, int32_t L)
 {
-    for (int shift = 0; shift <= 5; ++shift)
+    for (int shift = 0; shift <= 6; ++shift)
         if ((1 << shift) >= L) return (B << shift) <= SJD_ROWS_MAX ? shift : -1;
     return -1;
 }
@@ -845,9 +902,12 @@ static int forward_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int3
 {
     sjd_kv *kv0 = kvs[0];
     const SjdStreams sm = batch_streams(kvs, B, L);
-    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, s));
+    int32_t *errv[SJD_MAX_STREAMS] = {};
+    for (int b = 0; b < B; ++b) { errv[b] = &kvs[b]->state->err; kvs[b]->last_stream = s; }
+    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, errv, s));
     double toks = 0;
     for (int b = 0; b < B; ++b) toks += kvs[b]->n_upper + L;
+    if (kv0->prof) toks = kv0->prof_kv_tokens;
     return forward_rows_bf16(m, kv0, sm, L, L, toks, kv0->logits, s);
 }
 
@@ -879,6 +939,7 @@ extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t 
     SJD_TRY(check_batch(m, kvs, B, kv0->dec_L, true));
     hipStream_t s = (hipStream_t)stream;
     SJD_TRY(prepare_batch_table(kvs, B, s));
+    for (int b = 0; b < B; ++b) kvs[b]->last_stream = s;
     if (!kv0->use_graph) {
         for (int i = 0; i < n_steps; ++i) SJD_TRY(decode_one_batch(m, kvs, B, s));
         return SJD_OK;
@@ -903,12 +964,14 @@ extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t 
         e = hipStreamEndCapture(cs, &g);
         if (rc == SJD_OK && e != hipSuccess) { sjd_set_hip_error(e, "hipStreamEndCapture"); rc = SJD_EHIP; }
         (void)hipStreamDestroy(cs);
+        for (int b = 0; b < B; ++b) kvs[b]->last_stream = s;
         if (rc != SJD_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
         kv0->bgraph = g;
         e = hipGraphInstantiate(&kv0->bgraph_exec, g, nullptr, nullptr, 0);
         if (e != hipSuccess) { sjd_set_hip_error(e, "hipGraphInstantiate"); drop_batch_graph(kv0); return SJD_EHIP; }
         memcpy(&kv0->bkey, &key, sizeof(key));    // byte copy: the comparison above is one too
     }
+    for (int b = 0; b < B; ++b) kvs[b]->last_stream = s;     // (the capture above went through a stream of its own)
     for (int i = 0; i < n_steps; ++i) HIP_TRY(hipGraphLaunch(kv0->bgraph_exec, s));
     return SJD_OK;
 }
@@ -984,7 +1047,10 @@ extern "C" int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, c
             all_done &= done;
             if (!done) most_left = std::max(most_left, N - 1 - fixed);
         }
-        if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every iteration fixes at least one token per image
+        if (enq > 4 * (N + 8)) {                  // cannot happen: every iteration fixes at least one token per image
+            snprintf(g_hip_msg, sizeof(g_hip_msg), "sjd_generate_batch: %d iterations enqueued without finishing %d tokens", enq, N);
+            return SJD_EHIP;
+        }
     }
     auto t2 = std::chrono::steady_clock::now();
     for (int b = 0; b < B; ++b) {
@@ -1039,8 +1105,7 @@ static int generate_common(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
                            int32_t n_u_embeds, float guidance, int32_t N, int32_t L, const sjd_sampler *smp,
                            const sjd_init *init, uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats)
 {
-    if (!m || !kv || kv->m != m || !out_tokens || N < 1 || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
-    if (guided && L > SJD_STREAM_ROWS) return SJD_EINVAL;
+    if (!m || !kv || kv->m != m || !out_tokens || N < 1 || L < 1 || L > window_max(m, guided)) return SJD_EINVAL;
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
     if (n_ids + n_embeds + N + L > m->cfg.max_seq) return SJD_ESEQ;
     if (guided && n_u_ids + n_u_embeds + N + L > m->cfg.max_seq) return SJD_ESEQ;
@@ -1059,7 +1124,10 @@ static int generate_common(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t
         SJD_TRY(sjd_decode_steps(m, kv, k, s));
         enq += k;
         SJD_TRY(sjd_decode_status(kv, &fixed, nullptr, &done));
-        if (enq > 4 * (N + 8)) return SJD_EHIP;   // cannot happen: every iteration fixes at least one token
+        if (enq > 4 * (N + 8)) {                  // cannot happen: every iteration fixes at least one token
+            snprintf(g_hip_msg, sizeof(g_hip_msg), "sjd_generate: %d iterations enqueued without finishing %d tokens", enq, N);
+            return SJD_EHIP;
+        }
     }
     auto t2 = std::chrono::steady_clock::now();
     SJD_TRY(sjd_decode_result(kv, out_tokens, stats));
@@ -1101,7 +1169,16 @@ static int profile_steps(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_
     sjd_launch_hook = &prof.hook;
     int rc = SJD_OK;
     for (int i = 0; i < n_steps && rc == SJD_OK; ++i) {
-        rc = one();
+        // cached positions this iteration's attention reads, from the device-resident lengths (every
+        // stream: its cache plus the window rows; a finished image reads nothing)
+        double toks = 0;
+        for (int b = 0; b < (B ? B : 1) && rc == SJD_OK; ++b) {
+            SjdState st;
+            rc = state_read(kvs[b], &st);
+            if (rc == SJD_OK && !st.done) toks += st.n + st.L_eff + (kvs[b]->cfg_on ? st.n_u + st.L_eff : 0);
+        }
+        kv->prof_kv_tokens = toks;
+        if (rc == SJD_OK) rc = one();
         if (rc == SJD_OK) rc = prof.drain(out, s);
     }
     // second pass: the projections of n_steps iterations alone, back to back, inside one event pair
@@ -1267,26 +1344,32 @@ extern "C" int sjd_dist(const float *logits, int32_t rows, int32_t V_s, const sj
 }
 
 struct GemmScratch {
-    void *Ap = nullptr, *Wp = nullptr; float *out = nullptr;
-    ~GemmScratch() { for (void *p : {Ap, Wp, (void *)out}) if (p) (void)hipFree(p); }
+    void *Ap = nullptr, *Wp = nullptr, *part = nullptr; float *out = nullptr;
+    ~GemmScratch() { for (void *p : {Ap, Wp, part, (void *)out}) if (p) (void)hipFree(p); }
 };
 
 extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_t N, int32_t K, float *C,
                              void *stream)
 {
-    if (!A || !W || !C || M < 1 || M > SJD_ROWS_MAX || N < 1 || K < 1) return SJD_EINVAL;
+    if (!A || !W || !C || M < 1 || M > (dtype == 0 ? SJD_ROWS_F32 : SJD_ROWS_MAX) || N < 1 || K < 1) return SJD_EINVAL;
     if (dtype < 0 || dtype > 2) return SJD_EINVAL;
     if (dtype >= 1 && (N % 16 || K % 32)) return SJD_EINVAL;
     if (dtype == 0 && K % 4) return SJD_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     const size_t es = elt_size(dtype);
+    const bool wide = dtype >= 1 && M > SJD_ROWS_SKINNY;
     GemmScratch g;
     SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4 + 2048));   // rows past M and the tile behind stay zero
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
+    const size_t part_elems = wide ? (size_t)8 * SJD_ROWS_MAX * N : 0;      // (room for up to 8 K-slices)
+    if (wide) SJD_TRY(dev_alloc(&g.part, part_elems * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.tn = 1; lin.wk = 0; lin.u = 0; lin.w = W;
+    memset(&lin, 0, sizeof(lin));
+    lin.N = N; lin.K = K; lin.tn = 1; lin.w = W;
     if (dtype >= 1) {
-        if (dtype == 1) SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
+        // the wide kernel reads the 3-byte planes only (exact for bf16 values: their low byte is zero)
+        if (dtype == 1 && !wide) SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
+        else if (dtype == 1) SJD_TRY(sjd_bf16_rows_to_act24((const bf16_t *)A, M, K, g.Ap, s));
         else SJD_TRY(sjd_f32_rows_to_act24((const float *)A, M, K, g.Ap, s));     // hi / lo planes
         SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * es));
         sjd_choose_tiles(&lin);
@@ -1295,7 +1378,7 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
         SjdGemmEpi ep;
         memset(&ep, 0, sizeof(ep));
         ep.kind = SJD_EPI_STORE; ep.out = g.out;
-        SJD_TRY(sjd_launch_gemm_bf16(&lin, g.Ap, dtype == 2, nullptr, 0.f, M, ep, s));
+        SJD_TRY(sjd_launch_gemm_bf16(&lin, g.Ap, dtype == 2 || wide, nullptr, 0.f, M, ep, (float *)g.part, part_elems, s));
     } else {
         HIP_TRY(hipMemcpyAsync(g.Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
         SJD_TRY(sjd_launch_gemm(0, &lin, g.Ap, M, g.out, nullptr, s));
@@ -1311,16 +1394,31 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     // iters < 0: rotate through enough weight copies that none is still in the last-level cache
     const bool cold = iters < 0;
     if (cold) iters = -iters;
-    if (M < 1 || M > SJD_ROWS_MAX || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
-    if (tn < 1 || N % (16 * tn) || (u != 0 && u != 2 && u != 4)) return SJD_EINVAL;       // (0: the model's choice)
+    if (M < 1 || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
+    if (tn < 1 || tn > 3 || N % (16 * tn)) return SJD_EINVAL;
+    // More rows than one forward computes: an off-path measurement of the wide kernel's matrix-core rate.  The
+    // rows are cut into chunks of SJD_ROWS_MAX, each a launch pair of its own over the same weights (which
+    // then come from the last-level cache for every chunk after the first).
+    const int chunks = (M + SJD_ROWS_MAX - 1) / SJD_ROWS_MAX, rows = chunks > 1 ? SJD_ROWS_MAX : M;
+    // wk >= 100 asks for the wide kernel at any row count, with wk - 100 K-slices (0 = automatic) and u
+    // weight groups per wave (0 = automatic)
+    const bool force_wide = wk >= 100;
+    if (force_wide) wk -= 100;
+    const bool wide = rows > SJD_ROWS_SKINNY || force_wide;
+    if (!wide && (u != 0 && u != 2 && u != 4)) return SJD_EINVAL;       // (0: the model's choice)
     const size_t wbytes = (size_t)N * K * 2;
     const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
     GemmScratch g;
     SJD_TRY(dev_alloc(&g.Ap, (size_t)SJD_ROWS_MAX * K * 4 + 2048));
     SJD_TRY(dev_alloc(&g.Wp, wbytes * copies));
     SJD_TRY(dev_alloc((void **)&g.out, (size_t)SJD_ROWS_MAX * N * 4));
+    const size_t part_elems = wide ? (size_t)8 * SJD_ROWS_MAX * N : 0;      // (room for up to 8 K-slices)
+    if (wide) SJD_TRY(dev_alloc(&g.part, part_elems * 4));
     SjdLinear lin;
-    lin.N = N; lin.K = K; lin.tn = tn; lin.wk = wk; lin.u = u; lin.w = g.Wp;
+    memset(&lin, 0, sizeof(lin));
+    lin.N = N; lin.K = K; lin.tn = tn; lin.w = g.Wp;
+    if (wide) { lin.wks = wk; lin.wg = u; lin.wide_from = 1; }      // wide kernel: K-slices and weight groups per wave (0 = automatic)
+    else { lin.wk = wk; lin.u = u; }
     SjdGemmEpi ep;
     memset(&ep, 0, sizeof(ep));
     ep.kind = SJD_EPI_STORE; ep.out = g.out;
@@ -1328,12 +1426,18 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     HIP_TRY(hipEventCreate(&e0));
     if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); sjd_set_hip_error(e, "hipEventCreate"); return SJD_EHIP; }
     int rc = SJD_OK;
-    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = sjd_launch_gemm_bf16(&lin, g.Ap, true, nullptr, 0.f, M, ep, 0);
+    auto one = [&]() {
+        int r = SJD_OK;
+        for (int c = 0; c < chunks && r == SJD_OK; ++c)
+            r = sjd_launch_gemm_bf16(&lin, g.Ap, true, nullptr, 0.f, rows, ep, (float *)g.part, part_elems, 0);
+        return r;
+    };
+    for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = one();
     if (rc == SJD_OK) {
         (void)hipEventRecord(e0, 0);
         for (int i = 0; i < iters && rc == SJD_OK; ++i) {
             lin.w = (const char *)g.Wp + (size_t)(i % copies) * wbytes;
-            rc = sjd_launch_gemm_bf16(&lin, g.Ap, true, nullptr, 0.f, M, ep, 0);
+            rc = one();
         }
         (void)hipEventRecord(e1, 0);
         (void)hipEventSynchronize(e1);

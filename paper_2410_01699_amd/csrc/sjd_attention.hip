@@ -27,7 +27,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(const float *
                                                                    const SjdState *st)
 {
     if (st->done) return;
-    constexpr int ROWS = SJD_ROWS_MAX;
+    constexpr int ROWS = SJD_ROWS_F32;
     constexpr int RG = ATT_THREADS / HD;          // row groups in the PV phase
     constexpr int RPT = (ROWS + RG - 1) / RG;     // rows per thread there
     __shared__ float qs[ROWS][HD + 1];
@@ -124,7 +124,7 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, int splits, 
                                     const SjdState *st)
 {
     if (st->done) return;
-    constexpr int ROWS = SJD_ROWS_MAX;
+    constexpr int ROWS = SJD_ROWS_F32;
     const int head = blockIdx.x;
     for (int e = threadIdx.x; e < rows * HD; e += blockDim.x) {
         const int r = e / HD, j = e % HD;
@@ -178,16 +178,18 @@ __device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &
 template <int HD, int MT>
 __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__restrict__ qact, SjdStreams sm,
                                                             size_t layer_off, int d, int nblk_cache, int rows,
-                                                            int splits, float *__restrict__ part)
+                                                            int splits, int qgroups, float *__restrict__ part)
 {
-    // blockIdx.z = stream: its own cache and cache length, queries in rows (stream << shift)..
-    const int stream = blockIdx.z;
+    // blockIdx.z = (stream, query group): the stream has its own cache and cache length and its queries in
+    // rows (stream << shift)..; a stream with more than MT * 16 rows is covered by several groups of
+    // MT * 16 consecutive queries, each walking the keys on its own
+    const int stream = blockIdx.z / qgroups, qbase = (blockIdx.z % qgroups) * (MT * 16);
     const SjdStreamEntry ent = stream_entry(sm, stream);
     if (*ent.done) return;
     const int n = *ent.n;
     const bf16_t *__restrict__ kvc = ent.kvc + layer_off;
-    const int row0 = stream << sm.shift;
-    part += (size_t)stream * gridDim.x * splits * (MT * 16 * HD + 2 * MT * 16);
+    const int row0 = (stream << sm.shift) + qbase;
+    part += (size_t)blockIdx.z * gridDim.x * splits * (MT * 16 * HD + 2 * MT * 16);
     constexpr int KS = HD / 32;      // k-steps of the score product
     constexpr int DT = HD / 16;      // output dim tiles
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
                     s_[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[h][ks][0], qh, s_[h], 0, 0, 0);
                 }
             }
-            const int qrow = mt * 16 + c;
+            const int qrow = qbase + mt * 16 + c;    // row inside the stream's window
             float p_[8];
             float mx = m_run[mt];
 #pragma unroll
@@ -344,14 +346,14 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
 #define ATT_MAX_SPLITS 16
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
-                                                        void *__restrict__ out, int shift)
+                                                        void *__restrict__ out, int shift, int qgroups)
 {
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
-    const int head = blockIdx.x, stream = blockIdx.z;
-    const float *base = part + ((size_t)stream * gridDim.x + head) * splits * REC;
+    const int head = blockIdx.x, stream = blockIdx.z / qgroups, qbase = (blockIdx.z % qgroups) * (MT * 16);
+    const float *base = part + ((size_t)blockIdx.z * gridDim.x + head) * splits * REC;
     const int u = blockIdx.y * 256 + threadIdx.x;
-    if (u >= rows * Q4) return;
+    if (u >= min(rows - qbase, MT * 16) * Q4) return;
     const int q = u / Q4, j4 = u % Q4;
     float ms[ATT_MAX_SPLITS], ls[ATT_MAX_SPLITS];
     f32x4 os[ATT_MAX_SPLITS];
@@ -374,7 +376,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         den += w * ls[s];
     }
     const f32x4 o = num * (1.0f / den);
-    act24_store4(out, q + (stream << shift), head * HD + j4 * 4, d / 32, o[0], o[1], o[2], o[3]);
+    act24_store4(out, (stream << shift) + qbase + q, head * HD + j4 * 4, d / 32, o[0], o[1], o[2], o[3]);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -396,10 +398,12 @@ int32_t sjd_attention_splits(const sjd_model *m)
 
 size_t sjd_attention_part_elems(const sjd_model *m)
 {
-    // one stream of 32 rows at the full number of key splits; two streams of 16 rows need the same, and
-    // up to SJD_MAX_STREAMS streams split their keys less finely (never below one split each)
+    if (m->cfg.dtype == 0) return (size_t)m->cfg.n_heads * sjd_attention_splits(m) * (SJD_ROWS_F32 * m->hd + 2 * SJD_ROWS_F32);
+    // (stream, query group) pairs of up to 32 rows each: one or two of them run at the full number of key
+    // splits, more of them (up to SJD_MAX_STREAMS) split their keys less finely (never below one split
+    // each), so that pairs x splits stays within 2 x the full number
     const int splits = std::max(sjd_attention_splits(m), SJD_MAX_STREAMS / 2);
-    return (size_t)m->cfg.n_heads * splits * (SJD_ROWS_MAX * m->hd + 2 * SJD_ROWS_MAX);
+    return (size_t)m->cfg.n_heads * 2 * splits * (32 * m->hd + 2 * 32);
 }
 
 template <typename T, int HD>
@@ -423,14 +427,17 @@ static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
 {
     const int d = m->cfg.d_model, H = m->cfg.n_heads;
     const size_t off = (size_t)layer * kv->k_layer_stride;
-    // the partial-record buffer is sized for one stream of 32 rows at att_splits key splits; more than
-    // two streams (of at most 16 rows each) share it by splitting their keys less finely
-    const int splits = sm.count <= 2 ? kv->att_splits : std::max(1, 2 * kv->att_splits / sm.count);
-    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, splits, sm.count), dim3(64 * AW), 0, s, kv->qact, sm, off, d,
-                       kv->nblk, rows, splits, kv->att_part);
+    // (stream, query group) pairs: the partial-record buffer holds two of them at att_splits key splits;
+    // more of them share it by splitting their keys less finely
+    const int qgroups = (rows + MT * 16 - 1) / (MT * 16), pairs = sm.count * qgroups;
+    const int splits = pairs <= 2 ? kv->att_splits : std::max(1, 2 * kv->att_splits / pairs);
+    if (pairs * splits > 2 * std::max(kv->att_splits, SJD_MAX_STREAMS / 2)) return SJD_EINVAL;    // (what att_part holds)
+    const int grows = std::min(rows, MT * 16);
+    SJD_LAUNCH((attn_split_kernel<HD, MT>), dim3(H, splits, pairs), dim3(64 * AW), 0, s, kv->qact, sm, off, d,
+                       kv->nblk, rows, splits, qgroups, kv->att_part);
     HIP_TRY(hipGetLastError());
-    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (rows * (HD / 4) + 255) / 256, sm.count), dim3(256), 0, s, kv->att_part,
-                       splits, d, rows, kv->att_out, sm.shift);
+    SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (grows * (HD / 4) + 255) / 256, pairs), dim3(256), 0, s, kv->att_part,
+                       splits, d, rows, kv->att_out, sm.shift, qgroups);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -440,8 +447,8 @@ static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t ro
 {
     if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows > (1 << sm.shift) || (sm.count << sm.shift) > SJD_ROWS_MAX)
         return SJD_EINVAL;
-    if (sm.count > 1 || rows <= 16) return launch_mfma_t<HD, 1>(m, kv, layer, rows, sm, s);
-    return launch_mfma_t<HD, 2>(m, kv, layer, rows, sm, s);
+    if (rows <= 16) return launch_mfma_t<HD, 1>(m, kv, layer, rows, sm, s);
+    return launch_mfma_t<HD, 2>(m, kv, layer, rows, sm, s);     // 32 queries per (stream, query group)
 }
 
 int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)

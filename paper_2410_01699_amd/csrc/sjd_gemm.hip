@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 int sjd_launch_gemm(int32_t dtype, const SjdLinear *lin, const void *act, int32_t rows, float *part,
                     const SjdState *st, hipStream_t s)
 {
-    if (rows < 1 || rows > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (rows < 1 || rows > SJD_ROWS_F32) return SJD_EINVAL;
     const int N = lin->N, K = lin->K;
     if (dtype == 0) {
         if (K % 4) return SJD_EINVAL;

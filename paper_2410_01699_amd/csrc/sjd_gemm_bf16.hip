@@ -31,140 +31,11 @@
 //    stream (O and down projections), SiLU(gate)*up (gate and up rows are interleaved inside each
 //    tile when packed, so a lane holds both), RoPE + KV-cache write (Q/K rows of a head are packed
 //    as (j, j+hd/2) pairs, so the rotation is lane-local).
-#include "sjd_internal.h"
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-// hi = bf16(x) (round to nearest even), lo = bf16(x - hi)
-__device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &lo)
-{
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const __bf16 h = (__bf16)x[e];
-        hi[e] = h;
-        lo[e] = (__bf16)(x[e] - (float)h);
-    }
-}
-
-__device__ __forceinline__ uint32_t pack_hi2(float a, float b, float &ra, float &rb)
-{
-    const bf16_t ha = f32_to_bf16(a), hb = f32_to_bf16(b);
-    ra = a - bf16_to_f32(ha); rb = b - bf16_to_f32(hb);
-    return (uint32_t)ha | ((uint32_t)hb << 16);
-}
-
-// What an epilogue needs from memory besides the sums; fetched while the weights stream.
-struct EpiPre {
-    f32x4 x;                  // RESID: current residual values
-    uint2 gn;                 // RESID: 4 bf16 gains of the normalisation that follows
-    float c0, s0, c1, s1;     // QKV: RoPE factors of this thread's two pairs
-    int pos;                  // QKV: absolute position of row m in its stream's cache
-    int row;                  // QKV: row index inside the stream
-    bf16_t *cache;            // QKV: this layer of the stream's cache (NULL: the row belongs to no stream)
-};
-
-template <int EPI>
-__device__ __forceinline__ void preload_epilogue(const SjdGemmEpi &ep, int N, int m, int n0, EpiPre &pre)
-{
-    if (EPI == SJD_EPI_RESID) {
-        pre.x = *reinterpret_cast<const f32x4 *>(ep.out + act_off(m, n0, N / 32));
-        pre.gn = ep.out24 ? *reinterpret_cast<const uint2 *>(ep.gain_next + n0) : make_uint2(0u, 0u);
-    } else if (EPI == SJD_EPI_QKV) {
-        const int half = ep.hd >> 1;
-        // the stream that owns row m: its cache length and cache (the loop index is uniform, so the
-        // table reads are scalar loads; the selection is per lane)
-        const int stream = m >> ep.sm.shift;
-        pre.row = m & ((1 << ep.sm.shift) - 1);
-        int n_s = ep.sm.count > 0 ? *ep.sm.first.n : 0;
-        pre.cache = (stream == 0 && ep.sm.count > 0) ? ep.sm.first.kvc + ep.layer_off : nullptr;
-        for (int s = 1; s < ep.sm.count; ++s) {            // uniform index: scalar table reads
-            const SjdStreamEntry e = ep.sm.table[s];
-            const int n_here = *e.n;
-            if (s == stream) { n_s = n_here; pre.cache = e.kvc + ep.layer_off; }
-        }
-        pre.pos = min(n_s + pre.row, ep.max_seq - 1);   // rows past the window are computed but never stored
-        // (V fragments fetch factors they do not use: no branch around the loads)
-        const int j = ((n0 % ep.d) % ep.hd) >> 1;
-        const float2 cc = *reinterpret_cast<const float2 *>(ep.cosT + (size_t)pre.pos * half + j);
-        const float2 ss = *reinterpret_cast<const float2 *>(ep.sinT + (size_t)pre.pos * half + j);
-        pre.c0 = cc.x; pre.c1 = cc.y; pre.s0 = ss.x; pre.s1 = ss.y;
-    }
-}
-
-// One accumulator fragment: lane l of the MFMA result holds features n0..n0+3 (packed order) of
-// token m.  v = final sums.
-template <int EPI>
-__device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int m, int n0, f32x4 v, const EpiPre &pre)
-{
-    if (EPI == SJD_EPI_STORE) {
-        *reinterpret_cast<f32x4 *>(ep.out + (size_t)m * N + n0) = v;
-    } else if (EPI == SJD_EPI_RESID) {
-        const f32x4 y = pre.x + v;
-        *reinterpret_cast<f32x4 *>(ep.out + act_off(m, n0, N / 32)) = y;
-        if (ep.out24) {
-            // what the projection behind the next normalisation reads: x * gain in planes, and this
-            // tile's share of sum(x^2) of token m (lanes l, l^16, l^32, l^48 hold its 16 features)
-            act24_store4(ep.out24, m, n0, N / 32, y[0] * __uint_as_float(pre.gn.x << 16),
-                         y[1] * __uint_as_float(pre.gn.x & 0xFFFF0000u), y[2] * __uint_as_float(pre.gn.y << 16),
-                         y[3] * __uint_as_float(pre.gn.y & 0xFFFF0000u));
-            float sq = fmaf(y[0], y[0], fmaf(y[1], y[1], fmaf(y[2], y[2], y[3] * y[3])));
-            sq += __shfl_xor(sq, 16);
-            sq += __shfl_xor(sq, 32);
-            if ((threadIdx.x & 48) == 0) ep.ssq_out[(size_t)m * ssq_stride(N) + (n0 >> 4)] = sq;
-        }
-    } else if (EPI == SJD_EPI_SILU) {
-        // packed rows: (gate f, up f, gate f+1, up f+1)
-        const int f = n0 >> 1;
-        act24_store2(ep.ffn, m, f, ep.F / 32, v[0] / (1.0f + __expf(-v[0])) * v[1], v[2] / (1.0f + __expf(-v[2])) * v[3]);
-    } else {   // SJD_EPI_QKV
-        const int d = ep.d, hd = ep.hd, half = hd >> 1;
-        const int pos = pre.pos;
-        if (n0 < 2 * d) {
-            // Q or K: packed order inside a head is (j, j+half, j+1, j+1+half, ...)
-            const int is_k = n0 >= d;
-            const int c = n0 - (is_k ? d : 0);
-            const int head = c / hd, j = (c % hd) >> 1;
-            const float c0 = pre.c0, s0 = pre.s0, c1 = pre.c1, s1 = pre.s1;
-            const float r0 = v[0] * c0 - v[1] * s0, r0p = v[1] * c0 + v[0] * s0;   // dims j, j+half
-            const float r1 = v[2] * c1 - v[3] * s1, r1p = v[3] * c1 + v[2] * s1;   // dims j+1, j+1+half
-            if (!is_k) {
-                float *q = ep.qact + (size_t)m * d + head * hd + j;
-                *reinterpret_cast<float2 *>(q) = make_float2(r0, r1);
-                *reinterpret_cast<float2 *>(q + half) = make_float2(r0p, r1p);
-            } else if (pre.row < ep.rows_valid && pre.cache) {
-                bf16_t *rec = pre.cache + kv_block_off(head, pos >> 5, ep.nblk, hd);
-                const int kk = pos & 31;
-                float la, lb, dummy0, dummy1;
-                uint32_t hi = pack_hi2(r0, r1, la, lb);
-                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j, hd, 0)) = hi;
-                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j, hd, 1)) = pack_hi2(la, lb, dummy0, dummy1);
-                hi = pack_hi2(r0p, r1p, la, lb);
-                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 0)) = hi;
-                *reinterpret_cast<uint32_t *>(rec + kv_k_off(kk, j + half, hd, 1)) = pack_hi2(la, lb, dummy0, dummy1);
-            }
-        } else if (pre.row < ep.rows_valid && pre.cache) {
-            // V: natural feature order
-            const int col = n0 - 2 * d;
-            const int head = col / hd, dim = col % hd;
-            bf16_t *rec = pre.cache + kv_block_off(head, pos >> 5, ep.nblk, hd);
-            const int kk = pos & 31;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const bf16_t h = f32_to_bf16(v[r]);
-                rec[kv_v_off(kk, dim + r, hd, 0)] = h;
-                rec[kv_v_off(kk, dim + r, hd, 1)] = f32_to_bf16(v[r] - bf16_to_f32(h));
-            }
-        }
-    }
-}
+#include "sjd_gemm_epi.h"
 
 // ---------------------------------------------------------------------------------------------
 // in-workgroup split-K
 // ---------------------------------------------------------------------------------------------
-#define SJD_PRO_PLAIN 0     // fp32 activations as they are
-#define SJD_PRO_NORM 1      // planes of x * gain; the token factors rsqrt(mean(x^2) + eps) come from partial sums
-#define SJD_PRO_A24 2       // activations in hi / lo planes, as they are
 template <int MT, int TN, int WK, int U, int EPI, int PRO>
 __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__restrict__ Wp,
                                                             const void *__restrict__ Xv,
@@ -201,9 +72,9 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     constexpr bool A24 = PRO != SJD_PRO_PLAIN;
     const f32x4 *xp = reinterpret_cast<const f32x4 *>(Xv) + lane;
     const uint2 *xl = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
-    // an all-zero weight tile: the tile behind the activations (fp32: tile 2 KT of 2 KiB; planes: tile
-    // 2 KT of the hi plane, 1 KiB)
-    const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(xp + (size_t)2 * KT * (A24 ? 64 : 128));
+    // an all-zero weight tile: the tile behind the activations (fp32: tile SJD_MTILES * KT of 2 KiB;
+    // planes: tile SJD_MTILES * KT of the hi plane, 1 KiB)
+    const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(xp + (size_t)SJD_MTILES * KT * (A24 ? 64 : 128));
 
     bf16x8 a0[U][TN], a1[U][TN];
     f32x4 b0[U][MT][2], b1[U][MT][2];
@@ -218,7 +89,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         const int kr_ = ki_ + rot;                                                                \
         const int kq_ = kr_ >= kt1 ? kr_ - klen : kr_;                                            \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {   /* L2 hits first: they return first */ \
-            const size_t tix_ = ok_ ? (size_t)mt * KT + kq_ : (size_t)2 * KT;                     \
+            const size_t tix_ = ok_ ? (size_t)mt * KT + kq_ : (size_t)SJD_MTILES * KT;            \
             if (A24) {                                                                            \
                 b[u][mt][0] = xp[tix_ * 64];                          /* 8 bf16 of the hi plane */ \
                 const uint2 l_ = xl[tix_ * 64];                                                   \
@@ -402,6 +273,25 @@ __global__ void f32_rows_to_act24_kernel(const float *__restrict__ src, size_t n
     }
 }
 
+// row-major bf16 [rows][K] -> hi / lo planes (test hook; exact: the byte plane is zero)
+__global__ void bf16_rows_to_act24_kernel(const bf16_t *__restrict__ src, size_t n, int K, void *__restrict__ dst)
+{
+    const int KT = K / 32;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t i = act24_idx((int)(e / K), (int)(e % K), KT);
+        ((bf16_t *)dst)[i] = src[e];
+        ((uint8_t *)dst)[act24_lo_base(KT) + i] = 0;
+    }
+}
+
+int sjd_bf16_rows_to_act24(const bf16_t *src, int32_t rows, int32_t K, void *dst, hipStream_t s)
+{
+    if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
+    SJD_LAUNCH(bf16_rows_to_act24_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
 int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s)
 {
     if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
@@ -438,7 +328,7 @@ void sjd_choose_tiles(SjdLinear *lin)
             best_tn = t;
         }
     }
-    lin->tn = best_tn; lin->wk = 0; lin->u = 0;
+    lin->tn = best_tn; lin->wk = 0; lin->u = 0; lin->wg = 0; lin->wks = 0; lin->wide_from = 0;
 }
 
 template <int MT, int TN, int WK, int U, int PRO>
@@ -474,9 +364,13 @@ static int launch_epi(const SjdLinear *lin, const void *act, const float *ssq_in
 }
 
 int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const float *ssq_in, float eps, int32_t rows,
-                         const SjdGemmEpi &ep, hipStream_t s)
+                         const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s)
 {
     if (rows < 1 || rows > SJD_ROWS_MAX || (ssq_in && !act24)) return SJD_EINVAL;
+    if (rows > SJD_ROWS_SKINNY || (lin->wide_from > 0 && rows >= lin->wide_from && act24 && part)) {
+        if (!act24) return SJD_EINVAL;
+        return sjd_launch_gemm_wide(lin, act, ssq_in, eps, rows, ep, part, part_elems, s);
+    }
     if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;

@@ -1,0 +1,315 @@
+// bf16 projections of a window forward with MORE than 32 rows (paper Sec. 4.1 Step 2 for windows of 64
+// tokens, for guided windows of 32 -- two contexts -- and for batches of images that share one pass
+// over the weights): C[M x N] = A[M x K] * W^T, M = 33 .. 128.
+//
+// With this many rows a workgroup can no longer afford a private copy of the activations per wave (M
+// rows cost M * 96 bytes of activations per KiB of weights), so the roles inside a workgroup change
+// with respect to the skinny kernel:
+//  - the four waves of a workgroup split N: each streams its own packed weight groups (the same
+//    layout the skinny kernel reads: every weight byte still leaves HBM once and goes straight into
+//    the registers of the one wave that uses it);
+//  - all four walk the SAME k-steps, and the activation tiles of a k-step (hi plane as stored, second
+//    operand rebuilt once from the byte plane) are staged in LDS by the workgroup and read from there
+//    by every wave: L2 -> CU activation traffic drops by the number of waves, and the rebuild of the
+//    second operand is done once per workgroup;
+//  - K is split across workgroups (grid.y) wherever N alone gives too few of them; every workgroup
+//    writes its fp32 sums as whole accumulator fragments, and a second kernel adds the K-slices in
+//    slice order (deterministic), applies the token factors of a folded RMSNorm and runs the same
+//    epilogues as the skinny kernel (residual, SiLU * up, RoPE + cache write, plain store).
+// At M = 128 the two MFMAs per weight tile and M-tile price the matrix cores at about 9.8 TB/s of
+// weights, so the kernel is still bound by HBM, at roughly half of the bf16 MFMA peak: the one regime
+// of this path where matrix-core utilisation is a meaningful number.
+#include "sjd_gemm_epi.h"
+
+#include <algorithm>
+#include <mutex>
+
+// one pipeline stage = KU k-steps; LDS holds two stages of MT activation tiles as hi and lo operands
+#define WIDE_WAVES 4
+
+template <int MT, int TN, int G, int KU>
+__global__ __launch_bounds__(64 * WIDE_WAVES) void gemm_wide_kernel(const bf16_t *__restrict__ Wp,
+                                                                    const void *__restrict__ Xv, int N, int K, int kps,
+                                                                    f32x4 *__restrict__ part)
+{
+    constexpr int TNE = TN * G;               // 16-feature tiles per wave
+    constexpr int TPS = KU * MT;              // activation tiles per stage
+    constexpr int APT = TPS / WIDE_WAVES;     // of which each wave fetches
+    static_assert(TPS % WIDE_WAVES == 0, "the waves share the staging of a stage evenly");
+    extern __shared__ bf16x8 act_lds[];       // [2 stages][KU][MT][plane][64 lanes]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int KT = K / 32, NT = N / 16, groups = NT / TN;
+    const int k0 = blockIdx.y * kps, k1 = min(KT, k0 + kps);
+
+    const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(Xv) + lane;
+    const uint2 *xl = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
+    const size_t ztile = (size_t)SJD_MTILES * KT;        // the all-zero tile behind every activation matrix
+    const bf16x8 *zw = xp + ztile * 64;
+    // this wave's packed weight groups (a group past the end reads the zero tile and stores nothing)
+    const bf16x8 *wp[G];
+    int grp[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        grp[j] = (blockIdx.x * WIDE_WAVES + wave) * G + j;
+        wp[j] = grp[j] < groups ? reinterpret_cast<const bf16x8 *>(Wp) + (size_t)grp[j] * KT * TN * 64 + lane : nullptr;
+    }
+
+    f32x4 acc[MT][TNE];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < TNE; ++t) acc[mt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    bf16x8 a0[KU][TNE], a1[KU][TNE];
+    bf16x8 ah[APT];
+    uint2 al[APT];
+
+    // All loads are unconditional: a k-step past this workgroup's slice fetches the zero tile.
+#define LOAD_ACT(kbase)                                                                               \
+    _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                                 \
+        const int ti_ = i * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT, kk_ = (kbase) + u_;     \
+        const size_t tix_ = kk_ < k1 ? (size_t)mt_ * KT + kk_ : ztile;                                \
+        ah[i] = xp[tix_ * 64];                                                                        \
+        al[i] = xl[tix_ * 64];                                                                        \
+    }
+#define STORE_ACT(buf)                                                                                \
+    _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                                 \
+        const int ti_ = i * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT;                         \
+        const f32x4 hv_ = __builtin_bit_cast(f32x4, ah[i]);                                           \
+        bf16x8 bl_;                                                                                   \
+        /* value = hi bits | lo byte << 8 (as fp32); second operand = value - hi, exact */            \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                               \
+            const uint32_t hw_ = __float_as_uint(hv_[e >> 1]);                                        \
+            const uint32_t lw_ = (e < 4) ? al[i].x : al[i].y;                                         \
+            const uint32_t hb_ = (e & 1) ? (hw_ & 0xFFFF0000u) : (hw_ << 16);                         \
+            const uint32_t lb_ = ((lw_ >> (8 * (e & 3))) & 0xFFu) << 8;                               \
+            bl_[e] = (__bf16)(__uint_as_float(hb_ | lb_) - __uint_as_float(hb_));                     \
+        }                                                                                             \
+        bf16x8 *dst_ = act_lds + ((((buf) * KU + u_) * MT + mt_) * 2) * 64 + lane;                    \
+        dst_[0] = ah[i];                                                                              \
+        dst_[64] = bl_;                                                                               \
+    }
+#define LOAD_W(a, kbase)                                                                              \
+    _Pragma("unroll") for (int u = 0; u < KU; ++u) {                                                  \
+        const int kk_ = (kbase) + u;                                                                  \
+        _Pragma("unroll") for (int j = 0; j < G; ++j)                                                 \
+            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                         \
+                a[u][j * TN + tn] = __builtin_nontemporal_load(                                       \
+                    (kk_ < k1 && wp[j]) ? wp[j] + ((size_t)kk_ * TN + tn) * 64 : zw);                 \
+    }
+#define COMPUTE(a, buf)                                                                               \
+    _Pragma("unroll") for (int u = 0; u < KU; ++u)                                                    \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                           \
+            const bf16x8 *src_ = act_lds + ((((buf) * KU + u) * MT + mt) * 2) * 64 + lane;            \
+            const bf16x8 bh_ = src_[0], bl_ = src_[64];                                               \
+            _Pragma("unroll") for (int t = 0; t < TNE; ++t) {                                         \
+                acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][t], bh_, acc[mt][t], 0, 0, 0); \
+                acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][t], bl_, acc[mt][t], 0, 0, 0); \
+            }                                                                                         \
+        }
+
+    // prologue: first stage into buffer 0
+    LOAD_ACT(k0)
+    LOAD_W(a0, k0)
+    STORE_ACT(0)
+    __syncthreads();
+    // Each round: request the next stage (activations first: they come from L2 and are wanted first),
+    // multiply the current one, park the next stage's activations in the other LDS buffer.  The barrier at
+    // the end of a round orders "every wave has read buffer b" before "buffer b is overwritten" one round
+    // later, and "buffer b^1 is written" before "buffer b^1 is read" in the next round.
+    for (int kt = k0;;) {
+        LOAD_ACT(kt + KU)
+        LOAD_W(a1, kt + KU)
+        __builtin_amdgcn_sched_barrier(0);
+        COMPUTE(a0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        STORE_ACT(1)
+        __syncthreads();
+        kt += KU;
+        if (kt >= k1) break;
+        LOAD_ACT(kt + KU)
+        LOAD_W(a0, kt + KU)
+        __builtin_amdgcn_sched_barrier(0);
+        COMPUTE(a1, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        STORE_ACT(0)
+        __syncthreads();
+        kt += KU;
+        if (kt >= k1) break;
+    }
+#undef LOAD_ACT
+#undef STORE_ACT
+#undef LOAD_W
+#undef COMPUTE
+
+    // fp32 sums of this K-slice, as whole accumulator fragments: [slice][m tile][n tile][lane]
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        if (grp[j] >= groups) continue;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int ntile = grp[j] * TN + tn;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                part[(((size_t)blockIdx.y * MT + mt) * NT + ntile) * 64 + lane] = acc[mt][j * TN + tn];
+        }
+    }
+}
+
+// Second kernel: adds the K-slices of every accumulator fragment in slice order, applies
+// rsqrt(mean(x^2) + eps) of each token when an RMSNorm is folded into the projection (PRO_NORM: the
+// planes held x * gain and ssq_in the per-16-feature sums of squares of x), and runs the epilogue.
+// Workgroup (x, mt): M-tile mt, EPI_TILES consecutive n tiles; lane l of a wave holds features
+// 16 ntile + 4 (l / 16) .. + 4 of token 16 mt + l % 16, exactly as the MFMA left them.
+#define EPI_TILES 8
+template <int EPI, int PRO>
+__global__ __launch_bounds__(256) void gemm_wide_epilogue_kernel(const f32x4 *__restrict__ part, int KS, int MT, int NT,
+                                                                 const float *__restrict__ ssq_in, float eps, int N, int K,
+                                                                 SjdGemmEpi ep)
+{
+    __shared__ float rs[16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+    const int mt = blockIdx.y;
+    if (PRO == SJD_PRO_NORM) {
+        // 16 threads per token add every 16th float4 of its row of partial sums, then fold
+        const int tok = threadIdx.x >> 4, sl = threadIdx.x & 15;
+        const int NQ = ssq_stride(K) / 4;
+        const f32x4 *pp = reinterpret_cast<const f32x4 *>(ssq_in + (size_t)(mt * 16 + tok) * (NQ * 4));
+        float t = 0.f;
+        for (int i = sl; i < NQ; i += 16) { const f32x4 v = pp[i]; t += (v[0] + v[1]) + (v[2] + v[3]); }
+        t += __shfl_xor(t, 8);
+        t += __shfl_xor(t, 4);
+        t += __shfl_xor(t, 2);
+        t += __shfl_xor(t, 1);
+        if (sl == 0) rs[tok] = rsqrtf(t / (float)K + eps);
+        __syncthreads();
+    }
+    const float scale = PRO == SJD_PRO_NORM ? rs[c] : 1.0f;
+    for (int i = wave; i < EPI_TILES; i += 4) {
+        const int ntile = blockIdx.x * EPI_TILES + i;
+        if (ntile >= NT) break;
+        const int f_m = mt * 16 + c, f_n0 = ntile * 16 + g * 4;
+        EpiPre pre;
+        preload_epilogue<EPI>(ep, N, f_m, f_n0, pre);
+        f32x4 v = part[((size_t)mt * NT + ntile) * 64 + lane];
+        for (int y = 1; y < KS; ++y) v += part[(((size_t)y * MT + mt) * NT + ntile) * 64 + lane];
+        if (PRO == SJD_PRO_NORM) v *= scale;
+        apply_epilogue<EPI>(ep, N, f_m, f_n0, v, pre);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launch
+// ---------------------------------------------------------------------------------------------
+static std::mutex g_wide_mutex;
+static size_t g_wide_lds[5][4][3] = {};      // dynamic LDS already enabled per (MT/2, TN, G) instantiation
+
+#define WIDE_KU 2
+template <int MT, int TN, int G>
+static int enable_lds_t()
+{
+    const size_t lds = (size_t)2 * WIDE_KU * MT * 2 * 1024;
+    if (lds <= 48 * 1024) return SJD_OK;
+    std::lock_guard<std::mutex> lock(g_wide_mutex);
+    if (g_wide_lds[MT / 2][TN][G] < lds) {
+        HIP_TRY(hipFuncSetAttribute((const void *)gemm_wide_kernel<MT, TN, G, WIDE_KU>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+        g_wide_lds[MT / 2][TN][G] = lds;
+    }
+    return SJD_OK;
+}
+
+// Dynamic LDS above the default limit has to be enabled per kernel; done when a cache handle is created,
+// so that launches recorded during graph capture never touch function attributes.
+int sjd_gemm_wide_setup()
+{
+    SJD_TRY((enable_lds_t<8, 1, 1>())); SJD_TRY((enable_lds_t<8, 1, 2>())); SJD_TRY((enable_lds_t<8, 2, 1>()));
+    SJD_TRY((enable_lds_t<8, 2, 2>())); SJD_TRY((enable_lds_t<8, 3, 1>()));
+    return SJD_OK;
+}
+
+template <int MT, int TN, int G>
+static int launch_wide_t(const SjdLinear *lin, const void *act, int ks, int kps, f32x4 *part, hipStream_t s)
+{
+    constexpr int KU = WIDE_KU;
+    const size_t lds = (size_t)2 * KU * MT * 2 * 1024;
+    SJD_TRY((enable_lds_t<MT, TN, G>()));
+    const int groups = lin->N / 16 / TN;
+    dim3 grid((groups + WIDE_WAVES * G - 1) / (WIDE_WAVES * G), ks);
+    SJD_LAUNCH((gemm_wide_kernel<MT, TN, G, KU>), grid, dim3(64 * WIDE_WAVES), lds, s, (const bf16_t *)lin->w, act, lin->N, lin->K,
+               kps, part);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+template <int MT>
+static int launch_wide_mt(const SjdLinear *lin, const void *act, int g, int ks, int kps, f32x4 *part, hipStream_t s)
+{
+    const int tn = lin->tn;
+    if (tn == 1 && g == 1) return launch_wide_t<MT, 1, 1>(lin, act, ks, kps, part, s);
+    if (tn == 1 && g == 2) return launch_wide_t<MT, 1, 2>(lin, act, ks, kps, part, s);
+    if (tn == 2 && g == 1) return launch_wide_t<MT, 2, 1>(lin, act, ks, kps, part, s);
+    if (tn == 2 && g == 2) return launch_wide_t<MT, 2, 2>(lin, act, ks, kps, part, s);
+    if (tn == 3 && g == 1) return launch_wide_t<MT, 3, 1>(lin, act, ks, kps, part, s);
+    return SJD_EINVAL;
+}
+
+// Workgroups and K-slices: about two workgroups per CU, every slice at least 8 k-steps long, and the
+// partial sums of all slices inside `part_elems` floats.
+void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, int *ks_out, int *kps_out)
+{
+    const int KT = lin->K / 32, groups = lin->N / 16 / lin->tn;
+    int g = lin->wg > 0 ? lin->wg : (lin->tn == 1 ? 2 : 1);
+    if (lin->tn == 3) g = 1;
+    if (g > 2) g = 2;
+    const int wgx = (groups + WIDE_WAVES * g - 1) / (WIDE_WAVES * g);
+    int ks = lin->wks > 0 ? lin->wks : (384 + wgx - 1) / wgx;
+    ks = std::max(1, std::min(ks, KT / 8 > 0 ? KT / 8 : 1));
+    const size_t per_slice = (size_t)mt * 16 * lin->N;
+    while (ks > 1 && per_slice * ks > part_elems) --ks;
+    int kps = (KT + ks - 1) / ks;
+    kps = (kps + 1) & ~1;                       // whole stages
+    ks = (KT + kps - 1) / kps;
+    *g_out = g; *ks_out = ks; *kps_out = kps;
+}
+
+int sjd_launch_gemm_wide(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,
+                         const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s)
+{
+    if (rows < 1 || rows > SJD_ROWS_MAX || !part) return SJD_EINVAL;
+    if (lin->tn < 1 || lin->tn > 3 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
+    if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
+    int mt = (rows + 15) / 16;
+    mt = (mt + 1) & ~1;                          // variants for 32, 64, 96 and 128 rows
+    if ((size_t)mt * 16 * lin->N > part_elems) return SJD_EINVAL;
+    int g, ks, kps;
+    sjd_wide_plan(lin, mt, part_elems, &g, &ks, &kps);
+    f32x4 *p4 = reinterpret_cast<f32x4 *>(part);
+    int rc;
+    switch (mt) {
+        case 2: rc = launch_wide_mt<2>(lin, act, g, ks, kps, p4, s); break;
+        case 4: rc = launch_wide_mt<4>(lin, act, g, ks, kps, p4, s); break;
+        case 6: rc = launch_wide_mt<6>(lin, act, g, ks, kps, p4, s); break;
+        default: rc = launch_wide_mt<8>(lin, act, g, ks, kps, p4, s); break;
+    }
+    SJD_TRY(rc);
+    const int NT = lin->N / 16;
+    dim3 grid((NT + EPI_TILES - 1) / EPI_TILES, mt);
+#define GO(EPI, PRO) SJD_LAUNCH((gemm_wide_epilogue_kernel<EPI, PRO>), grid, dim3(256), 0, s, p4, ks, mt, NT, ssq_in, eps, lin->N, lin->K, ep)
+    if (ssq_in) {
+        switch (ep.kind) {
+            case SJD_EPI_STORE: GO(SJD_EPI_STORE, SJD_PRO_NORM); break;
+            case SJD_EPI_SILU: GO(SJD_EPI_SILU, SJD_PRO_NORM); break;
+            case SJD_EPI_QKV: GO(SJD_EPI_QKV, SJD_PRO_NORM); break;
+            default: return SJD_EINVAL;
+        }
+    } else {
+        switch (ep.kind) {
+            case SJD_EPI_STORE: GO(SJD_EPI_STORE, SJD_PRO_A24); break;
+            case SJD_EPI_RESID: GO(SJD_EPI_RESID, SJD_PRO_A24); break;
+            default: return SJD_EINVAL;
+        }
+    }
+#undef GO
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}

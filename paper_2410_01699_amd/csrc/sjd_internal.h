@@ -6,7 +6,10 @@
 
 #include "sjd.h"
 
-#define SJD_ROWS_MAX 32  // rows (window slots or prefill chunk) one forward pass handles
+#define SJD_ROWS_MAX SJD_MAX_ROWS       // rows (window slots of all streams, or a prefill chunk) one forward pass handles
+#define SJD_MTILES (SJD_ROWS_MAX / 16)  // 16-row tiles of an activation matrix
+#define SJD_ROWS_SKINNY 32              // up to here the skinny projection kernel runs, above it the wide one
+#define SJD_ROWS_F32 32                 // fp32 models (launch-bound toys): rows per forward, largest window
 
 typedef unsigned short bf16_t;  // raw bf16 bit pattern
 
@@ -72,15 +75,18 @@ struct SjdState {
     int32_t steps;      // window forwards executed
     int32_t accept_hist[65];
     int32_t n_u;        // length of the second (unconditional) cache when guidance is on
+    int32_t err;        // set by a kernel that was handed bad device-side input (SJD_DEVERR_*); the calls that
+                        // read the state report it as SJD_EINVAL, sjd_kv_reset / sjd_prefill clear it
 };
+#define SJD_DEVERR_TOKEN_ID 1   // a token id outside [0, vocab_total) reached the embedding (its row was taken as zero)
+#define SJD_DEVERR_IMG_POS 2    // sjd_step with img_pos0 beyond the cache length (the step was not executed)
 // Two token streams share one window forward when classifier-free guidance is on: stream 0 is the
 // conditional context (cache length n), stream 1 the unconditional one (cache length n_u).
 __device__ __forceinline__ int state_n(const SjdState *st, int stream) { return stream ? st->n_u : st->n; }
-#define SJD_STREAM_ROWS 16   // rows per stream in a two-stream forward (stream 1 starts at row 16)
 
 // Token streams that share one window forward of a bf16 model: the two contexts of one image under
 // classifier-free guidance, or one context per image in batched decoding.  Stream s owns rows
-// [s << shift, (s + 1) << shift) of every activation matrix (count << shift <= 32), has its own cache
+// [s << shift, (s + 1) << shift) of every activation matrix (count << shift <= SJD_ROWS_MAX), has its own cache
 // and its own cache length; the weights are streamed once for all of them.
 #define SJD_MAX_STREAMS 8
 struct SjdStreamEntry {
@@ -106,9 +112,9 @@ __device__ __forceinline__ SjdStreamEntry stream_entry(const SjdStreams &sm, int
 // Activations of bf16 models are laid out in the B-operand order of v_mfma_f32_16x16x32_bf16, so that a
 // wave fetches the 16 x 32 tile of a k-step with contiguous loads.  As fp32 (the residual stream, which
 // is accumulated at full precision and read and written by the residual epilogues only; the operands of
-// the hooks that run the projection kernel alone): element (row m, column k) of a [32 x K] matrix
-// lives at act_off(m, k, K/32) floats: tile (m/16, k/32) of 512 floats, inside it two halves (k%8 < 4,
-// >= 4) of 64 lanes x 4 floats, lane = 16 * ((k%32)/8) + m%16.
+// the hooks that run the projection kernel alone): element (row m, column k) of a [SJD_ROWS_MAX x K]
+// matrix lives at act_off(m, k, K/32) floats: tile (m/16, k/32) of 512 floats, inside it two halves
+// (k%8 < 4, >= 4) of 64 lanes x 4 floats, lane = 16 * ((k%32)/8) + m%16.
 __host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
 {
     return (((size_t)(m >> 4) * KT + (k >> 5)) * 2 + ((k >> 2) & 1)) * 256 + ((((k & 31) >> 3) * 16 + (m & 15)) << 2) + (k & 3);
@@ -122,14 +128,15 @@ __host__ __device__ __forceinline__ size_t act_off(int m, int k, int KT)
 // that follows, plus per-token sums of squares (ssq_stride).  Every byte a projection reads passes
 // through its CU's vector memory pipeline at the same cost, whether it comes from HBM or from L2, so
 // a quarter less activation traffic is time saved on the shapes whose workgroups read more activation
-// than weight bytes.  Plane layout for a [32 x K] matrix: tiles (m/16, k/32) of 512 values, value
-// index act24_idx(); the hi plane holds 2*K/32 tiles plus one all-zero tile, the lo plane follows it.
+// than weight bytes.  Plane layout for a [SJD_ROWS_MAX x K] matrix: tiles (m/16, k/32) of 512 values,
+// value index act24_idx(); the hi plane holds SJD_MTILES * K/32 tiles plus one all-zero tile, the lo
+// plane follows it.
 __host__ __device__ __forceinline__ size_t act24_idx(int m, int k, int KT)
 {
     return (((size_t)(m >> 4) * KT + (k >> 5)) << 9) + ((((k & 31) >> 3) * 16 + (m & 15)) << 3) + (k & 7);
 }
-__host__ __device__ __forceinline__ size_t act24_lo_base(int KT) { return (size_t)(2 * KT + 1) * 1024; }   // bytes
-__host__ __device__ __forceinline__ size_t act24_bytes(int KT) { return (size_t)(2 * KT + 1) * 1536; }
+__host__ __device__ __forceinline__ size_t act24_lo_base(int KT) { return (size_t)(SJD_MTILES * KT + 1) * 1024; }   // bytes
+__host__ __device__ __forceinline__ size_t act24_bytes(int KT) { return (size_t)(SJD_MTILES * KT + 1) * 1536; }
 // fp32 -> 16 significant bits (round to nearest even), returned in fp32 position: bits 31..16 are the
 // hi plane entry, bits 15..8 the lo plane entry
 __device__ __forceinline__ uint32_t f32_to_act24(float x)
@@ -138,7 +145,7 @@ __device__ __forceinline__ uint32_t f32_to_act24(float x)
     u += 0x7Fu + ((u >> 8) & 1u);
     return u & 0xFFFFFF00u;
 }
-// Row length (floats) of the per-token partial sums of squares a writer of a [32 x K] residual matrix
+// Row length (floats) of the per-token partial sums of squares a writer of a residual matrix
 // leaves, one per 16 features; padded (with zeros nobody writes) to whole float4.
 __host__ __device__ __forceinline__ int ssq_stride(int K) { return (K / 16 + 3) & ~3; }
 // planes of 4 consecutive values (k a multiple of 4) / of 2 (k even) of row m
@@ -192,6 +199,8 @@ struct SjdLinear {
     int32_t tn;       // bf16: 16-wide output tiles per workgroup
     int32_t wk;       // bf16: waves per workgroup splitting K (0 = chosen at launch)
     int32_t u;        // bf16: k-steps per prefetch stage (0 = chosen at launch)
+    int32_t wg, wks;  // bf16, wide kernel (more than 32 rows): weight groups per wave, K-slices (0 = chosen at launch)
+    int32_t wide_from;   // bf16: rows from which the wide kernel runs (0 = above SJD_ROWS_SKINNY)
 };
 
 // what the bf16 GEMM does with its final fp32 values
@@ -267,6 +276,8 @@ struct sjd_kv {
     int32_t *g_nacc;      // [1]
     float *q_first;       // [V_s]
     int32_t n_upper;      // host-side upper bound of the device-resident n
+    SjdState *state_host; // pinned host copy the state is read into
+    hipStream_t last_stream;   // stream of the handle's most recent enqueue: reading the state waits for it only
     // device-resident decoding loop (sjd_decode_*)
     int32_t dec_active, dec_N, dec_L;
     sjd_sampler dec_smp;
@@ -293,14 +304,16 @@ struct sjd_kv {
     int32_t graph_cfg_on;   // stream mode and guidance weight the captured iteration was recorded with
     float graph_cfg_scale;
     void *prof;           // SjdProfiler* while sjd_profile_steps runs, else NULL
+    double prof_kv_tokens;   // while profiling: cached positions (all streams) the next iteration's attention reads
 };
 
 // ---- kernel launchers (each returns SJD_OK or an SJD_E* code) --------------------------------
 // `st` (device, fp32 models' kernels) lets a kernel skip its work once a generation has finished; NULL = always run.
 // bf16 models: `rows` rows per stream, stream s from ids[s] (device ids; all streams share emb_rows when
 // that is given instead), written at row s << sm.shift.  fp32 models: one stream, ids[0].
+// err[s] (device, may be NULL): receives SJD_DEVERR_TOKEN_ID when an id of stream s lies outside the vocabulary
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, void *x24, float *ssq, hipStream_t s);
+                     const SjdStreams &sm, float *x, void *x24, float *ssq, int32_t *const *err, hipStream_t s);
 int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
 int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
@@ -317,10 +330,17 @@ void sjd_choose_tiles(SjdLinear *lin);
 // bf16 projection: act = the 3-byte planes described at act24_idx() (act24 set) or fp32 [SJD_ROWS_MAX x K]
 // in act_off order.  ssq_in != NULL (planes only): the planes hold x * gain and ssq_in the partial sums
 // of squares of x ([rows][ssq_stride(K)]); the projection applies rsqrt(mean(x^2) + eps) per row.
+// More than SJD_ROWS_SKINNY rows go to the wide kernel (planes only), which needs `part`: room for the fp32
+// sums of its K-slices (part_elems floats, at least 16 * ceil(rows / 16) * N); NULL = skinny kernel only.
 int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const float *ssq_in, float eps, int32_t rows,
-                         const SjdGemmEpi &ep, hipStream_t s);
+                         const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s);
+int sjd_launch_gemm_wide(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,
+                         const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s);
+void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, int *ks_out, int *kps_out);
+int sjd_gemm_wide_setup();
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
 int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s);
+int sjd_bf16_rows_to_act24(const bf16_t *src, int32_t rows, int32_t K, void *dst, hipStream_t s);
 // fp32 models: `stream` 0 / 1 selects the cache and length of the handle
 int sjd_launch_attention_f32(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream, hipStream_t s);
 // bf16 models: `rows` query rows per stream of sm against that stream's cache

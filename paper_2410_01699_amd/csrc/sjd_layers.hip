@@ -18,25 +18,30 @@ template <> struct Act<bf16_t> {
 // x24 and the sums of squares of x per 16 features in ssq.  Stream
 // blockIdx.z takes its ids from ids.p[stream] and writes rows (stream << shift)..; one thread per 4
 // consecutive features; grid (rows per stream, d / 1024, streams).
-struct EmbedIds { const int32_t *p[SJD_MAX_STREAMS]; };
+struct EmbedIds { const int32_t *p[SJD_MAX_STREAMS]; int32_t *err[SJD_MAX_STREAMS]; };
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, const float *emb_rows, int d, int shift,
-                                                    float *x, void *x24, const bf16_t *gain, float *ssq)
+                                                    float *x, void *x24, const bf16_t *gain, float *ssq, int vocab)
 {
     const int stream = blockIdx.z;
     const int r = blockIdx.x;
     const int j = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (j >= d) return;       // (d is a multiple of 32 in bf16 models: whole groups of 4 threads leave)
     float4 v;
-    if (emb_rows) {
+    // an id outside the vocabulary (the ids come from caller-supplied device memory) reads nothing: its
+    // row is zero and the error flag of the handle's state is raised
+    const int id = emb_rows ? 0 : ids.p[stream][r];
+    if (id < 0 || id >= vocab) {
+        v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j == 0 && ids.err[stream]) *ids.err[stream] = SJD_DEVERR_TOKEN_ID;
+    } else if (emb_rows) {
         v = *reinterpret_cast<const float4 *>(emb_rows + (size_t)r * d + j);
     } else if (sizeof(T) == 2) {
-        const int id = ids.p[stream][r];
         const uint2 u = *reinterpret_cast<const uint2 *>(reinterpret_cast<const bf16_t *>(E) + (size_t)id * d + j);
         v = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
                         __uint_as_float(u.y & 0xFFFF0000u));
     } else {
-        v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(E) + (size_t)ids.p[stream][r] * d + j);
+        v = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(E) + (size_t)id * d + j);
     }
     const int row = (stream << shift) + r;
     float *dst = sizeof(T) == 2 ? x + act_off(row, j, d / 32) : x + (size_t)row * d + j;
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *part, int
 #define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
 
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, void *x24, float *ssq, hipStream_t s)
+                     const SjdStreams &sm, float *x, void *x24, float *ssq, int32_t *const *err, hipStream_t s)
 {
     if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows < 1 || rows > (1 << sm.shift) ||
         (sm.count << sm.shift) > SJD_ROWS_MAX)
@@ -160,12 +165,15 @@ int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float 
     if (m->cfg.dtype == 1 && (!x24 || !ssq)) return SJD_EINVAL;
     const int d = m->cfg.d_model;
     EmbedIds e;
-    for (int i = 0; i < SJD_MAX_STREAMS; ++i) e.p[i] = (ids && i < sm.count) ? ids[i] : nullptr;
+    for (int i = 0; i < SJD_MAX_STREAMS; ++i) {
+        e.p[i] = (ids && i < sm.count) ? ids[i] : nullptr;
+        e.err[i] = (err && i < sm.count) ? err[i] : nullptr;
+    }
     const dim3 grid(rows, (d + 1023) / 1024, sm.count);
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)nullptr, ssq);
+        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)nullptr, ssq, m->cfg.vocab_total);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)m->layers[0].g1, ssq);
+        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)m->layers[0].g1, ssq, m->cfg.vocab_total);
     LAUNCH_CHECK();
     return SJD_OK;
 }

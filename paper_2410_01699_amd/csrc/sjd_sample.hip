@@ -16,6 +16,8 @@
 // reduction order: sums that decide anything are taken in 40-bit fixed point.
 #include "sjd_internal.h"
 
+#include <mutex>
+
 #define DIST_THREADS 1024
 #define DIST_WAVES (DIST_THREADS / 64)
 
@@ -700,7 +702,7 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
     const int lane_ = threadIdx.x & 63;
     const int flag_ = lane_ == 0 ? 1 : (lane_ < L ? a.acc_flag[lane_] : 0);
     const unsigned long long run_ = __ballot(flag_ != 0);
-    const int acc = __ffsll((long long)~run_) - 1;
+    const int acc = ~run_ ? __ffsll((long long)~run_) - 1 : 64;     // (a window of 64 accepted whole leaves no zero bit)
     const int n_model = (a.init.flags & SJD_INIT_NO_REFINE) ? 1 : L - acc + 1;
     const int n_hist = sn.img_pos0 + acc;
     const int back = a.init.mode == 1 ? a.init.row_stride : a.init.mode == 2 ? 1 : 0;   // repeat-above / -left
@@ -812,7 +814,7 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_tail_kernel(TailArgs a)
     const int lane_ = threadIdx.x & 63;
     const int flag_ = lane_ == 0 ? 1 : (lane_ < L ? a.acc_flag[lane_] : 0);
     const unsigned long long run_ = __ballot(flag_ != 0);
-    const int acc = __ffsll((long long)~run_) - 1;
+    const int acc = ~run_ ? __ffsll((long long)~run_) - 1 : 64;     // (a window of 64 accepted whole leaves no zero bit)
     const int n_model = (a.init.flags & SJD_INIT_NO_REFINE) ? 1 : L - acc + 1;
     const int n_hist = sn.img_pos0 + acc;
     const int stride = a.init.row_stride;
@@ -936,9 +938,12 @@ static int ept_class(int V) { const int e = (V + DIST_THREADS - 1) / DIST_THREAD
         default: { constexpr int EPT = 32; STMT; } break; \
     }
 static size_t g_lds_set[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+static std::mutex g_lds_mutex;      // (handles may be created from several host threads)
 static int ensure_lds(int which, int cls, size_t bytes)
 {
-    if (bytes <= 48 * 1024 || bytes <= g_lds_set[which][cls]) return SJD_OK;
+    if (bytes <= 48 * 1024) return SJD_OK;
+    std::lock_guard<std::mutex> lock(g_lds_mutex);
+    if (bytes <= g_lds_set[which][cls]) return SJD_OK;
     const void *fn = nullptr;
     EPT_SWITCH(cls, fn = which == 0 ? (const void *)sjd_rows_kernel<EPT>
                        : which == 1 ? (const void *)sjd_dist_kernel<EPT> : (const void *)sjd_first_window_kernel<EPT>)
@@ -956,7 +961,7 @@ int sjd_sample_setup(int32_t V)
 
 int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
 {
-    if (v->V < 1 || v->V > SJD_MAX_SAMP_VOCAB || v->L < 1 || v->L > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (v->V < 1 || v->V > SJD_MAX_SAMP_VOCAB || v->L < 1 || v->L > SJD_MAX_WINDOW) return SJD_EINVAL;
     size_t lds = (size_t)v->V * 4;
     SJD_TRY(ensure_lds(0, ept_class(v->V), lds));
     RowsArgs r;
@@ -1002,7 +1007,7 @@ int sjd_launch_dist(const float *logits, const float *logits_u, float cfg_scale,
 int sjd_launch_first_window(const float *q_first, int32_t L, int32_t V, int32_t lo, const sjd_init *init,
                             uint64_t seed, int32_t *draft, float *p_old, hipStream_t s)
 {
-    if (V < 1 || V > SJD_MAX_SAMP_VOCAB || L < 1 || L > SJD_ROWS_MAX) return SJD_EINVAL;
+    if (V < 1 || V > SJD_MAX_SAMP_VOCAB || L < 1 || L > SJD_MAX_WINDOW) return SJD_EINVAL;
     size_t lds = (size_t)V * 4;
     SJD_TRY(ensure_lds(2, ept_class(V), lds));
     EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_first_window_kernel<EPT>, dim3(L), dim3(DIST_THREADS), lds, s, q_first, L, V, lo,

@@ -55,7 +55,8 @@ def _teardown(B, m, kvs):
     B.sjd_free_model(m)
 
 
-@pytest.mark.parametrize("nb,L", [(2, 16), (4, 8), (8, 4), (3, 7), (2, 9), (1, 32), (5, 1)])
+@pytest.mark.parametrize("nb,L", [(2, 16), (4, 8), (8, 4), (3, 7), (2, 9), (1, 32), (5, 1),
+                                  (8, 16), (4, 32), (2, 64), (6, 13), (2, 40), (3, 32)])
 def test_batched_forward_logits(B, nb, L):
     _say(f"batched forward B={nb} L={L}")
     blob, m, kvs, prompts = _setup(B, nb)
@@ -89,19 +90,19 @@ def test_batched_forward_logits(B, nb, L):
 
 def test_batched_forward_7b_layer_shapes(B):
     """the 7B layer shapes (d 4096, 32 heads of 128, FFN 11008, 8192 sampled codes of 65536), two layers:
-    two windows of 16 and four of 8 in one forward"""
+    two windows of 16 and four of 8 in one forward (32 rows), then eight of 16 and four of 32 (128 rows)"""
     shape = synth.ModelShape(2, 4096, 32, 11008, 65536, 57344, 65536, 200, synth.DTYPE_BF16)
-    blob, m, kvs, _ = _setup(B, 4, shape)
-    oms = [oracle.Model(shape, blob) for _ in range(4)]
+    blob, m, kvs, _ = _setup(B, 8, shape)
+    oms = [oracle.Model(shape, blob) for _ in range(8)]
     try:
         V = shape.v_s
         smp = B.sjd_sampler(8, 1.0); init = B.sjd_init(0, 0, -1)
         q = torch.empty(V, dtype=torch.float32, device="cuda")
-        prompts = [synth.random_tokens(20 + 17 * b, 0, 57344, seed=10 + b) for b in range(4)]
-        for b in range(4):
+        prompts = [synth.random_tokens(20 + 17 * b, 0, 57344, seed=10 + b) for b in range(8)]
+        for b in range(8):
             B.sjd_prefill(m, kvs[b], prompts[b], None, smp, init, q)
             oms[b].prefill(prompts[b])
-        for nb, L in ((2, 16), (4, 8)):
+        for nb, L in ((2, 16), (4, 8), (8, 16), (4, 32)):
             _say(f"7b shapes: batched forward B={nb} L={L}")
             toks = np.stack([synth.random_tokens(L, 57344, 65536, seed=nb * 10 + b) for b in range(nb)])
             out = torch.empty((nb, L, V), dtype=torch.float32, device="cuda")
@@ -119,7 +120,8 @@ def test_batched_forward_7b_layer_shapes(B):
             om.close()
 
 
-@pytest.mark.parametrize("nb,L,mode,use_graph", [(2, 16, 0, True), (4, 8, 1, True), (3, 5, 4, False), (8, 4, 3, True)])
+@pytest.mark.parametrize("nb,L,mode,use_graph", [(2, 16, 0, True), (4, 8, 1, True), (3, 5, 4, False), (8, 4, 3, True),
+                                                 (8, 16, 0, True), (2, 64, 1, True), (4, 32, 4, False)])
 def test_batched_loop_bit_exact_given_gpu_logits(B, nb, L, mode, use_graph):
     """every iteration of the batched loop == the oracle's verification of the same logits, per image"""
     _say(f"batched loop B={nb} L={L} mode={mode} graph={use_graph}")
@@ -216,8 +218,8 @@ def test_batch_errors(B):
     blob, m, kvs, prompts = _setup(B, 3)
     try:
         smp = B.sjd_sampler(300, 1.0); init = B.sjd_init(0, 9, -1)
-        with pytest.raises(B.SjdError) as e:              # three windows of 16 do not fit 32 rows
-            B.sjd_generate_batch(m, kvs, prompts, None, 32, 16, smp, init, [1, 2, 3])
+        with pytest.raises(B.SjdError) as e:              # three windows of 64 do not fit 128 rows
+            B.sjd_generate_batch(m, kvs, prompts, None, 32, 64, smp, init, [1, 2, 3])
         assert e.value.code == B.SJD_EINVAL
         with pytest.raises(B.SjdError) as e:              # the same handle twice
             B.sjd_generate_batch(m, [kvs[0], kvs[0]], prompts[:2], None, 32, 8, smp, init, [1, 2])

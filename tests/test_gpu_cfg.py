@@ -90,7 +90,7 @@ def test_guided_window_logits(B, case):
         tol, w = TOL_BF16, 3.0
     elif case == "hd128_bf16":
         # a long conditional prompt (many key splits) against a one-token unconditional one
-        shape = synth.ModelShape(2, 512, 4, 1024, 4096, 2048, 4096, 700, synth.DTYPE_BF16)
+        shape = synth.ModelShape(2, 512, 4, 1024, 4096, 2048, 4096, 800, synth.DTYPE_BF16)
         blob = synth.make_weights(shape, seed=11)
         pc = synth.random_tokens(600, 0, 2048, seed=1)
         pu = synth.random_tokens(1, 0, 2048, seed=2)
@@ -111,7 +111,11 @@ def test_guided_window_logits(B, case):
             assert np.max(np.abs(p.q_last.cpu().numpy() - q_ref)) < 1e-5
         toks = synth.random_tokens(64, shape.samp_lo, shape.samp_hi, seed=3)
         n_img, worst = 0, 0.0
-        for lo_, hi_, keep in ((0, 16, 5), (16, 21, 5), (21, 22, 1), (22, 38, 16), (38, 47, 2)):
+        windows = [(0, 16, 5), (16, 21, 5), (21, 22, 1), (22, 38, 16), (38, 47, 2)]
+        if shape.dtype == synth.DTYPE_BF16:
+            # two contexts of 32, 17 and 64 rows: the wide projection kernel, attention in groups of 32 queries
+            windows += [(0, 32, 3), (32, 49, 17), (0, 64, 1)]
+        for lo_, hi_, keep in windows:
             t = toks[lo_:hi_]
             _say(f"  window at image position {n_img} L={len(t)}")
             got = p.gpu_logits(t)
@@ -190,12 +194,14 @@ def test_guidance_weight_zero_and_one(B):
         B.sjd_kv_free(kv); B.sjd_free_model(m)
 
 
-def test_cfg_step_bit_exact_given_gpu_logits(B):
+@pytest.mark.parametrize("L", [16, 32, 64])
+def test_cfg_step_bit_exact_given_gpu_logits(B, L):
     """sjd_step under guidance: verification of the guided logits is bit-exact, and both caches advance
-    by the accepted count (the next window's guided logits stay on the oracle's)."""
-    shape = synth.ModelShape(2, 256, 4, 512, 2048, 1024, 2048, 160, synth.DTYPE_BF16)
+    by the accepted count (the next window's guided logits stay on the oracle's).  Windows of 32 and 64
+    make forwards of 64 and 128 rows."""
+    shape = synth.ModelShape(2, 256, 4, 512, 2048, 1024, 2048, 600, synth.DTYPE_BF16)
     blob = synth.make_weights(shape, seed=8)
-    V, lo, L, K, w = shape.v_s, shape.samp_lo, 16, 300, 3.0
+    V, lo, K, w = shape.v_s, shape.samp_lo, 300, 3.0
     smp = B.sjd_sampler(K, 1.0); init = B.sjd_init(1, 16, 2047)
     osmp = oracle.Sampler(K, 1.0); oinit = oracle.Init(1, 16, 2047)
     p = Pair(B, shape, blob, synth.random_tokens(20, 0, 1024, seed=1), synth.random_tokens(6, 0, 1024, seed=2), w,

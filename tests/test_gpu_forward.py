@@ -60,7 +60,15 @@ class Gpu:
                                          (1, 16, 8192, 4096),
                                          # bf16 weights, fp32 activations handed over in 3 bytes per value
                                          (2, 16, 4096, 11008), (2, 32, 4096, 4096), (2, 7, 48, 96), (2, 32, 1536, 4096),
-                                         (2, 21, 256, 320)])
+                                         (2, 21, 256, 320),
+                                         # more than 32 rows: the wide kernel (waves split N, K-slices added by a
+                                         # second kernel), at the four 7B shapes + LM head, at 775M shapes, and at
+                                         # ragged sizes (rows not a multiple of 16, fewer weight groups than waves)
+                                         (1, 64, 12288, 4096), (2, 128, 12288, 4096), (1, 128, 4096, 4096),
+                                         (2, 64, 4096, 4096), (2, 128, 4096, 11008), (1, 64, 4096, 11008),
+                                         (2, 64, 22016, 4096), (1, 128, 22016, 4096), (2, 128, 8192, 4096),
+                                         (1, 96, 4608, 1536), (2, 48, 1536, 4096), (2, 33, 48, 96), (1, 100, 256, 320),
+                                         (2, 77, 80, 2080)])
 def test_gemm_against_fp64(B, dtype, M, N, K):
     _say(f"gemm dtype={dtype} M={M} N={N} K={K}")
     rng = np.random.default_rng(N + K)
@@ -348,12 +356,17 @@ def test_step_errors(B):
 
 
 # ------------------------------------------------------------------ full size, launch configuration of the benchmark
-def test_forward_and_step_7b_full_size(B):
-    """The 7B workload at its real shape (32 layers, d=4096, window 16, 8192 sampled codes of 65536):
-    every logit of one window against the fp64 oracle, then one whole sjd_step whose verification must
-    be bit-exact given the GPU's logits."""
-    w = synth.WORKLOADS["7b_32x32"]
-    _say("7b: generating weights")
+@pytest.mark.parametrize("workload,window", [("7b_32x32", 0), ("7b_48x48", 0), ("7b_32x32", 64)])
+def test_forward_and_step_7b_full_size(B, workload, window):
+    """The 7B workloads at their real shape (32 layers, d=4096, 8192 sampled codes of 65536; window 16 on the
+    32 x 32 grid, window 32 with a forced row-end token every 49 positions on the 48 x 48 grid, and a window
+    of 64, which runs on the wide projection kernel): every logit of one window against the fp64 oracle,
+    then one whole sjd_step whose verification must be bit-exact given the GPU's logits."""
+    import dataclasses
+    w = synth.WORKLOADS[workload]
+    if window:
+        w = dataclasses.replace(w, window=window)
+    _say(f"7b: {workload} window {w.window}: generating weights")
     blob = synth.make_weights(w.shape, seed=0, threads=16)
     ids, _ = synth.make_prompt(w)
     om = oracle.Model(w.shape, blob)
@@ -390,7 +403,7 @@ def test_forward_and_step_7b_full_size(B):
         # the launch configuration the benchmark times: the device-resident loop replaying its captured
         # iteration.  Every iteration against the oracle's verification of the same logits (taken with
         # the forward hook, which leaves the loop state alone), then the finished image token by token.
-        N = 40
+        N = 40 if w.row_stride == 32 else 60               # (the 49-token rows: past the first forced row end)
         osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(w.init_mode, w.row_stride, w.eol_id)
         B.sjd_kv_use_graph(g.kv, True)
         B.sjd_prefill(g.m, g.kv, ids, None, smp, init, q_last)
@@ -540,6 +553,87 @@ def test_forward_bf16_long_cache_window32(B):
                (toks[114:146], 5)]
     worst = _check_forward(B, shape, blob, prompt, windows, TOL_BF16)
     _say(f"bf16 long cache worst {worst:.3e}")
+
+
+def test_forward_bf16_windows_above_32_rows(B):
+    """windows of 33 .. 128 rows (the wide projection kernel; attention in query groups of 32) on a cache
+    that grows past several 32-position blocks, and a prompt pre-filled in chunks of 128 rows"""
+    shape = synth.ModelShape(4, 256, 4, 512, 2048, 1024, 2048, 700, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=7)
+    prompt = synth.random_tokens(300, 0, 1024, seed=1)          # chunks of 128 + 128 + 44 rows
+    toks = synth.random_tokens(400, 1024, 2048, seed=2)
+    windows = [(toks[:64], 9), (toks[64:112], 48), (toks[112:145], 33), (toks[145:273], 128), (toks[273:370], 1),
+               (toks[300:364], 64)]
+    worst = _check_forward(B, shape, blob, prompt, windows, TOL_BF16)
+    _say(f"bf16 wide windows worst {worst:.3e}")
+    # head size 128 and 32, d_model 96 (6 partial sums of squares per token), non-unit gains
+    for shape in (synth.ModelShape(2, 512, 4, 1024, 4096, 2048, 4096, 500, synth.DTYPE_BF16),
+                  synth.ModelShape(2, 96, 3, 160, 512, 0, 512, 500, synth.DTYPE_BF16, rope_theta=1e6, rms_eps=3e-3)):
+        blob = _random_gains(shape, synth.make_weights(shape, seed=9, std=0.05), 13)
+        prompt = synth.random_tokens(150, 0, shape.samp_lo or 512, seed=1)
+        toks = synth.random_tokens(300, shape.samp_lo, shape.samp_hi, seed=2)
+        worst = _check_forward(B, shape, blob, prompt, [(toks[:64], 64), (toks[64:164], 7), (toks[100:228], 128)], TOL_BF16)
+        _say(f"bf16 wide windows d={shape.d_model} worst {worst:.3e}")
+
+
+def test_forward_bf16_7b_dims_two_layers_wide(B):
+    """the 7B layer shapes with two layers: windows of 64 and 128 rows, and a 70-token prompt (one wide chunk)"""
+    shape = synth.ModelShape(2, 4096, 32, 11008, 65536, 57344, 65536, 400, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=0, threads=16)
+    prompt = synth.random_tokens(70, 0, 57344, seed=1)
+    toks = synth.random_tokens(200, 57344, 65536, seed=2)
+    worst = _check_forward(B, shape, blob, prompt, [(toks[:64], 5), (toks[64:192], 128)], TOL_BF16)
+    _say(f"7b dims, 2 layers, wide windows worst {worst:.3e}")
+
+
+def test_step_and_generation_with_window_64(B):
+    """sjd_step with a window of 64 on a bf16 model: verification bit-exact given the GPU's logits (the accept
+    scan over all 64 lanes), cache advance; then whole generations through the graph loop: valid tokens"""
+    shape = synth.ModelShape(2, 256, 4, 512, 2048, 1024, 2048, 400, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=8)
+    g = Gpu(B, shape, blob)
+    try:
+        V, lo, L, K = shape.v_s, shape.samp_lo, 64, 300
+        smp = B.sjd_sampler(K, 1.0); init = B.sjd_init(1, 16, 2047)
+        osmp = oracle.Sampler(K, 1.0); oinit = oracle.Init(1, 16, 2047)
+        prompt = synth.random_tokens(20, 0, 1024, seed=1)
+        q_last = torch.empty(V, dtype=torch.float32, device="cuda")
+        B.sjd_prefill(g.m, g.kv, prompt, None, smp, init, q_last)
+        draft = torch.zeros(L, dtype=torch.int32, device="cuda")
+        p_old = torch.zeros((L, V), dtype=torch.float32, device="cuda")
+        B.sjd_first_window(g.m, q_last, L, init, 42, draft, p_old)
+        na = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nd = torch.zeros(L, dtype=torch.int32, device="cuda"); pn = torch.zeros_like(p_old)
+        hist, n = [], 20
+        for c in range(1, 7):
+            _say(f"  L=64 step {c} n={n}")
+            d_h, p_h = draft.cpu().numpy(), p_old.cpu().numpy()
+            logits = g.logits(d_h)
+            want = oracle.verify(logits, p_h, d_h, lo, osmp, oinit, len(hist), np.array(hist, np.int32), 42, c)
+            B.sjd_step(g.m, g.kv, draft, p_old, L, smp, init, len(hist), 42, c, na, nd, pn)
+            torch.cuda.synchronize()
+            a = int(na.item())
+            assert a == want[0]
+            assert np.array_equal(nd.cpu().numpy(), want[1])
+            assert np.array_equal(pn.cpu().numpy().view(np.uint32), want[2].view(np.uint32))
+            hist += d_h[:a].tolist()
+            n += a
+            assert B.sjd_kv_len(g.kv) == n
+            draft, nd = nd, draft; p_old, pn = pn, p_old
+        # greedy decoding with a window of 64 = greedy AR of the GPU's own forward (Jacobi fixed point)
+        N = 96
+        t64, s64 = B.sjd_generate(g.m, g.kv, prompt, None, N, 64, B.sjd_sampler(1, 1.0), B.sjd_init(0, 16, -1), 3)
+        t1, s1 = B.sjd_generate(g.m, g.kv, prompt, None, N, 1, B.sjd_sampler(1, 1.0), B.sjd_init(0, 16, -1), 3)
+        assert s1.steps == N - 1 and s64.steps <= N - 1
+        # (bf16 logits of a 64-row and of a 1-row forward differ in the last bits: identical unless an arg-max
+        # is a near tie, which the seeds here do not hit)
+        assert np.array_equal(t64, t1)
+        toks, st = B.sjd_generate(g.m, g.kv, prompt, None, N, 64, smp, init, 5)
+        assert toks.min() >= lo and toks.max() < shape.samp_hi and np.all(toks[15::16] == 2047)
+        hist_ = np.array(list(st.accept_hist))
+        assert hist_.sum() == st.steps and int((hist_ * np.arange(65)).sum()) in (N - 1, N)
+    finally:
+        g.close()
 
 
 def test_forward_bf16_7b_dims_two_layers(B):

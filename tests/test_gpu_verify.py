@@ -108,7 +108,7 @@ def _run_verify_probs(B, q, p_old, draft, lo, init, img_pos0, hist, seed, counte
 
 
 @pytest.mark.parametrize("L,V,support", [(2, 8, 6), (8, 1024, 64), (16, 8192, 2000), (32, 8192, 2000), (16, 16384, 2000),
-                                         (5, 1000, 37), (32, 100, 100)])
+                                         (5, 1000, 37), (32, 100, 100), (64, 8192, 2000), (64, 1000, 37), (47, 2048, 300)])
 def test_verify_probs_bit_exact(B, L, V, support):
     rng = np.random.default_rng(L * 1000 + V)
     lo = 57344 if V == 8192 else 3
@@ -176,7 +176,7 @@ def test_verify_probs_init_strategies(B, mode, stride, eol, flags):
                 assert np.array_equal(ring_b.view(np.uint32), ring_a.view(np.uint32))
 
 
-@pytest.mark.parametrize("L,V,K", [(8, 1024, 64), (16, 8192, 2000), (32, 8192, 2000), (16, 16384, 2000)])
+@pytest.mark.parametrize("L,V,K", [(8, 1024, 64), (16, 8192, 2000), (32, 8192, 2000), (16, 16384, 2000), (64, 8192, 2000)])
 def test_verify_from_logits_bit_exact(B, L, V, K):
     """the launch configuration of the real workloads (window x sampling vocabulary x top-K)"""
     rng = np.random.default_rng(V + L)
