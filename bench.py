@@ -113,6 +113,12 @@ def main():
                     help="comma-separated workloads measured afterwards in child processes and summarised under "
                          "config.also_measured ('none' = skip; default: every other configuration when the 7B default "
                          "runs unmodified)")
+    ap.add_argument("--gemm-bench", default=None, metavar="M,N,K,tn,wk,u[,iters]",
+                    help="only time the bf16 projection kernel alone at one shape and tiling (sjd_gemm_bench; cold weights "
+                         "when iters < 0, default -40): for counter runs on single kernels")
+    ap.add_argument("--verify-scaled", action="store_true",
+                    help="only time the sampling-distribution kernel (top-K + softmax of Step 3) at a scaled shape: 4096 "
+                         "logits rows in one launch, where it is a bandwidth problem rather than a launch (off-path evidence)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 1 GiB (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -139,6 +145,42 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
         return
+    if args.gemm_bench:
+        v = [int(x) for x in args.gemm_bench.split(",")]
+        M_, N_, K_, tn_, wk_, u_ = v[:6]
+        it_ = v[6] if len(v) > 6 else -40
+        us = B.sjd_gemm_bench(M_, N_, K_, tn_, wk_, u_, it_)
+        by = N_ * K_ * 2
+        print(json.dumps({"M": M_, "N": N_, "K": K_, "tn": tn_, "wk": wk_, "u": u_, "iters": it_, "us_per_launch": us,
+                          "weight_GBps": by / us / 1e3, "frac_of_hbm_peak": by / us / 1e3 / HBM_PEAK_GBS,
+                          "mfma_TFLOPs_hi_and_lo": 4.0 * M_ * N_ * K_ / us / 1e6}))
+        return
+    if args.verify_scaled:
+        # Step 3's distribution kernel on many independent rows at once.  Algorithmic bytes: one fp32 logits row in,
+        # one fp32 probability row out.  Timed with events on the stream the launches go to (torch's current = default).
+        out = {"kernel": "sjd_dist_kernel (top-K select + softmax, one 1024-thread workgroup per row)", "peak_GBps": HBM_PEAK_GBS,
+               "shapes": []}
+        for V, K in ((8192, 2000), (16384, 2000), (8192, 8192)):
+            rows = 4096
+            z = torch.from_numpy(synth.random_logits(rows, V, seed=5)).cuda()
+            q = torch.empty_like(z)
+            smp = B.sjd_sampler(K, 1.0)
+            for _ in range(3):
+                B.sjd_dist(z, rows, V, smp, None, q)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            iters = 20
+            e0.record()
+            for _ in range(iters):
+                B.sjd_dist(z, rows, V, smp, None, q)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / iters
+            by = rows * V * 8
+            out["shapes"].append({"rows": rows, "V_s": V, "top_k": K, "us_per_launch": us, "algorithmic_bytes": by,
+                                  "GBps": by / us / 1e3, "frac_of_hbm_peak": by / us / 1e3 / HBM_PEAK_GBS,
+                                  "rows_per_s": rows / us * 1e6})
+        print(json.dumps(out))
+        return
     w = synth.WORKLOADS[args.workload]
     import dataclasses
     if args.window > 0:
@@ -149,6 +191,10 @@ def main():
         w = dataclasses.replace(w, init_mode=args.init_mode)
     if args.temperature > 0:
         w = dataclasses.replace(w, temperature=args.temperature)
+    # (a larger window than the workload's own needs a few more cache rows)
+    need = w.n_prompt_ids + w.n_prompt_embeds + w.n_image_tokens + w.window
+    if need > w.shape.max_seq:
+        w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, max_seq=need))
     shape = w.shape
     t0 = time.perf_counter()
     blob = synth.make_weights(shape, seed=0, threads=16)

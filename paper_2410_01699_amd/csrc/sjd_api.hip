@@ -402,6 +402,13 @@ static int window_max(const sjd_model *m, bool guided)
     return m->cfg.dtype == 1 ? w : std::min(w, SJD_ROWS_F32);
 }
 
+// Which form the activations of a forward over `grows` rows take between its kernels: the 2-byte lo plane
+// (second MFMA operand ready made, 4 bytes per value) from SJD_LO16_FROM_ROWS rows on, the 1-byte lo plane
+// (3 bytes per value, second operand rebuilt by every wave) below.  One choice per forward: every producer
+// and every consumer of a forward agree.
+static int g_lo16_from_rows = SJD_LO16_FROM_ROWS;
+static bool rows_use_lo16(int grows) { return grows >= g_lo16_from_rows; }
+
 // ---- the window forward (Step 2) ------------------------------------------------------------
 // rows = rows computed (<= 32), rows_valid = rows whose K/V are written.  Inputs already in kv->x.
 static double lin_bytes(const sjd_model *m, const SjdLinear &l) { return (double)l.N * l.K * elt_size(m->cfg.dtype); }
@@ -475,6 +482,8 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     const int d = m->cfg.d_model, F = m->cfg.d_ffn;
     const float eps = m->cfg.rms_eps;
     const int grows = ((sm.count - 1) << sm.shift) + rows;      // rows the projections compute
+    const bool lo16 = rows_use_lo16(grows);
+    const int form = lo16 ? SJD_ACT_P4 : SJD_ACT_P3;
     // upper bound of the K/V bytes one layer's attention reads (hi + lo planes)
     const double kv_bytes_layer = 2.0 * kv_tokens_upper * d * 4;
     SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
@@ -483,8 +492,8 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     e_res = e_qkv; e_silu = e_qkv; e_lm = e_qkv;
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
     e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid; e_qkv.max_seq = m->cfg.max_seq;
-    e_res.kind = SJD_EPI_RESID; e_res.out = kv->x; e_res.out24 = kv->x24; e_res.ssq_out = kv->ssq;
-    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = kv->ffn; e_silu.F = F;
+    e_res.kind = SJD_EPI_RESID; e_res.out = kv->x; e_res.out24 = kv->x24; e_res.ssq_out = kv->ssq; e_res.lo16 = lo16;
+    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = kv->ffn; e_silu.F = F; e_silu.lo16 = lo16;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
     const void *x = kv->x24, *att = kv->att_out, *ffn = kv->ffn;     // hi / lo planes, 3 bytes per value
     // x24 holds x * (gain of the normalisation the next projection sits behind), kv->ssq its partial
@@ -494,15 +503,15 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     for (int l = 0; l < m->cfg.n_layers; ++l) {
         const SjdLayer &L = m->layers[l];
         e_qkv.layer_off = (size_t)l * kv->k_layer_stride;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, true, ssq, eps, grows, e_qkv, kv->part, kv->part_elems, s));
-        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, form, ssq, eps, grows, e_qkv, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, lo16, s));
         e_res.gain_next = (const bf16_t *)L.g2;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, true, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, true, ssq, eps, grows, e_silu, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, form, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, form, ssq, eps, grows, e_silu, kv->part, kv->part_elems, s));
         e_res.gain_next = (const bf16_t *)(l + 1 < m->cfg.n_layers ? m->layers[l + 1].g1 : m->gf);
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, true, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, form, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
     }
-    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, true, ssq, eps, grows, e_lm, kv->part, kv->part_elems, s));
+    PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, form, ssq, eps, grows, e_lm, kv->part, kv->part_elems, s));
     return SJD_OK;
 }
 
@@ -518,7 +527,8 @@ static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const fl
         const SjdStreams sm = handle_streams(kv, stream_mode, rows);
         const int32_t *idv[SJD_MAX_STREAMS] = {ids, ids};
         int32_t *errv[SJD_MAX_STREAMS] = {&kv->state->err, &kv->state->err};
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, kv->x24, kv->ssq, errv, s));
+        const bool lo16 = rows_use_lo16(((sm.count - 1) << sm.shift) + rows);
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, sm, kv->x, kv->x24, kv->ssq, errv, lo16, s));
         // (only the profiler uses the count: it has read the true lengths before the iteration)
         const double toks = kv->prof ? kv->prof_kv_tokens
                                      : (stream_mode == 1 ? 0 : kv->n_upper + rows) + (stream_mode == 0 ? 0 : kv->n_upper_u + rows);
@@ -529,7 +539,7 @@ static int forward_window(sjd_model *m, sjd_kv *kv, const int32_t *ids, const fl
     const int32_t *idv[SJD_MAX_STREAMS] = {ids};
     int32_t *errv[SJD_MAX_STREAMS] = {&kv->state->err};
     for (int stream = (stream_mode == 1 ? 1 : 0); stream <= (stream_mode == 0 ? 0 : 1); ++stream) {
-        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, kv->x24, kv->ssq, errv, s));
+        PROF(kv, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, idv, emb_rows, rows, one, kv->x, kv->x24, kv->ssq, errv, false, s));
         SJD_TRY(forward_rows_f32(m, kv, rows, rows_valid, stream,
                                  logits + (stream_mode == 2 && stream ? ((size_t)1 << cfg_shift(rows)) * m->V_s : 0), s));
     }
@@ -904,7 +914,8 @@ static int forward_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int3
     const SjdStreams sm = batch_streams(kvs, B, L);
     int32_t *errv[SJD_MAX_STREAMS] = {};
     for (int b = 0; b < B; ++b) { errv[b] = &kvs[b]->state->err; kvs[b]->last_stream = s; }
-    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, errv, s));
+    const bool lo16 = rows_use_lo16(((sm.count - 1) << sm.shift) + L);
+    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, errv, lo16, s));
     double toks = 0;
     for (int b = 0; b < B; ++b) toks += kvs[b]->n_upper + L;
     if (kv0->prof) toks = kv0->prof_kv_tokens;
@@ -1370,7 +1381,7 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
         // the wide kernel reads the 3-byte planes only (exact for bf16 values: their low byte is zero)
         if (dtype == 1 && !wide) SJD_TRY(sjd_bf16_rows_to_f32((const bf16_t *)A, M, K, (float *)g.Ap, s));
         else if (dtype == 1) SJD_TRY(sjd_bf16_rows_to_act24((const bf16_t *)A, M, K, g.Ap, s));
-        else SJD_TRY(sjd_f32_rows_to_act24((const float *)A, M, K, g.Ap, s));     // hi / lo planes
+        else SJD_TRY(sjd_f32_rows_to_act24((const float *)A, M, K, g.Ap, wide, s));     // hi / lo planes
         SJD_TRY(dev_alloc(&g.Wp, (size_t)N * K * es));
         sjd_choose_tiles(&lin);
         SJD_TRY(sjd_repack_bf16((const bf16_t *)W, (bf16_t *)g.Wp, N, K, lin.tn, 0, 0, 0, s));
@@ -1378,7 +1389,8 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
         SjdGemmEpi ep;
         memset(&ep, 0, sizeof(ep));
         ep.kind = SJD_EPI_STORE; ep.out = g.out;
-        SJD_TRY(sjd_launch_gemm_bf16(&lin, g.Ap, dtype == 2 || wide, nullptr, 0.f, M, ep, (float *)g.part, part_elems, s));
+        SJD_TRY(sjd_launch_gemm_bf16(&lin, g.Ap, wide ? SJD_ACT_P4 : dtype == 2 ? SJD_ACT_P3 : SJD_ACT_F32, nullptr, 0.f, M, ep,
+                                     (float *)g.part, part_elems, s));
     } else {
         HIP_TRY(hipMemcpyAsync(g.Ap, A, (size_t)M * K * es, hipMemcpyDeviceToDevice, s));
         SJD_TRY(sjd_launch_gemm(0, &lin, g.Ap, M, g.out, nullptr, s));
@@ -1405,6 +1417,9 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     const bool force_wide = wk >= 100;
     if (force_wide) wk -= 100;
     const bool wide = rows > SJD_ROWS_SKINNY || force_wide;
+    // skinny kernel: u + 10 reads the activations in their 4-byte form (2-byte lo plane) instead of 3 bytes
+    int form = wide ? SJD_ACT_P4 : SJD_ACT_P3;
+    if (!wide && u >= 10) { u -= 10; form = SJD_ACT_P4; }
     if (!wide && (u != 0 && u != 2 && u != 4)) return SJD_EINVAL;       // (0: the model's choice)
     const size_t wbytes = (size_t)N * K * 2;
     const int copies = cold ? (int)((((size_t)1 << 30) + wbytes - 1) / wbytes) + 1 : 1;
@@ -1429,7 +1444,7 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     auto one = [&]() {
         int r = SJD_OK;
         for (int c = 0; c < chunks && r == SJD_OK; ++c)
-            r = sjd_launch_gemm_bf16(&lin, g.Ap, true, nullptr, 0.f, rows, ep, (float *)g.part, part_elems, 0);
+            r = sjd_launch_gemm_bf16(&lin, g.Ap, form, nullptr, 0.f, rows, ep, (float *)g.part, part_elems, 0);
         return r;
     };
     for (int i = 0; i < 3 && rc == SJD_OK; ++i) rc = one();

@@ -346,7 +346,7 @@ __global__ __launch_bounds__(64 * AW) void attn_split_kernel(const float *__rest
 #define ATT_MAX_SPLITS 16
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part, int splits, int d, int rows,
-                                                        void *__restrict__ out, int shift, int qgroups)
+                                                        void *__restrict__ out, int shift, int qgroups, int lo16)
 {
     constexpr int REC = MT * 16 * HD + 2 * MT * 16;
     constexpr int Q4 = HD / 4;
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
         den += w * ls[s];
     }
     const f32x4 o = num * (1.0f / den);
-    act24_store4(out, (stream << shift) + qbase + q, head * HD + j4 * 4, d / 32, o[0], o[1], o[2], o[3]);
+    act24_store4(out, (stream << shift) + qbase + q, head * HD + j4 * 4, d / 32, o[0], o[1], o[2], o[3], lo16 != 0);
 }
 
 int32_t sjd_attention_splits(const sjd_model *m)
@@ -423,7 +423,8 @@ static int launch_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows,
 }
 
 template <int HD, int MT>
-static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)
+static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, bool lo16,
+                         hipStream_t s)
 {
     const int d = m->cfg.d_model, H = m->cfg.n_heads;
     const size_t off = (size_t)layer * kv->k_layer_stride;
@@ -437,27 +438,29 @@ static int launch_mfma_t(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t 
                        kv->nblk, rows, splits, qgroups, kv->att_part);
     HIP_TRY(hipGetLastError());
     SJD_LAUNCH((attn_merge_kernel<HD, MT>), dim3(H, (grows * (HD / 4) + 255) / 256, pairs), dim3(256), 0, s, kv->att_part,
-                       splits, d, rows, kv->att_out, sm.shift, qgroups);
+                       splits, d, rows, kv->att_out, sm.shift, qgroups, lo16 ? 1 : 0);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
 
 template <int HD>
-static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)
+static int launch_mfma(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, bool lo16,
+                       hipStream_t s)
 {
     if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows > (1 << sm.shift) || (sm.count << sm.shift) > SJD_ROWS_MAX)
         return SJD_EINVAL;
-    if (rows <= 16) return launch_mfma_t<HD, 1>(m, kv, layer, rows, sm, s);
-    return launch_mfma_t<HD, 2>(m, kv, layer, rows, sm, s);     // 32 queries per (stream, query group)
+    if (rows <= 16) return launch_mfma_t<HD, 1>(m, kv, layer, rows, sm, lo16, s);
+    return launch_mfma_t<HD, 2>(m, kv, layer, rows, sm, lo16, s);     // 32 queries per (stream, query group)
 }
 
-int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s)
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, bool lo16,
+                         hipStream_t s)
 {
     const int hd = m->hd;
     if (m->cfg.dtype != 1) return SJD_EINVAL;
-    if (hd == 32) return launch_mfma<32>(m, kv, layer, rows, sm, s);
-    if (hd == 64) return launch_mfma<64>(m, kv, layer, rows, sm, s);
-    if (hd == 128) return launch_mfma<128>(m, kv, layer, rows, sm, s);
+    if (hd == 32) return launch_mfma<32>(m, kv, layer, rows, sm, lo16, s);
+    if (hd == 64) return launch_mfma<64>(m, kv, layer, rows, sm, lo16, s);
+    if (hd == 128) return launch_mfma<128>(m, kv, layer, rows, sm, lo16, s);
     return SJD_EINVAL;
 }
 

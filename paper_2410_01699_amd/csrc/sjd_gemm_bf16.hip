@@ -69,9 +69,12 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(Wp) + (size_t)blockIdx.x * KT * TN * 64 + lane;
     // this lane's activation values: token c (+16 mt), columns 32 kt + 8 g .. +8, as two float4, or as
     // 8 bf16 of the hi plane and 8 bytes of the lo plane
-    constexpr bool A24 = PRO != SJD_PRO_PLAIN;
+    constexpr bool A24 = PRO != SJD_PRO_PLAIN;                                  // operand planes (3 or 4 bytes per value)
+    constexpr bool L16 = PRO == SJD_PRO_NORM16 || PRO == SJD_PRO_A16;           // the lo plane holds bf16 values
+    constexpr bool NORM = PRO == SJD_PRO_NORM || PRO == SJD_PRO_NORM16;
     const f32x4 *xp = reinterpret_cast<const f32x4 *>(Xv) + lane;
     const uint2 *xl = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
+    const f32x4 *xp16 = reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
     // an all-zero weight tile: the tile behind the activations (fp32: tile SJD_MTILES * KT of 2 KiB;
     // planes: tile SJD_MTILES * KT of the hi plane, 1 KiB)
     const bf16x8 *zw = reinterpret_cast<const bf16x8 *>(xp + (size_t)SJD_MTILES * KT * (A24 ? 64 : 128));
@@ -90,7 +93,10 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         const int kq_ = kr_ >= kt1 ? kr_ - klen : kr_;                                            \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {   /* L2 hits first: they return first */ \
             const size_t tix_ = ok_ ? (size_t)mt * KT + kq_ : (size_t)SJD_MTILES * KT;            \
-            if (A24) {                                                                            \
+            if (L16) {                                                                            \
+                b[u][mt][0] = xp[tix_ * 64];                          /* 8 bf16 of either plane */ \
+                b[u][mt][1] = xp16[tix_ * 64];                                                    \
+            } else if (A24) {                                                                     \
                 b[u][mt][0] = xp[tix_ * 64];                          /* 8 bf16 of the hi plane */ \
                 const uint2 l_ = xl[tix_ * 64];                                                   \
                 b[u][mt][1][0] = __uint_as_float(l_.x); b[u][mt][1][1] = __uint_as_float(l_.y);   \
@@ -106,7 +112,10 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     _Pragma("unroll") for (int u = 0; u < U; ++u)                                                 \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                       \
             bf16x8 bh_, bl_;                                                                      \
-            if (A24) {                                                                            \
+            if (L16) {                                                                            \
+                bh_ = __builtin_bit_cast(bf16x8, b[u][mt][0]);                                    \
+                bl_ = __builtin_bit_cast(bf16x8, b[u][mt][1]);                                    \
+            } else if (A24) {                                                                     \
                 /* value = hi bits | lo byte << 8 (as fp32); second operand = value - hi, exact */ \
                 bh_ = __builtin_bit_cast(bf16x8, b[u][mt][0]);                                    \
                 _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                   \
@@ -139,7 +148,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     constexpr int PJ = 4;
     f32x4 pr[MT][PJ];
     const int NQ = ssq_stride(K) / 4, slice = wave * 4 + g;
-    if (PRO == SJD_PRO_NORM) {
+    if (NORM) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const f32x4 *pp = reinterpret_cast<const f32x4 *>(ssq_in + (size_t)(mt * 16 + c) * (NQ * 4));
@@ -181,7 +190,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) red[wave][mt * TN + tn][lane] = acc[mt][tn];
-    if (PRO == SJD_PRO_NORM) {
+    if (NORM) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             float t = 0.f;
@@ -201,7 +210,7 @@ __global__ __launch_bounds__(64 * WK) void gemm_fused_kernel(const bf16_t *__res
         f32x4 v = red[0][f_mtn][lane];
 #pragma unroll
         for (int w = 1; w < WK; ++w) v += red[w][f_mtn][lane];
-        if (PRO == SJD_PRO_NORM) {
+        if (NORM) {
             float sq = ssq[0][f_m];
 #pragma unroll
             for (int w = 1; w < WK; ++w) sq += ssq[w][f_m];
@@ -262,14 +271,15 @@ __global__ void bf16_rows_to_f32_kernel(const bf16_t *__restrict__ src, size_t n
 }
 
 // row-major fp32 [rows][K] -> hi / lo planes (test hook)
-__global__ void f32_rows_to_act24_kernel(const float *__restrict__ src, size_t n, int K, void *__restrict__ dst)
+__global__ void f32_rows_to_act24_kernel(const float *__restrict__ src, size_t n, int K, void *__restrict__ dst, int lo16)
 {
     const int KT = K / 32;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
         const uint32_t v = f32_to_act24(src[e]);
         const size_t i = act24_idx((int)(e / K), (int)(e % K), KT);
         ((bf16_t *)dst)[i] = (bf16_t)(v >> 16);
-        ((uint8_t *)dst)[act24_lo_base(KT) + i] = (uint8_t)(v >> 8);
+        if (lo16) *reinterpret_cast<bf16_t *>((uint8_t *)dst + act24_lo_base(KT) + 2 * i) = (bf16_t)act24_lo16(v);
+        else ((uint8_t *)dst)[act24_lo_base(KT) + i] = (uint8_t)(v >> 8);
     }
 }
 
@@ -279,8 +289,7 @@ __global__ void bf16_rows_to_act24_kernel(const bf16_t *__restrict__ src, size_t
     const int KT = K / 32;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
         const size_t i = act24_idx((int)(e / K), (int)(e % K), KT);
-        ((bf16_t *)dst)[i] = src[e];
-        ((uint8_t *)dst)[act24_lo_base(KT) + i] = 0;
+        ((bf16_t *)dst)[i] = src[e];       // (the lo plane stays as allocated: zero in either form)
     }
 }
 
@@ -292,10 +301,10 @@ int sjd_bf16_rows_to_act24(const bf16_t *src, int32_t rows, int32_t K, void *dst
     return SJD_OK;
 }
 
-int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s)
+int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, bool lo16, hipStream_t s)
 {
     if (rows < 1 || rows > SJD_ROWS_MAX || K < 32 || K % 32) return SJD_EINVAL;
-    SJD_LAUNCH(f32_rows_to_act24_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst);
+    SJD_LAUNCH(f32_rows_to_act24_kernel, dim3(256), dim3(256), 0, s, src, (size_t)rows * K, K, dst, lo16 ? 1 : 0);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -339,7 +348,7 @@ static int launch_epi(const SjdLinear *lin, const void *act, const float *ssq_in
         dim3 grid(lin->N / (16 * TN)), block(64 * WK);
         const bf16_t *W = (const bf16_t *)lin->w;
 #define GO(EPI) SJD_LAUNCH((gemm_fused_kernel<MT, TN, WK, U, EPI, PRO>), grid, block, 0, s, W, act, ssq_in, eps, lin->N, lin->K, ep)
-        if constexpr (PRO == SJD_PRO_A24) {
+        if constexpr (PRO == SJD_PRO_A24 || PRO == SJD_PRO_A16) {
             // (the plane activations feed the residual projections; the plain store serves the test hook)
             switch (ep.kind) {
                 case SJD_EPI_STORE: GO(SJD_EPI_STORE); break;
@@ -363,12 +372,13 @@ static int launch_epi(const SjdLinear *lin, const void *act, const float *ssq_in
     }
 }
 
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const float *ssq_in, float eps, int32_t rows,
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const float *ssq_in, float eps, int32_t rows,
                          const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s)
 {
-    if (rows < 1 || rows > SJD_ROWS_MAX || (ssq_in && !act24)) return SJD_EINVAL;
+    const bool act24 = form != SJD_ACT_F32, lo16 = form == SJD_ACT_P4;
+    if (rows < 1 || rows > SJD_ROWS_MAX || (ssq_in && !act24) || form < 0 || form > 2) return SJD_EINVAL;
     if (rows > SJD_ROWS_SKINNY || (lin->wide_from > 0 && rows >= lin->wide_from && act24 && part)) {
-        if (!act24) return SJD_EINVAL;
+        if (!lo16 && !(lin->wide_from > 0)) return SJD_EINVAL;     // (the wide kernel reads the 4-byte planes only)
         return sjd_launch_gemm_wide(lin, act, ssq_in, eps, rows, ep, part, part_elems, s);
     }
     if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
@@ -391,6 +401,8 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, cons
         if (mt != 1 || wk != 4) return SJD_EINVAL;       // (the only deep variants built)
 #define DEEP(TN)                                                                                      \
         if (tn == TN) {                                                                               \
+            if (lo16 && ssq_in) return launch_epi<1, TN, 4, 4, SJD_PRO_NORM16>(lin, act, ssq_in, eps, ep, s); \
+            if (lo16) return launch_epi<1, TN, 4, 4, SJD_PRO_A16>(lin, act, ssq_in, eps, ep, s);      \
             if (ssq_in) return launch_epi<1, TN, 4, 4, SJD_PRO_NORM>(lin, act, ssq_in, eps, ep, s);   \
             if (act24) return launch_epi<1, TN, 4, 4, SJD_PRO_A24>(lin, act, ssq_in, eps, ep, s);     \
             return launch_epi<1, TN, 4, 4, SJD_PRO_PLAIN>(lin, act, ssq_in, eps, ep, s);              \
@@ -404,11 +416,15 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, cons
     if (mt == MT && tn == TN) {                                                                           \
         if constexpr (MT * TN <= 4) {                                                                     \
             if (wk == 4) {                                                                                \
+                if (lo16 && ssq_in) return launch_epi<MT, TN, 4, 2, SJD_PRO_NORM16>(lin, act, ssq_in, eps, ep, s); \
+                if (lo16) return launch_epi<MT, TN, 4, 2, SJD_PRO_A16>(lin, act, ssq_in, eps, ep, s);         \
                 if (ssq_in) return launch_epi<MT, TN, 4, 2, SJD_PRO_NORM>(lin, act, ssq_in, eps, ep, s);      \
                 if (act24) return launch_epi<MT, TN, 4, 2, SJD_PRO_A24>(lin, act, ssq_in, eps, ep, s);      \
                 return launch_epi<MT, TN, 4, 2, SJD_PRO_PLAIN>(lin, act, ssq_in, eps, ep, s);               \
             }                                                                                             \
         } else if (wk == 4) return SJD_EINVAL;                                                            \
+        if (lo16 && ssq_in) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM16>(lin, act, ssq_in, eps, ep, s);    \
+        if (lo16) return launch_epi<MT, TN, 8, 2, SJD_PRO_A16>(lin, act, ssq_in, eps, ep, s);                 \
         if (ssq_in) return launch_epi<MT, TN, 8, 2, SJD_PRO_NORM>(lin, act, ssq_in, eps, ep, s);              \
         if (act24) return launch_epi<MT, TN, 8, 2, SJD_PRO_A24>(lin, act, ssq_in, eps, ep, s);              \
         return launch_epi<MT, TN, 8, 2, SJD_PRO_PLAIN>(lin, act, ssq_in, eps, ep, s);                       \

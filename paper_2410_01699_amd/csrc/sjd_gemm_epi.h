@@ -9,6 +9,8 @@
 #define SJD_PRO_PLAIN 0     // fp32 activations as they are
 #define SJD_PRO_NORM 1      // planes of x * gain; the token factors rsqrt(mean(x^2) + eps) come from partial sums
 #define SJD_PRO_A24 2       // activations in hi / lo planes, as they are
+#define SJD_PRO_NORM16 3    // as SJD_PRO_NORM, the lo plane in its 2-byte form (the second operand ready made)
+#define SJD_PRO_A16 4       // as SJD_PRO_A24, the lo plane in its 2-byte form
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -84,7 +86,7 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
             // tile's share of sum(x^2) of token m (lanes l, l^16, l^32, l^48 hold its 16 features)
             act24_store4(ep.out24, m, n0, N / 32, y[0] * __uint_as_float(pre.gn.x << 16),
                          y[1] * __uint_as_float(pre.gn.x & 0xFFFF0000u), y[2] * __uint_as_float(pre.gn.y << 16),
-                         y[3] * __uint_as_float(pre.gn.y & 0xFFFF0000u));
+                         y[3] * __uint_as_float(pre.gn.y & 0xFFFF0000u), ep.lo16 != 0);
             float sq = fmaf(y[0], y[0], fmaf(y[1], y[1], fmaf(y[2], y[2], y[3] * y[3])));
             sq += __shfl_xor(sq, 16);
             sq += __shfl_xor(sq, 32);
@@ -93,7 +95,7 @@ __device__ __forceinline__ void apply_epilogue(const SjdGemmEpi &ep, int N, int 
     } else if (EPI == SJD_EPI_SILU) {
         // packed rows: (gate f, up f, gate f+1, up f+1)
         const int f = n0 >> 1;
-        act24_store2(ep.ffn, m, f, ep.F / 32, v[0] / (1.0f + __expf(-v[0])) * v[1], v[2] / (1.0f + __expf(-v[2])) * v[3]);
+        act24_store2(ep.ffn, m, f, ep.F / 32, v[0] / (1.0f + __expf(-v[0])) * v[1], v[2] / (1.0f + __expf(-v[2])) * v[3], ep.lo16 != 0);
     } else {   // SJD_EPI_QKV
         const int d = ep.d, hd = ep.hd, half = hd >> 1;
         const int pos = pre.pos;

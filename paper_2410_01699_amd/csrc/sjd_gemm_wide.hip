@@ -10,8 +10,8 @@
 //    the registers of the one wave that uses it);
 //  - all four walk the SAME k-steps, and the activation tiles of a k-step (hi plane as stored, second
 //    operand rebuilt once from the byte plane) are staged in LDS by the workgroup and read from there
-//    by every wave: L2 -> CU activation traffic drops by the number of waves, and the rebuild of the
-//    second operand is done once per workgroup;
+//    by every wave: L2 -> CU activation traffic drops by the number of waves.  The producers of a wide
+//    forward's activations write the second operand ready made (2-byte lo plane), so staging is a copy;
 //  - K is split across workgroups (grid.y) wherever N alone gives too few of them; every workgroup
 //    writes its fp32 sums as whole accumulator fragments, and a second kernel adds the K-slices in
 //    slice order (deterministic), applies the token factors of a folded RMSNorm and runs the same
@@ -28,7 +28,7 @@
 #define WIDE_WAVES 4
 
 template <int MT, int TN, int G, int KU>
-__global__ __launch_bounds__(64 * WIDE_WAVES) void gemm_wide_kernel(const bf16_t *__restrict__ Wp,
+__global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf16_t *__restrict__ Wp,
                                                                     const void *__restrict__ Xv, int N, int K, int kps,
                                                                     f32x4 *__restrict__ part)
 {
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(64 * WIDE_WAVES) void gemm_wide_kernel(const bf16_t
     const int k0 = blockIdx.y * kps, k1 = min(KT, k0 + kps);
 
     const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(Xv) + lane;
-    const uint2 *xl = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;
+    const bf16x8 *xl = reinterpret_cast<const bf16x8 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;   // 2-byte lo plane
     const size_t ztile = (size_t)SJD_MTILES * KT;        // the all-zero tile behind every activation matrix
     const bf16x8 *zw = xp + ztile * 64;
     // this wave's packed weight groups (a group past the end reads the zero tile and stores nothing)
@@ -59,35 +59,30 @@ __global__ __launch_bounds__(64 * WIDE_WAVES) void gemm_wide_kernel(const bf16_t
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int t = 0; t < TNE; ++t) acc[mt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    bf16x8 a0[KU][TNE], a1[KU][TNE];
-    bf16x8 ah[APT];
-    uint2 al[APT];
+    // Weights: a ring of WD stages in registers, requested WD - 1 stages ahead of their use (a stage is
+    // KU k-steps; HBM latency under load is several stages long).  Activations: both operand planes come
+    // ready made (the forward's producers write the 2-byte lo plane), so a stage is requested from L2 one
+    // stage ahead into registers and parked in LDS, tile by tile, between the products of the stage before.
+    constexpr int WD = TNE >= 3 ? 3 : 4;      // stages of weights in registers (three where a stage is 6 tiles)
+    bf16x8 a_[WD][KU][TNE];
+    bf16x8 sh_[APT], sl_[APT];
 
     // All loads are unconditional: a k-step past this workgroup's slice fetches the zero tile.
 #define LOAD_ACT(kbase)                                                                               \
     _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                                 \
         const int ti_ = i * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT, kk_ = (kbase) + u_;     \
         const size_t tix_ = kk_ < k1 ? (size_t)mt_ * KT + kk_ : ztile;                                \
-        ah[i] = xp[tix_ * 64];                                                                        \
-        al[i] = xl[tix_ * 64];                                                                        \
+        sh_[i] = xp[tix_ * 64];                                                                       \
+        sl_[i] = xl[tix_ * 64];                                                                       \
     }
-#define STORE_ACT(buf)                                                                                \
-    _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                                 \
-        const int ti_ = i * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT;                         \
-        const f32x4 hv_ = __builtin_bit_cast(f32x4, ah[i]);                                           \
-        bf16x8 bl_;                                                                                   \
-        /* value = hi bits | lo byte << 8 (as fp32); second operand = value - hi, exact */            \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                               \
-            const uint32_t hw_ = __float_as_uint(hv_[e >> 1]);                                        \
-            const uint32_t lw_ = (e < 4) ? al[i].x : al[i].y;                                         \
-            const uint32_t hb_ = (e & 1) ? (hw_ & 0xFFFF0000u) : (hw_ << 16);                         \
-            const uint32_t lb_ = ((lw_ >> (8 * (e & 3))) & 0xFFu) << 8;                               \
-            bl_[e] = (__bf16)(__uint_as_float(hb_ | lb_) - __uint_as_float(hb_));                     \
-        }                                                                                             \
+#define PARK_TILE(buf, i)                                                                             \
+    {                                                                                                 \
+        const int ti_ = (i) * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT;                       \
         bf16x8 *dst_ = act_lds + ((((buf) * KU + u_) * MT + mt_) * 2) * 64 + lane;                    \
-        dst_[0] = ah[i];                                                                              \
-        dst_[64] = bl_;                                                                               \
+        dst_[0] = sh_[i];                                                                             \
+        dst_[64] = sl_[i];                                                                            \
     }
+#define STORE_ACT(buf) _Pragma("unroll") for (int i = 0; i < APT; ++i) PARK_TILE(buf, i)
 #define LOAD_W(a, kbase)                                                                              \
     _Pragma("unroll") for (int u = 0; u < KU; ++u) {                                                  \
         const int kk_ = (kbase) + u;                                                                  \
@@ -96,50 +91,59 @@ __global__ __launch_bounds__(64 * WIDE_WAVES) void gemm_wide_kernel(const bf16_t
                 a[u][j * TN + tn] = __builtin_nontemporal_load(                                       \
                     (kk_ < k1 && wp[j]) ? wp[j] + ((size_t)kk_ * TN + tn) * 64 : zw);                 \
     }
-#define COMPUTE(a, buf)                                                                               \
-    _Pragma("unroll") for (int u = 0; u < KU; ++u)                                                    \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                           \
-            const bf16x8 *src_ = act_lds + ((((buf) * KU + u) * MT + mt) * 2) * 64 + lane;            \
-            const bf16x8 bh_ = src_[0], bl_ = src_[64];                                               \
-            _Pragma("unroll") for (int t = 0; t < TNE; ++t) {                                         \
-                acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][t], bh_, acc[mt][t], 0, 0, 0); \
-                acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][t], bl_, acc[mt][t], 0, 0, 0); \
+    // One stage of products.  The operand pairs of the STEPS = KU * MT (k-step, M-tile) steps are fetched from
+    // LDS PD steps ahead of the MFMAs that use them, through a ring of PD + 1 register pairs, and the parking
+    // of the next stage's activations is spread over the last steps (by then its loads have landed): a
+    // scheduling barrier after every step keeps this order in the instruction stream (left to itself the
+    // compiler reuses one register pair and waits for every LDS read in turn).
+#define COMPUTE_AND_PARK(a, buf, buf_store)                                                           \
+    {                                                                                                 \
+        constexpr int STEPS = KU * MT, PD = STEPS < 3 ? STEPS : 3;                                    \
+        bf16x8 bq_[PD + 1][2];                                                                        \
+        const bf16x8 *base_ = act_lds + (size_t)(buf) * STEPS * 128 + lane;                           \
+        _Pragma("unroll") for (int p = 0; p < PD; ++p) { bq_[p][0] = base_[p * 128]; bq_[p][1] = base_[p * 128 + 64]; } \
+        _Pragma("unroll") for (int st = 0; st < STEPS; ++st) {                                        \
+            if (st + PD < STEPS) {                                                                    \
+                bq_[(st + PD) % (PD + 1)][0] = base_[(st + PD) * 128];                                \
+                bq_[(st + PD) % (PD + 1)][1] = base_[(st + PD) * 128 + 64];                           \
             }                                                                                         \
-        }
-
-    // prologue: first stage into buffer 0
+            const int u = st / MT, mt = st % MT;                                                      \
+            _Pragma("unroll") for (int t = 0; t < TNE; ++t) {                                         \
+                acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][t], bq_[st % (PD + 1)][0], acc[mt][t], 0, 0, 0); \
+                acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][t], bq_[st % (PD + 1)][1], acc[mt][t], 0, 0, 0); \
+            }                                                                                         \
+            if (st >= STEPS - APT) PARK_TILE(buf_store, st - (STEPS - APT))                           \
+            __builtin_amdgcn_sched_barrier(0);                                                        \
+        }                                                                                             \
+    }
+    // Round r (stage r at k-steps kt .. kt + KU): request stage r + 1's activations and stage r + WD - 1's
+    // weights, multiply stage r from LDS buffer r % 2 and park stage r + 1's activations in the other
+    // buffer.  The barrier at the end of a round orders "every wave has read buffer b" before "buffer b is
+    // overwritten" one round later, and "buffer b ^ 1 is written" before it is read in the next round.
+    // prologue: stage 0 of the activations, stages 0 .. WD - 2 of the weights; stage 0 into buffer 0
     LOAD_ACT(k0)
-    LOAD_W(a0, k0)
+#pragma unroll
+    for (int r = 0; r < WD - 1; ++r) LOAD_W(a_[r], k0 + r * KU)
     STORE_ACT(0)
     __syncthreads();
-    // Each round: request the next stage (activations first: they come from L2 and are wanted first),
-    // multiply the current one, park the next stage's activations in the other LDS buffer.  The barrier at
-    // the end of a round orders "every wave has read buffer b" before "buffer b is overwritten" one round
-    // later, and "buffer b^1 is written" before "buffer b^1 is read" in the next round.
-    for (int kt = k0;;) {
-        LOAD_ACT(kt + KU)
-        LOAD_W(a1, kt + KU)
-        __builtin_amdgcn_sched_barrier(0);
-        COMPUTE(a0, 0)
-        __builtin_amdgcn_sched_barrier(0);
-        STORE_ACT(1)
-        __syncthreads();
-        kt += KU;
-        if (kt >= k1) break;
-        LOAD_ACT(kt + KU)
-        LOAD_W(a0, kt + KU)
-        __builtin_amdgcn_sched_barrier(0);
-        COMPUTE(a1, 1)
-        __builtin_amdgcn_sched_barrier(0);
-        STORE_ACT(0)
-        __syncthreads();
-        kt += KU;
-        if (kt >= k1) break;
+    constexpr int PERIOD = WD % 2 ? 2 * WD : WD;      // rounds after which both ring positions repeat
+    for (int kt = k0; kt < k1;) {
+#pragma unroll
+        for (int r = 0; r < PERIOD; ++r) {
+            LOAD_ACT(kt + KU)
+            LOAD_W(a_[(r + WD - 1) % WD], kt + (WD - 1) * KU)
+            __builtin_amdgcn_sched_barrier(0);
+            COMPUTE_AND_PARK(a_[r % WD], r & 1, (r + 1) & 1)
+            __syncthreads();
+            kt += KU;
+            if (kt >= k1) break;
+        }
     }
 #undef LOAD_ACT
 #undef STORE_ACT
+#undef PARK_TILE
 #undef LOAD_W
-#undef COMPUTE
+#undef COMPUTE_AND_PARK
 
     // fp32 sums of this K-slice, as whole accumulator fragments: [slice][m tile][n tile][lane]
 #pragma unroll
@@ -253,8 +257,8 @@ static int launch_wide_mt(const SjdLinear *lin, const void *act, int g, int ks, 
     return SJD_EINVAL;
 }
 
-// Workgroups and K-slices: about two workgroups per CU, every slice at least 8 k-steps long, and the
-// partial sums of all slices inside `part_elems` floats.
+// Workgroups and K-slices: every slice at least 8 k-steps long, and the partial sums of all slices inside
+// `part_elems` floats.
 void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, int *ks_out, int *kps_out)
 {
     const int KT = lin->K / 32, groups = lin->N / 16 / lin->tn;
@@ -262,7 +266,10 @@ void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, 
     if (lin->tn == 3) g = 1;
     if (g > 2) g = 2;
     const int wgx = (groups + WIDE_WAVES * g - 1) / (WIDE_WAVES * g);
-    int ks = lin->wks > 0 ? lin->wks : (384 + wgx - 1) / wgx;
+    // K-slices (measured on the 7B shapes at 64 and 128 rows): about 256 workgroups where N alone gives at
+    // most 128 of them; 4 slices up to 256, 2 up to 512 (more slices cost more partial-sum traffic than the
+    // extra workgroups win), none above
+    int ks = lin->wks > 0 ? lin->wks : wgx >= 512 ? 1 : wgx >= 256 ? 2 : wgx > 128 ? 4 : (256 + wgx - 1) / wgx;
     ks = std::max(1, std::min(ks, KT / 8 > 0 ? KT / 8 : 1));
     const size_t per_slice = (size_t)mt * 16 * lin->N;
     while (ks > 1 && per_slice * ks > part_elems) --ks;

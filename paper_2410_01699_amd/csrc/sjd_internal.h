@@ -9,6 +9,7 @@
 #define SJD_ROWS_MAX SJD_MAX_ROWS       // rows (window slots of all streams, or a prefill chunk) one forward pass handles
 #define SJD_MTILES (SJD_ROWS_MAX / 16)  // 16-row tiles of an activation matrix
 #define SJD_ROWS_SKINNY 32              // up to here the skinny projection kernel runs, above it the wide one
+#define SJD_LO16_FROM_ROWS 33           // forwards with at least this many rows keep the 2-byte lo plane (see sjd_api.hip)
 #define SJD_ROWS_F32 32                 // fp32 models (launch-bound toys): rows per forward, largest window
 
 typedef unsigned short bf16_t;  // raw bf16 bit pattern
@@ -136,7 +137,11 @@ __host__ __device__ __forceinline__ size_t act24_idx(int m, int k, int KT)
     return (((size_t)(m >> 4) * KT + (k >> 5)) << 9) + ((((k & 31) >> 3) * 16 + (m & 15)) << 3) + (k & 7);
 }
 __host__ __device__ __forceinline__ size_t act24_lo_base(int KT) { return (size_t)(SJD_MTILES * KT + 1) * 1024; }   // bytes
-__host__ __device__ __forceinline__ size_t act24_bytes(int KT) { return (size_t)(SJD_MTILES * KT + 1) * 1536; }
+// Forwards of more than SJD_ROWS_SKINNY rows (the wide projection kernel) keep the second operand ready
+// made: the lo plane then holds bf16(value - hi) (exact: 8 significant bits), 2 bytes per value in the
+// same index order, so that a tile of either plane goes from L2 straight into LDS.  Same numbers, 4
+// bytes per value instead of 3.  A buffer is allocated for the larger form.
+__host__ __device__ __forceinline__ size_t act24_bytes(int KT) { return (size_t)(SJD_MTILES * KT + 1) * 2048; }
 // fp32 -> 16 significant bits (round to nearest even), returned in fp32 position: bits 31..16 are the
 // hi plane entry, bits 15..8 the lo plane entry
 __device__ __forceinline__ uint32_t f32_to_act24(float x)
@@ -145,24 +150,37 @@ __device__ __forceinline__ uint32_t f32_to_act24(float x)
     u += 0x7Fu + ((u >> 8) & 1u);
     return u & 0xFFFFFF00u;
 }
+// the second operand of a value in that form, as bf16 bits: value - hi (exact)
+__device__ __forceinline__ uint32_t act24_lo16(uint32_t u)
+{
+    return __float_as_uint(__uint_as_float(u) - __uint_as_float(u & 0xFFFF0000u)) >> 16;
+}
 // Row length (floats) of the per-token partial sums of squares a writer of a residual matrix
 // leaves, one per 16 features; padded (with zeros nobody writes) to whole float4.
 __host__ __device__ __forceinline__ int ssq_stride(int K) { return (K / 16 + 3) & ~3; }
-// planes of 4 consecutive values (k a multiple of 4) / of 2 (k even) of row m
-__device__ __forceinline__ void act24_store4(void *base, int m, int k, int KT, float v0, float v1, float v2, float v3)
+// planes of 4 consecutive values (k a multiple of 4) / of 2 (k even) of row m; lo16: the 2-byte lo plane
+__device__ __forceinline__ void act24_store4(void *base, int m, int k, int KT, float v0, float v1, float v2, float v3,
+                                             bool lo16)
 {
     const uint32_t a = f32_to_act24(v0), b = f32_to_act24(v1), c = f32_to_act24(v2), d = f32_to_act24(v3);
     const size_t i = act24_idx(m, k, KT);
     *reinterpret_cast<uint2 *>((bf16_t *)base + i) = make_uint2((a >> 16) | (b & 0xFFFF0000u), (c >> 16) | (d & 0xFFFF0000u));
-    *reinterpret_cast<uint32_t *>((uint8_t *)base + act24_lo_base(KT) + i) =
-        ((a >> 8) & 0xFFu) | (b & 0xFF00u) | ((c << 8) & 0xFF0000u) | ((d << 16) & 0xFF000000u);
+    if (lo16)
+        *reinterpret_cast<uint2 *>((uint8_t *)base + act24_lo_base(KT) + 2 * i) =
+            make_uint2(act24_lo16(a) | (act24_lo16(b) << 16), act24_lo16(c) | (act24_lo16(d) << 16));
+    else
+        *reinterpret_cast<uint32_t *>((uint8_t *)base + act24_lo_base(KT) + i) =
+            ((a >> 8) & 0xFFu) | (b & 0xFF00u) | ((c << 8) & 0xFF0000u) | ((d << 16) & 0xFF000000u);
 }
-__device__ __forceinline__ void act24_store2(void *base, int m, int k, int KT, float v0, float v1)
+__device__ __forceinline__ void act24_store2(void *base, int m, int k, int KT, float v0, float v1, bool lo16)
 {
     const uint32_t a = f32_to_act24(v0), b = f32_to_act24(v1);
     const size_t i = act24_idx(m, k, KT);
     *reinterpret_cast<uint32_t *>((bf16_t *)base + i) = (a >> 16) | (b & 0xFFFF0000u);
-    *reinterpret_cast<uint16_t *>((uint8_t *)base + act24_lo_base(KT) + i) = (uint16_t)(((a >> 8) & 0xFFu) | (b & 0xFF00u));
+    if (lo16)
+        *reinterpret_cast<uint32_t *>((uint8_t *)base + act24_lo_base(KT) + 2 * i) = act24_lo16(a) | (act24_lo16(b) << 16);
+    else
+        *reinterpret_cast<uint16_t *>((uint8_t *)base + act24_lo_base(KT) + i) = (uint16_t)(((a >> 8) & 0xFFu) | (b & 0xFF00u));
 }
 //
 // KV cache of bf16 models: per layer, per head, per block of 32 positions one contiguous record of
@@ -217,6 +235,7 @@ struct SjdGemmEpi {
     const bf16_t *gain_next;     // RESID: [N] gain of the normalisation that follows
     float *ssq_out;              // RESID: [rows][ssq_stride(N)] sum of squares of the updated rows per 16 features
     void *ffn; int32_t F;                                         // SILU: [rows][F] in act24 planes
+    int32_t lo16;                // RESID, SILU: the planes they write carry the 2-byte lo plane (wide forwards)
     float *qact; const float *cosT, *sinT;                        // QKV
     int32_t d, hd, nblk, rows_valid, max_seq;                     // rows_valid: rows per stream whose K/V are stored
 };
@@ -312,8 +331,9 @@ struct sjd_kv {
 // bf16 models: `rows` rows per stream, stream s from ids[s] (device ids; all streams share emb_rows when
 // that is given instead), written at row s << sm.shift.  fp32 models: one stream, ids[0].
 // err[s] (device, may be NULL): receives SJD_DEVERR_TOKEN_ID when an id of stream s lies outside the vocabulary
+// lo16: x24 gets the 2-byte lo plane (the forward runs on the wide projection kernel)
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, void *x24, float *ssq, int32_t *const *err, hipStream_t s);
+                     const SjdStreams &sm, float *x, void *x24, float *ssq, int32_t *const *err, bool lo16, hipStream_t s);
 int sjd_launch_rmsnorm(const sjd_model *m, float *x, const float *part, int32_t n_part, size_t part_stride,
                        const void *gain, int32_t rows, void *h, const SjdState *st, hipStream_t s);
 int sjd_launch_rope_kv(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t stream, const float *part, int32_t n_part,
@@ -332,19 +352,23 @@ void sjd_choose_tiles(SjdLinear *lin);
 // of squares of x ([rows][ssq_stride(K)]); the projection applies rsqrt(mean(x^2) + eps) per row.
 // More than SJD_ROWS_SKINNY rows go to the wide kernel (planes only), which needs `part`: room for the fp32
 // sums of its K-slices (part_elems floats, at least 16 * ceil(rows / 16) * N); NULL = skinny kernel only.
-int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, bool act24, const float *ssq_in, float eps, int32_t rows,
+#define SJD_ACT_F32 0     // fp32 values in act_off order (test hook)
+#define SJD_ACT_P3 1      // operand planes, 1-byte lo plane (3 bytes per value)
+#define SJD_ACT_P4 2      // operand planes, 2-byte lo plane (4 bytes per value)
+int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const float *ssq_in, float eps, int32_t rows,
                          const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s);
 int sjd_launch_gemm_wide(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,
                          const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s);
 void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, int *ks_out, int *kps_out);
 int sjd_gemm_wide_setup();
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);
-int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, hipStream_t s);
-int sjd_bf16_rows_to_act24(const bf16_t *src, int32_t rows, int32_t K, void *dst, hipStream_t s);
+int sjd_f32_rows_to_act24(const float *src, int32_t rows, int32_t K, void *dst, bool lo16, hipStream_t s);
+int sjd_bf16_rows_to_act24(const bf16_t *src, int32_t rows, int32_t K, void *dst, hipStream_t s);    // (either lo form: zeros)
 // fp32 models: `stream` 0 / 1 selects the cache and length of the handle
 int sjd_launch_attention_f32(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, int32_t stream, hipStream_t s);
 // bf16 models: `rows` query rows per stream of sm against that stream's cache
-int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, hipStream_t s);
+int sjd_launch_attention(const sjd_model *m, sjd_kv *kv, int32_t layer, int32_t rows, const SjdStreams &sm, bool lo16,
+                         hipStream_t s);
 int32_t sjd_attention_splits(const sjd_model *m);
 size_t sjd_attention_part_elems(const sjd_model *m);
 // sampling / verification

@@ -21,7 +21,7 @@ template <> struct Act<bf16_t> {
 struct EmbedIds { const int32_t *p[SJD_MAX_STREAMS]; int32_t *err[SJD_MAX_STREAMS]; };
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, const float *emb_rows, int d, int shift,
-                                                    float *x, void *x24, const bf16_t *gain, float *ssq, int vocab)
+                                                    float *x, void *x24, const bf16_t *gain, float *ssq, int vocab, int lo16)
 {
     const int stream = blockIdx.z;
     const int r = blockIdx.x;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const T *E, EmbedIds ids, co
     if (sizeof(T) == 2) {
         const uint2 gn = *reinterpret_cast<const uint2 *>(gain + j);
         act24_store4(x24, row, j, d / 32, v.x * __uint_as_float(gn.x << 16), v.y * __uint_as_float(gn.x & 0xFFFF0000u),
-                     v.z * __uint_as_float(gn.y << 16), v.w * __uint_as_float(gn.y & 0xFFFF0000u));
+                     v.z * __uint_as_float(gn.y << 16), v.w * __uint_as_float(gn.y & 0xFFFF0000u), lo16 != 0);
         float sq = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w)));
         sq += __shfl_xor(sq, 1);                      // 4 consecutive threads hold 16 consecutive features
         sq += __shfl_xor(sq, 2);
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *part, int
 #define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
 
 int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float *emb_rows, int32_t rows,
-                     const SjdStreams &sm, float *x, void *x24, float *ssq, int32_t *const *err, hipStream_t s)
+                     const SjdStreams &sm, float *x, void *x24, float *ssq, int32_t *const *err, bool lo16, hipStream_t s)
 {
     if (sm.count < 1 || sm.count > SJD_MAX_STREAMS || rows < 1 || rows > (1 << sm.shift) ||
         (sm.count << sm.shift) > SJD_ROWS_MAX)
@@ -171,9 +171,9 @@ int sjd_launch_embed(const sjd_model *m, const int32_t *const *ids, const float 
     }
     const dim3 grid(rows, (d + 1023) / 1024, sm.count);
     if (m->cfg.dtype == 0)
-        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)nullptr, ssq, m->cfg.vocab_total);
+        SJD_LAUNCH(embed_kernel<float>, grid, dim3(256), 0, s, (const float *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)nullptr, ssq, m->cfg.vocab_total, lo16 ? 1 : 0);
     else
-        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)m->layers[0].g1, ssq, m->cfg.vocab_total);
+        SJD_LAUNCH(embed_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)m->E, e, emb_rows, d, sm.shift, x, x24, (const bf16_t *)m->layers[0].g1, ssq, m->cfg.vocab_total, lo16 ? 1 : 0);
     LAUNCH_CHECK();
     return SJD_OK;
 }
