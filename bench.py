@@ -116,6 +116,10 @@ def main():
     ap.add_argument("--gemm-bench", default=None, metavar="M,N,K,tn,wk,u[,iters]",
                     help="only time the bf16 projection kernel alone at one shape and tiling (sjd_gemm_bench; cold weights "
                          "when iters < 0, default -40): for counter runs on single kernels")
+    ap.add_argument("--gemm-sweep", default=None, metavar="M[,M...]",
+                    help="only sweep the projection kernels alone over the 7B and 775M layer shapes at these row counts "
+                         "(cold weights): skinny kernel with 3- and 4-byte activation planes and its wave / prefetch "
+                         "variants up to 32 rows, wide kernel with its K-slice / group variants at any row count")
     ap.add_argument("--verify-scaled", action="store_true",
                     help="only time the sampling-distribution kernel (top-K + softmax of Step 3) at a scaled shape: 4096 "
                          "logits rows in one launch, where it is a bandwidth problem rather than a launch (off-path evidence)")
@@ -154,6 +158,35 @@ def main():
         print(json.dumps({"M": M_, "N": N_, "K": K_, "tn": tn_, "wk": wk_, "u": u_, "iters": it_, "us_per_launch": us,
                           "weight_GBps": by / us / 1e3, "frac_of_hbm_peak": by / us / 1e3 / HBM_PEAK_GBS,
                           "mfma_TFLOPs_hi_and_lo": 4.0 * M_ * N_ * K_ / us / 1e6}))
+        return
+    if args.gemm_sweep:
+        shapes = {"7b_qkv": (12288, 4096, 3), "7b_o": (4096, 4096, 1), "7b_gate_up": (22016, 4096, 2), "7b_down": (4096, 11008, 1),
+                  "7b_lm_head": (8192, 4096, 2), "775m_qkv": (4608, 1536, 2), "775m_o": (1536, 1536, 1),
+                  "775m_gate_up": (8192, 1536, 2), "775m_down": (1536, 4096, 1)}
+        rows_out = []
+        for M_ in [int(x) for x in args.gemm_sweep.split(",")]:
+            for name, (N_, K_, tn_) in shapes.items():
+                res = {}
+                if M_ <= 32:
+                    for wk_ in (4, 8):
+                        for u_ in (2, 4):
+                            for f_, fname in ((0, "3B"), (10, "4B")):
+                                try:
+                                    res[f"skinny wk{wk_} u{u_} {fname}"] = B.sjd_gemm_bench(M_, N_, K_, tn_, wk_, u_ + f_, -40)
+                                except B.SjdError:
+                                    pass
+                for g_ in ((1, 2) if tn_ == 1 else (1,)):
+                    for ks_ in (1, 2, 3, 4, 6, 8):
+                        try:
+                            res[f"wide g{g_} ks{ks_}"] = B.sjd_gemm_bench(M_, N_, K_, tn_, 100 + ks_, g_, -40)
+                        except B.SjdError:
+                            pass
+                best = sorted(res.items(), key=lambda kv: kv[1])
+                rows_out.append({"M": M_, "shape": name, "N": N_, "K": K_, "weight_MB": N_ * K_ * 2 / 1e6,
+                                 "us": {k: round(v, 2) for k, v in best},
+                                 "best": best[0][0], "best_TBps": N_ * K_ * 2 / best[0][1] / 1e6})
+                log(f"M={M_} {name}: " + "  ".join(f"{k}: {v:.1f}us" for k, v in best[:5]))
+        print(json.dumps({"gemm_sweep": rows_out}))
         return
     if args.verify_scaled:
         # Step 3's distribution kernel on many independent rows at once.  Algorithmic bytes: one fp32 logits row in,

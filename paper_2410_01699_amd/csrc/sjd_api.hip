@@ -153,6 +153,11 @@ extern "C" int sjd_init_model(const sjd_config *cfg, const void *host_weights, s
         off += 2 * f * d;
         rc = linear(off, (int)d, (int)f, 0, &L->down); if (rc) return fail(rc);
         off += d * f;
+        // From 17 rows on the skinny kernel reads two M-tiles of activations per weight tile in every wave; a
+        // projection with one weight tile per workgroup and a long reduction (the 7B down projection: 256
+        // workgroups, each re-reading 32 x 11008 activations) is then faster on the wide kernel, whose waves
+        // share the activations through LDS (measured alone on cold weights: 23.6 against 29.9 us).
+        if (cfg->dtype == 1 && L->down.tn == 1 && L->down.N >= 4096 && L->down.K >= 2 * L->down.N) L->down.wide_from = 17;
     }
     m->gf = plain(off, d); if (!m->gf) return fail(SJD_EHIP);
     off += d;
@@ -482,8 +487,14 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     const int d = m->cfg.d_model, F = m->cfg.d_ffn;
     const float eps = m->cfg.rms_eps;
     const int grows = ((sm.count - 1) << sm.shift) + rows;      // rows the projections compute
+    // Which kernel each projection runs on decides the form of the buffer it reads (its producer writes
+    // that form): the residual stream's planes feed QKV, gate/up and the LM head, which go wide together
+    // (above SJD_ROWS_SKINNY rows); the attention output feeds O and the FFN hidden feeds down, which may go
+    // wide from fewer rows on (SjdLinear::wide_from).
     const bool lo16 = rows_use_lo16(grows);
     const int form = lo16 ? SJD_ACT_P4 : SJD_ACT_P3;
+    auto goes_wide = [&](const SjdLinear &lin) { return lo16 || (lin.wide_from > 0 && grows >= lin.wide_from); };
+    const bool o_wide = goes_wide(m->layers[0].o), down_wide = goes_wide(m->layers[0].down);
     // upper bound of the K/V bytes one layer's attention reads (hi + lo planes)
     const double kv_bytes_layer = 2.0 * kv_tokens_upper * d * 4;
     SjdGemmEpi e_qkv, e_res, e_silu, e_lm;
@@ -493,7 +504,7 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
     e_qkv.kind = SJD_EPI_QKV; e_qkv.qact = kv->qact; e_qkv.cosT = m->rope_cos; e_qkv.sinT = m->rope_sin;
     e_qkv.d = d; e_qkv.hd = m->hd; e_qkv.nblk = kv->nblk; e_qkv.rows_valid = rows_valid; e_qkv.max_seq = m->cfg.max_seq;
     e_res.kind = SJD_EPI_RESID; e_res.out = kv->x; e_res.out24 = kv->x24; e_res.ssq_out = kv->ssq; e_res.lo16 = lo16;
-    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = kv->ffn; e_silu.F = F; e_silu.lo16 = lo16;
+    e_silu.kind = SJD_EPI_SILU; e_silu.ffn = kv->ffn; e_silu.F = F; e_silu.lo16 = down_wide;
     e_lm.kind = SJD_EPI_STORE; e_lm.out = logits;
     const void *x = kv->x24, *att = kv->att_out, *ffn = kv->ffn;     // hi / lo planes, 3 bytes per value
     // x24 holds x * (gain of the normalisation the next projection sits behind), kv->ssq its partial
@@ -504,12 +515,12 @@ static int forward_rows_bf16(sjd_model *m, sjd_kv *kv, const SjdStreams &sm, int
         const SjdLayer &L = m->layers[l];
         e_qkv.layer_off = (size_t)l * kv->k_layer_stride;
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.qkv), sjd_launch_gemm_bf16(&L.qkv, x, form, ssq, eps, grows, e_qkv, kv->part, kv->part_elems, s));
-        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, lo16, s));
+        PROF(kv, SJD_PROF_ATTENTION, kv_bytes_layer, sjd_launch_attention(m, kv, l, rows, sm, o_wide, s));
         e_res.gain_next = (const bf16_t *)L.g2;
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, form, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.o), sjd_launch_gemm_bf16(&L.o, att, o_wide ? SJD_ACT_P4 : SJD_ACT_P3, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
         PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.gu), sjd_launch_gemm_bf16(&L.gu, x, form, ssq, eps, grows, e_silu, kv->part, kv->part_elems, s));
         e_res.gain_next = (const bf16_t *)(l + 1 < m->cfg.n_layers ? m->layers[l + 1].g1 : m->gf);
-        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, form, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
+        PROF(kv, SJD_PROF_GEMM, lin_bytes(m, L.down), sjd_launch_gemm_bf16(&L.down, ffn, down_wide ? SJD_ACT_P4 : SJD_ACT_P3, nullptr, 0.f, grows, e_res, kv->part, kv->part_elems, s));
     }
     PROF(kv, SJD_PROF_GEMM, lin_bytes(m, m->lm), sjd_launch_gemm_bf16(&m->lm, x, form, ssq, eps, grows, e_lm, kv->part, kv->part_elems, s));
     return SJD_OK;

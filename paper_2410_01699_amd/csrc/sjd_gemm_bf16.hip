@@ -377,8 +377,10 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const 
 {
     const bool act24 = form != SJD_ACT_F32, lo16 = form == SJD_ACT_P4;
     if (rows < 1 || rows > SJD_ROWS_MAX || (ssq_in && !act24) || form < 0 || form > 2) return SJD_EINVAL;
-    if (rows > SJD_ROWS_SKINNY || (lin->wide_from > 0 && rows >= lin->wide_from && act24 && part)) {
-        if (!lo16 && !(lin->wide_from > 0)) return SJD_EINVAL;     // (the wide kernel reads the 4-byte planes only)
+    // the wide kernel: above SJD_ROWS_SKINNY rows, or from lin->wide_from rows on; it reads the 4-byte planes
+    const bool wide = rows > SJD_ROWS_SKINNY || (lin->wide_from > 0 && rows >= lin->wide_from && lo16 && part);
+    if (wide) {
+        if (!lo16) return SJD_EINVAL;
         return sjd_launch_gemm_wide(lin, act, ssq_in, eps, rows, ep, part, part_elems, s);
     }
     if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
