@@ -63,7 +63,8 @@ __global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf1
     // KU k-steps; HBM latency under load is several stages long).  Activations: both operand planes come
     // ready made (the forward's producers write the 2-byte lo plane), so a stage is requested from L2 one
     // stage ahead into registers and parked in LDS, tile by tile, between the products of the stage before.
-    constexpr int WD = TNE >= 3 ? 3 : 4;      // stages of weights in registers (three where a stage is 6 tiles)
+    // stages of weights in registers: four, three or two, at most 32 weight tiles (128 registers) in all
+    constexpr int WD = KU * TNE <= 4 ? 4 : KU * TNE <= 8 ? 3 : 2;
     bf16x8 a_[WD][KU][TNE];
     bf16x8 sh_[APT], sl_[APT];
 
@@ -207,7 +208,11 @@ __global__ __launch_bounds__(256) void gemm_wide_epilogue_kernel(const f32x4 *__
 static std::mutex g_wide_mutex;
 static size_t g_wide_lds[5][4][3] = {};      // dynamic LDS already enabled per (MT/2, TN, G) instantiation
 
-#define WIDE_KU 2
+// k-steps per stage: 16 (k-step, M-tile) products between two workgroup barriers whatever the row count (a
+// stage of few products would spend its time in the barrier); half of that where a wave holds 3 or 4 weight
+// tiles per k-step
+constexpr int wide_ku(int MT, int TNE) { return MT == 2 ? (TNE >= 3 ? 4 : 8) : MT == 4 ? (TNE >= 3 ? 2 : 4) : 2; }
+#define WIDE_KU wide_ku(MT, TN * G)
 template <int MT, int TN, int G>
 static int enable_lds_t()
 {
@@ -228,6 +233,8 @@ int sjd_gemm_wide_setup()
 {
     SJD_TRY((enable_lds_t<8, 1, 1>())); SJD_TRY((enable_lds_t<8, 1, 2>())); SJD_TRY((enable_lds_t<8, 2, 1>()));
     SJD_TRY((enable_lds_t<8, 2, 2>())); SJD_TRY((enable_lds_t<8, 3, 1>()));
+    SJD_TRY((enable_lds_t<4, 1, 1>())); SJD_TRY((enable_lds_t<4, 1, 2>())); SJD_TRY((enable_lds_t<4, 2, 1>()));
+    SJD_TRY((enable_lds_t<2, 1, 1>())); SJD_TRY((enable_lds_t<2, 1, 2>())); SJD_TRY((enable_lds_t<2, 2, 1>()));
     return SJD_OK;
 }
 
@@ -262,7 +269,9 @@ static int launch_wide_mt(const SjdLinear *lin, const void *act, int g, int ks, 
 void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, int *ks_out, int *kps_out)
 {
     const int KT = lin->K / 32, groups = lin->N / 16 / lin->tn;
-    int g = lin->wg > 0 ? lin->wg : (lin->tn == 1 ? 2 : 1);
+    // two weight groups per wave: one-tile groups, and two-tile groups of a long N up to 64 rows (at more rows
+    // the accumulators of four tiles per M-tile no longer fit the registers)
+    int g = lin->wg > 0 ? lin->wg : (lin->tn == 1 || (lin->tn == 2 && mt <= 4 && groups >= 512) ? 2 : 1);
     if (lin->tn == 3) g = 1;
     if (g > 2) g = 2;
     const int wgx = (groups + WIDE_WAVES * g - 1) / (WIDE_WAVES * g);
@@ -270,11 +279,13 @@ void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, 
     // most 128 of them; 4 slices up to 256, 2 up to 512 (more slices cost more partial-sum traffic than the
     // extra workgroups win), none above
     int ks = lin->wks > 0 ? lin->wks : wgx >= 512 ? 1 : wgx >= 256 ? 2 : wgx > 128 ? 4 : (256 + wgx - 1) / wgx;
+    if (lin->wks <= 0 && lin->tn == 2 && g == 2) ks = 2;      // (measured: 86 wide workgroups x 2 beat x 3 and x 4)
     ks = std::max(1, std::min(ks, KT / 8 > 0 ? KT / 8 : 1));
     const size_t per_slice = (size_t)mt * 16 * lin->N;
     while (ks > 1 && per_slice * ks > part_elems) --ks;
+    const int ku = wide_ku(mt, lin->tn * g);
     int kps = (KT + ks - 1) / ks;
-    kps = (kps + 1) & ~1;                       // whole stages
+    kps = (kps + ku - 1) / ku * ku;             // whole stages
     ks = (KT + kps - 1) / kps;
     *g_out = g; *ks_out = ks; *kps_out = kps;
 }
