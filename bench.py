@@ -166,7 +166,7 @@ def main():
         rows_out = []
         for M_ in [int(x) for x in args.gemm_sweep.split(",")]:
             for name, (N_, K_, tn_) in shapes.items():
-                res = {}
+                res = {"model's choice": B.sjd_gemm_bench(M_, N_, K_, tn_, 0, 0, -40)}
                 if M_ <= 32:
                     for wk_ in (4, 8):
                         for u_ in (2, 4):
@@ -175,7 +175,7 @@ def main():
                                     res[f"skinny wk{wk_} u{u_} {fname}"] = B.sjd_gemm_bench(M_, N_, K_, tn_, wk_, u_ + f_, -40)
                                 except B.SjdError:
                                     pass
-                for g_ in ((1, 2) if tn_ == 1 else (1,)):
+                for g_ in ((1, 2) if tn_ < 3 else (1,)):
                     for ks_ in (1, 2, 3, 4, 6, 8):
                         try:
                             res[f"wide g{g_} ks{ks_}"] = B.sjd_gemm_bench(M_, N_, K_, tn_, 100 + ks_, g_, -40)

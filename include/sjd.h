@@ -116,8 +116,9 @@ int sjd_prefill(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, con
  * unconditional prompt into a second cache of the same handle.  From then on every window forward
  * runs both contexts on the same draft tokens (one pass over the weights, 2 x L rows) and Step 3
  * works on z = z_uncond + guidance * (z_cond - z_uncond); both caches advance by the accepted
- * count.  q_last is overwritten with the guided distribution of the first image token.  Windows are
- * limited to 16 tokens while guidance is on; the next sjd_prefill switches it off.                */
+ * count.  q_last is overwritten with the guided distribution of the first image token.  Windows go
+ * up to SJD_MAX_WINDOW tokens with guidance on as well (two contexts x 64 rows = SJD_MAX_ROWS; fp32
+ * models: 32); the next sjd_prefill switches it off.                                             */
 int sjd_prefill_uncond(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
                        int32_t n_embeds, float guidance, const sjd_sampler *smp, const sjd_init *init, float *q_last,
                        void *stream);
@@ -149,7 +150,7 @@ int sjd_generate(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, co
                  int32_t n_embeds, int32_t N, int32_t L, const sjd_sampler *smp, const sjd_init *init,
                  uint64_t philox_seed, int32_t *out_tokens, sjd_stats *stats);
 
-/* sjd_generate with classifier-free guidance: both prompts, then the guided loop (L <= 16).      */
+/* sjd_generate with classifier-free guidance: both prompts, then the guided loop.                */
 int sjd_generate_cfg(sjd_model *m, sjd_kv *kv, const int32_t *ids, int32_t n_ids, const float *embeds,
                      int32_t n_embeds, const int32_t *uncond_ids, int32_t n_uncond_ids, const float *uncond_embeds,
                      int32_t n_uncond_embeds, float guidance, int32_t N, int32_t L, const sjd_sampler *smp,
@@ -176,9 +177,10 @@ int sjd_kv_use_graph(sjd_kv *kv, int32_t on);
 
 /* Per-kernel-class timing: runs n_steps iterations of the loop above kernel by kernel, every launch
  * carrying a start/stop HIP event pair that the runtime stamps with the kernel's own begin and end
- * (on `stream`), and adds up milliseconds, launch counts and algorithmic HBM bytes (weights for the
- * projections, K/V records for attention, logits + both probability windows for the verification)
- * per class.  The per-launch intervals include a few microseconds of dispatch latency each, so the
+ * (on `stream`), and adds up milliseconds, launch counts and HBM bytes (weights for the
+ * projections; for attention the K/V records, as stored -- hi and lo halves, twice the bf16 size --
+ * of the positions each profiled step really attended over; logits + both probability windows for
+ * the verification) per class.  The per-launch intervals include a few microseconds of dispatch latency each, so the
  * projections (the dominant class) are timed a second time: the projection launches of n_steps
  * iterations alone, back to back in one event interval (ms_gemm_back_to_back; the same number of
  * launches and bytes as in the per-launch pass).  Synchronises.                                */
@@ -203,8 +205,8 @@ int sjd_profile_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t
  * over the weights serves B x L rows, so an iteration costs little more than for one image and the
  * throughput grows almost B-fold.  Each image keeps its own handle (cache, loop state, random
  * stream); Steps 3 and 4 run per image exactly as in sjd_decode_steps.  bf16 models, no guidance;
- * the B windows must fit the 32 rows of one projection launch: L <= 16 for B = 2, L <= 8 for
- * B <= 4, L <= 4 for B <= 8.  The first handle lends its activation buffers and, with graphs on,
+ * the B windows (each rounded up to a power of two of rows) must fit the SJD_MAX_ROWS rows of one
+ * forward: L <= 64 for B = 2, L <= 32 for B <= 4, L <= 16 for B <= 8.  The first handle lends its activation buffers and, with graphs on,
  * holds the captured iteration (re-captured when the set of handles or their settings change).
  *
  * sjd_decode_steps_batch: every handle has been through sjd_prefill + sjd_decode_begin with the same
