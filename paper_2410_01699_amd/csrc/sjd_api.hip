@@ -1443,7 +1443,8 @@ extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32
     SjdLinear lin;
     memset(&lin, 0, sizeof(lin));
     lin.N = N; lin.K = K; lin.tn = tn; lin.w = g.Wp;
-    if (wide) { lin.wks = wk; lin.wg = u; lin.wide_from = 1; }      // wide kernel: K-slices and weight groups per wave (0 = automatic)
+    if (force_wide && u == 7 && rows > 16 && rows <= 32 && tn == 2) { lin.whole_k_rows = 32; form = SJD_ACT_P3; }   // the wide kernel's whole-K variant
+    else if (wide) { lin.wks = wk; lin.wg = u; lin.wide_from = 1; }      // wide kernel: K-slices and weight groups per wave (0 = automatic)
     else { lin.wk = wk; lin.u = u; }
     SjdGemmEpi ep;
     memset(&ep, 0, sizeof(ep));

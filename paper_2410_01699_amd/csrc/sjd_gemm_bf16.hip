@@ -338,6 +338,8 @@ void sjd_choose_tiles(SjdLinear *lin)
         }
     }
     lin->tn = best_tn; lin->wk = 0; lin->u = 0; lin->wg = 0; lin->wks = 0; lin->wide_from = 0;
+    // two-tile groups, at least 512 of them (N >= 16384): three per workgroup still give one workgroup to most CUs
+    lin->whole_k_rows = (best_tn == 2 && tiles / 2 >= 512) ? 32 : 0;
 }
 
 template <int MT, int TN, int WK, int U, int PRO>
@@ -383,6 +385,10 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const 
         if (!lo16) return SJD_EINVAL;
         return sjd_launch_gemm_wide(lin, act, ssq_in, eps, rows, ep, part, part_elems, s);
     }
+    // the wide kernel's whole-K variant (shapes whose N alone fills the chip; activations in the 3-byte form)
+    // (measured inside 7B iterations: 5 % of an iteration at 32 rows; at 16 rows the skinny kernel is 2 % ahead)
+    if (rows > 16 && rows <= lin->whole_k_rows && form == SJD_ACT_P3 && ep.kind != SJD_EPI_QKV)
+        return sjd_launch_gemm_wide3(lin, act, ssq_in, eps, rows, ep, s);
     if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;
     const int mt = rows <= 16 ? 1 : 2;

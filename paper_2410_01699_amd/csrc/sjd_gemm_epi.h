@@ -26,6 +26,23 @@ __device__ __forceinline__ void split8(const float (&x)[8], bf16x8 &hi, bf16x8 &
     }
 }
 
+// second operand of 8 values from their hi plane entry (8 bf16) and their byte plane entry (8 bytes):
+// value = hi bits | lo byte << 8 (as fp32); second operand = bf16(value - hi), exact
+__device__ __forceinline__ bf16x8 lo_from_byte_plane(bf16x8 hi, uint2 lo8)
+{
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const u32x4 hw = __builtin_bit_cast(u32x4, hi);
+    bf16x8 lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t hw_ = hw[e >> 1], lw_ = (e < 4) ? lo8.x : lo8.y;
+        const uint32_t hb_ = (e & 1) ? (hw_ & 0xFFFF0000u) : (hw_ << 16);
+        const uint32_t lb_ = ((lw_ >> (8 * (e & 3))) & 0xFFu) << 8;
+        lo[e] = (__bf16)(__uint_as_float(hb_ | lb_) - __uint_as_float(hb_));
+    }
+    return lo;
+}
+
 __device__ __forceinline__ uint32_t pack_hi2(float a, float b, float &ra, float &rb)
 {
     const bf16_t ha = f32_to_bf16(a), hb = f32_to_bf16(b);

@@ -27,22 +27,52 @@
 // one pipeline stage = KU k-steps; LDS holds two stages of MT activation tiles as hi and lo operands
 #define WIDE_WAVES 4
 
-template <int MT, int TN, int G, int KU>
-__global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf16_t *__restrict__ Wp,
-                                                                    const void *__restrict__ Xv, int N, int K, int kps,
-                                                                    f32x4 *__restrict__ part)
+// The whole-K variant (FUSED: grid.y = 1, NW = 3 waves): for a projection with so many output features that N
+// alone fills the chip (gate/up of the 7B model: 688 weight groups = 230 workgroups of three), up to 32 rows.
+// The workgroup holds final sums, so it runs the epilogue itself (no partial sums, no second kernel), and it
+// reads the activations in the 3-byte form the skinny kernel's other consumers of the same buffer read (P3:
+// the second operand is rebuilt once per workgroup while a tile is parked in LDS).
+template <int EPI, bool NORM, int MT, int TNE>
+__device__ __forceinline__ void wide_fused_tail(const f32x4 (&acc)[MT][TNE], int TN, const int *grp, int groups, int N,
+                                                const float *rs, const SjdGemmEpi &ep)
+{
+    const int lane = threadIdx.x & 63, g4 = lane >> 4, c = lane & 15;
+#pragma unroll
+    for (int t = 0; t < TNE; ++t) {
+        const int j = t / TN;
+        if (grp[j] >= groups) continue;
+        const int ntile = grp[j] * TN + t % TN;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int f_m = mt * 16 + c, f_n0 = ntile * 16 + g4 * 4;
+            EpiPre pre;
+            preload_epilogue<EPI>(ep, N, f_m, f_n0, pre);
+            f32x4 v = acc[mt][t];
+            if (NORM) v *= rs[f_m];
+            apply_epilogue<EPI>(ep, N, f_m, f_n0, v, pre);
+        }
+    }
+}
+
+template <int MT, int TN, int G, int KU, int NW, bool P3, bool FUSED>
+__global__ __launch_bounds__(64 * NW, 2) void gemm_wide_kernel(const bf16_t *__restrict__ Wp,
+                                                            const void *__restrict__ Xv, int N, int K, int kps,
+                                                            f32x4 *__restrict__ part, const float *__restrict__ ssq_in,
+                                                            float eps, SjdGemmEpi ep)
 {
     constexpr int TNE = TN * G;               // 16-feature tiles per wave
     constexpr int TPS = KU * MT;              // activation tiles per stage
-    constexpr int APT = TPS / WIDE_WAVES;     // of which each wave fetches
-    static_assert(TPS % WIDE_WAVES == 0, "the waves share the staging of a stage evenly");
+    constexpr int APT = TPS / NW;             // of which each wave fetches
+    static_assert(TPS % NW == 0 && APT >= 1, "the waves share the staging of a stage evenly");
     extern __shared__ bf16x8 act_lds[];       // [2 stages][KU][MT][plane][64 lanes]
+    __shared__ float rs_s[MT * 16];           // FUSED: token factors of a folded RMSNorm
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int KT = K / 32, NT = N / 16, groups = NT / TN;
     const int k0 = blockIdx.y * kps, k1 = min(KT, k0 + kps);
 
     const bf16x8 *xp = reinterpret_cast<const bf16x8 *>(Xv) + lane;
     const bf16x8 *xl = reinterpret_cast<const bf16x8 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;   // 2-byte lo plane
+    const uint2 *xl8 = reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(Xv) + act24_lo_base(KT)) + lane;     // 1-byte lo plane (P3)
     const size_t ztile = (size_t)SJD_MTILES * KT;        // the all-zero tile behind every activation matrix
     const bf16x8 *zw = xp + ztile * 64;
     // this wave's packed weight groups (a group past the end reads the zero tile and stores nothing)
@@ -50,7 +80,7 @@ __global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf1
     int grp[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) {
-        grp[j] = (blockIdx.x * WIDE_WAVES + wave) * G + j;
+        grp[j] = (blockIdx.x * NW + wave) * G + j;
         wp[j] = grp[j] < groups ? reinterpret_cast<const bf16x8 *>(Wp) + (size_t)grp[j] * KT * TN * 64 + lane : nullptr;
     }
 
@@ -67,21 +97,24 @@ __global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf1
     constexpr int WD = KU * TNE <= 4 ? 4 : KU * TNE <= 8 ? 3 : 2;
     bf16x8 a_[WD][KU][TNE];
     bf16x8 sh_[APT], sl_[APT];
+    uint2 s8_[APT];                           // (P3: the byte plane entries instead of sl_)
 
     // All loads are unconditional: a k-step past this workgroup's slice fetches the zero tile.
 #define LOAD_ACT(kbase)                                                                               \
     _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                                 \
-        const int ti_ = i * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT, kk_ = (kbase) + u_;     \
+        const int ti_ = i * NW + wave, u_ = ti_ / MT, mt_ = ti_ % MT, kk_ = (kbase) + u_;             \
         const size_t tix_ = kk_ < k1 ? (size_t)mt_ * KT + kk_ : ztile;                                \
         sh_[i] = xp[tix_ * 64];                                                                       \
-        sl_[i] = xl[tix_ * 64];                                                                       \
+        if constexpr (P3) s8_[i] = xl8[tix_ * 64];                                                    \
+        else sl_[i] = xl[tix_ * 64];                                                                  \
     }
 #define PARK_TILE(buf, i)                                                                             \
     {                                                                                                 \
-        const int ti_ = (i) * WIDE_WAVES + wave, u_ = ti_ / MT, mt_ = ti_ % MT;                       \
+        const int ti_ = (i) * NW + wave, u_ = ti_ / MT, mt_ = ti_ % MT;                               \
         bf16x8 *dst_ = act_lds + ((((buf) * KU + u_) * MT + mt_) * 2) * 64 + lane;                    \
         dst_[0] = sh_[i];                                                                             \
-        dst_[64] = sl_[i];                                                                            \
+        if constexpr (P3) dst_[64] = lo_from_byte_plane(sh_[i], s8_[i]);                              \
+        else dst_[64] = sl_[i];                                                                       \
     }
 #define STORE_ACT(buf) _Pragma("unroll") for (int i = 0; i < APT; ++i) PARK_TILE(buf, i)
 #define LOAD_W(a, kbase)                                                                              \
@@ -125,6 +158,20 @@ __global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf1
     LOAD_ACT(k0)
 #pragma unroll
     for (int r = 0; r < WD - 1; ++r) LOAD_W(a_[r], k0 + r * KU)
+    if constexpr (FUSED) {
+        // sum(x^2) of every token from the partial sums its writer left (four threads per token, fixed order)
+        if (ssq_in && threadIdx.x < MT * 64) {
+            const int tok = threadIdx.x >> 2, sl = threadIdx.x & 3;
+            const int NQ = ssq_stride(K) / 4;
+            const f32x4 *pp = reinterpret_cast<const f32x4 *>(ssq_in + (size_t)tok * (NQ * 4));
+            float t = 0.f;
+#pragma unroll 8
+            for (int i = sl; i < NQ; i += 4) { const f32x4 v = pp[i]; t += (v[0] + v[1]) + (v[2] + v[3]); }
+            t += __shfl_xor(t, 1);
+            t += __shfl_xor(t, 2);
+            if (sl == 0) rs_s[tok] = rsqrtf(t / (float)K + eps);
+        }
+    }
     STORE_ACT(0)
     __syncthreads();
     constexpr int PERIOD = WD % 2 ? 2 * WD : WD;      // rounds after which both ring positions repeat
@@ -146,6 +193,18 @@ __global__ __launch_bounds__(64 * WIDE_WAVES, 2) void gemm_wide_kernel(const bf1
 #undef LOAD_W
 #undef COMPUTE_AND_PARK
 
+    if constexpr (FUSED) {
+        // the whole reduction was this workgroup's: final sums, epilogue here
+        switch (ep.kind) {
+            case SJD_EPI_SILU: wide_fused_tail<SJD_EPI_SILU, true, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep); break;
+            case SJD_EPI_RESID: wide_fused_tail<SJD_EPI_RESID, false, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep); break;
+            default:
+                if (ssq_in) wide_fused_tail<SJD_EPI_STORE, true, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep);
+                else wide_fused_tail<SJD_EPI_STORE, false, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep);
+                break;
+        }
+        return;
+    }
     // fp32 sums of this K-slice, as whole accumulator fragments: [slice][m tile][n tile][lane]
 #pragma unroll
     for (int j = 0; j < G; ++j) {
@@ -220,7 +279,7 @@ static int enable_lds_t()
     if (lds <= 48 * 1024) return SJD_OK;
     std::lock_guard<std::mutex> lock(g_wide_mutex);
     if (g_wide_lds[MT / 2][TN][G] < lds) {
-        HIP_TRY(hipFuncSetAttribute((const void *)gemm_wide_kernel<MT, TN, G, WIDE_KU>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        HIP_TRY(hipFuncSetAttribute((const void *)gemm_wide_kernel<MT, TN, G, WIDE_KU, WIDE_WAVES, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
         g_wide_lds[MT / 2][TN][G] = lds;
     }
@@ -246,8 +305,8 @@ static int launch_wide_t(const SjdLinear *lin, const void *act, int ks, int kps,
     SJD_TRY((enable_lds_t<MT, TN, G>()));
     const int groups = lin->N / 16 / TN;
     dim3 grid((groups + WIDE_WAVES * G - 1) / (WIDE_WAVES * G), ks);
-    SJD_LAUNCH((gemm_wide_kernel<MT, TN, G, KU>), grid, dim3(64 * WIDE_WAVES), lds, s, (const bf16_t *)lin->w, act, lin->N, lin->K,
-               kps, part);
+    SJD_LAUNCH((gemm_wide_kernel<MT, TN, G, KU, WIDE_WAVES, false, false>), grid, dim3(64 * WIDE_WAVES), lds, s,
+               (const bf16_t *)lin->w, act, lin->N, lin->K, kps, part, (const float *)nullptr, 0.f, SjdGemmEpi{});
     HIP_TRY(hipGetLastError());
     return SJD_OK;
 }
@@ -288,6 +347,32 @@ void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, 
     kps = (kps + ku - 1) / ku * ku;             // whole stages
     ks = (KT + kps - 1) / kps;
     *g_out = g; *ks_out = ks; *kps_out = kps;
+}
+
+// The whole-K variant: three waves per workgroup, two-tile weight groups, activations in the 3-byte form, up to 32
+// rows, epilogue in the kernel.  Stages of 6 k-steps (12 activation tiles, four per wave).
+#define WIDE3_KU 6
+template <int MT>
+static int launch_wide3_t(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, const SjdGemmEpi &ep,
+                          hipStream_t s)
+{
+    const size_t lds = (size_t)2 * WIDE3_KU * MT * 2 * 1024;          // 24 or 48 KB
+    const int groups = lin->N / 16 / 2, KT = lin->K / 32;
+    dim3 grid((groups + 2) / 3, 1);
+    SJD_LAUNCH((gemm_wide_kernel<MT, 2, 1, WIDE3_KU, 3, true, true>), grid, dim3(192), lds, s, (const bf16_t *)lin->w, act, lin->N,
+               lin->K, KT, (f32x4 *)nullptr, ssq_in, eps, ep);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
+int sjd_launch_gemm_wide3(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,
+                          const SjdGemmEpi &ep, hipStream_t s)
+{
+    if (rows < 1 || rows > 32 || lin->tn != 2 || lin->N % 32 || lin->K % 32) return SJD_EINVAL;
+    const bool ok = ssq_in ? (ep.kind == SJD_EPI_STORE || ep.kind == SJD_EPI_SILU) : (ep.kind == SJD_EPI_STORE || ep.kind == SJD_EPI_RESID);
+    if (!ok) return SJD_EINVAL;
+    if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
+    return launch_wide3_t<2>(lin, act, ssq_in, eps, ep, s);       // (two M-tiles whatever the row count)
 }
 
 int sjd_launch_gemm_wide(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,

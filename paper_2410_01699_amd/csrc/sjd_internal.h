@@ -219,6 +219,7 @@ struct SjdLinear {
     int32_t u;        // bf16: k-steps per prefetch stage (0 = chosen at launch)
     int32_t wg, wks;  // bf16, wide kernel (more than 32 rows): weight groups per wave, K-slices (0 = chosen at launch)
     int32_t wide_from;   // bf16: rows from which the wide kernel runs (0 = above SJD_ROWS_SKINNY)
+    int32_t whole_k_rows;   // bf16: from 17 up to this many rows (at most 32) the wide kernel's whole-K variant runs (0 = never)
 };
 
 // what the bf16 GEMM does with its final fp32 values
@@ -359,6 +360,8 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const 
                          const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s);
 int sjd_launch_gemm_wide(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,
                          const SjdGemmEpi &ep, float *part, size_t part_elems, hipStream_t s);
+int sjd_launch_gemm_wide3(const SjdLinear *lin, const void *act, const float *ssq_in, float eps, int32_t rows,
+                          const SjdGemmEpi &ep, hipStream_t s);
 void sjd_wide_plan(const SjdLinear *lin, int mt, size_t part_elems, int *g_out, int *ks_out, int *kps_out);
 int sjd_gemm_wide_setup();
 int sjd_bf16_rows_to_f32(const bf16_t *src, int32_t rows, int32_t K, float *dst, hipStream_t s);

@@ -61,6 +61,11 @@ class Gpu:
                                          # bf16 weights, fp32 activations handed over in 3 bytes per value
                                          (2, 16, 4096, 11008), (2, 32, 4096, 4096), (2, 7, 48, 96), (2, 32, 1536, 4096),
                                          (2, 21, 256, 320),
+                                         # 17..32 rows of a shape whose N alone fills the chip: the wide kernel's
+                                         # whole-K variant (three waves per workgroup, epilogue in the kernel), with
+                                         # a last workgroup of one and of two weight groups, and a reduction shorter
+                                         # than one pipeline stage
+                                         (2, 32, 22016, 4096), (2, 21, 22016, 4096), (2, 25, 16384, 96),
                                          # more than 32 rows: the wide kernel (waves split N, K-slices added by a
                                          # second kernel), at the four 7B shapes + LM head, at 775M shapes, and at
                                          # ragged sizes (rows not a multiple of 16, fewer weight groups than waves)
