@@ -940,17 +940,19 @@ static int decode_one_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, hipStre
     const int32_t *ids[SJD_MAX_STREAMS] = {};
     for (int b = 0; b < B; ++b) ids[b] = kvs[b]->g_draft;
     SJD_TRY(forward_batch(m, kvs, B, ids, L, s));
+    SjdVerifyArgs vs[SJD_MAX_STREAMS];
+    memset(vs, 0, sizeof(vs));
     for (int b = 0; b < B; ++b) {
         sjd_kv *kv = kvs[b];
-        SjdVerifyArgs v;
-        memset(&v, 0, sizeof(v));
+        SjdVerifyArgs &v = vs[b];
         v.logits = kv0->logits + ((size_t)b << shift) * m->V_s; v.p_old = kv->g_p; v.draft = kv->g_draft; v.L = L;
         v.V = m->V_s; v.lo = m->cfg.samp_lo; v.smp = kv->dec_smp; v.init = kv->dec_init; v.seed = kv->dec_seed;
         v.state = kv->state; v.kv_tokens = kv->tokens; v.n_accepted = kv->g_nacc; v.new_draft = kv->g_draft;
         v.p_new = kv->g_p; v.ring = kv->ring; v.q = kv->q; v.tok_smp = kv->tok_smp; v.tok_res = kv->tok_res;
         v.acc_flag = kv->acc_flag; v.draft_snap = kv->draft_snap; v.snap = kv->snap;
-        PROF(kv0, SJD_PROF_VERIFY, 3.0 * L * m->V_s * 4, sjd_launch_verify(&v, s));
     }
+    // Steps 3-4 of all B images side by side
+    PROF(kv0, SJD_PROF_VERIFY, 3.0 * B * L * m->V_s * 4, sjd_launch_verify_batch(vs, B, s));
     return SJD_OK;
 }
 

@@ -402,6 +402,7 @@ struct SjdVerifyArgs {
     void *snap;              // 32 bytes: per-step scalars frozen for the second kernel
 };
 int sjd_launch_verify(const SjdVerifyArgs *a, hipStream_t s);
+int sjd_launch_verify_batch(const SjdVerifyArgs *a, int32_t B, hipStream_t s);   // a[B]: one per image, same L, V, init mode
 int sjd_sample_setup(int32_t V);   // raise the dynamic-LDS limit of the sampling kernels for vocabulary V
 int sjd_launch_dist(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
                     const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s);

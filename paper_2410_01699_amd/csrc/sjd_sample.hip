@@ -16,6 +16,7 @@
 // reduction order: sums that decide anything are taken in 40-bit fixed point.
 #include "sjd_internal.h"
 
+#include <cstring>
 #include <mutex>
 
 #define DIST_THREADS 1024
@@ -585,7 +586,7 @@ struct RowsArgs {
 };
 
 template <int EPT>
-__global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
+__device__ __forceinline__ void rows_body(const RowsArgs &a)
 {
     extern __shared__ uint32_t buf[];
     __shared__ DistShared sh;
@@ -671,6 +672,15 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a)
     }
 }
 
+template <int EPT>
+__global__ __launch_bounds__(DIST_THREADS) void sjd_rows_kernel(RowsArgs a) { rows_body<EPT>(a); }
+
+// The images of a batch verified side by side: blockIdx.y picks the image's arguments.
+template <class Args>
+struct ArgsBatch { Args a[SJD_MAX_STREAMS]; };
+template <int EPT>
+__global__ __launch_bounds__(DIST_THREADS) void sjd_rows_batch_kernel(ArgsBatch<RowsArgs> ab) { rows_body<EPT>(ab.a[blockIdx.y]); }
+
 struct FinalArgs {
     int32_t L, V, lo;
     sjd_init init;
@@ -688,7 +698,7 @@ struct FinalArgs {
 };
 
 #define FIN_PARTS 8     // workgroups sharing the copy of one distribution row
-__global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
+__device__ __forceinline__ void finalize_body(const FinalArgs &a)
 {
     const StepSnap sn = *a.snap;
     if (!sn.active) return;
@@ -782,6 +792,9 @@ __global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a)
     }
 }
 
+__global__ __launch_bounds__(256) void sjd_finalize_kernel(FinalArgs a) { finalize_body(a); }
+__global__ __launch_bounds__(256) void sjd_finalize_batch_kernel(ArgsBatch<FinalArgs> ab) { finalize_body(ab.a[blockIdx.z]); }
+
 // Initialisers (c) and (d) of Sec. 4.2, run after the finalize kernel (which has given every new slot
 // the uniform initialisation): a new slot that finds a recorded distribution becomes a fresh draw from
 // it and carries that row.
@@ -804,7 +817,7 @@ struct TailArgs {
 };
 
 template <int EPT>
-__global__ __launch_bounds__(DIST_THREADS) void sjd_tail_kernel(TailArgs a)
+__device__ __forceinline__ void tail_body(const TailArgs &a)
 {
     __shared__ DistShared sh;
     const StepSnap sn = *a.snap;
@@ -843,6 +856,11 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_tail_kernel(TailArgs a)
     float *dst = a.p_new + (size_t)j * V;
     for (int t = threadIdx.x; t < V; t += DIST_THREADS) dst[t] = src[t];
 }
+
+template <int EPT>
+__global__ __launch_bounds__(DIST_THREADS) void sjd_tail_kernel(TailArgs a) { tail_body<EPT>(a); }
+template <int EPT>
+__global__ __launch_bounds__(DIST_THREADS) void sjd_tail_batch_kernel(ArgsBatch<TailArgs> ab) { tail_body<EPT>(ab.a[blockIdx.y]); }
 
 template <int EPT>
 __global__ __launch_bounds__(DIST_THREADS) void sjd_dist_kernel(const float *logits, const float *logits_u, float cfg_scale,
@@ -937,7 +955,7 @@ static int ept_class(int V) { const int e = (V + DIST_THREADS - 1) / DIST_THREAD
         case 2: { constexpr int EPT = 16; STMT; } break; \
         default: { constexpr int EPT = 32; STMT; } break; \
     }
-static size_t g_lds_set[3][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+static size_t g_lds_set[4][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
 static std::mutex g_lds_mutex;      // (handles may be created from several host threads)
 static int ensure_lds(int which, int cls, size_t bytes)
 {
@@ -946,7 +964,8 @@ static int ensure_lds(int which, int cls, size_t bytes)
     if (bytes <= g_lds_set[which][cls]) return SJD_OK;
     const void *fn = nullptr;
     EPT_SWITCH(cls, fn = which == 0 ? (const void *)sjd_rows_kernel<EPT>
-                       : which == 1 ? (const void *)sjd_dist_kernel<EPT> : (const void *)sjd_first_window_kernel<EPT>)
+                       : which == 1 ? (const void *)sjd_dist_kernel<EPT>
+                       : which == 2 ? (const void *)sjd_first_window_kernel<EPT> : (const void *)sjd_rows_batch_kernel<EPT>)
     HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
     g_lds_set[which][cls] = bytes;
     return SJD_OK;
@@ -955,39 +974,70 @@ static int ensure_lds(int which, int cls, size_t bytes)
 int sjd_sample_setup(int32_t V)
 {
     const size_t lds = (size_t)V * 4;
-    for (int which = 0; which < 3; ++which) SJD_TRY(ensure_lds(which, ept_class(V), lds));
+    for (int which = 0; which < 4; ++which) SJD_TRY(ensure_lds(which, ept_class(V), lds));
     return SJD_OK;
 }
 
-int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
+static void fill_verify_args(const SjdVerifyArgs *v, RowsArgs &r, FinalArgs &f, TailArgs &t)
 {
-    if (v->V < 1 || v->V > SJD_MAX_SAMP_VOCAB || v->L < 1 || v->L > SJD_MAX_WINDOW) return SJD_EINVAL;
-    size_t lds = (size_t)v->V * 4;
-    SJD_TRY(ensure_lds(0, ept_class(v->V), lds));
-    RowsArgs r;
     r.logits = v->logits; r.logits_u = v->logits_u; r.cfg_scale = v->cfg_scale; r.q_in = v->q_in; r.p_old = v->p_old;
     r.draft = v->draft;
     r.L = v->L; r.V = v->V; r.lo = v->lo; r.smp = v->smp; r.init = v->init; r.seed = v->seed;
     r.state = v->state; r.img_pos0 = v->img_pos0; r.counter = v->counter;
     r.q = v->q; r.tok_smp = v->tok_smp; r.tok_res = v->tok_res; r.acc_flag = v->acc_flag;
     r.draft_snap = v->draft_snap; r.snap = reinterpret_cast<StepSnap *>(v->snap);
-    EPT_SWITCH(ept_class(v->V), SJD_LAUNCH(sjd_rows_kernel<EPT>, dim3(v->L), dim3(DIST_THREADS), lds, s, r))
-    HIP_TRY(hipGetLastError());
-    FinalArgs f;
     f.L = v->L; f.V = v->V; f.lo = v->lo; f.init = v->init; f.seed = v->seed; f.hist = v->hist;
     f.state = v->state; f.kv_tokens = v->kv_tokens; f.q = v->q; f.tok_smp = v->tok_smp; f.tok_res = v->tok_res;
     f.acc_flag = v->acc_flag; f.draft_snap = v->draft_snap; f.snap = reinterpret_cast<const StepSnap *>(v->snap);
     f.n_accepted = v->n_accepted; f.new_draft = v->new_draft; f.p_new = v->p_new;
-    if (v->init.mode == 4 && (!v->ring || v->init.row_stride < 1)) return SJD_EINVAL;
     f.p_old = v->p_old; f.ring = v->ring;
+    t.V = v->V; t.lo = v->lo; t.init = v->init; t.seed = v->seed; t.q = v->q; t.ring = v->ring;
+    t.acc_flag = v->acc_flag; t.snap = reinterpret_cast<const StepSnap *>(v->snap); t.new_draft = v->new_draft;
+    t.p_new = v->p_new;
+}
+
+int sjd_launch_verify(const SjdVerifyArgs *v, hipStream_t s)
+{
+    if (v->V < 1 || v->V > SJD_MAX_SAMP_VOCAB || v->L < 1 || v->L > SJD_MAX_WINDOW) return SJD_EINVAL;
+    if (v->init.mode == 4 && (!v->ring || v->init.row_stride < 1)) return SJD_EINVAL;
+    size_t lds = (size_t)v->V * 4;
+    SJD_TRY(ensure_lds(0, ept_class(v->V), lds));
+    RowsArgs r; FinalArgs f; TailArgs t;
+    fill_verify_args(v, r, f, t);
+    EPT_SWITCH(ept_class(v->V), SJD_LAUNCH(sjd_rows_kernel<EPT>, dim3(v->L), dim3(DIST_THREADS), lds, s, r))
+    HIP_TRY(hipGetLastError());
     SJD_LAUNCH(sjd_finalize_kernel, dim3(v->L, FIN_PARTS), dim3(256), 0, s, f);
     HIP_TRY(hipGetLastError());
     if (v->init.mode == 3 || v->init.mode == 4) {
-        TailArgs t;
-        t.V = v->V; t.lo = v->lo; t.init = v->init; t.seed = v->seed; t.q = v->q; t.ring = v->ring;
-        t.acc_flag = v->acc_flag; t.snap = reinterpret_cast<const StepSnap *>(v->snap); t.new_draft = v->new_draft;
-        t.p_new = v->p_new;
         EPT_SWITCH(ept_class(v->V), SJD_LAUNCH(sjd_tail_kernel<EPT>, dim3(v->L), dim3(DIST_THREADS), 0, s, t))
+        HIP_TRY(hipGetLastError());
+    }
+    return SJD_OK;
+}
+
+// Steps 3-4 of B images in the same two or three launches (the images are independent: every workgroup works on
+// one image's rows with that image's arguments).  All B share window size, vocabulary and initialiser mode.
+int sjd_launch_verify_batch(const SjdVerifyArgs *v, int32_t B, hipStream_t s)
+{
+    if (B < 1 || B > SJD_MAX_STREAMS) return SJD_EINVAL;
+    if (B == 1) return sjd_launch_verify(v, s);
+    ArgsBatch<RowsArgs> rb; ArgsBatch<FinalArgs> fb; ArgsBatch<TailArgs> tb;
+    std::memset(&rb, 0, sizeof(rb)); std::memset(&fb, 0, sizeof(fb)); std::memset(&tb, 0, sizeof(tb));
+    for (int b = 0; b < B; ++b) {
+        if (v[b].V != v[0].V || v[b].L != v[0].L || v[b].init.mode != v[0].init.mode) return SJD_EINVAL;
+        if (v[b].V < 1 || v[b].V > SJD_MAX_SAMP_VOCAB || v[b].L < 1 || v[b].L > SJD_MAX_WINDOW) return SJD_EINVAL;
+        if (v[b].init.mode == 4 && (!v[b].ring || v[b].init.row_stride < 1)) return SJD_EINVAL;
+        fill_verify_args(&v[b], rb.a[b], fb.a[b], tb.a[b]);
+    }
+    const int L = v[0].L, V = v[0].V;
+    size_t lds = (size_t)V * 4;
+    SJD_TRY(ensure_lds(3, ept_class(V), lds));
+    EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_rows_batch_kernel<EPT>, dim3(L, B), dim3(DIST_THREADS), lds, s, rb))
+    HIP_TRY(hipGetLastError());
+    SJD_LAUNCH(sjd_finalize_batch_kernel, dim3(L, FIN_PARTS, B), dim3(256), 0, s, fb);
+    HIP_TRY(hipGetLastError());
+    if (v[0].init.mode == 3 || v[0].init.mode == 4) {
+        EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_tail_batch_kernel<EPT>, dim3(L, B), dim3(DIST_THREADS), 0, s, tb))
         HIP_TRY(hipGetLastError());
     }
     return SJD_OK;
