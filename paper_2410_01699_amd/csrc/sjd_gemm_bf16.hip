@@ -387,7 +387,8 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const 
     }
     // the wide kernel's whole-K variant (shapes whose N alone fills the chip; activations in the 3-byte form)
     // (measured inside 7B iterations: 5 % of an iteration at 32 rows; at 16 rows the skinny kernel is 2 % ahead)
-    if (rows > 16 && rows <= lin->whole_k_rows && form == SJD_ACT_P3 && ep.kind != SJD_EPI_QKV)
+    if (rows > 16 && rows <= lin->whole_k_rows && form == SJD_ACT_P3 &&
+        (ep.kind == SJD_EPI_SILU || ep.kind == SJD_EPI_STORE) && (ssq_in || ep.kind == SJD_EPI_STORE))
         return sjd_launch_gemm_wide3(lin, act, ssq_in, eps, rows, ep, s);
     if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
     if (lin->tn < 1 || lin->N % (16 * lin->tn) || lin->K % 32) return SJD_EINVAL;

@@ -197,7 +197,6 @@ __global__ __launch_bounds__(64 * NW, 2) void gemm_wide_kernel(const bf16_t *__r
         // the whole reduction was this workgroup's: final sums, epilogue here
         switch (ep.kind) {
             case SJD_EPI_SILU: wide_fused_tail<SJD_EPI_SILU, true, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep); break;
-            case SJD_EPI_RESID: wide_fused_tail<SJD_EPI_RESID, false, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep); break;
             default:
                 if (ssq_in) wide_fused_tail<SJD_EPI_STORE, true, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep);
                 else wide_fused_tail<SJD_EPI_STORE, false, MT, TNE>(acc, TN, grp, groups, N, rs_s, ep);
@@ -369,9 +368,9 @@ int sjd_launch_gemm_wide3(const SjdLinear *lin, const void *act, const float *ss
                           const SjdGemmEpi &ep, hipStream_t s)
 {
     if (rows < 1 || rows > 32 || lin->tn != 2 || lin->N % 32 || lin->K % 32) return SJD_EINVAL;
-    const bool ok = ssq_in ? (ep.kind == SJD_EPI_STORE || ep.kind == SJD_EPI_SILU) : (ep.kind == SJD_EPI_STORE || ep.kind == SJD_EPI_RESID);
+    // (plain store with or without a folded RMSNorm, SiLU(gate) * up behind one: what the shapes that come here use)
+    const bool ok = ssq_in ? (ep.kind == SJD_EPI_STORE || ep.kind == SJD_EPI_SILU) : ep.kind == SJD_EPI_STORE;
     if (!ok) return SJD_EINVAL;
-    if (ep.kind == SJD_EPI_RESID && ep.out24 && (!ep.gain_next || !ep.ssq_out)) return SJD_EINVAL;
     return launch_wide3_t<2>(lin, act, ssq_in, eps, ep, s);       // (two M-tiles whatever the row count)
 }
 

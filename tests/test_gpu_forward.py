@@ -219,8 +219,9 @@ def test_forward_775m_bf16(B):
     w = synth.WORKLOADS["775m"]
     blob = synth.make_weights(w.shape, seed=0)
     ids, emb = synth.make_prompt(w)
-    toks = synth.random_tokens(32, 0, w.shape.v_s, seed=4)
-    worst = _check_forward(B, w.shape, blob, ids, [(toks[:16], 6), (toks[16:32], 16)], TOL_BF16, embeds=emb)
+    toks = synth.random_tokens(64, 0, w.shape.v_s, seed=4)
+    # (the 32-row window sends the LM head, 16384 outputs, through the wide kernel's whole-K variant)
+    worst = _check_forward(B, w.shape, blob, ids, [(toks[:16], 6), (toks[16:32], 16), (toks[32:64], 20)], TOL_BF16, embeds=emb)
     _say(f"775m bf16 worst {worst:.3e}")
 
 
