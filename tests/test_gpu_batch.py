@@ -120,6 +120,66 @@ def test_batched_forward_7b_layer_shapes(B):
             om.close()
 
 
+def test_batched_forward_and_steps_7b_full_size(B):
+    """Eight images x 16 drafts on the full 7B model (32 layers; forwards of 128 rows on the wide projection
+    kernel, Steps 3-4 of the eight images in shared launches), in the configuration `bench.py --batch 8` times:
+    the logits of three of the images against the fp64 oracle (each image on its own prompt and cache), then
+    three iterations of the captured batched loop whose verification must be bit-exact per image given the
+    GPU's own logits."""
+    w = synth.WORKLOADS["7b_32x32"]
+    shape, nb, L = w.shape, 8, 16
+    _say("7b batch: generating weights")
+    blob = synth.make_weights(shape, seed=0, threads=16)
+    m = B.sjd_init_model(B.config_from_shape(shape), blob)
+    kvs = [B.sjd_kv_create(m) for _ in range(nb)]
+    om = oracle.Model(shape, blob)
+    try:
+        V, lo = shape.v_s, shape.samp_lo
+        smp = B.sjd_sampler(w.top_k, w.temperature); init = B.sjd_init(w.init_mode, w.row_stride, w.eol_id)
+        osmp = oracle.Sampler(w.top_k, w.temperature); oinit = oracle.Init(w.init_mode, w.row_stride, w.eol_id)
+        prompts = [synth.random_tokens(12 + 7 * b, 0, lo, seed=10 + b) for b in range(nb)]
+        q = torch.empty(V, dtype=torch.float32, device="cuda")
+        N = 40
+        st = []
+        B.sjd_kv_use_graph(kvs[0], True)
+        for b in range(nb):
+            B.sjd_prefill(m, kvs[b], prompts[b], None, smp, init, q)
+            B.sjd_decode_begin(m, kvs[b], q, N, L, smp, init, 70 + b)
+            torch.cuda.synchronize()
+            d, p = oracle.first_window(q.cpu().numpy(), L, lo, oinit, 70 + b)
+            st.append({"draft": d, "p": p, "hist": [], "c": 0})
+        logits = torch.empty((nb, L, V), dtype=torch.float32, device="cuda")
+        for it in range(3):
+            toks = np.stack([s["draft"] for s in st]).astype(np.int32)
+            B.sjd_forward_logits_batch(m, kvs, _dev(toks), L, logits)
+            torch.cuda.synchronize()
+            lg = logits.cpu().numpy()
+            if it == 0:
+                for b in (0, 3, 7):
+                    _say(f"7b batch: oracle prefill + window of image {b} (fp64 on the host)")
+                    om.prefill(prompts[b])
+                    ref = om.forward_tokens(len(prompts[b]), toks[b])
+                    err = float(np.max(np.abs(lg[b] - ref)))
+                    _say(f"7b batch: image {b} worst logit error {err:.3e}")
+                    assert err < TOL_BF16, (b, err)
+            for b, s in enumerate(st):
+                s["c"] += 1
+                a, nd, pn = oracle.verify(lg[b], s["p"], s["draft"], lo, osmp, oinit, len(s["hist"]),
+                                          np.array(s["hist"], np.int32), 70 + b, s["c"])
+                s["hist"] += [int(t) for t in s["draft"][:a]]
+                s["draft"] = np.concatenate([nd, s["draft"][L:]]).astype(np.int32)
+                s["p"] = np.concatenate([pn, s["p"][L:]])
+            _say(f"7b batch: loop iteration {it + 1}")
+            B.sjd_decode_steps_batch(m, kvs, 1)
+            torch.cuda.synchronize()
+            for b, s in enumerate(st):
+                fixed, steps, done = B.sjd_decode_status(kvs[b])
+                assert fixed == len(s["hist"]) and steps == s["c"] and not done, (it, b, fixed, len(s["hist"]))
+    finally:
+        _teardown(B, m, kvs)
+        om.close()
+
+
 @pytest.mark.parametrize("nb,L,mode,use_graph", [(2, 16, 0, True), (4, 8, 1, True), (3, 5, 4, False), (8, 4, 3, True),
                                                  (8, 16, 0, True), (2, 64, 1, True), (4, 32, 4, False)])
 def test_batched_loop_bit_exact_given_gpu_logits(B, nb, L, mode, use_graph):
