@@ -74,7 +74,7 @@ def _amp(w):
     return abs(w) + abs(1.0 - w)
 
 
-@pytest.mark.parametrize("case", ["tiny_fp32", "small_bf16", "hd128_bf16", "7b_dims_bf16"])
+@pytest.mark.parametrize("case", ["tiny_fp32", "small_bf16", "hd128_bf16", "7b_dims_bf16", "7b_full_bf16"])
 def test_guided_window_logits(B, case):
     if case == "tiny_fp32":
         shape = synth.WORKLOADS["tiny"].shape
@@ -95,6 +95,14 @@ def test_guided_window_logits(B, case):
         pc = synth.random_tokens(600, 0, 2048, seed=1)
         pu = synth.random_tokens(1, 0, 2048, seed=2)
         tol, w = TOL_BF16, 7.5
+    elif case == "7b_full_bf16":
+        # the paper's guided setup at its real shape (Sec. 5.1: 7B model, guidance weight 3, window 32): two
+        # contexts x 32 rows = a 64-row forward through all 32 layers
+        shape = synth.WORKLOADS["7b_48x48"].shape
+        blob = synth.make_weights(shape, seed=0, threads=16)
+        pc = synth.random_tokens(40, 0, shape.samp_lo, seed=1)
+        pu = synth.random_tokens(9, 0, shape.samp_lo, seed=2)
+        tol, w = TOL_BF16, 3.0
     else:
         shape = synth.ModelShape(2, 4096, 32, 11008, 65536, 57344, 65536, 200, synth.DTYPE_BF16)
         blob = synth.make_weights(shape, seed=0, threads=16)
@@ -115,6 +123,8 @@ def test_guided_window_logits(B, case):
         if shape.dtype == synth.DTYPE_BF16:
             # two contexts of 32, 17 and 64 rows: the wide projection kernel, attention in groups of 32 queries
             windows += [(0, 32, 3), (32, 49, 17), (0, 64, 1)]
+        if case == "7b_full_bf16":
+            windows = [(0, 32, 3), (32, 48, 5)]          # (two fp64 oracles of 32 layers: keep it to two windows)
         for lo_, hi_, keep in windows:
             t = toks[lo_:hi_]
             _say(f"  window at image position {n_img} L={len(t)}")
