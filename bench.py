@@ -167,6 +167,12 @@ def main():
         for M_ in [int(x) for x in args.gemm_sweep.split(",")]:
             for name, (N_, K_, tn_) in shapes.items():
                 res = {"model's choice": B.sjd_gemm_bench(M_, N_, K_, tn_, 0, 0, -40)}
+                # plain reads of the same weight bytes: by as many workgroups as the skinny kernel launches, each a
+                # contiguous share (the kernel's own pattern), and the fastest plain read found (many workgroups
+                # sweeping the bytes together)
+                floor_us = B.sjd_gemm_bench(M_, N_, K_, 0, max(128, N_ // 16 // tn_), 0, -40)
+                sweep_wgs = 1024 if N_ * K_ * 2 >= 1024 * 16384 * 4 else 256
+                floor_best_us = B.sjd_gemm_bench(M_, N_, K_, 0, sweep_wgs, 1, -40)
                 if M_ <= 32:
                     for wk_ in (4, 8):
                         for u_ in (2, 4):
@@ -182,7 +188,7 @@ def main():
                         except B.SjdError:
                             pass
                 best = sorted(res.items(), key=lambda kv: kv[1])
-                rows_out.append({"M": M_, "shape": name, "N": N_, "K": K_, "weight_MB": N_ * K_ * 2 / 1e6,
+                rows_out.append({"M": M_, "shape": name, "N": N_, "K": K_, "weight_MB": N_ * K_ * 2 / 1e6, "plain_read_us": round(floor_us, 2), "plain_read_sweep_us": round(floor_best_us, 2),
                                  "us": {k: round(v, 2) for k, v in best},
                                  "best": best[0][0], "best_TBps": N_ * K_ * 2 / best[0][1] / 1e6})
                 log(f"M={M_} {name}: " + "  ".join(f"{k}: {v:.1f}us" for k, v in best[:5]))

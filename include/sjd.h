@@ -290,6 +290,10 @@ int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_t M, int32_
  * chunks of SJD_MAX_ROWS, one launch pair each over the same weights.
  * A negative `iters` times |iters| launches that rotate through more than 1 GiB of weight copies,
  * so that no launch finds its weights in the last-level cache (the situation inside a step).
+ * tn = 0 measures the floor instead of the projection: a kernel that only reads the same N x K x 2 bytes
+ * (wk workgroups of 256 threads, 0 = 256, four 16-byte loads per lane in flight; u = 0: every workgroup a
+ * contiguous share, as the projection kernels read their packed weights; u = 1: all workgroups sweep the bytes
+ * together, 4 KiB per wave and round).
  * SJD_EINVAL for an unsupported combination.                                                     */
 int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32_t wk, int32_t u, int32_t iters,
                    float *us_per_launch);

@@ -1413,13 +1413,78 @@ extern "C" int sjd_gemm_test(int32_t dtype, const void *A, const void *W, int32_
     return SJD_OK;
 }
 
+// The floor for a kernel that has to read `bytes` of weights: a plain streaming read of them (workgroup b takes
+// a contiguous share, its four waves a quarter each, four 16-byte loads per lane in flight), nothing else.
+typedef __attribute__((ext_vector_type(4))) float stream_f32x4;
+__global__ __launch_bounds__(256) void stream_read_kernel(const stream_f32x4 *__restrict__ p, size_t per16, float *out,
+                                                          int interleaved)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t q = per16 / 4;                       // 16-byte units per wave (a multiple of 64)
+    const stream_f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    stream_f32x4 acc = zero;
+    if (interleaved) {
+        // all workgroups sweep the buffer together: round r, workgroup b, wave w reads the 4 KiB chunk (r * grid + b) * 4 + w
+        const size_t rounds = q / 256;
+        for (size_t r = 0; r < rounds; ++r) {
+            const stream_f32x4 *src = p + (((r * gridDim.x + blockIdx.x) * 4 + wave) * 256) + lane;
+            const stream_f32x4 a = __builtin_nontemporal_load(src), b = __builtin_nontemporal_load(src + 64);
+            const stream_f32x4 c = __builtin_nontemporal_load(src + 128), d = __builtin_nontemporal_load(src + 192);
+            acc += (a + b) + (c + d);
+        }
+    } else {
+        const stream_f32x4 *src = p + (size_t)blockIdx.x * per16 + (size_t)wave * q + lane;
+        for (size_t i = 0; i + 64 <= q; i += 256) {
+            const stream_f32x4 a = __builtin_nontemporal_load(src + i);
+            const stream_f32x4 b = i + 128 <= q ? __builtin_nontemporal_load(src + i + 64) : zero;
+            const stream_f32x4 c = i + 192 <= q ? __builtin_nontemporal_load(src + i + 128) : zero;
+            const stream_f32x4 d = i + 256 <= q ? __builtin_nontemporal_load(src + i + 192) : zero;
+            acc += (a + b) + (c + d);
+        }
+    }
+    if ((acc[0] + acc[1]) + (acc[2] + acc[3]) == 1.2345e30f) out[blockIdx.x] = acc[0];      // (keeps the loads; never true on zeros)
+}
+
+static int stream_floor_bench(size_t bytes, int32_t wgs, int32_t interleaved, int32_t iters, float *us_per_launch)
+{
+    const bool cold = iters < 0;
+    if (cold) iters = -iters;
+    if (wgs <= 0) wgs = 256;
+    if (wgs > 65536 || bytes < (size_t)wgs * 16384) return SJD_EINVAL;
+    const size_t per16 = bytes / wgs / 16 / 1024 * 1024;            // 16-byte units per workgroup, a multiple of 4 waves x 4 KiB
+    const size_t used = per16 * 16 * wgs;
+    const int copies = cold ? (int)((((size_t)1 << 30) + used - 1) / used) + 1 : 1;
+    GemmScratch g;
+    SJD_TRY(dev_alloc(&g.Wp, used * copies));
+    SJD_TRY(dev_alloc((void **)&g.out, (size_t)wgs * 4));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); sjd_set_hip_error(e, "hipEventCreate"); return SJD_EHIP; }
+    for (int i = 0; i < 3; ++i)
+        SJD_LAUNCH(stream_read_kernel, dim3(wgs), dim3(256), 0, 0, (const stream_f32x4 *)g.Wp, per16, g.out, interleaved);
+    (void)hipEventRecord(e0, 0);
+    for (int i = 0; i < iters; ++i)
+        SJD_LAUNCH(stream_read_kernel, dim3(wgs), dim3(256), 0, 0,
+                   (const stream_f32x4 *)((const char *)g.Wp + (size_t)(i % copies) * used), per16, g.out, interleaved);
+    (void)hipEventRecord(e1, 0);
+    (void)hipEventSynchronize(e1);
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    *us_per_launch = ms * 1e3f / iters;
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
 extern "C" int sjd_gemm_bench(int32_t M, int32_t N, int32_t K, int32_t tn, int32_t wk, int32_t u, int32_t iters,
                               float *us_per_launch)
 {
+    if (M < 1 || N < 16 || K < 32 || N % 16 || K % 32 || iters == 0 || !us_per_launch) return SJD_EINVAL;
+    // tn = 0: no product, the plain streaming read of the same weight bytes by wk workgroups
+    if (tn == 0) return stream_floor_bench((size_t)N * K * 2, wk, u, iters, us_per_launch);
     // iters < 0: rotate through enough weight copies that none is still in the last-level cache
     const bool cold = iters < 0;
     if (cold) iters = -iters;
-    if (M < 1 || N < 16 || K < 32 || N % 16 || K % 32 || iters < 1 || !us_per_launch) return SJD_EINVAL;
     if (tn < 1 || tn > 3 || N % (16 * tn)) return SJD_EINVAL;
     // More rows than one forward computes: an off-path measurement of the wide kernel's matrix-core rate.  The
     // rows are cut into chunks of SJD_ROWS_MAX, each a launch pair of its own over the same weights (which
