@@ -1,23 +1,28 @@
 // bf16 projections of a window forward with MORE than 32 rows (paper Sec. 4.1 Step 2 for windows of 64
 // tokens, for guided windows of 32 -- two contexts -- and for batches of images that share one pass
-// over the weights): C[M x N] = A[M x K] * W^T, M = 33 .. 128.
+// over the weights): C[M x N] = A[M x K] * W^T, M = 33 .. 128; also the down projection from 17 rows on and,
+// in a whole-K variant, the gate/up projection at 17 .. 32 rows.
 //
 // With this many rows a workgroup can no longer afford a private copy of the activations per wave (M
 // rows cost M * 96 bytes of activations per KiB of weights), so the roles inside a workgroup change
 // with respect to the skinny kernel:
-//  - the four waves of a workgroup split N: each streams its own packed weight groups (the same
-//    layout the skinny kernel reads: every weight byte still leaves HBM once and goes straight into
-//    the registers of the one wave that uses it);
-//  - all four walk the SAME k-steps, and the activation tiles of a k-step (hi plane as stored, second
-//    operand rebuilt once from the byte plane) are staged in LDS by the workgroup and read from there
-//    by every wave: L2 -> CU activation traffic drops by the number of waves.  The producers of a wide
-//    forward's activations write the second operand ready made (2-byte lo plane), so staging is a copy;
+//  - the waves of a workgroup (four; three in the whole-K variant) split N: each streams its own packed
+//    weight groups (the same layout the skinny kernel reads: every weight byte still leaves HBM once and
+//    goes straight into the registers of the one wave that uses it);
+//  - all of them walk the SAME k-steps, and the activation tiles of a stage of k-steps are staged in LDS by
+//    the workgroup and read from there by every wave: L2 -> CU activation traffic drops by the number of
+//    waves.  The producers of a wide forward's activations write the second operand ready made (2-byte lo
+//    plane), so staging is a copy; the whole-K variant reads the 3-byte form and rebuilds the second operand
+//    once per workgroup while it parks a tile;
 //  - K is split across workgroups (grid.y) wherever N alone gives too few of them; every workgroup
 //    writes its fp32 sums as whole accumulator fragments, and a second kernel adds the K-slices in
 //    slice order (deterministic), applies the token factors of a folded RMSNorm and runs the same
-//    epilogues as the skinny kernel (residual, SiLU * up, RoPE + cache write, plain store).
+//    epilogues as the skinny kernel (residual, SiLU * up, RoPE + cache write, plain store).  (Adding the
+//    slices in the last workgroup to arrive instead was measured 3x slower: the device-scope fences around
+//    its arrival counter write back and invalidate the L2 of the XCD.)
 // At M = 128 the two MFMAs per weight tile and M-tile price the matrix cores at about 9.8 TB/s of
-// weights, so the kernel is still bound by HBM, at roughly half of the bf16 MFMA peak: the one regime
+// weights; measured, the kernel runs at about a third of the bf16 MFMA peak there, bound by what a CU pulls
+// through its L1 (2 bytes of activations per byte of weights at four waves per workgroup): the one regime
 // of this path where matrix-core utilisation is a meaningful number.
 #include "sjd_gemm_epi.h"
 
