@@ -197,7 +197,7 @@ def main():
     if args.verify_scaled:
         # Step 3's distribution kernel on many independent rows at once.  Algorithmic bytes: one fp32 logits row in,
         # one fp32 probability row out.  Timed with events on the stream the launches go to (torch's current = default).
-        out = {"kernel": "sjd_dist_kernel (top-K select + softmax, one 1024-thread workgroup per row)", "peak_GBps": HBM_PEAK_GBS,
+        out = {"kernel": "sjd_dist_kernel (top-K select + softmax, one workgroup per row: 256 threads for V_s <= 8192 and 512 up to 16384 at this row count)", "peak_GBps": HBM_PEAK_GBS,
                "shapes": []}
         for V, K in ((8192, 2000), (16384, 2000), (8192, 8192)):
             rows = 4096

@@ -164,20 +164,23 @@ __device__ __forceinline__ int wave_min_i32(int v)
     return min(min(r0, r1), min(r2, r3));
 }
 
-struct DistShared {
-    uint64_t wave_tot[DIST_WAVES];
-    uint64_t wave_tot2[DIST_WAVES];  // second draw of block_sample2
+template <int NWV>                   // NWV = waves per workgroup
+struct DistSharedT {
+    uint64_t wave_tot[NWV];
+    uint64_t wave_tot2[NWV];         // second draw of block_sample2
     int result2;
-    uint32_t wave_u32[DIST_WAVES];
+    uint32_t wave_u32[NWV];
     int hist[256];
-    int whist[DIST_WAVES][256];   // per-wave digit counts (keeps same-bin LDS atomics inside one wave)
+    int whist[NWV][256];          // per-wave digit counts (keeps same-bin LDS atomics inside one wave)
     uint32_t sel_prefix[2];       // result of a radix pass, double-buffered by pass parity
     int sel_rank[2];
-    int top4[DIST_WAVES][2];      // per-wave counts of the four highest top bytes (two 16-bit fields each)
+    int top4[NWV][2];             // per-wave counts of the four highest top bytes (two 16-bit fields each)
     int ncand;                    // keys sharing the 16 resolved bits, and the low halves of the first 64
     uint32_t cand[64];
     int result;
 };
+typedef DistSharedT<DIST_WAVES> DistShared;
+
 
 // Categorical draw from non-negative weights by inverse CDF over 40-bit fixed-point values taken
 // in index order: tau = floor(k32 * C / 2^32), result = first index whose inclusive prefix sum
@@ -298,14 +301,17 @@ __device__ void block_sample2(W1 w1, W2 w2, int V, uint32_t k1, uint32_t k2, Dis
 // logit-space form is used): z = z_u + w * (z_c - z_u), three separately rounded fp32 operations.
 __device__ __forceinline__ float guide(float zc, float zu, float w) { return __fadd_rn(zu, __fmul_rn(w, __fsub_rn(zc, zu))); }
 
-template <int EPT>
+// NT threads per workgroup: 1024 for the rows of a decoding iteration (shortest time per row); fewer where
+// many independent rows run at once (more rows per CU in flight).  Results do not depend on NT: every sum that
+// decides anything is an integer.
+template <int EPT, int NT = DIST_THREADS>
 __device__ void block_dist(const float *__restrict__ z, const float *__restrict__ z_u, float cfg_scale, int V, int top_k,
-                           float T, int forced, uint32_t *buf, DistShared *sh)
+                           float T, int forced, uint32_t *buf, DistSharedT<NT / 64> *sh)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float *qb = reinterpret_cast<float *>(buf);
     if (forced >= 0) {
-        for (int t = tid; t < V; t += DIST_THREADS) qb[t] = (t == forced) ? 1.0f : 0.0f;
+        for (int t = tid; t < V; t += NT) qb[t] = (t == forced) ? 1.0f : 0.0f;
         __syncthreads();
         return;
     }
@@ -314,25 +320,25 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
     float zr[EPT];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        const int t = tid + j * DIST_THREADS;
+        const int t = tid + j * NT;
         zr[j] = t < V ? z[t] : 0.0f;
     }
     if (z_u) {
         float zu[EPT];
 #pragma unroll
         for (int j = 0; j < EPT; ++j) {
-            const int t = tid + j * DIST_THREADS;
+            const int t = tid + j * NT;
             zu[j] = t < V ? z_u[t] : 0.0f;
         }
 #pragma unroll
         for (int j = 0; j < EPT; ++j) zr[j] = guide(zr[j], zu[j], cfg_scale);
     }
-    // every thread keeps the keys of its own elements (t = tid + j * DIST_THREADS) in registers; the
+    // every thread keeps the keys of its own elements (t = tid + j * NT) in registers; the
     // copy in LDS serves the steps that walk the row in a different order
     uint32_t kr[EPT];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        const int t = tid + j * DIST_THREADS;
+        const int t = tid + j * NT;
         kr[j] = 0;
         if (t < V) {
             uint32_t k = order_key(zr[j]);
@@ -346,20 +352,20 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
     if (tid == 0) sh->ncand = 0;
     __syncthreads();
     kmax = 0;
-    for (int w = 0; w < DIST_WAVES; ++w) kmax = sh->wave_u32[w] > kmax ? sh->wave_u32[w] : kmax;
+    for (int w = 0; w < (NT / 64); ++w) kmax = sh->wave_u32[w] > kmax ? sh->wave_u32[w] : kmax;
 
     if (top_k == 1 || T == 0.0f) {
         // lowest index holding the maximum
         int best = 0x7FFFFFFF;
-        for (int t = tid; t < V; t += DIST_THREADS) if (buf[t] == kmax) best = min(best, t);
+        for (int t = tid; t < V; t += NT) if (buf[t] == kmax) best = min(best, t);
         best = wave_min_i32(best);
         __syncthreads();
         if (lane == 0) sh->hist[wave] = best;
         __syncthreads();
         best = 0x7FFFFFFF;
-        for (int w = 0; w < DIST_WAVES; ++w) best = min(best, sh->hist[w]);
+        for (int w = 0; w < (NT / 64); ++w) best = min(best, sh->hist[w]);
         __syncthreads();
-        for (int t = tid; t < V; t += DIST_THREADS) qb[t] = (t == best) ? 1.0f : 0.0f;
+        for (int t = tid; t < V; t += NT) qb[t] = (t == best) ? 1.0f : 0.0f;
         __syncthreads();
         return;
     }
@@ -381,7 +387,7 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
             uint32_t cnt = 0;
 #pragma unroll
             for (int j = 0; j < EPT; ++j) {
-                const int t = tid + j * DIST_THREADS;
+                const int t = tid + j * NT;
                 if (t < V) {
                     const uint32_t diff = dmax - (kr[j] >> 24);
                     if (diff < 4u) cnt += 1u << (8 * diff);
@@ -394,7 +400,7 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
             if (lane == 0) { sh->top4[wave][0] = lo; sh->top4[wave][1] = hi; }
             __syncthreads();
             lo = 0; hi = 0;
-            for (int w = 0; w < DIST_WAVES; ++w) { lo += sh->top4[w][0]; hi += sh->top4[w][1]; }
+            for (int w = 0; w < (NT / 64); ++w) { lo += sh->top4[w][0]; hi += sh->top4[w][1]; }
             const int c0 = lo & 0xFFFF, c1 = (lo >> 16) & 0xFFFF, c2 = hi & 0xFFFF, c3 = (hi >> 16) & 0xFFFF;
             int digit = -1, before = 0;
             if (rank <= c0) { digit = (int)dmax; }
@@ -416,7 +422,7 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
 #pragma unroll
                 for (int j = 0; j < EPT; ++j) {
                     const uint32_t k = kr[j];
-                    if (tid + j * DIST_THREADS < V && (k & mask) == prefix) {
+                    if (tid + j * NT < V && (k & mask) == prefix) {
                         const int pos = atomicAdd(&sh->ncand, 1);
                         if (pos < 64) sh->cand[pos] = k & 0xFFFFu;
                     }
@@ -450,13 +456,13 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
 #pragma unroll
             for (int j = 0; j < EPT; ++j) {
                 const uint32_t k = kr[j];
-                if (tid + j * DIST_THREADS < V && (k & mask) == prefix) atomicAdd(&sh->whist[wave][(k >> shift) & 255u], 1);
+                if (tid + j * NT < V && (k & mask) == prefix) atomicAdd(&sh->whist[wave][(k >> shift) & 255u], 1);
             }
             __syncthreads();
             if (tid < 256) {
                 int c = 0;
 #pragma unroll
-                for (int w = 0; w < DIST_WAVES; ++w) c += sh->whist[w][tid];
+                for (int w = 0; w < (NT / 64); ++w) c += sh->whist[w][tid];
                 sh->hist[tid] = c;
             }
             __syncthreads();
@@ -487,19 +493,19 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
         // entries equal to kth: do they all fit?
         int eq = 0;
 #pragma unroll
-        for (int j = 0; j < EPT; ++j) eq += (tid + j * DIST_THREADS < V) && kr[j] == kth;
+        for (int j = 0; j < EPT; ++j) eq += (tid + j * NT < V) && kr[j] == kth;
         eq = wave_sum_i32(eq);
         if (lane == 0) sh->hist[wave] = eq;
         __syncthreads();
         eq = 0;
-        for (int w = 0; w < DIST_WAVES; ++w) eq += sh->hist[w];
+        for (int w = 0; w < (NT / 64); ++w) eq += sh->hist[w];
         __syncthreads();
         if (eq > room) {
             // ties cut the K-th value: keep the `room` lowest indices.  Wave w scans its contiguous
             // index range; a tie that loses gets its key lowered to kth - 1 so that the test
             // `key >= kth` below drops it (kth == 0 only arises from NaN logits, which are
             // outside the contract).
-            const int span = ((V + DIST_WAVES * 64 - 1) / (DIST_WAVES * 64)) * 64;
+            const int span = ((V + (NT / 64) * 64 - 1) / ((NT / 64) * 64)) * 64;
             const int beg = wave * span, end = min(V, beg + span);
             int cnt = 0;
             for (int t = beg + lane; t < end; t += 64) cnt += buf[t] == kth;
@@ -519,7 +525,7 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
             __syncthreads();
 #pragma unroll
             for (int j = 0; j < EPT; ++j) {           // the keys of lost ties changed: take them again
-                const int t = tid + j * DIST_THREADS;
+                const int t = tid + j * NT;
                 if (t < V) kr[j] = buf[t];
             }
         }
@@ -532,7 +538,7 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const uint32_t k = kr[j];
-        const bool keep = tid + j * DIST_THREADS < V && (!cut || k >= kth);
+        const bool keep = tid + j * NT < V && (!cut || k >= kth);
         float e = 0.0f;
         if (keep) {
             float x = __fdiv_rn(__fsub_rn(key_to_float(k), m), T);   // the key still holds the logit's bits
@@ -545,11 +551,11 @@ __device__ void block_dist(const float *__restrict__ z, const float *__restrict_
     if (lane == 0) sh->wave_tot[wave] = csum;
     __syncthreads();
     uint64_t C = 0;
-    for (int w = 0; w < DIST_WAVES; ++w) C += sh->wave_tot[w];
+    for (int w = 0; w < (NT / 64); ++w) C += sh->wave_tot[w];
     const float Z = __fmul_rn(__ull2float_rn(C), 0x1p-40f);
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        const int t = tid + j * DIST_THREADS;
+        const int t = tid + j * NT;
         if (t < V) qb[t] = (er[j] != 0.0f) ? __fdiv_rn(er[j], Z) : 0.0f;     // (over the keys: same storage)
     }
     __syncthreads();
@@ -862,17 +868,17 @@ __global__ __launch_bounds__(DIST_THREADS) void sjd_tail_kernel(TailArgs a) { ta
 template <int EPT>
 __global__ __launch_bounds__(DIST_THREADS) void sjd_tail_batch_kernel(ArgsBatch<TailArgs> ab) { tail_body<EPT>(ab.a[blockIdx.y]); }
 
-template <int EPT>
-__global__ __launch_bounds__(DIST_THREADS) void sjd_dist_kernel(const float *logits, const float *logits_u, float cfg_scale,
-                                                                int V, sjd_sampler smp, const int32_t *forced, float *q)
+template <int EPT, int NT = DIST_THREADS>
+__global__ __launch_bounds__(NT) void sjd_dist_kernel(const float *logits, const float *logits_u, float cfg_scale,
+                                                      int V, sjd_sampler smp, const int32_t *forced, float *q)
 {
     extern __shared__ uint32_t buf[];
-    __shared__ DistShared sh;
+    __shared__ DistSharedT<NT / 64> sh;
     const int row = blockIdx.x;
-    block_dist<EPT>(logits + (size_t)row * V, logits_u ? logits_u + (size_t)row * V : nullptr, cfg_scale, V, smp.top_k,
-                    smp.temperature, forced ? forced[row] : -1, buf, &sh);
+    block_dist<EPT, NT>(logits + (size_t)row * V, logits_u ? logits_u + (size_t)row * V : nullptr, cfg_scale, V, smp.top_k,
+                        smp.temperature, forced ? forced[row] : -1, buf, &sh);
     const float *qb = reinterpret_cast<const float *>(buf);
-    for (int t = threadIdx.x; t < V; t += DIST_THREADS) q[(size_t)row * V + t] = qb[t];
+    for (int t = threadIdx.x; t < V; t += NT) q[(size_t)row * V + t] = qb[t];
 }
 
 // First window (step counter 0): slot 0 ~ q_first, slots 1..L-1 by the init strategy.
@@ -1043,10 +1049,34 @@ int sjd_launch_verify_batch(const SjdVerifyArgs *v, int32_t B, hipStream_t s)
     return SJD_OK;
 }
 
+// Many independent rows in one launch (far more than the chip has CUs): workgroups of 256 or 512 threads with 32
+// values per thread, so that a CU has four or two rows in flight instead of one; same results bit for bit.
+#define DIST_MANY_ROWS 512
+template <int NT>
+static int launch_dist_many(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
+                            const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s)
+{
+    static std::mutex mu;
+    static size_t lds_set = 0;
+    const size_t lds = (size_t)V * 4;
+    if (lds > 48 * 1024) {
+        std::lock_guard<std::mutex> lock(mu);
+        if (lds > lds_set) {
+            HIP_TRY(hipFuncSetAttribute((const void *)sjd_dist_kernel<32, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            lds_set = lds;
+        }
+    }
+    SJD_LAUNCH((sjd_dist_kernel<32, NT>), dim3(rows), dim3(NT), lds, s, logits, logits_u, cfg_scale, V, *smp, forced, q);
+    HIP_TRY(hipGetLastError());
+    return SJD_OK;
+}
+
 int sjd_launch_dist(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
                     const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s)
 {
     if (V < 1 || V > SJD_MAX_SAMP_VOCAB || rows < 1) return SJD_EINVAL;
+    if (rows >= DIST_MANY_ROWS && V <= 256 * 32) return launch_dist_many<256>(logits, logits_u, cfg_scale, rows, V, smp, forced, q, s);
+    if (rows >= DIST_MANY_ROWS && V <= 512 * 32) return launch_dist_many<512>(logits, logits_u, cfg_scale, rows, V, smp, forced, q, s);
     size_t lds = (size_t)V * 4;
     SJD_TRY(ensure_lds(1, ept_class(V), lds));
     EPT_SWITCH(ept_class(V), SJD_LAUNCH(sjd_dist_kernel<EPT>, dim3(rows), dim3(DIST_THREADS), lds, s, logits, logits_u, cfg_scale, V, *smp, forced, q))

@@ -51,6 +51,27 @@ def test_dist_bit_exact(B, V, K, T):
         assert np.array_equal(got[r].view(np.uint32), want.view(np.uint32)), (r, np.abs(got[r] - want).max())
 
 
+@pytest.mark.parametrize("V,K,T", [(8192, 2000, 1.0), (16384, 2000, 1.0), (3000, 429, 0.8), (8192, 8192, 1.0), (5000, 1, 1.0),
+                                   (12000, 300, 0.0), (20000, 2000, 1.0), (64, 10, 1.0)])
+def test_dist_many_rows_bit_exact(B, V, K, T):
+    """hundreds of independent rows in one launch take the 256- or 512-thread variant of the distribution kernel
+    (several rows per CU in flight; vocabularies above 16384 stay on the 1024-thread one): every row must come out
+    bit for bit as the oracle's, ties at the K-th value, all-equal rows and forced rows included"""
+    _say(f"dist, 700 rows: V={V} K={K} T={T}")
+    rows = 700
+    z = synth.random_logits(rows, V, seed=V + K + 1)
+    z[0, ::7] = 0.25                      # many equal values around the K-th
+    z[1] = 0.0                            # everything ties
+    z[2, 10:40] = z[2].max() + 1          # ties at the top
+    z[3] = np.round(z[3] * 4) / 4         # coarse grid: ties everywhere
+    forced = np.full(rows, -1, np.int32)
+    forced[5] = V - 1; forced[699] = 0
+    got = _gpu_dist(B, z, K, T, forced=forced)
+    for r in range(rows):
+        want = oracle.dist(z[r], K, T, forced=int(forced[r]))
+        assert np.array_equal(got[r].view(np.uint32), want.view(np.uint32)), (r, np.abs(got[r] - want).max())
+
+
 def test_dist_ties_and_forced(B):
     _say("dist ties/forced")
     V = 3000
