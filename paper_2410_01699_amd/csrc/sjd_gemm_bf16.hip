@@ -398,7 +398,9 @@ int sjd_launch_gemm_bf16(const SjdLinear *lin, const void *act, int form, const 
     // of which can run its epilogue while another streams) measured 2-8 % faster inside a 7B iteration
     // than eight where a workgroup holds at most three accumulator fragments; eight with four or more.
     int wk = lin->wk;
-    if (wk == 0) wk = mt * tn <= 3 ? 4 : 8;
+    // (four fragments over a short reduction -- eight waves would walk fewer than 16 k-steps each -- also run
+    // better on four waves: 12-21 % on the 775M shapes at 32 rows)
+    if (wk == 0) wk = (mt * tn <= 3 || (mt * tn == 4 && lin->K / 32 / 8 < 16)) ? 4 : 8;
     if (wk != 8 && wk != 4) return SJD_EINVAL;
     // k-steps per prefetch stage: 0 = automatic.  Four instead of two: 1 % of a 7B iteration and 1.4 % of a
     // 775M one, for 16 rows and four waves that each walk at least 32 k-steps (alone on cold weights
