@@ -977,10 +977,12 @@ static int ensure_lds(int which, int cls, size_t bytes)
     return SJD_OK;
 }
 
+template <int NT> static int ensure_lds_many(size_t lds);
 int sjd_sample_setup(int32_t V)
 {
     const size_t lds = (size_t)V * 4;
     for (int which = 0; which < 4; ++which) SJD_TRY(ensure_lds(which, ept_class(V), lds));
+    if (V > 256 * 32 && V <= 512 * 32) SJD_TRY(ensure_lds_many<512>(lds));      // (the many-rows variant of sjd_dist)
     return SJD_OK;
 }
 
@@ -1053,19 +1055,25 @@ int sjd_launch_verify_batch(const SjdVerifyArgs *v, int32_t B, hipStream_t s)
 // values per thread, so that a CU has four or two rows in flight instead of one; same results bit for bit.
 #define DIST_MANY_ROWS 512
 template <int NT>
-static int launch_dist_many(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
-                            const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s)
+static int ensure_lds_many(size_t lds)
 {
     static std::mutex mu;
     static size_t lds_set = 0;
-    const size_t lds = (size_t)V * 4;
-    if (lds > 48 * 1024) {
-        std::lock_guard<std::mutex> lock(mu);
-        if (lds > lds_set) {
-            HIP_TRY(hipFuncSetAttribute((const void *)sjd_dist_kernel<32, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            lds_set = lds;
-        }
+    if (lds <= 48 * 1024) return SJD_OK;
+    std::lock_guard<std::mutex> lock(mu);
+    if (lds > lds_set) {
+        HIP_TRY(hipFuncSetAttribute((const void *)sjd_dist_kernel<32, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        lds_set = lds;
     }
+    return SJD_OK;
+}
+
+template <int NT>
+static int launch_dist_many(const float *logits, const float *logits_u, float cfg_scale, int32_t rows, int32_t V,
+                            const sjd_sampler *smp, const int32_t *forced, float *q, hipStream_t s)
+{
+    const size_t lds = (size_t)V * 4;
+    SJD_TRY(ensure_lds_many<NT>(lds));
     SJD_LAUNCH((sjd_dist_kernel<32, NT>), dim3(rows), dim3(NT), lds, s, logits, logits_u, cfg_scale, V, *smp, forced, q);
     HIP_TRY(hipGetLastError());
     return SJD_OK;
