@@ -2,8 +2,8 @@
 z = z_u + w (z_c - z_u)  (Sec. 5.1 gives the weight; logit-space guidance is the assumed mechanism).
 
 The oracle side is two independent transformer oracles (one per context) whose logits are combined by
-oracle.guide.  Bars as elsewhere, with the logit tolerance scaled by |w| + |1 - w| (the factor by which
-the combination amplifies the error of each forward).
+oracle.guide.  Bars as elsewhere: the guided logits themselves stay within 1e-4 (fp32 models) / 2e-2 (bf16
+models) of the oracle's, although the combination amplifies the error of each forward by up to |w| + |1 - w|.
 """
 import sys
 
@@ -70,10 +70,6 @@ class Pair:
         return oracle.guide(zc, zu, self.w)
 
 
-def _amp(w):
-    return abs(w) + abs(1.0 - w)
-
-
 @pytest.mark.parametrize("case", ["tiny_fp32", "small_bf16", "hd128_bf16", "7b_dims_bf16", "7b_full_bf16"])
 def test_guided_window_logits(B, case):
     if case == "tiny_fp32":
@@ -132,10 +128,10 @@ def test_guided_window_logits(B, case):
             ref = p.ref_logits(n_img, t)
             err = float(np.max(np.abs(got - ref)))
             worst = max(worst, err)
-            assert err < tol * _amp(w), (n_img, err)
+            assert err < tol, (n_img, err)
             n_img += keep
             B.sjd_kv_set_len(p.kv, p.Pc + n_img)       # moves both caches
-        _say(f"  worst guided-logit error {worst:.3e} (bar {tol * _amp(w):.1e})")
+        _say(f"  worst guided-logit error {worst:.3e} (bar {tol:.1e})")
     finally:
         p.close()
 
@@ -159,7 +155,7 @@ def test_guided_logits_with_embedding_row_prompts(B):
             got = p.gpu_logits(toks[lo_:hi_])
             ref = p.ref_logits(n_img, toks[lo_:hi_])
             err = float(np.max(np.abs(got - ref)))
-            assert err < TOL_BF16 * _amp(w), (n_img, err)
+            assert err < TOL_BF16, (n_img, err)
             n_img += keep
             B.sjd_kv_set_len(p.kv, p.Pc + n_img)
     finally:
@@ -228,7 +224,7 @@ def test_cfg_step_bit_exact_given_gpu_logits(B, L):
             d_h, p_h = draft.cpu().numpy(), p_old.cpu().numpy()
             logits = p.gpu_logits(d_h)                          # guided logits of the same forward
             err = float(np.max(np.abs(logits - p.ref_logits(len(hist), d_h))))
-            assert err < TOL_BF16 * _amp(w), (c, err)
+            assert err < TOL_BF16, (c, err)
             want = oracle.verify(logits, p_h, d_h, lo, osmp, oinit, len(hist), np.array(hist, np.int32), 42, c)
             B.sjd_step(p.m, p.kv, draft, p_old, L, smp, init, len(hist), 42, c, na, nd, pn)
             torch.cuda.synchronize()
