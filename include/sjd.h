@@ -18,6 +18,9 @@
  *  - Probabilities and logits are fp32 rows over the SAMPLING vocabulary: column t stands for
  *    token id samp_lo + t, V_s = samp_hi - samp_lo columns per row.
  *  - All decisions are deterministic functions of the inputs: identical calls give identical bits.
+ *  - Threads: a model is read-only once built; a cache handle (sjd_kv) is used by one host thread at a
+ *    time.  Different handles of one model may be driven from different host threads on different streams
+ *    at the same time (the handles of one batched call belong to that call).
  */
 #ifndef SJD_H
 #define SJD_H

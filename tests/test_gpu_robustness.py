@@ -167,3 +167,61 @@ def test_resume_from_persisted_state_is_bit_exact(B, dtype, mode):
             assert np.abs(pn.view(np.float32) - pn2.view(np.float32)).max() < (1e-5 if dtype == synth.DTYPE_F32 else 2e-3)
     finally:
         B.sjd_kv_free(kv); B.sjd_kv_free(kv2); B.sjd_free_model(m)
+
+
+@pytest.mark.parametrize("use_graph", [True, False])
+def test_two_handles_on_two_streams_from_two_host_threads(B, use_graph):
+    """Handles of one model are independent: two host threads, each decoding an image on its own handle and its
+    own stream at the same time (prefill, the device-resident loop in pieces, status polls in between), get exactly
+    the tokens each gets when it runs alone."""
+    import threading
+    _say(f"two threads, two streams, graph={use_graph}")
+    shape = synth.ModelShape(3, 256, 4, 512, 2048, 1024, 2048, 260, synth.DTYPE_BF16)
+    blob = synth.make_weights(shape, seed=8)
+    m = B.sjd_init_model(B.config_from_shape(shape), blob)
+    kvs = [B.sjd_kv_create(m) for _ in range(2)]
+    try:
+        V, L, N = shape.v_s, 16, 150
+        smp, init = B.sjd_sampler(300, 1.0), B.sjd_init(1, 10, 2047)
+        prompts = [synth.random_tokens(20 + 30 * i, 0, 1024, seed=3 + i) for i in range(2)]
+
+        def decode(i, stream, out, errs):
+            try:
+                q = qs[i]
+                B.sjd_kv_use_graph(kvs[i], use_graph)
+                B.sjd_prefill(m, kvs[i], prompts[i], None, smp, init, q, stream=stream)
+                B.sjd_decode_begin(m, kvs[i], q, N, L, smp, init, 100 + i, stream=stream)
+                done, guard = False, 0
+                while not done:
+                    B.sjd_decode_steps(m, kvs[i], 3, stream=stream)
+                    _, _, done = B.sjd_decode_status(kvs[i])
+                    guard += 1
+                    assert guard < 4 * N
+                toks, st = B.sjd_decode_result(kvs[i], N)
+                out[i] = (toks.copy(), st.steps)
+            except Exception as e:                      # noqa: BLE001  (reported by the main thread)
+                errs.append((i, repr(e)))
+
+        streams = [torch.cuda.Stream() for _ in range(2)]
+        qs = [torch.empty(V, dtype=torch.float32, device="cuda") for _ in range(2)]     # (allocated up front)
+        torch.cuda.synchronize()
+        alone, errs = {}, []
+        for i in range(2):
+            decode(i, streams[i], alone, errs)
+        assert not errs, errs
+        for rep in range(2):
+            both = {}
+            th = [threading.Thread(target=decode, args=(i, streams[i], both, errs)) for i in range(2)]
+            for t in th:
+                t.start()
+            for t in th:
+                t.join(timeout=120)
+            assert not errs, errs
+            for i in range(2):
+                assert i in both, "a thread did not finish"
+                assert np.array_equal(both[i][0], alone[i][0]) and both[i][1] == alone[i][1], (rep, i)
+    finally:
+        torch.cuda.synchronize()
+        for kv in kvs:
+            B.sjd_kv_free(kv)
+        B.sjd_free_model(m)
