@@ -257,9 +257,9 @@ def main():
     u_ids = synth.random_tokens(max(1, (len(ids) + len(emb)) // 4), 0, shape.samp_lo or shape.vocab_total, seed=77)
     rows_per_image = (1 << max(0, (L - 1).bit_length())) if nb > 1 else L
     rows_needed = rows_per_image * nb * (2 if guided else 1)
-    if L > B.SJD_MAX_WINDOW or rows_needed > B.SJD_MAX_ROWS or (nb > 1 and (guided or shape.dtype != 1 or nb > 8)):
+    if L > B.SJD_MAX_WINDOW or rows_needed > B.SJD_MAX_ROWS or (nb > 1 and (shape.dtype != 1 or nb * (2 if guided else 1) > 8)):
         print(f"bench.py: window {L} x batch {nb}{' x 2 contexts' if guided else ''} does not fit one forward "
-              f"(at most {B.SJD_MAX_ROWS} rows, windows up to {B.SJD_MAX_WINDOW}; batches need a bf16 model and no --cfg)",
+              f"(at most {B.SJD_MAX_ROWS} rows and 8 contexts, windows up to {B.SJD_MAX_WINDOW}; batches need a bf16 model)",
               file=sys.stderr)
         sys.exit(2)
     # every image of a batch has its own prompt (same length, different ids)
@@ -365,7 +365,37 @@ def main():
     # ---- whole images: tokens/s (the headline), forward passes per image, SJD vs ordinary AR (window 1) ----
     extra = {}
 
+    class _LoopStats:
+        pass
+
+    def generate_guided_batch(window, ini, seed):
+        """guided batches have no one-call entry point: prefill both contexts of every image, then drive the batched
+        loop in pieces (a few iterations per call, never more than the image furthest from its end can still take)"""
+        for b, h in enumerate(kvs):
+            B.sjd_prefill(m, h, prompts[b] if len(ids) else ids, emb, smp, ini, q_first)
+            B.sjd_prefill_uncond(m, h, u_ids, None, args.cfg, smp, ini, q_first)
+            B.sjd_decode_begin(m, h, q_first, N, window, smp, ini, seed * nb + b)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        most_left, all_done, n_steps = N - 1, False, 0
+        while not all_done:
+            k = max(1, min(8, (most_left + window - 1) // window))
+            B.sjd_decode_steps_batch(m, kvs, k)
+            all_done, most_left = True, 0
+            for h in kvs:
+                fixed, st_steps, done = B.sjd_decode_status(h)
+                all_done &= done
+                n_steps = max(n_steps, st_steps)
+                if not done:
+                    most_left = max(most_left, N - 1 - fixed)
+        st = _LoopStats()
+        st.ms_decode = (time.perf_counter() - t) * 1e3
+        st.steps = n_steps
+        return None, st
+
     def generate(window, ini, seed):
+        if nb > 1 and guided:
+            return generate_guided_batch(window, ini, seed)
         if nb > 1:
             t, sts = B.sjd_generate_batch(m, kvs, prompts, None if not len(emb) else [emb] * nb, N, window, smp, ini,
                                           [seed * nb + b for b in range(nb)])

@@ -207,18 +207,21 @@ int sjd_profile_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t
  * B independent images share every window forward (Sec. 4.1 Step 2 for B windows at once): one pass
  * over the weights serves B x L rows, so an iteration costs little more than for one image and the
  * throughput grows almost B-fold.  Each image keeps its own handle (cache, loop state, random
- * stream); Steps 3 and 4 run per image exactly as in sjd_decode_steps.  bf16 models, no guidance;
- * the B windows (each rounded up to a power of two of rows) must fit the SJD_MAX_ROWS rows of one
- * forward: L <= 64 for B = 2, L <= 32 for B <= 4, L <= 16 for B <= 8.  The first handle lends its activation buffers and, with graphs on,
+ * stream); Steps 3 and 4 run per image exactly as in sjd_decode_steps.  bf16 models.  Guidance: all
+ * handles guided (each after its own sjd_prefill_uncond, each with its own weight) or none; a guided
+ * image brings two contexts.  The contexts' windows (each rounded up to a power of two of rows) must
+ * fit the SJD_MAX_ROWS rows of one forward, at most 8 contexts: L <= 64 for 2 contexts, L <= 32 for
+ * up to 4, L <= 16 for up to 8.  The first handle lends its activation buffers and, with graphs on,
  * holds the captured iteration (re-captured when the set of handles or their settings change).
  *
- * sjd_decode_steps_batch: every handle has been through sjd_prefill + sjd_decode_begin with the same
- * L, sampler and initialiser (seeds may differ); poll and collect per handle with
+ * sjd_decode_steps_batch: every handle has been through sjd_prefill (+ sjd_prefill_uncond) +
+ * sjd_decode_begin with the same L, sampler and initialiser (seeds may differ); poll and collect per handle with
  * sjd_decode_status / sjd_decode_result.  A handle whose image is complete sits out further
  * iterations.  kvs: host array of B distinct handles.                                          */
 int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t n_steps, void *stream);
 
-/* Prompts to images for B handles.  ids / embeds: host arrays of B host pointers (embeds and
+/* Prompts to images for B handles, without guidance (it pre-fills every handle anew; guided batches go
+ * through the pieces above).  ids / embeds: host arrays of B host pointers (embeds and
  * n_embeds may be NULL), out_tokens host [B x N], stats host [B] or NULL (times are the batch's). */
 int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *const *ids, const int32_t *n_ids,
                        const float *const *embeds, const int32_t *n_embeds, int32_t N, int32_t L,
@@ -230,7 +233,8 @@ int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_
  * logits dev [L x V_s] fp32 (the guided logits while guidance is on).  Does not advance n.     */
 int sjd_forward_logits(sjd_model *m, sjd_kv *kv, const int32_t *tokens, int32_t L, float *logits, void *stream);
 
-/* The same for B handles in one forward: tokens dev [B x L], logits dev [B x L x V_s].  A handle
+/* The same for B handles in one forward: tokens dev [B x L], logits dev [B x L x V_s] (of guided handles:
+ * the guided logits).  A handle
  * inside a generation (sjd_decode_begin) whose image is complete is skipped: its rows of `logits`
  * are left as they are.                                                                          */
 int sjd_forward_logits_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *tokens, int32_t L,

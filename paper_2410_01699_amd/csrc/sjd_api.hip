@@ -873,12 +873,18 @@ static int batch_shift(int32_t B, int32_t L)
     return -1;
 }
 
-static int check_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t L, bool decoding)
+// streams of a batch: one per handle, two (conditional, unconditional) when the handles run guided
+static int batch_stream_count(sjd_kv *const *kvs, int32_t B) { return kvs[0]->cfg_on ? 2 * B : B; }
+
+// guided: 0 = the handles' guidance state does not matter (they are about to be pre-filled anew),
+// 1 = all guided or none (with every guided handle's second cache in place)
+static int check_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t L, bool decoding, int guided = 1)
 {
     if (!m || !kvs || B < 1 || B > SJD_MAX_STREAMS || m->cfg.dtype != 1) return SJD_EINVAL;
     for (int b = 0; b < B; ++b) {
         sjd_kv *kv = kvs[b];
-        if (!kv || kv->m != m || kv->cfg_on) return SJD_EINVAL;
+        if (!kv || kv->m != m) return SJD_EINVAL;
+        if (guided && (kv->cfg_on != kvs[0]->cfg_on || (kv->cfg_on && !kv->k_u))) return SJD_EINVAL;
         for (int c = 0; c < b; ++c) if (kvs[c] == kv) return SJD_EINVAL;
         if (decoding) {
             const sjd_kv *k0 = kvs[0];
@@ -888,7 +894,9 @@ static int check_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, int32_t L, b
                 return SJD_EINVAL;
         }
     }
-    return batch_shift(B, L) < 0 ? SJD_EINVAL : SJD_OK;
+    const int S = guided ? batch_stream_count(kvs, B) : B;
+    if (S > SJD_MAX_STREAMS) return SJD_EINVAL;
+    return batch_shift(S, L) < 0 ? SJD_EINVAL : SJD_OK;
 }
 
 // The table of the batch lives in the first handle; it is rewritten (after the stream has drained:
@@ -899,7 +907,11 @@ static int prepare_batch_table(sjd_kv *const *kvs, int32_t B, hipStream_t s)
     sjd_kv *kv0 = kvs[0];
     SjdStreamEntry want[SJD_MAX_STREAMS];
     memset(want, 0, sizeof(want));
-    for (int b = 0; b < B; ++b) want[b] = handle_entry(kvs[b], false);
+    if (kv0->cfg_on) {
+        for (int b = 0; b < B; ++b) { want[2 * b] = handle_entry(kvs[b], false); want[2 * b + 1] = handle_entry(kvs[b], true); }
+    } else {
+        for (int b = 0; b < B; ++b) want[b] = handle_entry(kvs[b], false);
+    }
     if (memcmp(want, kv0->btab_host, sizeof(want)) == 0) return SJD_OK;
     HIP_TRY(hipStreamSynchronize(s));
     HIP_TRY(hipMemcpy(kv0->btab, want, sizeof(want), hipMemcpyHostToDevice));
@@ -911,24 +923,30 @@ static SjdStreams batch_streams(sjd_kv *const *kvs, int32_t B, int32_t L)
 {
     SjdStreams sm;
     memset(&sm, 0, sizeof(sm));
-    sm.count = B; sm.shift = batch_shift(B, L);
+    sm.count = batch_stream_count(kvs, B); sm.shift = batch_shift(sm.count, L);
     sm.first = handle_entry(kvs[0], false);
     sm.table = kvs[0]->btab;
     return sm;
 }
 
-// one window forward for all handles: handle b's tokens ids[b] (device), rows b << shift of the
-// first handle's activation buffers and of its logits buffer
+// one window forward for all handles: handle b's tokens ids[b] (device); its rows are rows b << shift of the
+// first handle's activation buffers and of its logits buffer (guided: rows 2b << shift for the conditional
+// context, (2b + 1) << shift for the unconditional one, both fed the same tokens)
 static int forward_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int32_t *const *ids, int32_t L, hipStream_t s)
 {
     sjd_kv *kv0 = kvs[0];
     const SjdStreams sm = batch_streams(kvs, B, L);
+    const int per = kv0->cfg_on ? 2 : 1;
+    const int32_t *ids_s[SJD_MAX_STREAMS] = {};
     int32_t *errv[SJD_MAX_STREAMS] = {};
-    for (int b = 0; b < B; ++b) { errv[b] = &kvs[b]->state->err; kvs[b]->last_stream = s; }
+    for (int b = 0; b < B; ++b) {
+        for (int c = 0; c < per; ++c) { ids_s[per * b + c] = ids[b]; errv[per * b + c] = &kvs[b]->state->err; }
+        kvs[b]->last_stream = s;
+    }
     const bool lo16 = rows_use_lo16(((sm.count - 1) << sm.shift) + L);
-    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, errv, lo16, s));
+    PROF(kv0, SJD_PROF_ELEMENTWISE, 0, sjd_launch_embed(m, ids_s, nullptr, L, sm, kv0->x, kv0->x24, kv0->ssq, errv, lo16, s));
     double toks = 0;
-    for (int b = 0; b < B; ++b) toks += kvs[b]->n_upper + L;
+    for (int b = 0; b < B; ++b) toks += kvs[b]->n_upper + L + (kv0->cfg_on ? kvs[b]->n_upper_u + L : 0);
     if (kv0->prof) toks = kv0->prof_kv_tokens;
     return forward_rows_bf16(m, kv0, sm, L, L, toks, kv0->logits, s);
 }
@@ -936,7 +954,7 @@ static int forward_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, const int3
 static int decode_one_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, hipStream_t s)
 {
     sjd_kv *kv0 = kvs[0];
-    const int L = kv0->dec_L, shift = batch_shift(B, L);
+    const int L = kv0->dec_L, per = kv0->cfg_on ? 2 : 1, shift = batch_shift(per * B, L);
     const int32_t *ids[SJD_MAX_STREAMS] = {};
     for (int b = 0; b < B; ++b) ids[b] = kvs[b]->g_draft;
     SJD_TRY(forward_batch(m, kvs, B, ids, L, s));
@@ -945,7 +963,8 @@ static int decode_one_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, hipStre
     for (int b = 0; b < B; ++b) {
         sjd_kv *kv = kvs[b];
         SjdVerifyArgs &v = vs[b];
-        v.logits = kv0->logits + ((size_t)b << shift) * m->V_s; v.p_old = kv->g_p; v.draft = kv->g_draft; v.L = L;
+        v.logits = kv0->logits + ((size_t)(per * b) << shift) * m->V_s; v.p_old = kv->g_p; v.draft = kv->g_draft; v.L = L;
+        if (per == 2) { v.logits_u = kv0->logits + ((size_t)(2 * b + 1) << shift) * m->V_s; v.cfg_scale = kv->cfg_scale; }
         v.V = m->V_s; v.lo = m->cfg.samp_lo; v.smp = kv->dec_smp; v.init = kv->dec_init; v.seed = kv->dec_seed;
         v.state = kv->state; v.kv_tokens = kv->tokens; v.n_accepted = kv->g_nacc; v.new_draft = kv->g_draft;
         v.p_new = kv->g_p; v.ring = kv->ring; v.q = kv->q; v.tok_smp = kv->tok_smp; v.tok_res = kv->tok_res;
@@ -974,7 +993,9 @@ extern "C" int sjd_decode_steps_batch(sjd_model *m, sjd_kv *const *kvs, int32_t 
     for (int b = 0; b < B; ++b) {
         key.kv[b] = kvs[b]; key.state[b] = kvs[b]->state; key.cache[b] = kvs[b]->k; key.ring[b] = kvs[b]->ring;
         key.seed[b] = kvs[b]->dec_seed;
+        if (kv0->cfg_on) { key.cache_u[b] = kvs[b]->k_u; key.cfg_scale[b] = kvs[b]->cfg_scale; }
     }
+    key.cfg_on = kv0->cfg_on;
     if (kv0->bgraph_exec && memcmp(&key, &kv0->bkey, sizeof(key)) != 0) drop_batch_graph(kv0);
     if (!kv0->bgraph_exec) {
         // one iteration of all handles; what varies between iterations lives in device memory
@@ -1027,11 +1048,17 @@ extern "C" int sjd_forward_logits_batch(sjd_model *m, sjd_kv *const *kvs, int32_
     const int32_t *ids[SJD_MAX_STREAMS] = {};
     for (int b = 0; b < B; ++b) ids[b] = tokens + (size_t)b * L;
     SJD_TRY(forward_batch(m, kvs, B, ids, L, s));
-    // rows b << shift .. of the shared logits buffer -> [B][L][V_s]
+    // rows b << shift .. of the shared logits buffer -> [B][L][V_s] (guided: the two contexts' rows combined)
     const size_t V = m->V_s;
-    for (int b = 0; b < B; ++b)
-        HIP_TRY(hipMemcpyAsync(logits + (size_t)b * L * V, kvs[0]->logits + ((size_t)b << sm.shift) * V, (size_t)L * V * 4,
-                               hipMemcpyDeviceToDevice, s));
+    for (int b = 0; b < B; ++b) {
+        if (kvs[0]->cfg_on) {
+            SJD_TRY(sjd_launch_guide(kvs[0]->logits + ((size_t)(2 * b) << sm.shift) * V, kvs[0]->logits + ((size_t)(2 * b + 1) << sm.shift) * V,
+                                     kvs[b]->cfg_scale, (size_t)L * V, logits + (size_t)b * L * V, s));
+        } else {
+            HIP_TRY(hipMemcpyAsync(logits + (size_t)b * L * V, kvs[0]->logits + ((size_t)b << sm.shift) * V, (size_t)L * V * 4,
+                                   hipMemcpyDeviceToDevice, s));
+        }
+    }
     return SJD_OK;
 }
 
@@ -1041,7 +1068,7 @@ extern "C" int sjd_generate_batch(sjd_model *m, sjd_kv *const *kvs, int32_t B, c
                                   int32_t *out_tokens, sjd_stats *stats)
 {
     if (!ids || !n_ids || !philox_seeds || !out_tokens || N < 1) return SJD_EINVAL;
-    SJD_TRY(check_batch(m, kvs, B, L, false));
+    SJD_TRY(check_batch(m, kvs, B, L, false, 0));       // (every handle is pre-filled anew below, which ends guidance)
     SJD_TRY(check_sampling(smp, init, m->cfg.samp_lo, m->cfg.samp_hi));
     for (int b = 0; b < B; ++b)
         if (n_ids[b] + (n_embeds ? n_embeds[b] : 0) + N + L > m->cfg.max_seq) return SJD_ESEQ;

@@ -314,6 +314,9 @@ struct sjd_kv {
         sjd_sampler smp;
         sjd_init init;
         const void *kv[SJD_MAX_STREAMS], *state[SJD_MAX_STREAMS], *cache[SJD_MAX_STREAMS], *ring[SJD_MAX_STREAMS];
+        const void *cache_u[SJD_MAX_STREAMS];      // guided batches: the handles' second caches ...
+        float cfg_scale[SJD_MAX_STREAMS];          // ... and their guidance weights
+        int32_t cfg_on;
         uint64_t seed[SJD_MAX_STREAMS];
     } bkey;
     SjdStreamEntry *cfg_tab;                   // device [2]: the two contexts of this handle under guidance

@@ -310,3 +310,113 @@ def test_batch_errors(B):
             _teardown(B, m32, k32)
     finally:
         _teardown(B, m, kvs)
+
+
+# ------------------------------------------------------------------ guided batches (two contexts per image)
+@pytest.mark.parametrize("nb,L,mode,use_graph", [(2, 16, 0, True), (4, 16, 1, True), (3, 7, 4, False), (2, 32, 3, True), (4, 9, 0, False)])
+def test_guided_batch_logits_and_loop(B, nb, L, mode, use_graph):
+    """Batched decoding under classifier-free guidance: every image brings a conditional and an unconditional
+    context (2 x nb streams in one forward, its rows 2b and 2b + 1), each image with its own guidance weight.
+    Guided logits of every image against two oracles per image (oracle.guide of their logits); then the whole
+    batched loop, iteration by iteration, against oracle verifications fed the GPU's guided logits: accepted
+    counts and tokens bit-exact per image, both caches of every image advancing together."""
+    _say(f"guided batch B={nb} L={L} mode={mode} graph={use_graph}")
+    blob, m, kvs, prompts = _setup(B, nb)
+    ocs = [oracle.Model(SHAPE, blob) for _ in range(nb)]
+    ous = [oracle.Model(SHAPE, blob) for _ in range(nb)]
+    try:
+        V, lo = SHAPE.v_s, SHAPE.samp_lo
+        stride, eol, K = 6, 2047, 300
+        N = [stride * (8 - 3 * (b % 2)) for b in range(nb)]
+        ws = [3.0, 1.5, 7.5, 2.0][:nb]
+        uprompts = [synth.random_tokens(3 + 4 * b, 0, 1024, seed=40 + b) for b in range(nb)]
+        smp = B.sjd_sampler(K, 1.0); init = B.sjd_init(mode, stride, eol)
+        osmp = oracle.Sampler(K, 1.0); oinit = oracle.Init(mode, stride, eol)
+        q = torch.empty(V, dtype=torch.float32, device="cuda")
+        B.sjd_kv_use_graph(kvs[0], use_graph)
+        st = []
+        for b in range(nb):
+            B.sjd_prefill(m, kvs[b], prompts[b], None, smp, init, q)
+            B.sjd_prefill_uncond(m, kvs[b], uprompts[b], None, ws[b], smp, init, q)
+            B.sjd_decode_begin(m, kvs[b], q, N[b], L, smp, init, 90 + b)
+            torch.cuda.synchronize()
+            ocs[b].prefill(prompts[b]); ous[b].prefill(uprompts[b])
+            d, p = oracle.first_window(q.cpu().numpy(), L, lo, oinit, 90 + b)
+            st.append({"draft": d, "p": p, "hist": [], "c": 0, "done": False,
+                       "ring": np.zeros((stride, V), np.float32) if mode == 4 else None})
+        logits = torch.empty((nb, L, V), dtype=torch.float32, device="cuda")
+        for it in range(4 * max(N)):
+            if all(s["done"] for s in st):
+                break
+            toks = np.stack([s["draft"] for s in st]).astype(np.int32)
+            B.sjd_forward_logits_batch(m, kvs, _dev(toks), L, logits)
+            torch.cuda.synchronize()
+            lg = logits.cpu().numpy()
+            for b, s in enumerate(st):
+                if s["done"]:
+                    continue
+                n_acc = len(s["hist"])
+                if it < 3:
+                    zc = ocs[b].forward_tokens(len(prompts[b]) + n_acc, toks[b])
+                    zu = ous[b].forward_tokens(len(uprompts[b]) + n_acc, toks[b])
+                    err = float(np.max(np.abs(lg[b] - oracle.guide(zc, zu, ws[b]))))
+                    assert err < TOL_BF16, (it, b, err)
+                s["c"] += 1
+                Le = min(L, N[b] - n_acc)
+                a, nd, pn = oracle.verify(lg[b][:Le], s["p"][:Le], s["draft"][:Le], lo, osmp, oinit, n_acc,
+                                          np.array(s["hist"], np.int32), 90 + b, s["c"], ring=s["ring"])
+                if it < 3:
+                    # (the oracles' caches take the accepted tokens too: positions behind both prompts)
+                    ocs[b].forward_tokens(len(prompts[b]) + n_acc, toks[b]); ocs[b].kv_set_len(len(prompts[b]) + n_acc + a)
+                    ous[b].forward_tokens(len(uprompts[b]) + n_acc, toks[b]); ous[b].kv_set_len(len(uprompts[b]) + n_acc + a)
+                s["hist"] += [int(t) for t in s["draft"][:a]]
+                s["draft"] = np.concatenate([nd, s["draft"][Le:]]).astype(np.int32)
+                s["p"] = np.concatenate([pn, s["p"][Le:]])
+                s["done"] = len(s["hist"]) >= N[b] - 1
+            B.sjd_decode_steps_batch(m, kvs, 1)
+            torch.cuda.synchronize()
+            for b, s in enumerate(st):
+                fixed, steps, done = B.sjd_decode_status(kvs[b])
+                assert fixed == len(s["hist"]), (it, b, fixed, len(s["hist"]))
+                assert steps == s["c"] and bool(done) == s["done"], (it, b)
+                assert B.sjd_kv_len(kvs[b]) == len(prompts[b]) + fixed
+        assert all(s["done"] for s in st)
+        for b, s in enumerate(st):
+            want = np.array(s["hist"][:N[b]], np.int32)
+            if len(want) < N[b]:
+                want = np.append(want, s["draft"][0]).astype(np.int32)
+            got, stats = B.sjd_decode_result(kvs[b], N[b])
+            assert np.array_equal(got, want), (b, np.nonzero(got != want)[0][:5])
+            assert np.all(got[stride - 1::stride] == eol)
+    finally:
+        _teardown(B, m, kvs)
+        for om in ocs + ous:
+            om.close()
+
+
+def test_guided_batch_refuses_mixed_and_oversized_sets(B):
+    """all handles of a batch are guided or none is; two contexts per image count against the eight streams and the
+    128 rows of a forward"""
+    blob, m, kvs, prompts = _setup(B, 5)
+    try:
+        V = SHAPE.v_s
+        smp = B.sjd_sampler(8, 1.0); init = B.sjd_init(0, 0, -1)
+        q = torch.empty(V, dtype=torch.float32, device="cuda")
+        for b in range(5):
+            B.sjd_prefill(m, kvs[b], prompts[b], None, smp, init, q)
+            if b != 1:
+                B.sjd_prefill_uncond(m, kvs[b], prompts[b][:2], None, 3.0, smp, init, q)
+        out = torch.empty((5, 16, V), dtype=torch.float32, device="cuda")
+        toks = _dev(np.zeros((5, 16), np.int32) + 1500)
+        with pytest.raises(B.SjdError):                 # mixed
+            B.sjd_forward_logits_batch(m, kvs[:2], toks, 16, out)
+        B.sjd_prefill_uncond(m, kvs[1], prompts[1][:2], None, 3.0, smp, init, q)
+        B.sjd_forward_logits_batch(m, kvs[:4], toks, 16, out)          # 8 streams x 16 rows: fits
+        with pytest.raises(B.SjdError):                 # 10 streams
+            B.sjd_forward_logits_batch(m, kvs, toks, 16, out)
+        with pytest.raises(B.SjdError):                 # 8 streams x 32 rows
+            B.sjd_forward_logits_batch(m, kvs[:4], _dev(np.zeros((4, 32), np.int32) + 1500), 32,
+                                       torch.empty((4, 32, V), dtype=torch.float32, device="cuda"))
+        torch.cuda.synchronize()
+    finally:
+        _teardown(B, m, kvs)
