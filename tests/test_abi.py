@@ -79,3 +79,18 @@ def test_static_verify_checks_its_arguments_and_its_limit_without_gpu():
                                None)
     assert rc == binding.SJD_ELIMIT
     assert b"static scratch" in lib.sjd_strerror(rc)
+
+
+def test_binding_constants_equal_the_header():
+    """limits and error codes are typed twice (C header, Python binding): they must agree"""
+    from paper_2410_01699_amd import binding
+    src = open(os.path.join(ROOT, "include", "sjd.h")).read()
+
+    def define(name):
+        m = re.search(r"#define\s+" + name + r"\s+\(?([^)\n/]+)\)?", src)
+        assert m, name
+        return int(eval(m.group(1).strip(), {"__builtins__": {}}))          # plain integer expressions only
+
+    for name in ("SJD_OK", "SJD_EINVAL", "SJD_ENOMEM", "SJD_ESEQ", "SJD_EHIP", "SJD_ELIMIT", "SJD_MAX_WINDOW", "SJD_MAX_ROWS",
+                 "SJD_STATIC_VERIFY_FLOATS", "SJD_MAX_SAMP_VOCAB"):
+        assert define(name) == getattr(binding, name), name
